@@ -1,0 +1,260 @@
+"""ctypes front end of the CPU oracle (``pcg_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: the tests, the smoke check and the CPU-baseline leg
+of the benchmark call this; the product path never does and shares no code
+with it.  Arrays are numpy, on the host.  Logits are ``float32`` arrays, or
+``uint16`` arrays holding bfloat16 bit patterns (``bf16_bits`` converts a torch
+bf16 tensor).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "pcg_oracle.c")
+_LIB = os.path.join(_HERE, "libpcg_oracle.so")
+
+F32, BF16 = 0, 1
+NEAR_TIE = 1e-6
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain -O2, OpenMP only for the batch loop)."""
+    stale = (not os.path.exists(_LIB)
+             or os.path.getmtime(_LIB) < max(os.path.getmtime(_SRC),
+                                             os.path.getmtime(os.path.join(_HERE, "pcg_oracle.h"))))
+    if force or stale:
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-fopenmp", "-fPIC",
+                               "-shared", _SRC, "-o", _LIB, "-lm"])
+    return _LIB
+
+
+class _Trace(C.Structure):
+    _fields_ = [("T_prop", C.c_void_p), ("D_prop", C.c_void_p), ("near_acc", C.c_void_p),
+                ("near_grp", C.c_void_p), ("near_tok", C.c_void_p), ("flags", C.c_void_p),
+                ("res_S", C.c_void_p), ("res_lo", C.c_void_p), ("res_hi", C.c_void_p),
+                ("R_norm", C.c_void_p)]
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(build())
+        _lib.pcg_ref_philox4x32_10.restype = None
+        _lib.pcg_ref_uniforms.restype = None
+        _lib.pcg_ref_uniforms.argtypes = [C.c_uint64, C.c_uint64, C.c_uint32, C.c_uint32,
+                                          C.c_void_p, C.c_void_p, C.c_void_p]
+        for name in ("pcg_ref_softmax_row", "pcg_ref_count_mult", "pcg_ref_canonicalize",
+                     "pcg_ref_validate", "pcg_ref_group_probs", "pcg_ref_verify_u",
+                     "pcg_ref_verify"):
+            getattr(_lib, name).restype = C.c_int
+    return _lib
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else C.c_void_p(a.ctypes.data)
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(a), dtype=np.int32)
+
+
+def bf16_bits(t) -> np.ndarray:
+    """torch.bfloat16 CPU tensor -> uint16 numpy array of its bit patterns."""
+    import torch
+    assert t.dtype == torch.bfloat16 and t.device.type == "cpu"
+    return t.contiguous().view(torch.int16).numpy().view(np.uint16)
+
+
+def bf16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
+    return (bits.astype(np.uint32) << 16).view(np.float32)
+
+
+def _logits(a) -> tuple[np.ndarray, int]:
+    """Accept float32 / uint16(bf16 bits) numpy arrays or torch CPU tensors."""
+    if not isinstance(a, np.ndarray):
+        import torch
+        if isinstance(a, torch.Tensor):
+            a = bf16_bits(a) if a.dtype == torch.bfloat16 else a.detach().cpu().numpy()
+    a = np.asarray(a)
+    if a.dtype == np.uint16:
+        return np.ascontiguousarray(a), BF16
+    if a.dtype == np.float32:
+        return np.ascontiguousarray(a), F32
+    raise TypeError(f"logits must be float32 or uint16 (bf16 bits), got {a.dtype}")
+
+
+class OracleError(RuntimeError):
+    pass
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise OracleError(f"{what} failed with code {rc}")
+
+
+def philox4x32_10(ctr, key) -> np.ndarray:
+    c = np.asarray(ctr, dtype=np.uint32).copy()
+    k = np.asarray(key, dtype=np.uint32).copy()
+    out = np.zeros(4, dtype=np.uint32)
+    lib().pcg_ref_philox4x32_10(_p(c), _p(k), _p(out))
+    return out
+
+
+def uniforms(seed: int, offset: int, b: int, i: int) -> tuple[float, float, float]:
+    ua, ug, ut = C.c_double(), C.c_double(), C.c_double()
+    lib().pcg_ref_uniforms(C.c_uint64(seed), C.c_uint64(offset), C.c_uint32(b), C.c_uint32(i),
+                           C.byref(ua), C.byref(ug), C.byref(ut))
+    return ua.value, ug.value, ut.value
+
+
+def softmax_row(logits, temperature: float = 1.0) -> np.ndarray:
+    a, dt = _logits(logits)
+    assert a.ndim == 1
+    out = np.empty(a.shape[0], dtype=np.float64)
+    _check(lib().pcg_ref_softmax_row(_p(a), C.c_int(dt), C.c_int64(a.shape[0]),
+                                     C.c_double(temperature), _p(out)), "softmax_row")
+    return out
+
+
+@dataclass
+class Groups:
+    """Canonical group membership: CSR group -> tokens plus per-token multiplicity."""
+    V: int
+    G: int
+    row_ptr: np.ndarray   # int32 [G+1]
+    members: np.ndarray   # int32 [nnz]
+    mult: np.ndarray      # int32 [V]
+
+    @property
+    def nnz(self) -> int:
+        return int(self.row_ptr[-1])
+
+
+def count_mult(V: int, row_ptr, members) -> np.ndarray:
+    row_ptr, members = _i32(row_ptr), _i32(members)
+    mult = np.empty(V, dtype=np.int32)
+    _check(lib().pcg_ref_count_mult(C.c_int32(V), C.c_int32(len(row_ptr) - 1), _p(row_ptr),
+                                    _p(members), _p(mult)), "count_mult")
+    return mult
+
+
+def canonicalize(V: int, row_ptr, members) -> Groups:
+    """Append a singleton group for every token that is in no group; fill mult."""
+    row_ptr, members = _i32(row_ptr), _i32(members)
+    G = len(row_ptr) - 1
+    oG, onnz = C.c_int32(), C.c_int64()
+    _check(lib().pcg_ref_canonicalize(C.c_int32(V), C.c_int32(G), _p(row_ptr), _p(members),
+                                      C.byref(oG), C.byref(onnz), None, None, None),
+           "canonicalize(size)")
+    rp = np.empty(oG.value + 1, dtype=np.int32)
+    mem = np.empty(max(onnz.value, 1), dtype=np.int32)
+    mult = np.empty(V, dtype=np.int32)
+    _check(lib().pcg_ref_canonicalize(C.c_int32(V), C.c_int32(G), _p(row_ptr), _p(members),
+                                      C.byref(oG), C.byref(onnz), _p(rp), _p(mem), _p(mult)),
+           "canonicalize")
+    return Groups(V, oG.value, rp, mem[:onnz.value], mult)
+
+
+def validate(g: Groups) -> int:
+    return lib().pcg_ref_validate(C.c_int32(g.V), C.c_int32(g.G), _p(g.row_ptr), _p(g.members),
+                                  _p(g.mult))
+
+
+def group_probs(g: Groups, logits, temperature: float = 1.0) -> np.ndarray:
+    """[rows, V] logits -> [rows, G] float64 group probabilities (Eq. 5)."""
+    a, dt = _logits(logits)
+    assert a.ndim == 2 and a.shape[1] == g.V
+    out = np.empty((a.shape[0], g.G), dtype=np.float64)
+    _check(lib().pcg_ref_group_probs(C.c_int32(g.V), C.c_int32(g.G), _p(g.row_ptr),
+                                     _p(g.members), _p(g.mult), _p(a), C.c_int(dt),
+                                     C.c_int64(a.shape[0]), C.c_int64(a.shape[1]),
+                                     C.c_double(temperature), _p(out)), "group_probs")
+    return out
+
+
+@dataclass
+class VerifyResult:
+    accept_len: np.ndarray     # int32 [B]
+    out_tokens: np.ndarray     # int32 [B, K+1], unused tail = -1
+    out_groups: np.ndarray     # int32 [B, K+1]
+    T_prop: np.ndarray         # float64 [B, K]  (NaN where not evaluated)
+    D_prop: np.ndarray
+    near_acc: np.ndarray       # uint8 [B, K]
+    near_grp: np.ndarray       # uint8 [B]
+    near_tok: np.ndarray       # uint8 [B]
+    flags: np.ndarray          # uint8 [B]
+    res_S: np.ndarray          # float64 [B]
+    res_lo: np.ndarray
+    res_hi: np.ndarray
+    R_norm: Optional[np.ndarray]   # float64 [B, G] when requested
+    threads: int = 1
+
+
+def _strides(a: np.ndarray, batch_stride, pos_stride):
+    """Element strides of a [B, P, V] array; explicit values override (0 = shared rows)."""
+    bs = a.shape[1] * a.shape[2] if batch_stride is None else batch_stride
+    ps = a.shape[2] if pos_stride is None else pos_stride
+    return C.c_int64(bs), C.c_int64(ps)
+
+
+def verify(g: Groups, target_logits, draft_logits, prop_tokens, prop_groups, *,
+           temperature: float = 1.0, seed: int = 0, offset: int = 0,
+           uniforms_explicit: Optional[tuple[np.ndarray, np.ndarray, np.ndarray]] = None,
+           B: Optional[int] = None, tgt_batch_stride=None, dft_batch_stride=None,
+           want_R: bool = False, nthreads: int = 1) -> VerifyResult:
+    """One speculative step (Algorithm 1) for B sequences.
+
+    target_logits [Bt, K+1, V], draft_logits [Bd, >=K, V].  ``B`` together with
+    a batch stride of 0 lets many sequences share one set of rows.  With
+    ``uniforms_explicit = (u_acc [B,K], u_grp [B,K+1], u_tok [B,K+1])`` the
+    draws are taken from the arrays instead of Philox(seed, offset).
+    """
+    tgt, dt = _logits(target_logits)
+    dft, dt2 = _logits(draft_logits)
+    assert dt == dt2 and tgt.ndim == 3 and dft.ndim == 3
+    K = tgt.shape[1] - 1
+    assert dft.shape[1] >= K and tgt.shape[2] == g.V and dft.shape[2] == g.V
+    if B is None:
+        B = tgt.shape[0]
+    ptok = _i32(prop_tokens).reshape(B, K)
+    pgrp = _i32(prop_groups).reshape(B, K)
+    tbs, tps = _strides(tgt, tgt_batch_stride, None)
+    dbs, dps = _strides(dft, dft_batch_stride, None)
+
+    al = np.empty(B, dtype=np.int32)
+    otok = np.empty((B, K + 1), dtype=np.int32)
+    ogrp = np.empty((B, K + 1), dtype=np.int32)
+    res = VerifyResult(al, otok, ogrp,
+                       np.empty((B, K)), np.empty((B, K)), np.zeros((B, K), np.uint8),
+                       np.zeros(B, np.uint8), np.zeros(B, np.uint8), np.zeros(B, np.uint8),
+                       np.empty(B), np.empty(B), np.empty(B),
+                       np.empty((B, g.G)) if want_R else None)
+    tr = _Trace(res.T_prop.ctypes.data, res.D_prop.ctypes.data, res.near_acc.ctypes.data,
+                res.near_grp.ctypes.data, res.near_tok.ctypes.data, res.flags.ctypes.data,
+                res.res_S.ctypes.data, res.res_lo.ctypes.data, res.res_hi.ctypes.data,
+                res.R_norm.ctypes.data if want_R else None)
+    common = [C.c_int32(g.V), C.c_int32(g.G), _p(g.row_ptr), _p(g.members), _p(g.mult),
+              _p(tgt), _p(dft), C.c_int(dt), C.c_int32(B), C.c_int32(K), tbs, tps, dbs, dps,
+              C.c_double(temperature), _p(ptok), _p(pgrp)]
+    outs = [_p(al), _p(otok), _p(ogrp), C.byref(tr)]
+    if uniforms_explicit is not None:
+        ua, ug, ut = (np.ascontiguousarray(x, dtype=np.float64) for x in uniforms_explicit)
+        assert ua.shape == (B, K) and ug.shape == (B, K + 1) and ut.shape == (B, K + 1)
+        rc = lib().pcg_ref_verify_u(*common, _p(ua), _p(ug), _p(ut), *outs, C.c_int32(nthreads))
+    else:
+        used = C.c_int32(1)
+        rc = lib().pcg_ref_verify(*common, C.c_uint64(seed), C.c_uint64(offset), *outs,
+                                  C.c_int32(nthreads), C.byref(used))
+        res.threads = used.value
+    _check(rc, "verify")
+    return res

@@ -1,0 +1,428 @@
+/*
+ * pcg_oracle.c -- plain CPU reference for PCG group-level verification.
+ * TEST INFRASTRUCTURE ONLY; see pcg_oracle.h.  Double precision, plain loops,
+ * steps in the order the paper gives them.
+ */
+#include "pcg_oracle.h"
+
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* ------------------------------------------------------------------------- */
+/* Philox4x32-10 (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as   */
+/* easy as 1, 2, 3", SC'11).                                                 */
+/* ------------------------------------------------------------------------- */
+
+void pcg_ref_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]) {
+  uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+  uint32_t k0 = key[0], k1 = key[1];
+  for (int round = 0; round < 10; ++round) {
+    uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+    uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+    uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+    uint32_t n1 = (uint32_t)p1;
+    uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+    uint32_t n3 = (uint32_t)p0;
+    c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+void pcg_ref_uniforms(uint64_t seed, uint64_t offset, uint32_t b, uint32_t i,
+                      double *u_acc, double *u_grp, double *u_tok) {
+  uint32_t ctr[4] = {(uint32_t)offset, (uint32_t)(offset >> 32), b, i};
+  uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+  uint32_t w[4];
+  pcg_ref_philox4x32_10(ctr, key, w);
+  const double scale = 1.0 / 16777216.0; /* 2^-24: the draw is exact in fp32 and fp64 */
+  if (u_acc) *u_acc = (double)(w[0] >> 8) * scale;
+  if (u_grp) *u_grp = (double)(w[1] >> 8) * scale;
+  if (u_tok) *u_tok = (double)(w[2] >> 8) * scale;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Row softmax.                                                              */
+/* ------------------------------------------------------------------------- */
+
+static double logit_at(const void *base, int dtype, int64_t idx) {
+  if (dtype == PCG_REF_F32) return (double)((const float *)base)[idx];
+  /* bfloat16: the upper 16 bits of an IEEE binary32 */
+  uint32_t bits = (uint32_t)((const uint16_t *)base)[idx] << 16;
+  float f;
+  memcpy(&f, &bits, sizeof f);
+  return (double)f;
+}
+
+static int softmax_row_at(const void *base, int dtype, int64_t first, int64_t V,
+                          double temperature, double *prob) {
+  double mx = -INFINITY;
+  for (int64_t t = 0; t < V; ++t) {
+    double x = logit_at(base, dtype, first + t) / temperature;
+    if (isnan(x) || x == INFINITY) return PCG_REF_ERR_ROW;
+    prob[t] = x;
+    if (x > mx) mx = x;
+  }
+  if (mx == -INFINITY) return PCG_REF_ERR_ROW;
+  double Z = 0.0;
+  for (int64_t t = 0; t < V; ++t) {
+    prob[t] = exp(prob[t] - mx);
+    Z += prob[t];
+  }
+  for (int64_t t = 0; t < V; ++t) prob[t] /= Z;
+  return PCG_REF_OK;
+}
+
+int pcg_ref_softmax_row(const void *logits, int dtype, int64_t V, double temperature,
+                        double *prob) {
+  if (!logits || !prob || V < 1 || !(temperature > 0.0)) return PCG_REF_ERR_ARG;
+  if (dtype != PCG_REF_F32 && dtype != PCG_REF_BF16) return PCG_REF_ERR_ARG;
+  return softmax_row_at(logits, dtype, 0, V, temperature, prob);
+}
+
+/* ------------------------------------------------------------------------- */
+/* Group membership.                                                         */
+/* ------------------------------------------------------------------------- */
+
+static int csr_shape_ok(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members) {
+  if (row_ptr[0] != 0) return 0;
+  for (int32_t g = 0; g < G; ++g)
+    if (row_ptr[g + 1] < row_ptr[g]) return 0;
+  for (int32_t j = 0; j < row_ptr[G]; ++j)
+    if (members[j] < 0 || members[j] >= V) return 0;
+  return 1;
+}
+
+int pcg_ref_count_mult(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members,
+                       int32_t *mult) {
+  if (V < 1 || G < 0 || !row_ptr || !mult || (G > 0 && row_ptr[G] > 0 && !members))
+    return PCG_REF_ERR_ARG;
+  if (!csr_shape_ok(V, G, row_ptr, members)) return PCG_REF_ERR_CSR;
+  for (int32_t v = 0; v < V; ++v) mult[v] = 0;
+  for (int32_t j = 0; j < row_ptr[G]; ++j) mult[members[j]] += 1;
+  return PCG_REF_OK;
+}
+
+int pcg_ref_canonicalize(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members,
+                         int32_t *out_G, int64_t *out_nnz, int32_t *out_row_ptr,
+                         int32_t *out_members, int32_t *out_mult) {
+  if (V < 1 || G < 0 || !row_ptr || !out_G || !out_nnz) return PCG_REF_ERR_ARG;
+  if (G > 0 && row_ptr[G] > 0 && !members) return PCG_REF_ERR_ARG;
+  if (!csr_shape_ok(V, G, row_ptr, members)) return PCG_REF_ERR_CSR;
+  int32_t *cnt = (int32_t *)calloc((size_t)V, sizeof(int32_t));
+  if (!cnt) return PCG_REF_ERR_NOMEM;
+  int32_t nnz = row_ptr[G];
+  for (int32_t j = 0; j < nnz; ++j) cnt[members[j]] += 1;
+  int32_t uncovered = 0;
+  for (int32_t v = 0; v < V; ++v)
+    if (cnt[v] == 0) ++uncovered;
+  *out_G = G + uncovered;
+  *out_nnz = (int64_t)nnz + uncovered;
+  if (out_row_ptr && out_members && out_mult) {
+    for (int32_t g = 0; g <= G; ++g) out_row_ptr[g] = row_ptr[g];
+    for (int32_t j = 0; j < nnz; ++j) out_members[j] = members[j];
+    int32_t g = G, j = nnz;
+    for (int32_t v = 0; v < V; ++v) {
+      if (cnt[v] == 0) {        /* a token in no group acts as its own group */
+        out_members[j++] = v;
+        out_row_ptr[++g] = j;
+        out_mult[v] = 1;
+      } else {
+        out_mult[v] = cnt[v];
+      }
+    }
+  }
+  free(cnt);
+  return PCG_REF_OK;
+}
+
+int pcg_ref_validate(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members,
+                     const int32_t *mult) {
+  if (V < 1 || G < 1 || !row_ptr || !members || !mult) return PCG_REF_ERR_ARG;
+  if (!csr_shape_ok(V, G, row_ptr, members)) return PCG_REF_ERR_CSR;
+  int32_t *cnt = (int32_t *)calloc((size_t)V, sizeof(int32_t));
+  if (!cnt) return PCG_REF_ERR_NOMEM;
+  for (int32_t j = 0; j < row_ptr[G]; ++j) cnt[members[j]] += 1;
+  int rc = PCG_REF_OK;
+  for (int32_t v = 0; v < V; ++v)
+    if (cnt[v] < 1 || cnt[v] != mult[v]) rc = PCG_REF_ERR_CSR;
+  free(cnt);
+  return rc;
+}
+
+/* Eq. (5): the probability a row gives to group g when every token's mass is
+ * split equally over the mult[t] groups that hold it. */
+static double group_prob(const double *prob, const int32_t *row_ptr, const int32_t *members,
+                         const int32_t *mult, int32_t g) {
+  double s = 0.0;
+  for (int32_t j = row_ptr[g]; j < row_ptr[g + 1]; ++j) {
+    int32_t t = members[j];
+    s += prob[t] / (double)mult[t];
+  }
+  return s;
+}
+
+int pcg_ref_group_probs(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members,
+                        const int32_t *mult, const void *logits, int dtype, int64_t rows,
+                        int64_t row_stride, double temperature, double *out) {
+  if (!row_ptr || !members || !mult || !logits || !out) return PCG_REF_ERR_ARG;
+  if (V < 1 || G < 1 || rows < 0 || !(temperature > 0.0)) return PCG_REF_ERR_ARG;
+  if (dtype != PCG_REF_F32 && dtype != PCG_REF_BF16) return PCG_REF_ERR_ARG;
+  int rc = pcg_ref_validate(V, G, row_ptr, members, mult);
+  if (rc) return rc;
+  double *prob = (double *)malloc((size_t)V * sizeof(double));
+  if (!prob) return PCG_REF_ERR_NOMEM;
+  for (int64_t r = 0; r < rows && rc == PCG_REF_OK; ++r) {
+    rc = softmax_row_at(logits, dtype, r * row_stride, V, temperature, prob);
+    if (rc) break;
+    for (int32_t g = 0; g < G; ++g)
+      out[r * (int64_t)G + g] = group_prob(prob, row_ptr, members, mult, g);
+  }
+  free(prob);
+  return rc;
+}
+
+/* ------------------------------------------------------------------------- */
+/* One speculative step (Algorithm 1) for one sequence.                      */
+/* ------------------------------------------------------------------------- */
+
+typedef struct {
+  int32_t V, G;
+  const int32_t *row_ptr, *members, *mult;
+  const void *tgt, *dft;
+  int dtype;
+  int32_t B, K;
+  int64_t tbs, tps, dbs, dps;
+  double temperature;
+  const int32_t *prop_tokens, *prop_groups;
+  const double *u_acc, *u_grp, *u_tok;
+  int32_t *accept_len, *out_tokens, *out_groups;
+  const pcg_ref_trace *trace;
+} step_args;
+
+/* scratch: q [V], p [V], Tg [G], Dg [G], R [G] */
+static int verify_sequence(const step_args *a, int32_t b, double *q, double *p, double *Tg,
+                           double *Dg, double *R) {
+  const int32_t K = a->K, G = a->G;
+  const pcg_ref_trace *tr = a->trace;
+  int32_t *otok = a->out_tokens + (int64_t)b * (K + 1);
+  int32_t *ogrp = a->out_groups + (int64_t)b * (K + 1);
+  for (int32_t i = 0; i <= K; ++i) otok[i] = ogrp[i] = -1;
+  if (tr) {
+    for (int32_t i = 0; i < K; ++i) {
+      if (tr->T_prop) tr->T_prop[(int64_t)b * K + i] = NAN;
+      if (tr->D_prop) tr->D_prop[(int64_t)b * K + i] = NAN;
+      if (tr->near_acc) tr->near_acc[(int64_t)b * K + i] = 0;
+    }
+    if (tr->near_grp) tr->near_grp[b] = 0;
+    if (tr->near_tok) tr->near_tok[b] = 0;
+    if (tr->flags) tr->flags[b] = 0;
+  }
+
+  /* Draft positions in order; stop at the first rejected group. */
+  int32_t i = 0;
+  int rc;
+  while (i < K) {
+    rc = softmax_row_at(a->tgt, a->dtype, b * a->tbs + i * a->tps, a->V, a->temperature, q);
+    if (rc) return rc;
+    rc = softmax_row_at(a->dft, a->dtype, b * a->dbs + i * a->dps, a->V, a->temperature, p);
+    if (rc) return rc;
+    int32_t g = a->prop_groups[(int64_t)b * K + i];
+    if (g < 0 || g >= G) return PCG_REF_ERR_ARG;
+    double Tprop = group_prob(q, a->row_ptr, a->members, a->mult, g);
+    double Dprop = group_prob(p, a->row_ptr, a->members, a->mult, g);
+    double u = a->u_acc[(int64_t)b * K + i];
+    /* Eq. (7): accept iff u < min(1, T/D), written without the division so
+     * that D == 0 is defined: T > 0 accepts, T == 0 rejects. */
+    int accept = (u * Dprop < Tprop);
+    if (tr) {
+      if (tr->T_prop) tr->T_prop[(int64_t)b * K + i] = Tprop;
+      if (tr->D_prop) tr->D_prop[(int64_t)b * K + i] = Dprop;
+      if (tr->near_acc && fabs(u * Dprop - Tprop) < PCG_REF_NEAR_TIE * Dprop)
+        tr->near_acc[(int64_t)b * K + i] = 1;
+      if (tr->flags && Dprop == 0.0) tr->flags[b] |= 2;
+    }
+    if (!accept) break;
+    otok[i] = a->prop_tokens[(int64_t)b * K + i]; /* the draft token stands for its group */
+    ogrp[i] = g;
+    ++i;
+  }
+  a->accept_len[b] = i;
+
+  /* Decision row i: the rejected position, or the bonus position K. */
+  if (i == K) {
+    rc = softmax_row_at(a->tgt, a->dtype, b * a->tbs + i * a->tps, a->V, a->temperature, q);
+    if (rc) return rc;
+  }
+  for (int32_t g = 0; g < G; ++g) Tg[g] = group_prob(q, a->row_ptr, a->members, a->mult, g);
+  if (i < K) {
+    for (int32_t g = 0; g < G; ++g) Dg[g] = group_prob(p, a->row_ptr, a->members, a->mult, g);
+    for (int32_t g = 0; g < G; ++g) R[g] = Tg[g] > Dg[g] ? Tg[g] - Dg[g] : 0.0; /* Eq. (8) */
+  } else {
+    for (int32_t g = 0; g < G; ++g) R[g] = Tg[g]; /* bonus: nothing was proposed here */
+  }
+  double S = 0.0;
+  for (int32_t g = 0; g < G; ++g) S += R[g];
+  if (!(S > 0.0)) { /* cannot happen in exact arithmetic; fall back to T */
+    S = 0.0;
+    for (int32_t g = 0; g < G; ++g) { R[g] = Tg[g]; S += R[g]; }
+    if (tr && tr->flags) tr->flags[b] |= 1;
+  }
+
+  /* Inverse CDF over groups in ascending id: the first g whose running total
+   * strictly exceeds u*S.  Zero-mass groups can never be chosen. */
+  double ug = a->u_grp[(int64_t)b * (K + 1) + i];
+  double goal = ug * S;
+  double cum = 0.0, lo = 0.0, hi = 0.0;
+  int32_t gs = -1, last_pos = -1;
+  for (int32_t g = 0; g < G; ++g) {
+    if (R[g] > 0.0) last_pos = g;
+    double nxt = cum + R[g];
+    if (gs < 0 && nxt > goal) { gs = g; lo = cum; hi = nxt; }
+    cum = nxt;
+  }
+  if (gs < 0) { /* rounding at the top end: the last group that has mass */
+    gs = last_pos < 0 ? 0 : last_pos;
+    lo = cum - R[gs];
+    hi = cum;
+  }
+  if (tr) {
+    if (tr->res_S) tr->res_S[b] = S;
+    if (tr->res_lo) tr->res_lo[b] = lo / S;
+    if (tr->res_hi) tr->res_hi[b] = hi / S;
+    if (tr->near_grp) {
+      int near_lo = lo > 0.0 && (goal - lo) < PCG_REF_NEAR_TIE * S;
+      int near_hi = hi < cum && (hi - goal) < PCG_REF_NEAR_TIE * S;
+      tr->near_grp[b] = (uint8_t)(near_lo || near_hi);
+    }
+    if (tr->R_norm)
+      for (int32_t g = 0; g < G; ++g) tr->R_norm[(int64_t)b * G + g] = R[g] / S;
+  }
+
+  /* Eq. (10): token inside the emitted group, proportional to q(t)/mult[t]
+   * over the group's members in CSR order. */
+  int32_t beg = a->row_ptr[gs], end = a->row_ptr[gs + 1];
+  double C = 0.0;
+  for (int32_t j = beg; j < end; ++j) C += q[a->members[j]] / (double)a->mult[a->members[j]];
+  double ut = a->u_tok[(int64_t)b * (K + 1) + i];
+  double tgoal = ut * C;
+  double tc = 0.0, tlo = 0.0, thi = 0.0;
+  int32_t js = -1, jlast = -1;
+  for (int32_t j = beg; j < end; ++j) {
+    double c = q[a->members[j]] / (double)a->mult[a->members[j]];
+    if (c > 0.0) jlast = j;
+    double nxt = tc + c;
+    if (js < 0 && nxt > tgoal) { js = j; tlo = tc; thi = nxt; }
+    tc = nxt;
+  }
+  if (js < 0) { js = jlast; }
+  if (js < 0) { js = beg; } /* whole group has zero mass: only reachable through the fallback */
+  if (tr && tr->near_tok && C > 0.0 && thi > 0.0) {
+    int near_lo = tlo > 0.0 && (tgoal - tlo) < PCG_REF_NEAR_TIE * C;
+    int near_hi = thi < tc && (thi - tgoal) < PCG_REF_NEAR_TIE * C;
+    tr->near_tok[b] = (uint8_t)(near_lo || near_hi);
+  }
+  otok[i] = a->members[js];
+  ogrp[i] = gs;
+  return PCG_REF_OK;
+}
+
+int pcg_ref_verify_u(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members,
+                     const int32_t *mult, const void *target_logits, const void *draft_logits,
+                     int dtype, int32_t B, int32_t K, int64_t tgt_batch_stride,
+                     int64_t tgt_pos_stride, int64_t dft_batch_stride, int64_t dft_pos_stride,
+                     double temperature, const int32_t *prop_tokens, const int32_t *prop_groups,
+                     const double *u_acc, const double *u_grp, const double *u_tok,
+                     int32_t *accept_len, int32_t *out_tokens, int32_t *out_groups,
+                     const pcg_ref_trace *trace, int32_t nthreads) {
+  if (!row_ptr || !members || !mult || !target_logits || !draft_logits || !prop_tokens ||
+      !prop_groups || !u_acc || !u_grp || !u_tok || !accept_len || !out_tokens || !out_groups)
+    return PCG_REF_ERR_ARG;
+  if (V < 1 || G < 1 || B < 0 || K < 1 || !(temperature > 0.0)) return PCG_REF_ERR_ARG;
+  if (dtype != PCG_REF_F32 && dtype != PCG_REF_BF16) return PCG_REF_ERR_ARG;
+  int rc = pcg_ref_validate(V, G, row_ptr, members, mult);
+  if (rc) return rc;
+
+  step_args a;
+  a.V = V; a.G = G; a.row_ptr = row_ptr; a.members = members; a.mult = mult;
+  a.tgt = target_logits; a.dft = draft_logits; a.dtype = dtype; a.B = B; a.K = K;
+  a.tbs = tgt_batch_stride; a.tps = tgt_pos_stride; a.dbs = dft_batch_stride;
+  a.dps = dft_pos_stride; a.temperature = temperature;
+  a.prop_tokens = prop_tokens; a.prop_groups = prop_groups;
+  a.u_acc = u_acc; a.u_grp = u_grp; a.u_tok = u_tok;
+  a.accept_len = accept_len; a.out_tokens = out_tokens; a.out_groups = out_groups;
+  a.trace = trace;
+
+  if (nthreads < 1) nthreads = 1;
+  int status = PCG_REF_OK;
+#ifdef _OPENMP
+#pragma omp parallel num_threads(nthreads)
+#endif
+  {
+    size_t nd = 2 * (size_t)V + 3 * (size_t)G;
+    double *buf = (double *)malloc(nd * sizeof(double));
+    if (!buf) {
+#ifdef _OPENMP
+#pragma omp critical
+#endif
+      status = PCG_REF_ERR_NOMEM;
+    }
+#ifdef _OPENMP
+#pragma omp barrier
+#pragma omp for schedule(dynamic, 1)
+#endif
+    for (int32_t b = 0; b < B; ++b) {
+      if (!buf || status != PCG_REF_OK) continue;
+      int r = verify_sequence(&a, b, buf, buf + V, buf + 2 * (size_t)V,
+                              buf + 2 * (size_t)V + G, buf + 2 * (size_t)V + 2 * (size_t)G);
+      if (r) {
+#ifdef _OPENMP
+#pragma omp critical
+#endif
+        status = r;
+      }
+    }
+    free(buf);
+  }
+  return status;
+}
+
+int pcg_ref_verify(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members,
+                   const int32_t *mult, const void *target_logits, const void *draft_logits,
+                   int dtype, int32_t B, int32_t K, int64_t tgt_batch_stride,
+                   int64_t tgt_pos_stride, int64_t dft_batch_stride, int64_t dft_pos_stride,
+                   double temperature, const int32_t *prop_tokens, const int32_t *prop_groups,
+                   uint64_t seed, uint64_t offset, int32_t *accept_len, int32_t *out_tokens,
+                   int32_t *out_groups, const pcg_ref_trace *trace, int32_t nthreads,
+                   int32_t *threads_used) {
+  if (B < 0 || K < 1) return PCG_REF_ERR_ARG;
+  size_t nacc = (size_t)B * (size_t)K, nres = (size_t)B * ((size_t)K + 1);
+  double *u = (double *)malloc((nacc + 2 * nres + 1) * sizeof(double));
+  if (!u) return PCG_REF_ERR_NOMEM;
+  double *u_acc = u, *u_grp = u + nacc, *u_tok = u + nacc + nres;
+  for (int32_t b = 0; b < B; ++b) {
+    for (int32_t i = 0; i <= K; ++i) {
+      double ua, ug, ut;
+      pcg_ref_uniforms(seed, offset, (uint32_t)b, (uint32_t)i, &ua, &ug, &ut);
+      if (i < K) u_acc[(size_t)b * K + i] = ua;
+      u_grp[(size_t)b * (K + 1) + i] = ug;
+      u_tok[(size_t)b * (K + 1) + i] = ut;
+    }
+  }
+  if (nthreads < 1) nthreads = 1;
+#ifndef _OPENMP
+  nthreads = 1;
+#endif
+  if (threads_used) *threads_used = nthreads;
+  int rc = pcg_ref_verify_u(V, G, row_ptr, members, mult, target_logits, draft_logits, dtype, B,
+                            K, tgt_batch_stride, tgt_pos_stride, dft_batch_stride,
+                            dft_pos_stride, temperature, prop_tokens, prop_groups, u_acc, u_grp,
+                            u_tok, accept_len, out_tokens, out_groups, trace, nthreads);
+  free(u);
+  return rc;
+}

@@ -1,0 +1,198 @@
+/*
+ * pcg.h -- C ABI of libpcg: group-level verification for speculative decoding
+ * over acoustic tokens ("Principled Coarse-Graining", arXiv 2511.13732) on one
+ * AMD MI355X (gfx950).
+ *
+ * One call to pcg_verify is one speculative step for B sequences
+ * (Algorithm 1): softmax of target and draft logits over the vocabulary, the
+ * overlap-aware group probabilities of Eq. (5) with equal-split weights
+ * (Eq. 3), the group accept test of Eq. (7) on each proposed group until the
+ * first rejection, then a group drawn from the normalised residual of Eq. (8)
+ * and a token inside it by Eq. (10); when every proposal is accepted the extra
+ * ("bonus") position is drawn from the target's last row instead.
+ *
+ * Naming.  The paper's body writes q for the target model and p for the
+ * draft, Q_c / P_c for their group distributions.  This header uses
+ *     T[g] = target group probability,   D[g] = draft group probability,
+ * so the accept ratio is T/D and the residual is max(0, T - D).
+ *
+ * Conventions that hold for every entry point unless stated otherwise:
+ *   - pointers marked DEVICE point to memory of the current HIP device, are
+ *     owned by the caller and must stay valid until the stream has run the
+ *     call; pointers marked HOST are ordinary host memory;
+ *   - the library allocates no device memory: scratch comes in through
+ *     `workspace` (DEVICE, 256-byte aligned, size from the *_workspace_bytes
+ *     helpers) and may be reused by the next call on the same stream;
+ *   - calls only enqueue work on `hip_stream` (a hipStream_t, NULL = default
+ *     stream) and return without synchronising;
+ *   - the return value is PCG_OK (0) or a negative pcg_status; nothing is
+ *     thrown across the boundary; after PCG_ERR_HIP, pcg_last_hip_error()
+ *     gives the hipError_t;
+ *   - arguments are checked on the host before anything is launched, so a
+ *     call that returns an error has enqueued nothing.
+ */
+#ifndef PCG_H
+#define PCG_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { PCG_F32 = 0, PCG_BF16 = 1 } pcg_dtype;
+
+typedef enum {
+  PCG_OK = 0,
+  PCG_ERR_NULL_ARG = -1,
+  PCG_ERR_BAD_SHAPE = -2,          /* V, G, nnz, B, K, rows out of range                    */
+  PCG_ERR_BAD_DTYPE = -3,
+  PCG_ERR_BAD_STRIDE = -4,         /* a stride smaller than V (other than 0) or negative    */
+  PCG_ERR_BAD_TEMPERATURE = -5,    /* not a finite number > 0                               */
+  PCG_ERR_WORKSPACE_TOO_SMALL = -6,
+  PCG_ERR_BAD_CSR = -7,            /* host validation of the group membership failed        */
+  PCG_ERR_HIP = -8,                /* a HIP runtime call failed                             */
+  PCG_ERR_MISALIGNED = -9          /* workspace not 256-byte aligned, logits not element-aligned */
+} pcg_status;
+
+#define PCG_MAX_K 64               /* largest number of draft positions per step           */
+
+/*
+ * Group membership (Sec. 2.1, 2.2): the distinct Acoustic Similarity Groups as
+ * CSR group -> tokens, plus the per-token multiplicity N(t) of Eq. (3).
+ * All three arrays are DEVICE, read-only.  The structure itself is HOST.
+ *   row_ptr [G+1]  row_ptr[0] = 0, non-decreasing, row_ptr[G] = nnz
+ *   members [nnz]  token ids in [0, V); members of group g are
+ *                  members[row_ptr[g] .. row_ptr[g+1])
+ *   mult    [V]    mult[v] = number of CSR entries equal to v, >= 1 for all v
+ * A token listed twice in one group carries weight 2/mult there.  The arrays
+ * must describe a membership that pcg_groups_validate_host accepts; the
+ * kernels do not re-check them.
+ */
+typedef struct {
+  int32_t V;
+  int32_t G;
+  int64_t nnz;
+  const int32_t *row_ptr;
+  const int32_t *members;
+  const int32_t *mult;
+} pcg_groups;
+
+/*
+ * Optional counters a call adds to (DEVICE, caller zeroes them; may be NULL).
+ * "near" means the uniform draw fell within 1e-6 (on the unit interval) of a
+ * threshold that separates two outcomes, as judged in the kernel's own
+ * arithmetic.
+ */
+typedef struct {
+  uint32_t near_accept;        /* accept tests with |u*D - T| < 1e-6 * D                    */
+  uint32_t near_group;         /* residual group draws near an inner bin edge               */
+  uint32_t near_token;         /* in-group token draws near an inner bin edge               */
+  uint32_t zero_draft_mass;    /* evaluated proposals with D[g] == 0                        */
+  uint32_t residual_fallback;  /* rejected rows whose residual total was <= 0 (drawn from T)*/
+  uint32_t bad_proposal;       /* proposed group id outside [0, G): treated as rejected     */
+  uint32_t accepted_total;     /* sum of accept_len over the batch                          */
+  uint32_t sequences;          /* number of sequences processed                             */
+} pcg_diag;
+
+/* ---- group probabilities: Eq. (5) ------------------------------------------------------- */
+
+/*
+ * out[r*G + g] = sum over members t of group g of softmax(logits[r,:]/temperature)[t] / mult[t]
+ * for r in [0, rows).  No renormalisation is applied (Eq. 2 makes each row sum to 1).
+ *   logits            DEVICE [rows, V], element type `dt`, V-axis contiguous,
+ *                     row r starts at element r*row_stride (row_stride >= V)
+ *   out               DEVICE [rows, G] float32, row-major
+ *   workspace         DEVICE, >= pcg_group_probs_workspace_bytes(V, rows)
+ * Rows are independent; rows == 0 is a no-op.  Logits must be finite or -inf
+ * with at least one finite entry per row, else that row's output is NaN.
+ */
+int pcg_group_probs(const pcg_groups *groups, const void *logits, pcg_dtype dt, int64_t rows,
+                    int64_t row_stride, float temperature, float *out, void *workspace,
+                    size_t workspace_bytes, void *hip_stream);
+
+size_t pcg_group_probs_workspace_bytes(int32_t V, int64_t rows);
+
+/* ---- one speculative step: Algorithm 1 with Eq. (5), (7), (8), (10) --------------------- */
+
+/*
+ *   target_logits  DEVICE, row (b, i), i in [0, K], starts at element
+ *                  b*tgt_batch_stride + i*tgt_pos_stride; V-axis contiguous
+ *   draft_logits   DEVICE, row (b, i), i in [0, K), likewise with the dft strides (a
+ *                  [B, K+1, V] draft buffer can be passed; its last row is never read)
+ *   strides        in elements; each >= V, or 0 for a batch stride (all sequences then
+ *                  share the same rows)
+ *   prop_tokens    DEVICE int32 [B, K]  the draft's token at each position (only copied out)
+ *   prop_groups    DEVICE int32 [B, K]  the group drawn for it by Eq. (6)
+ *   seed, offset   Philox4x32-10 key and call counter: position (b, i) uses the block with
+ *                  counter (offset_lo, offset_hi, b, i) and key (seed_lo, seed_hi); its
+ *                  words 0, 1, 2 give the accept, group and token uniforms as
+ *                  (word >> 8) * 2^-24.  A decode loop passes its step index as `offset`.
+ *   accept_len     DEVICE int32 [B]     number of accepted proposals, in [0, K]
+ *   out_tokens     DEVICE int32 [B, K+1], out_groups likewise: entries [0, accept_len) are
+ *                  the accepted (prop_token, prop_group) pairs; entry accept_len is the
+ *                  resampled (rejection) or bonus (all accepted) pair; the rest is -1
+ *   diag           DEVICE pcg_diag*, may be NULL
+ *   workspace      DEVICE, >= pcg_verify_workspace_bytes(V, G, B, K)
+ * Accept test (Eq. 7): accept iff u * D[g] < T[g] (so D = 0 < T accepts, T = D = 0
+ * rejects).  Inverse-CDF draws take the first index whose running sum strictly exceeds
+ * u * total; zero-mass groups and tokens are never chosen.  The accept test never reads
+ * prop_tokens, so token-in-group consistency of the proposal is the caller's business.
+ * B == 0 is a no-op; 1 <= K <= PCG_MAX_K.
+ */
+int pcg_verify(const pcg_groups *groups, const void *target_logits, const void *draft_logits,
+               pcg_dtype dt, int32_t B, int32_t K, int64_t tgt_batch_stride,
+               int64_t tgt_pos_stride, int64_t dft_batch_stride, int64_t dft_pos_stride,
+               float temperature, const int32_t *prop_tokens, const int32_t *prop_groups,
+               uint64_t seed, uint64_t offset, int32_t *accept_len, int32_t *out_tokens,
+               int32_t *out_groups, pcg_diag *diag, void *workspace, size_t workspace_bytes,
+               void *hip_stream);
+
+size_t pcg_verify_workspace_bytes(int32_t V, int32_t G, int32_t B, int32_t K);
+
+/* ---- group membership on the host -------------------------------------------------------- */
+
+/* PCG_OK iff (row_ptr, members, mult), all HOST, form a membership the kernels may use (see
+ * pcg_groups above); PCG_ERR_BAD_CSR otherwise. */
+int pcg_groups_validate_host(int32_t V, int32_t G, const int32_t *row_ptr,
+                             const int32_t *members, const int32_t *mult);
+
+/*
+ * Make any CSR usable: a token that is in no group becomes its own singleton group
+ * (Eq. 1 puts every token in its own similarity group, so this is what the paper's
+ * construction implies).  Singletons are appended after the G given groups in
+ * ascending token order; mult is filled with the entry counts.  All pointers HOST.
+ * Call with out_row_ptr == NULL to obtain *out_G and *out_nnz, then again with
+ * out_row_ptr [*out_G + 1], out_members [*out_nnz], out_mult [V].
+ */
+int pcg_groups_canonicalize_host(int32_t V, int32_t G, const int32_t *row_ptr,
+                                 const int32_t *members, int32_t *out_G, int64_t *out_nnz,
+                                 int32_t *out_row_ptr, int32_t *out_members, int32_t *out_mult);
+
+/* ---- per-kernel timing (for the benchmark) ------------------------------------------------ */
+
+#define PCG_MAX_STAGES 8
+/*
+ * Between pcg_profile_begin and pcg_profile_end every pcg_verify / pcg_group_probs call
+ * brackets each of its kernels with HIP events on the call's stream (this costs time; leave
+ * it off otherwise).  pcg_profile_end synchronises those events and writes, for each stage,
+ * the mean duration in milliseconds over the recorded calls (HOST float [PCG_MAX_STAGES],
+ * unused entries 0), the number of calls (HOST) and returns PCG_OK.  At most `max_calls`
+ * calls are recorded; later ones run unrecorded.  Stage names: pcg_stage_name(i).
+ * Not thread-safe; one profile at a time.
+ */
+int pcg_profile_begin(int32_t max_calls);
+int pcg_profile_end(float *stage_ms, int32_t *calls);
+const char *pcg_stage_name(int32_t stage);
+
+/* ---- errors -------------------------------------------------------------------------------- */
+
+const char *pcg_strerror(int status);
+int pcg_last_hip_error(void);
+const char *pcg_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PCG_H */

@@ -320,14 +320,13 @@ static int verify_sequence(const step_args *a, int32_t b, double *q, double *p, 
     if (js < 0 && nxt > tgoal) { js = j; tlo = tc; thi = nxt; }
     tc = nxt;
   }
-  if (js < 0) { js = jlast; }
-  if (js < 0) { js = beg; } /* whole group has zero mass: only reachable through the fallback */
+  if (js < 0) { js = jlast; } /* rounding at the top end: the last member that has mass */
   if (tr && tr->near_tok && C > 0.0 && thi > 0.0) {
     int near_lo = tlo > 0.0 && (tgoal - tlo) < PCG_REF_NEAR_TIE * C;
     int near_hi = thi < tc && (thi - tgoal) < PCG_REF_NEAR_TIE * C;
     tr->near_tok[b] = (uint8_t)(near_lo || near_hi);
   }
-  otok[i] = a->members[js];
+  otok[i] = js < 0 ? -1 : a->members[js]; /* -1: the group holds no mass at all (invalid rows only) */
   ogrp[i] = gs;
   return PCG_REF_OK;
 }

@@ -1,0 +1,277 @@
+"""ctypes binding of libpcg.so: argument marshalling only."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+import torch
+
+F32, BF16 = 0, 1
+MAX_STAGES = 8
+_HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+class PcgError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__(f"{what}: {strerror(status)} (status {status})")
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "libpcg.so")
+
+
+class _GroupsStruct(C.Structure):
+    _fields_ = [("V", C.c_int32), ("G", C.c_int32), ("nnz", C.c_int64),
+                ("row_ptr", C.c_void_p), ("members", C.c_void_p), ("mult", C.c_void_p)]
+
+
+class Diag(C.Structure):
+    """Mirror of pcg_diag (eight uint32 counters)."""
+    _fields_ = [(n, C.c_uint32) for n in
+                ("near_accept", "near_group", "near_token", "zero_draft_mass",
+                 "residual_fallback", "bad_proposal", "accepted_total", "sequences")]
+    NAMES = [n for n, _ in _fields_]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """The loaded library.  There is no fallback: a missing build is an error."""
+    global _lib
+    if _lib is None:
+        path = lib_path()
+        if not os.path.exists(path):
+            raise RuntimeError(
+                f"{path} is missing: build it first (python -m paper_2511_13732_amd.build, or "
+                "__graft_entry__.build()); this package has no CPU or PyTorch fallback")
+        L = C.CDLL(path)
+        L.pcg_group_probs_workspace_bytes.restype = C.c_size_t
+        L.pcg_group_probs_workspace_bytes.argtypes = [C.c_int32, C.c_int64]
+        L.pcg_verify_workspace_bytes.restype = C.c_size_t
+        L.pcg_verify_workspace_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32]
+        L.pcg_group_probs.restype = C.c_int
+        L.pcg_group_probs.argtypes = [C.POINTER(_GroupsStruct), C.c_void_p, C.c_int, C.c_int64,
+                                      C.c_int64, C.c_float, C.c_void_p, C.c_void_p, C.c_size_t,
+                                      C.c_void_p]
+        L.pcg_verify.restype = C.c_int
+        L.pcg_verify.argtypes = [C.POINTER(_GroupsStruct), C.c_void_p, C.c_void_p, C.c_int,
+                                 C.c_int32, C.c_int32, C.c_int64, C.c_int64, C.c_int64, C.c_int64,
+                                 C.c_float, C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint64,
+                                 C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                 C.c_size_t, C.c_void_p]
+        L.pcg_groups_validate_host.restype = C.c_int
+        L.pcg_groups_validate_host.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                               C.c_void_p]
+        L.pcg_groups_canonicalize_host.restype = C.c_int
+        L.pcg_groups_canonicalize_host.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                                   C.POINTER(C.c_int32), C.POINTER(C.c_int64),
+                                                   C.c_void_p, C.c_void_p, C.c_void_p]
+        L.pcg_profile_begin.restype = C.c_int
+        L.pcg_profile_begin.argtypes = [C.c_int32]
+        L.pcg_profile_end.restype = C.c_int
+        L.pcg_profile_end.argtypes = [C.POINTER(C.c_float), C.POINTER(C.c_int32)]
+        L.pcg_stage_name.restype = C.c_char_p
+        L.pcg_stage_name.argtypes = [C.c_int32]
+        L.pcg_strerror.restype = C.c_char_p
+        L.pcg_strerror.argtypes = [C.c_int]
+        L.pcg_last_hip_error.restype = C.c_int
+        L.pcg_version.restype = C.c_char_p
+        _lib = L
+    return _lib
+
+
+def strerror(status: int) -> str:
+    return lib().pcg_strerror(status).decode()
+
+
+def version() -> str:
+    return lib().pcg_version().decode()
+
+
+def _check(status: int, what: str):
+    if status != 0:
+        raise PcgError(status, what)
+
+
+# --------------------------------------------------------------------------- groups
+
+def _np_i32(a) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(a), dtype=np.int32)
+
+
+def groups_validate_host(V: int, row_ptr, members, mult) -> int:
+    rp, mem, mu = _np_i32(row_ptr), _np_i32(members), _np_i32(mult)
+    return lib().pcg_groups_validate_host(V, len(rp) - 1, rp.ctypes.data, mem.ctypes.data,
+                                          mu.ctypes.data)
+
+
+def groups_canonicalize_host(V: int, row_ptr, members):
+    """(row_ptr, members, mult) with a singleton group appended for every uncovered token."""
+    rp, mem = _np_i32(row_ptr), _np_i32(members)
+    G = len(rp) - 1
+    oG, onnz = C.c_int32(), C.c_int64()
+    _check(lib().pcg_groups_canonicalize_host(V, G, rp.ctypes.data, mem.ctypes.data, C.byref(oG),
+                                              C.byref(onnz), None, None, None), "canonicalize")
+    orp = np.empty(oG.value + 1, np.int32)
+    omem = np.empty(max(1, onnz.value), np.int32)
+    omult = np.empty(V, np.int32)
+    _check(lib().pcg_groups_canonicalize_host(V, G, rp.ctypes.data, mem.ctypes.data, C.byref(oG),
+                                              C.byref(onnz), orp.ctypes.data, omem.ctypes.data,
+                                              omult.ctypes.data), "canonicalize")
+    return orp, omem[:onnz.value], omult
+
+
+class Groups:
+    """Group membership resident on a device (CSR group -> tokens + multiplicity)."""
+
+    def __init__(self, V: int, row_ptr: torch.Tensor, members: torch.Tensor, mult: torch.Tensor,
+                 nnz: int):
+        for t in (row_ptr, members, mult):
+            assert t.dtype == torch.int32 and t.is_contiguous()
+        self.V, self.G, self.nnz = int(V), int(row_ptr.numel() - 1), int(nnz)
+        self.row_ptr, self.members, self.mult = row_ptr, members, mult
+        self.device = row_ptr.device
+
+    @classmethod
+    def from_csr(cls, V: int, row_ptr, members, device="cuda") -> "Groups":
+        """Canonicalise and validate a host CSR with the library, then upload it."""
+        rp, mem, mult = groups_canonicalize_host(V, row_ptr, members)
+        _check(groups_validate_host(V, rp, mem, mult), "validate")
+        dev = torch.device(device)
+        up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+        return cls(V, up(rp), up(mem if len(mem) else np.zeros(1, np.int32)), up(mult), len(mem))
+
+    def struct(self) -> _GroupsStruct:
+        return _GroupsStruct(self.V, self.G, self.nnz, self.row_ptr.data_ptr(),
+                             self.members.data_ptr(), self.mult.data_ptr())
+
+
+# --------------------------------------------------------------------------- calls
+
+_workspaces: dict = {}
+
+
+def _workspace(device: torch.device, nbytes: int) -> torch.Tensor:
+    ws = _workspaces.get(device)
+    if ws is None or ws.numel() < nbytes:
+        ws = torch.empty(max(nbytes, 1 << 20), dtype=torch.uint8, device=device)
+        _workspaces[device] = ws
+    return ws
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"logits must be float32 or bfloat16, got {t.dtype}")
+
+
+def _stream(device) -> int:
+    return torch.cuda.current_stream(device).cuda_stream
+
+
+def group_probs_workspace_bytes(V: int, rows: int) -> int:
+    return lib().pcg_group_probs_workspace_bytes(V, rows)
+
+
+def verify_workspace_bytes(V: int, G: int, B: int, K: int) -> int:
+    return lib().pcg_verify_workspace_bytes(V, G, B, K)
+
+
+def group_probs(groups: Groups, logits: torch.Tensor, temperature: float = 1.0,
+                out: Optional[torch.Tensor] = None,
+                workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """[rows, V] logits -> [rows, G] float32 group probabilities (Eq. 5)."""
+    assert logits.dim() == 2 and logits.shape[1] == groups.V and logits.stride(1) == 1
+    assert logits.device == groups.device
+    rows = logits.shape[0]
+    if out is None:
+        out = torch.empty((rows, groups.G), dtype=torch.float32, device=logits.device)
+    assert out.shape == (rows, groups.G) and out.is_contiguous() and out.dtype == torch.float32
+    need = group_probs_workspace_bytes(groups.V, rows)
+    ws = _workspace(logits.device, need) if workspace is None else workspace
+    gs = groups.struct()
+    with torch.cuda.device(logits.device):
+        _check(lib().pcg_group_probs(C.byref(gs), logits.data_ptr(), _dtype_code(logits), rows,
+                                     logits.stride(0) if rows > 1 else groups.V,
+                                     float(temperature), out.data_ptr(), ws.data_ptr(),
+                                     ws.numel(), _stream(logits.device)), "pcg_group_probs")
+    return out
+
+
+@dataclass
+class VerifyOutput:
+    accept_len: torch.Tensor   # int32 [B]
+    out_tokens: torch.Tensor   # int32 [B, K+1], unused tail -1
+    out_groups: torch.Tensor   # int32 [B, K+1]
+
+
+def verify(groups: Groups, target_logits: torch.Tensor, draft_logits: torch.Tensor,
+           prop_tokens: torch.Tensor, prop_groups: torch.Tensor, *, temperature: float = 1.0,
+           seed: int = 0, offset: int = 0, out: Optional[VerifyOutput] = None,
+           diag: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+           B: Optional[int] = None) -> VerifyOutput:
+    """One speculative step (Algorithm 1) for B sequences.
+
+    target_logits [B, K+1, V], draft_logits [B, >=K, V] (float32 or bfloat16, last axis
+    contiguous); prop_tokens / prop_groups int32 [B, K].  ``B`` larger than the tensors'
+    batch with batch dimension 1 makes all sequences share the same rows (batch stride 0).
+    ``diag`` is an optional zero-initialised int32[8] device tensor that receives pcg_diag.
+    """
+    assert target_logits.dim() == 3 and draft_logits.dim() == 3
+    K, V = target_logits.shape[1] - 1, target_logits.shape[2]
+    assert V == groups.V and draft_logits.shape[2] == V and draft_logits.shape[1] >= K
+    assert target_logits.stride(2) == 1 and draft_logits.stride(2) == 1
+    assert target_logits.dtype == draft_logits.dtype
+    dev = target_logits.device
+    assert dev == groups.device == draft_logits.device
+    if B is None:
+        B = target_logits.shape[0]
+    shared = B != target_logits.shape[0]
+    if shared:
+        assert target_logits.shape[0] == 1 and draft_logits.shape[0] == 1
+    tbs = 0 if shared else (target_logits.stride(0) if B > 1 else 0)
+    dbs = 0 if shared else (draft_logits.stride(0) if B > 1 else 0)
+    assert prop_tokens.dtype == torch.int32 and prop_groups.dtype == torch.int32
+    assert prop_tokens.is_contiguous() and prop_groups.is_contiguous()
+    assert prop_tokens.numel() == B * K and prop_groups.numel() == B * K
+    if out is None:
+        out = VerifyOutput(torch.empty(B, dtype=torch.int32, device=dev),
+                           torch.empty((B, K + 1), dtype=torch.int32, device=dev),
+                           torch.empty((B, K + 1), dtype=torch.int32, device=dev))
+    need = verify_workspace_bytes(V, groups.G, B, K)
+    ws = _workspace(dev, need) if workspace is None else workspace
+    gs = groups.struct()
+    with torch.cuda.device(dev):
+        _check(lib().pcg_verify(C.byref(gs), target_logits.data_ptr(), draft_logits.data_ptr(),
+                                _dtype_code(target_logits), B, K, tbs, target_logits.stride(1),
+                                dbs, draft_logits.stride(1) if K > 1 else V, float(temperature),
+                                prop_tokens.data_ptr(), prop_groups.data_ptr(), seed, offset,
+                                out.accept_len.data_ptr(), out.out_tokens.data_ptr(),
+                                out.out_groups.data_ptr(),
+                                None if diag is None else diag.data_ptr(), ws.data_ptr(),
+                                ws.numel(), _stream(dev)), "pcg_verify")
+    return out
+
+
+def profile_begin(max_calls: int):
+    _check(lib().pcg_profile_begin(max_calls), "pcg_profile_begin")
+
+
+def profile_end() -> tuple[dict, int]:
+    """({stage name: mean milliseconds}, number of recorded calls)."""
+    ms = (C.c_float * MAX_STAGES)()
+    calls = C.c_int32()
+    _check(lib().pcg_profile_end(ms, C.byref(calls)), "pcg_profile_end")
+    out = {}
+    for i in range(MAX_STAGES):
+        name = lib().pcg_stage_name(i).decode()
+        if name:
+            out[name] = float(ms[i])
+    return out, calls.value

@@ -1,0 +1,373 @@
+// C ABI of libpcg (see include/pcg.h): argument checks, workspace carving, kernel sequencing.
+// No device memory is allocated here and nothing synchronises except pcg_profile_end.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstring>
+#include <vector>
+
+#include "pcg_kernels.h"
+
+namespace {
+
+using namespace pcg;
+
+thread_local int g_last_hip_error = 0;
+
+int hip_fail(hipError_t e) {
+  g_last_hip_error = (int) e;
+  return PCG_ERR_HIP;
+}
+
+constexpr size_t kAlign = 256;
+size_t align_up(size_t n) { return (n + kAlign - 1) / kAlign * kAlign; }
+
+// ---- per-kernel timing -------------------------------------------------------------------
+
+enum Stage { kStageStats = 0, kStageAccept, kStageTable, kStageGather, kStageFinalize, kNumStages };
+const char *const kStageNames[kNumStages] = {"row_stats", "accept", "table", "gather", "finalize"};
+
+struct Profile {
+  bool active = false;
+  int32_t max_calls = 0, calls = 0;
+  // per recorded call: one event before each stage and one after the last
+  std::vector<hipEvent_t> ev;
+  std::vector<uint8_t> used;   // which stages the call ran
+} g_prof;
+
+struct StageTimer {
+  hipStream_t stream;
+  int slot;          // index of the recorded call, -1 if not recording
+  explicit StageTimer(hipStream_t s) : stream(s), slot(-1) {
+    if (g_prof.active && g_prof.calls < g_prof.max_calls) slot = g_prof.calls++;
+  }
+  void begin(Stage st) {
+    if (slot < 0) return;
+    (void) hipEventRecord(g_prof.ev[(size_t) slot * 2 * kNumStages + 2 * st], stream);
+    g_prof.used[(size_t) slot * kNumStages + st] = 1;
+  }
+  void end(Stage st) {
+    if (slot < 0) return;
+    (void) hipEventRecord(g_prof.ev[(size_t) slot * 2 * kNumStages + 2 * st + 1], stream);
+  }
+};
+
+bool good_temperature(float t) { return std::isfinite(t) && t > 0.0f; }
+
+int check_groups(const pcg_groups *g) {
+  if (!g) return PCG_ERR_NULL_ARG;
+  if (!g->row_ptr || !g->mult) return PCG_ERR_NULL_ARG;
+  if (g->V < 1 || g->G < 1 || g->nnz < 0 || g->nnz > INT32_MAX) return PCG_ERR_BAD_SHAPE;
+  if (g->nnz > 0 && !g->members) return PCG_ERR_NULL_ARG;
+  return PCG_OK;
+}
+
+bool stride_ok(int64_t s, int32_t V, bool zero_allowed) {
+  return s >= V || (zero_allowed && s == 0);
+}
+
+struct Factors {
+  double cd;          // log2(e) / temperature
+  float c, c_lo;      // c = fp32(cd) (also the high piece), c_lo = fp32(cd - c)
+};
+Factors factors(float temperature) {
+  Factors f;
+  f.cd = 1.4426950408889634074 / (double) temperature;
+  f.c = (float) f.cd;
+  f.c_lo = (float) (f.cd - (double) f.c);
+  return f;
+}
+
+// rows of table staged per gather launch in pcg_group_probs
+int64_t group_probs_batch(int32_t V, int64_t rows) {
+  int64_t batch = ((int64_t) 64 << 20) / ((int64_t) V * 4);
+  if (batch < 8) batch = 8;
+  if (batch > 4096) batch = 4096;
+  if (batch > rows) batch = rows;
+  return batch;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t pcg_group_probs_workspace_bytes(int32_t V, int64_t rows) {
+  if (V < 1 || rows < 0) return 0;
+  const size_t parts = align_up((size_t) rows * stats_nparts(V) * sizeof(StatPart));
+  const size_t table = align_up((size_t) group_probs_batch(V, rows) * V * sizeof(float));
+  return parts + table + kAlign;
+}
+
+size_t pcg_verify_workspace_bytes(int32_t V, int32_t G, int32_t B, int32_t K) {
+  if (V < 1 || G < 1 || B < 0 || K < 1) return 0;
+  const size_t rows = (size_t) B * (2 * (size_t) K + 1);
+  return align_up(rows * stats_nparts(V) * sizeof(StatPart)) + align_up(rows * sizeof(RowStat)) +
+         align_up((size_t) B * V * sizeof(float)) + align_up((size_t) B * G * sizeof(float)) + kAlign;
+}
+
+int pcg_group_probs(const pcg_groups *groups, const void *logits, pcg_dtype dt, int64_t rows,
+                    int64_t row_stride, float temperature, float *out, void *workspace,
+                    size_t workspace_bytes, void *hip_stream) {
+  int rc = check_groups(groups);
+  if (rc) return rc;
+  if (dt != PCG_F32 && dt != PCG_BF16) return PCG_ERR_BAD_DTYPE;
+  if (rows < 0 || rows > ((int64_t) 1 << 40)) return PCG_ERR_BAD_SHAPE;
+  if (rows == 0) return PCG_OK;
+  if (!logits || !out || !workspace) return PCG_ERR_NULL_ARG;
+  if (!stride_ok(row_stride, groups->V, rows == 1)) return PCG_ERR_BAD_STRIDE;
+  if (!good_temperature(temperature)) return PCG_ERR_BAD_TEMPERATURE;
+  const bool bf16 = dt == PCG_BF16;
+  if (((uintptr_t) logits % (bf16 ? 2 : 4)) || ((uintptr_t) workspace % kAlign) ||
+      ((uintptr_t) out % 4))
+    return PCG_ERR_MISALIGNED;
+  if (workspace_bytes < pcg_group_probs_workspace_bytes(groups->V, rows))
+    return PCG_ERR_WORKSPACE_TOO_SMALL;
+  const int32_t nparts = stats_nparts(groups->V);
+  if (rows * nparts / 4 >= INT32_MAX) return PCG_ERR_BAD_SHAPE;
+
+  hipStream_t stream = (hipStream_t) hip_stream;
+  char *ws = (char *) workspace;
+  StatPart *parts = (StatPart *) ws;
+  ws += align_up((size_t) rows * nparts * sizeof(StatPart));
+  float *table = (float *) ws;
+
+  RowSet rs;
+  std::memset(&rs, 0, sizeof rs);
+  rs.base0 = logits;
+  rs.bs0 = row_stride;
+  rs.npos0 = 1;
+  rs.npos1 = 1;
+  rs.nrows0 = rows;
+  const Factors f = factors(temperature);
+
+  StageTimer tm(stream);
+  hipError_t e;
+  tm.begin(kStageStats);
+  if ((e = launch_row_stats(rs, bf16, groups->V, rows, f.c, parts, stream)) != hipSuccess)
+    return hip_fail(e);
+  tm.end(kStageStats);
+  const int64_t batch = group_probs_batch(groups->V, rows);
+  for (int64_t r0 = 0; r0 < rows; r0 += batch) {
+    const int32_t n = (int32_t) std::min(batch, rows - r0);
+    if (r0 == 0) tm.begin(kStageTable);
+    if ((e = launch_weights(rs, bf16, *groups, r0, n, f.c, f.c, f.c_lo, parts, table, stream)) !=
+        hipSuccess)
+      return hip_fail(e);
+    if (r0 == 0) { tm.end(kStageTable); tm.begin(kStageGather); }
+    if ((e = launch_gather(*groups, n, false, table, out + r0 * groups->G, stream)) != hipSuccess)
+      return hip_fail(e);
+    if (r0 == 0) tm.end(kStageGather);
+  }
+  return PCG_OK;
+}
+
+int pcg_verify(const pcg_groups *groups, const void *target_logits, const void *draft_logits,
+               pcg_dtype dt, int32_t B, int32_t K, int64_t tgt_batch_stride,
+               int64_t tgt_pos_stride, int64_t dft_batch_stride, int64_t dft_pos_stride,
+               float temperature, const int32_t *prop_tokens, const int32_t *prop_groups,
+               uint64_t seed, uint64_t offset, int32_t *accept_len, int32_t *out_tokens,
+               int32_t *out_groups, pcg_diag *diag, void *workspace, size_t workspace_bytes,
+               void *hip_stream) {
+  int rc = check_groups(groups);
+  if (rc) return rc;
+  if (dt != PCG_F32 && dt != PCG_BF16) return PCG_ERR_BAD_DTYPE;
+  if (B < 0 || B > (1 << 24) || K < 1 || K > PCG_MAX_K) return PCG_ERR_BAD_SHAPE;
+  if (B == 0) return PCG_OK;
+  if (!target_logits || !draft_logits || !prop_tokens || !prop_groups || !accept_len ||
+      !out_tokens || !out_groups || !workspace)
+    return PCG_ERR_NULL_ARG;
+  const int32_t V = groups->V;
+  if (!stride_ok(tgt_pos_stride, V, false) || !stride_ok(dft_pos_stride, V, K == 1) ||
+      !stride_ok(tgt_batch_stride, V, true) || !stride_ok(dft_batch_stride, V, true))
+    return PCG_ERR_BAD_STRIDE;
+  if (!good_temperature(temperature)) return PCG_ERR_BAD_TEMPERATURE;
+  const bool bf16 = dt == PCG_BF16;
+  const uintptr_t esz = bf16 ? 2 : 4;
+  if (((uintptr_t) target_logits % esz) || ((uintptr_t) draft_logits % esz) ||
+      ((uintptr_t) workspace % kAlign))
+    return PCG_ERR_MISALIGNED;
+  if (workspace_bytes < pcg_verify_workspace_bytes(V, groups->G, B, K))
+    return PCG_ERR_WORKSPACE_TOO_SMALL;
+  const int64_t rows = (int64_t) B * (2 * K + 1);
+  const int32_t nparts = stats_nparts(V);
+  if (rows * nparts / 4 >= INT32_MAX) return PCG_ERR_BAD_SHAPE;
+  if ((int64_t) B * ((V + 2047) / 2048) >= INT32_MAX) return PCG_ERR_BAD_SHAPE;
+
+  hipStream_t stream = (hipStream_t) hip_stream;
+  char *ws = (char *) workspace;
+  StatPart *parts = (StatPart *) ws;
+  ws += align_up((size_t) rows * nparts * sizeof(StatPart));
+  RowStat *rowstat = (RowStat *) ws;
+  ws += align_up((size_t) rows * sizeof(RowStat));
+  float *table = (float *) ws;
+  ws += align_up((size_t) B * V * sizeof(float));
+  float *R = (float *) ws;
+
+  RowSet rs;
+  rs.base0 = target_logits;
+  rs.base1 = draft_logits;
+  rs.bs0 = tgt_batch_stride;
+  rs.ps0 = tgt_pos_stride;
+  rs.bs1 = dft_batch_stride;
+  rs.ps1 = dft_pos_stride;
+  rs.npos0 = K + 1;
+  rs.npos1 = K;
+  rs.nrows0 = (int64_t) B * (K + 1);
+  const Factors f = factors(temperature);
+
+  StageTimer tm(stream);
+  hipError_t e;
+  tm.begin(kStageStats);
+  if ((e = launch_row_stats(rs, bf16, V, rows, f.c, parts, stream)) != hipSuccess) return hip_fail(e);
+  tm.end(kStageStats);
+  tm.begin(kStageAccept);
+  if ((e = launch_accept(rs, bf16, *groups, B, K, f.c, f.cd, parts, rowstat, prop_tokens,
+                         prop_groups, seed, offset, accept_len, out_tokens, out_groups, diag,
+                         stream)) != hipSuccess)
+    return hip_fail(e);
+  tm.end(kStageAccept);
+  tm.begin(kStageTable);
+  if ((e = launch_delta(rs, bf16, *groups, B, K, f.c, f.c_lo, rowstat, accept_len, table, stream)) !=
+      hipSuccess)
+    return hip_fail(e);
+  tm.end(kStageTable);
+  tm.begin(kStageGather);
+  if ((e = launch_gather(*groups, B, true, table, R, stream)) != hipSuccess) return hip_fail(e);
+  tm.end(kStageGather);
+  tm.begin(kStageFinalize);
+  if ((e = launch_finalize(rs, bf16, *groups, B, K, f.cd, rowstat, seed, offset, accept_len, R,
+                           out_tokens, out_groups, diag, stream)) != hipSuccess)
+    return hip_fail(e);
+  tm.end(kStageFinalize);
+  return PCG_OK;
+}
+
+// ---- per-kernel timing ---------------------------------------------------------------------
+
+int pcg_profile_begin(int32_t max_calls) {
+  if (g_prof.active || max_calls < 1 || max_calls > 100000) return PCG_ERR_BAD_SHAPE;
+  g_prof.ev.assign((size_t) max_calls * 2 * kNumStages, nullptr);
+  g_prof.used.assign((size_t) max_calls * kNumStages, 0);
+  for (auto &ev : g_prof.ev) {
+    hipError_t e = hipEventCreate(&ev);
+    if (e != hipSuccess) {
+      for (auto &x : g_prof.ev) if (x) (void) hipEventDestroy(x);
+      g_prof.ev.clear();
+      return hip_fail(e);
+    }
+  }
+  g_prof.max_calls = max_calls;
+  g_prof.calls = 0;
+  g_prof.active = true;
+  return PCG_OK;
+}
+
+int pcg_profile_end(float *stage_ms, int32_t *calls) {
+  if (!g_prof.active) return PCG_ERR_BAD_SHAPE;
+  if (!stage_ms || !calls) return PCG_ERR_NULL_ARG;
+  g_prof.active = false;
+  int rc = PCG_OK;
+  double sum[kNumStages] = {0};
+  int32_t cnt[kNumStages] = {0};
+  for (int32_t c = 0; c < g_prof.calls && rc == PCG_OK; ++c) {
+    for (int st = 0; st < kNumStages; ++st) {
+      if (!g_prof.used[(size_t) c * kNumStages + st]) continue;
+      hipEvent_t a = g_prof.ev[(size_t) c * 2 * kNumStages + 2 * st];
+      hipEvent_t b = g_prof.ev[(size_t) c * 2 * kNumStages + 2 * st + 1];
+      hipError_t e = hipEventSynchronize(b);
+      float ms = 0.f;
+      if (e == hipSuccess) e = hipEventElapsedTime(&ms, a, b);
+      if (e != hipSuccess) { rc = hip_fail(e); break; }
+      sum[st] += ms;
+      cnt[st] += 1;
+    }
+  }
+  for (int st = 0; st < PCG_MAX_STAGES; ++st)
+    stage_ms[st] = (st < kNumStages && cnt[st]) ? (float) (sum[st] / cnt[st]) : 0.f;
+  *calls = g_prof.calls;
+  for (auto &x : g_prof.ev) if (x) (void) hipEventDestroy(x);
+  g_prof.ev.clear();
+  g_prof.used.clear();
+  return rc;
+}
+
+const char *pcg_stage_name(int32_t stage) {
+  return (stage >= 0 && stage < kNumStages) ? kStageNames[stage] : "";
+}
+
+// ---- group membership on the host ----------------------------------------------------------
+
+static bool csr_well_formed(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members) {
+  if (row_ptr[0] != 0) return false;
+  for (int32_t g = 0; g < G; ++g)
+    if (row_ptr[g + 1] < row_ptr[g]) return false;
+  const int32_t nnz = row_ptr[G];
+  for (int32_t j = 0; j < nnz; ++j)
+    if ((uint32_t) members[j] >= (uint32_t) V) return false;
+  return true;
+}
+
+int pcg_groups_validate_host(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members,
+                             const int32_t *mult) {
+  if (!row_ptr || !members || !mult) return PCG_ERR_NULL_ARG;
+  if (V < 1 || G < 1) return PCG_ERR_BAD_SHAPE;
+  if (!csr_well_formed(V, G, row_ptr, members)) return PCG_ERR_BAD_CSR;
+  std::vector<int32_t> seen((size_t) V, 0);
+  for (int32_t j = 0, n = row_ptr[G]; j < n; ++j) ++seen[members[j]];
+  for (int32_t v = 0; v < V; ++v)
+    if (seen[v] == 0 || seen[v] != mult[v]) return PCG_ERR_BAD_CSR;
+  return PCG_OK;
+}
+
+int pcg_groups_canonicalize_host(int32_t V, int32_t G, const int32_t *row_ptr,
+                                 const int32_t *members, int32_t *out_G, int64_t *out_nnz,
+                                 int32_t *out_row_ptr, int32_t *out_members, int32_t *out_mult) {
+  if (!row_ptr || !out_G || !out_nnz) return PCG_ERR_NULL_ARG;
+  if (V < 1 || G < 0) return PCG_ERR_BAD_SHAPE;
+  if (G > 0 && row_ptr[G] > 0 && !members) return PCG_ERR_NULL_ARG;
+  if (!csr_well_formed(V, G, row_ptr, members)) return PCG_ERR_BAD_CSR;
+  const int32_t nnz = row_ptr[G];
+  std::vector<int32_t> seen((size_t) V, 0);
+  for (int32_t j = 0; j < nnz; ++j) ++seen[members[j]];
+  int32_t lonely = 0;
+  for (int32_t v = 0; v < V; ++v) lonely += seen[v] == 0;
+  *out_G = G + lonely;
+  *out_nnz = (int64_t) nnz + lonely;
+  if (!out_row_ptr) return PCG_OK;
+  if (!out_members || !out_mult) return PCG_ERR_NULL_ARG;
+  std::memcpy(out_row_ptr, row_ptr, sizeof(int32_t) * ((size_t) G + 1));
+  if (nnz) std::memcpy(out_members, members, sizeof(int32_t) * (size_t) nnz);
+  int32_t next_group = G, next_entry = nnz;
+  for (int32_t v = 0; v < V; ++v) {
+    out_mult[v] = seen[v] ? seen[v] : 1;
+    if (!seen[v]) {
+      out_members[next_entry++] = v;
+      out_row_ptr[++next_group] = next_entry;
+    }
+  }
+  return PCG_OK;
+}
+
+// ---- errors ----------------------------------------------------------------------------------
+
+const char *pcg_strerror(int status) {
+  switch (status) {
+    case PCG_OK: return "ok";
+    case PCG_ERR_NULL_ARG: return "a required pointer is NULL";
+    case PCG_ERR_BAD_SHAPE: return "a size argument is out of range";
+    case PCG_ERR_BAD_DTYPE: return "unknown logits dtype";
+    case PCG_ERR_BAD_STRIDE: return "a stride is smaller than V (and not an allowed 0)";
+    case PCG_ERR_BAD_TEMPERATURE: return "temperature must be finite and > 0";
+    case PCG_ERR_WORKSPACE_TOO_SMALL: return "workspace is smaller than *_workspace_bytes";
+    case PCG_ERR_BAD_CSR: return "group membership is not a valid CSR with matching multiplicities";
+    case PCG_ERR_HIP: return "a HIP runtime call failed (see pcg_last_hip_error)";
+    case PCG_ERR_MISALIGNED: return "a pointer is not aligned as required";
+    default: return "unknown status";
+  }
+}
+
+int pcg_last_hip_error(void) { return g_last_hip_error; }
+
+const char *pcg_version(void) { return "libpcg 0.1 (gfx950)"; }
+
+}  // extern "C"

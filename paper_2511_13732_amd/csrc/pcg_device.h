@@ -1,0 +1,162 @@
+// Device-side helpers shared by the libpcg kernels (gfx950, wave64).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace pcg {
+
+constexpr int kWave = 64;
+
+// ---------------------------------------------------------------------------------------------
+// Logit element access.  bfloat16 is the upper half of an IEEE binary32.
+// ---------------------------------------------------------------------------------------------
+
+template <bool BF16>
+__device__ __forceinline__ float logit_at(const void *row, int64_t t) {
+  if constexpr (BF16) {
+    return __uint_as_float((uint32_t) reinterpret_cast<const uint16_t *>(row)[t] << 16);
+  } else {
+    return reinterpret_cast<const float *>(row)[t];
+  }
+}
+
+__device__ __forceinline__ const void *elem_ptr(const void *base, int64_t elems, bool bf16) {
+  return reinterpret_cast<const char *>(base) + elems * (bf16 ? 2 : 4);
+}
+
+// Where the rows of a call live: set 0 = target rows (b, i), i < npos0; set 1 = draft rows
+// (b, i), i < npos1.  Row ids are [0, B*npos0) for set 0 followed by [B*npos0, ...) for set 1.
+// pcg_group_probs uses set 0 alone with npos0 = 1 and bs0 = row stride.
+struct RowSet {
+  const void *base0;
+  const void *base1;
+  int64_t bs0, ps0, bs1, ps1;   // strides in elements
+  int32_t npos0, npos1;
+  int64_t nrows0;               // B * npos0
+};
+
+__device__ __forceinline__ const void *row_base(const RowSet &rs, int64_t row, bool bf16) {
+  if (row < rs.nrows0) {
+    int64_t b = row / rs.npos0, i = row - b * rs.npos0;
+    return elem_ptr(rs.base0, b * rs.bs0 + i * rs.ps0, bf16);
+  }
+  row -= rs.nrows0;
+  int64_t b = row / rs.npos1, i = row - b * rs.npos1;
+  return elem_ptr(rs.base1, b * rs.bs1 + i * rs.ps1, bf16);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Cross-lane reductions through DPP (no LDS traffic).
+// ---------------------------------------------------------------------------------------------
+
+constexpr int kDppXor1 = 0xB1;         // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;         // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141;  // lane i <-> 7-i inside each 8
+constexpr int kDppMirror = 0x140;      // lane i <-> 15-i inside each row of 16
+constexpr int kDppBcast15 = 0x142;     // lane 15 of a row -> every lane of the next row
+constexpr int kDppBcast31 = 0x143;     // lane 31 -> rows 2 and 3
+
+// Value of the DPP source lane; lanes the row mask excludes receive `fallback`.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_get(float v, float fallback) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(fallback), __float_as_int(v),
+                                                    CTRL, ROW_MASK, 0xf, false));
+}
+
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_get(double v, double fallback) {
+  int2 s = *reinterpret_cast<int2 *>(&v), f = *reinterpret_cast<int2 *>(&fallback), r;
+  r.x = __builtin_amdgcn_update_dpp(f.x, s.x, CTRL, ROW_MASK, 0xf, false);
+  r.y = __builtin_amdgcn_update_dpp(f.y, s.y, CTRL, ROW_MASK, 0xf, false);
+  return *reinterpret_cast<double *>(&r);
+}
+
+// Sum over aligned sub-waves of W lanes (W a power of two, 1..64).  The total is valid in the
+// LAST lane of each sub-wave (for W <= 16 in all of its lanes).  Fixed tree, so the result does
+// not depend on scheduling.
+template <int W, typename T>
+__device__ __forceinline__ T subwave_sum(T v) {
+  if constexpr (W >= 2) v += dpp_get<kDppXor1, 0xf>(v, T(0));
+  if constexpr (W >= 4) v += dpp_get<kDppXor2, 0xf>(v, T(0));
+  if constexpr (W >= 8) v += dpp_get<kDppHalfMirror, 0xf>(v, T(0));
+  if constexpr (W >= 16) v += dpp_get<kDppMirror, 0xf>(v, T(0));
+  if constexpr (W >= 32) v += dpp_get<kDppBcast15, 0xa>(v, T(0));
+  if constexpr (W >= 64) v += dpp_get<kDppBcast31, 0xc>(v, T(0));
+  return v;
+}
+
+// Max over the whole wave, returned in every lane.
+__device__ __forceinline__ float wave_max(float v) {
+  v = fmaxf(v, dpp_get<kDppXor1, 0xf>(v, v));
+  v = fmaxf(v, dpp_get<kDppXor2, 0xf>(v, v));
+  v = fmaxf(v, dpp_get<kDppHalfMirror, 0xf>(v, v));
+  v = fmaxf(v, dpp_get<kDppMirror, 0xf>(v, v));
+  v = fmaxf(v, dpp_get<kDppBcast15, 0xa>(v, v));
+  v = fmaxf(v, dpp_get<kDppBcast31, 0xc>(v, v));
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+
+// Wave-wide sum / max through shuffles, result in every lane (for the small kernels).
+__device__ __forceinline__ double wave_sum_all(double v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+  return v;
+}
+__device__ __forceinline__ float wave_max_all(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
+  return v;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Philox4x32-10 (Salmon et al., SC'11), one block per (sequence, position).
+// ---------------------------------------------------------------------------------------------
+
+struct Uniforms {
+  float acc, grp, tok;   // 24-bit draws in [0, 1): exact in fp32 and fp64
+};
+
+__device__ __forceinline__ Uniforms philox_uniforms(uint64_t seed, uint64_t offset, uint32_t b,
+                                                    uint32_t i) {
+  uint32_t c0 = (uint32_t) offset, c1 = (uint32_t)(offset >> 32), c2 = b, c3 = i;
+  uint32_t k0 = (uint32_t) seed, k1 = (uint32_t)(seed >> 32);
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint32_t m0 = 0xD2511F53u, m1 = 0xCD9E8D57u;
+    uint32_t h0 = __umulhi(m0, c0), l0 = m0 * c0;
+    uint32_t h1 = __umulhi(m1, c2), l1 = m1 * c2;
+    c0 = h1 ^ c1 ^ k0;
+    c1 = l1;
+    c2 = h0 ^ c3 ^ k1;
+    c3 = l0;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  const float s = 1.0f / 16777216.0f;
+  Uniforms u;
+  u.acc = (float)(c0 >> 8) * s;
+  u.grp = (float)(c1 >> 8) * s;
+  u.tok = (float)(c2 >> 8) * s;
+  return u;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Per-row softmax statistics.
+// ---------------------------------------------------------------------------------------------
+
+// One wave's share of a row: the exact maximum m of its logits and z = sum 2^((x - m) * c).
+struct StatPart {
+  double z;
+  float m;
+  float pad;
+};
+
+// A whole row: M = max logit, Z = sum over the row of exp((x - M) / temperature).
+struct RowStat {
+  double Z;
+  float M;
+  float pad;
+};
+
+}  // namespace pcg

@@ -1,0 +1,40 @@
+// Launchers of the libpcg kernels (defined in pcg_kernels.hip).  Every launcher only enqueues
+// on `stream`; shapes have been checked by the C ABI layer before it is called.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/pcg.h"
+#include "pcg_device.h"
+
+namespace pcg {
+
+int32_t stats_nparts(int32_t V);
+
+hipError_t launch_row_stats(const RowSet &rs, bool bf16, int32_t V, int64_t nrows, float c,
+                            StatPart *parts, hipStream_t stream);
+
+hipError_t launch_accept(const RowSet &rs, bool bf16, const pcg_groups &g, int32_t B, int32_t K,
+                         float c, double cd, const StatPart *parts, RowStat *rowstat,
+                         const int32_t *prop_tokens, const int32_t *prop_groups, uint64_t seed,
+                         uint64_t offset, int32_t *accept_len, int32_t *out_tokens,
+                         int32_t *out_groups, pcg_diag *diag, hipStream_t stream);
+
+hipError_t launch_delta(const RowSet &rs, bool bf16, const pcg_groups &g, int32_t B, int32_t K,
+                        float c_hi, float c_lo, const RowStat *rowstat, const int32_t *accept_len,
+                        float *table, hipStream_t stream);
+
+hipError_t launch_weights(const RowSet &rs, bool bf16, const pcg_groups &g, int64_t row0,
+                          int32_t nrows, float c, float c_hi, float c_lo, const StatPart *parts,
+                          float *table, hipStream_t stream);
+
+hipError_t launch_gather(const pcg_groups &g, int32_t nrows, bool clamp, const float *table,
+                         float *out, hipStream_t stream);
+
+hipError_t launch_finalize(const RowSet &rs, bool bf16, const pcg_groups &g, int32_t B, int32_t K,
+                           double cd, const RowStat *rowstat, uint64_t seed, uint64_t offset,
+                           const int32_t *accept_len, float *R, int32_t *out_tokens,
+                           int32_t *out_groups, pcg_diag *diag, hipStream_t stream);
+
+}  // namespace pcg

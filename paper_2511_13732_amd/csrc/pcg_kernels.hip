@@ -1,0 +1,615 @@
+// HIP kernels of libpcg for gfx950 (MI355X) and their launchers.
+//
+// One speculative step (Algorithm 1) runs as five kernels on the caller's stream:
+//   row_stats  streams every logits row once: per-wave (max, sum of exponentials)   [HBM-bound]
+//   accept     per sequence: merges the row statistics, evaluates Eq. (5) on each proposed
+//              group, runs the accept test of Eq. (7) until the first rejection
+//   delta      per sequence, on its decision row: delta[t] = (q(t) - p(t)) / N(t)
+//              (q(t) / N(t) on the bonus row), so that T[g] - D[g] = sum of delta over G_g
+//   gather     the overlap-aware segmented gather-sum over the CSR membership with the
+//              delta row staged in LDS; writes R[g] = max(0, T[g] - D[g])            (Eq. 8)
+//   finalize   per sequence: inverse CDF over R for the group, then Eq. (10) for the token
+// pcg_group_probs runs row_stats, a weights kernel (q(t) / N(t)) and the same gather.
+#include "pcg_kernels.h"
+
+#include <math.h>
+
+namespace pcg {
+
+// =============================================================================================
+// row_stats: one wave per 2048-element part of a row.
+// =============================================================================================
+
+constexpr int kPartElems = 2048;      // elements per wave: 32 per lane
+constexpr int kStatsWaves = 4;        // waves per workgroup
+
+template <bool BF16, bool VEC>
+__global__ __launch_bounds__(kStatsWaves *kWave) void row_stats_kernel(RowSet rs, int32_t V,
+                                                                       int32_t nparts,
+                                                                       int64_t total_parts,
+                                                                       float c, StatPart *parts) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int64_t p = (int64_t) blockIdx.x * kStatsWaves + (threadIdx.x >> 6);
+  if (p >= total_parts) return;   // whole wave leaves together
+  const int64_t row = p / nparts;
+  const int32_t part = (int32_t)(p - row * nparts);
+  const void *rowp = row_base(rs, row, BF16);
+  const int32_t e0 = part * kPartElems;
+
+  float x[32];
+  if constexpr (VEC) {
+    if constexpr (BF16) {
+      // 4 loads of 16 bytes per lane; each load instruction covers 1 KiB of the row
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int32_t e = e0 + (j * kWave + lane) * 8;
+        if (e + 8 <= V) {
+          uint4 w = *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(rowp) + e);
+          const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            x[j * 8 + 2 * k] = __uint_as_float(ww[k] << 16);
+            x[j * 8 + 2 * k + 1] = __uint_as_float(ww[k] & 0xffff0000u);
+          }
+        } else {
+#pragma unroll
+          for (int k = 0; k < 8; ++k)
+            x[j * 8 + k] = (e + k < V) ? logit_at<true>(rowp, e + k) : -INFINITY;
+        }
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int32_t e = e0 + (j * kWave + lane) * 4;
+        if (e + 4 <= V) {
+          float4 w = *reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(rowp) + e);
+          x[j * 4] = w.x; x[j * 4 + 1] = w.y; x[j * 4 + 2] = w.z; x[j * 4 + 3] = w.w;
+        } else {
+#pragma unroll
+          for (int k = 0; k < 4; ++k)
+            x[j * 4 + k] = (e + k < V) ? logit_at<false>(rowp, e + k) : -INFINITY;
+        }
+      }
+    }
+  } else {
+#pragma unroll
+    for (int j = 0; j < 32; ++j) {
+      const int32_t e = e0 + j * kWave + lane;
+      x[j] = (e < V) ? logit_at<BF16>(rowp, e) : -INFINITY;
+    }
+  }
+
+  float m = x[0];
+#pragma unroll
+  for (int j = 1; j < 32; ++j) m = fmaxf(m, x[j]);
+  m = wave_max(m);
+
+  // exponentials relative to the wave's own maximum: (x - m) is exact for bf16 inputs, so
+  // the dominant terms carry no argument error
+  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+#pragma unroll
+  for (int j = 0; j < 32; j += 4) {
+    s0 += __builtin_amdgcn_exp2f((x[j] - m) * c);
+    s1 += __builtin_amdgcn_exp2f((x[j + 1] - m) * c);
+    s2 += __builtin_amdgcn_exp2f((x[j + 2] - m) * c);
+    s3 += __builtin_amdgcn_exp2f((x[j + 3] - m) * c);
+  }
+  double z = (double) ((s0 + s1) + (s2 + s3));
+  if (m == -INFINITY) z = 0.0;   // (-inf) - (-inf) is NaN: an all -inf part holds no mass
+  z = subwave_sum<64>(z);
+  if (lane == kWave - 1) {
+    StatPart sp;
+    sp.z = z;
+    sp.m = m;
+    sp.pad = 0.f;
+    parts[p] = sp;
+  }
+}
+
+// Merge the parts of one row inside a wave: every lane returns the row's (M, Z).
+// c must be the same fp32 factor row_stats used, so that 2^((x-m)c) * 2^((m-M)c) = 2^((x-M)c).
+__device__ __forceinline__ RowStat merge_row(const StatPart *parts, int64_t row, int32_t nparts,
+                                             float c, int lane) {
+  const StatPart *rp = parts + row * nparts;
+  float M = -INFINITY;
+  for (int32_t k = lane; k < nparts; k += kWave) M = fmaxf(M, rp[k].m);
+  M = wave_max_all(M);
+  double Z = 0.0;
+  for (int32_t k = lane; k < nparts; k += kWave) {
+    StatPart sp = rp[k];
+    if (sp.z > 0.0) Z += sp.z * exp2((double) (sp.m - M) * (double) c);
+  }
+  Z = wave_sum_all(Z);
+  RowStat r;
+  r.Z = Z;
+  r.M = M;
+  r.pad = 0.f;
+  return r;
+}
+
+// exp((x - M) / temperature) for one element, argument in two pieces so that its error stays
+// relative to the result: (x - M) * (c_hi + c_lo) with c_hi + c_lo = log2(e) / temperature.
+__device__ __forceinline__ float exp_rel(float x, float M, float c_hi, float c_lo) {
+  const float d = x - M;
+  return __builtin_amdgcn_exp2f(fmaf(d, c_hi, d * c_lo));
+}
+
+// =============================================================================================
+// accept: one workgroup per sequence.
+// =============================================================================================
+
+constexpr int kAcceptThreads = 256;
+
+template <bool BF16>
+__global__ __launch_bounds__(kAcceptThreads) void accept_kernel(
+    RowSet rs, int32_t V, int32_t G, int32_t K, int32_t nparts, float c, double cd,
+    const StatPart *parts, RowStat *rowstat, const int32_t *row_ptr, const int32_t *members,
+    const int32_t *mult, const int32_t *prop_tokens, const int32_t *prop_groups, uint64_t seed,
+    uint64_t offset, int32_t *accept_len, int32_t *out_tokens, int32_t *out_groups,
+    pcg_diag *diag) {
+  __shared__ RowStat st_t[PCG_MAX_K + 1];
+  __shared__ RowStat st_d[PCG_MAX_K];
+  __shared__ double Tp[PCG_MAX_K], Dp[PCG_MAX_K];
+  __shared__ int bad[PCG_MAX_K];
+
+  const int b = blockIdx.x;
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+  constexpr int nw = kAcceptThreads / kWave;
+  const int64_t B = rs.nrows0 / (K + 1);
+
+  // 1. row statistics of this sequence's 2K+1 rows
+  for (int r = wave; r < 2 * K + 1; r += nw) {
+    const bool is_t = r <= K;
+    const int64_t row = is_t ? (int64_t) b * (K + 1) + r : B * (K + 1) + (int64_t) b * K + (r - K - 1);
+    RowStat s = merge_row(parts, row, nparts, c, lane);
+    if (lane == 0) {
+      rowstat[row] = s;
+      if (is_t) st_t[r] = s; else st_d[r - K - 1] = s;
+    }
+  }
+  __syncthreads();
+
+  // 2. T_i[g], D_i[g] of the proposed group at every position (Eq. 5), one wave per position
+  for (int i = wave; i < K; i += nw) {
+    const int32_t g = prop_groups[(int64_t) b * K + i];
+    double at = 0.0, ad = 0.0;
+    const bool ok = g >= 0 && g < G;
+    if (ok) {
+      const void *trow = row_base(rs, (int64_t) b * (K + 1) + i, BF16);
+      const void *drow = row_base(rs, rs.nrows0 + (int64_t) b * K + i, BF16);
+      const float Mt = st_t[i].M, Md = st_d[i].M;
+      const int32_t beg = row_ptr[g], end = row_ptr[g + 1];
+      for (int32_t j = beg + lane; j < end; j += kWave) {
+        const int32_t t = members[j];
+        const double inv_m = 1.0 / (double) mult[t];
+        at += exp2((double) (logit_at<BF16>(trow, t) - Mt) * cd) * inv_m;
+        ad += exp2((double) (logit_at<BF16>(drow, t) - Md) * cd) * inv_m;
+      }
+    }
+    at = wave_sum_all(at);
+    ad = wave_sum_all(ad);
+    if (lane == 0) {
+      Tp[i] = ok ? at / st_t[i].Z : 0.0;
+      Dp[i] = ok ? ad / st_d[i].Z : 0.0;
+      bad[i] = !ok;
+    }
+  }
+  __syncthreads();
+
+  // 3. sequential accept scan with early exit (Algorithm 1); the draft token stands for its
+  //    group on accept
+  if (threadIdx.x == 0) {
+    int32_t *otok = out_tokens + (int64_t) b * (K + 1);
+    int32_t *ogrp = out_groups + (int64_t) b * (K + 1);
+    uint32_t near = 0, zero_d = 0, nbad = 0;
+    int i = 0;
+    for (; i < K; ++i) {
+      const double u = (double) philox_uniforms(seed, offset, (uint32_t) b, (uint32_t) i).acc;
+      const double T = Tp[i], D = Dp[i];
+      if (bad[i]) ++nbad;
+      else if (D == 0.0) ++zero_d;
+      if (fabs(u * D - T) < 1e-6 * D) ++near;
+      if (!(u * D < T)) break;
+      otok[i] = prop_tokens[(int64_t) b * K + i];
+      ogrp[i] = prop_groups[(int64_t) b * K + i];
+    }
+    accept_len[b] = i;
+    for (int k = i; k <= K; ++k) otok[k] = ogrp[k] = -1;
+    if (diag) {
+      if (near) atomicAdd(&diag->near_accept, near);
+      if (zero_d) atomicAdd(&diag->zero_draft_mass, zero_d);
+      if (nbad) atomicAdd(&diag->bad_proposal, nbad);
+      atomicAdd(&diag->accepted_total, (uint32_t) i);
+      atomicAdd(&diag->sequences, 1u);
+    }
+  }
+}
+
+// =============================================================================================
+// delta / weights: the per-token table the gather sums over.
+// =============================================================================================
+
+constexpr int kTableThreads = 256;
+constexpr int kTableTokens = 2048;    // tokens per workgroup
+
+// verify: on the decision row i* = accept_len[b] of sequence b,
+//   rejected (i* < K):  delta[t] = (q_{i*}(t) - p_{i*}(t)) / N(t)
+//   bonus    (i* = K):  delta[t] =  q_K(t) / N(t)
+template <bool BF16>
+__global__ __launch_bounds__(kTableThreads) void delta_kernel(
+    RowSet rs, int32_t V, int32_t K, int32_t nct, float c_hi, float c_lo, const RowStat *rowstat,
+    const int32_t *mult, const int32_t *accept_len, float *table) {
+  const int b = blockIdx.x / nct;
+  const int32_t istar = accept_len[b];
+  const bool rejected = istar < K;
+  const int64_t trow_id = (int64_t) b * (K + 1) + istar;
+  const int64_t drow_id = rs.nrows0 + (int64_t) b * K + (rejected ? istar : 0);
+  const void *trow = row_base(rs, trow_id, BF16);
+  const void *drow = row_base(rs, drow_id, BF16);
+  const RowStat st = rowstat[trow_id];
+  const RowStat sd = rowstat[drow_id];
+  const double izt = 1.0 / st.Z, izd = rejected ? 1.0 / sd.Z : 0.0;
+  float *out = table + (int64_t) b * V;
+  const int32_t t0 = (blockIdx.x % nct) * kTableTokens;
+#pragma unroll 4
+  for (int32_t k = threadIdx.x; k < kTableTokens; k += kTableThreads) {
+    const int32_t t = t0 + k;
+    if (t >= V) break;
+    const float et = exp_rel(logit_at<BF16>(trow, t), st.M, c_hi, c_lo);
+    // two rounded products and a rounded difference (no fused multiply-add), so that identical
+    // target and draft rows give exactly zero
+    double diff = __dmul_rn((double) et, izt);
+    if (rejected) {
+      const float ed = exp_rel(logit_at<BF16>(drow, t), sd.M, c_hi, c_lo);
+      diff = __dsub_rn(diff, __dmul_rn((double) ed, izd));
+    }
+    out[t] = (float) diff / (float) mult[t];
+  }
+}
+
+// group_probs: w[r][t] = softmax(row r)[t] / N(t) for a batch of rows starting at row0.
+template <bool BF16>
+__global__ __launch_bounds__(kTableThreads) void weights_kernel(
+    RowSet rs, int32_t V, int32_t nparts, int32_t nct, int64_t row0, float c, float c_hi,
+    float c_lo, const StatPart *parts, const int32_t *mult, float *table) {
+  __shared__ RowStat sh;
+  const int32_t local = blockIdx.x / nct;
+  const int64_t row = row0 + local;
+  if (threadIdx.x < kWave) {
+    RowStat s = merge_row(parts, row, nparts, c, threadIdx.x);
+    if (threadIdx.x == 0) sh = s;
+  }
+  __syncthreads();
+  const RowStat s = sh;
+  const double iz = 1.0 / s.Z;
+  const void *rowp = row_base(rs, row, BF16);
+  float *out = table + (int64_t) local * V;
+  const int32_t t0 = (blockIdx.x % nct) * kTableTokens;
+#pragma unroll 4
+  for (int32_t k = threadIdx.x; k < kTableTokens; k += kTableThreads) {
+    const int32_t t = t0 + k;
+    if (t >= V) break;
+    const float e = exp_rel(logit_at<BF16>(rowp, t), s.M, c_hi, c_lo);
+    out[t] = (float) ((double) e * iz) / (float) mult[t];
+  }
+}
+
+// =============================================================================================
+// gather: out[r][g] = sum over members t of G_g of table[r][t], table row staged in LDS.
+// =============================================================================================
+
+constexpr int kGatherThreads = 1024;
+constexpr int kTileMax = 40704;       // floats of LDS per workgroup (159 KiB of the 160 KiB)
+
+// Workgroup id -> (row, chunk).  Workgroups are dealt to the 8 XCDs round-robin by id, so all
+// chunks of one row are given ids that are equal mod 8: they then share that XCD's L2 for the
+// table row and none other holds it.
+template <int W, bool CLAMP>
+__global__ __launch_bounds__(kGatherThreads) void gather_kernel(
+    int32_t V, int32_t G, int32_t nrows, int32_t nchunks, int32_t groups_per_chunk,
+    int32_t ntiles, int32_t tile_len, const int32_t *row_ptr, const int32_t *members,
+    const float *table, float *out) {
+  __shared__ float tab[kTileMax];
+  const int xcd = blockIdx.x & 7;
+  const int y = blockIdx.x >> 3;
+  const int r = xcd + 8 * (y / nchunks);
+  const int chunk = y % nchunks;
+  if (r >= nrows) return;   // whole workgroup leaves together, before any barrier
+  const float *src = table + (int64_t) r * V;
+  float *dst = out + (int64_t) r * G;
+  const int32_t g_begin = chunk * groups_per_chunk;
+  const int32_t g_end = min(G, g_begin + groups_per_chunk);
+  constexpr int nsub = kGatherThreads / W;          // groups in flight per workgroup pass
+  const int sub = threadIdx.x / W, sl = threadIdx.x % W;
+
+  for (int tile = 0; tile < ntiles; ++tile) {
+    const int32_t t0 = tile * tile_len;
+    const int32_t tl = min(tile_len, V - t0);
+    if (tl <= 0) break;                             // uniform: no tile starts past the row
+    if (tile > 0) __syncthreads();                  // everyone is done reading the old tile
+    for (int32_t k = threadIdx.x; k < tl; k += kGatherThreads) tab[k] = src[t0 + k];
+    __syncthreads();
+    // every lane of a wave runs the same number of passes, so the DPP reduction below is
+    // always executed by full waves
+    for (int32_t gb = g_begin; gb < g_end; gb += nsub) {
+      const int32_t g = gb + sub;
+      const bool valid = g < g_end;
+      const int32_t beg = valid ? row_ptr[g] : 0, end = valid ? row_ptr[g + 1] : 0;
+      float acc = 0.f;
+      for (int32_t j = beg + sl; j < end; j += W) {
+        const uint32_t t = (uint32_t) (members[j] - t0);
+        if (t < (uint32_t) tl) acc += tab[t];
+      }
+      acc = subwave_sum<W>(acc);
+      if (valid && sl == W - 1) {
+        if (tile > 0) acc += dst[g];                // partial sum of the earlier tiles
+        if (CLAMP && tile == ntiles - 1) acc = fmaxf(acc, 0.f);
+        dst[g] = acc;
+      }
+    }
+  }
+}
+
+// =============================================================================================
+// finalize: group from the residual by inverse CDF, then the token inside it (Eq. 10).
+// =============================================================================================
+
+constexpr int kFinalThreads = 512;
+
+struct CdfPick {
+  int32_t index;    // first index whose running sum exceeds u * total; -1 if nothing has mass
+  double total, lo, hi;   // total mass; running sum before / after the chosen bin
+};
+
+// Inverse CDF over f(0..n-1) >= 0 by the whole workgroup.  Each thread owns a contiguous run,
+// so the running sum is the ascending one up to fp64 rounding.  All threads get the result.
+template <typename F>
+__device__ CdfPick block_inverse_cdf(int32_t n, F f, double u) {
+  __shared__ double wave_tot[kFinalThreads / kWave];
+  __shared__ int first_thread, last_pos;
+  __shared__ CdfPick res;
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+  const int32_t run = (n + kFinalThreads - 1) / kFinalThreads;
+  const int32_t lo_i = min(n, tid * run), hi_i = min(n, lo_i + run);
+  if (tid == 0) { first_thread = INT_MAX; last_pos = -1; }
+  double mine = 0.0;
+  int32_t my_last = -1;
+  for (int32_t k = lo_i; k < hi_i; ++k) {
+    const double v = f(k);
+    if (v > 0.0) { mine += v; my_last = k; }
+  }
+  // inclusive scan inside the wave, then across waves
+  double inc = mine;
+#pragma unroll
+  for (int o = 1; o < kWave; o <<= 1) {
+    const double up = __shfl_up(inc, o, kWave);
+    if (lane >= o) inc += up;
+  }
+  if (lane == kWave - 1) wave_tot[wave] = inc;
+  __syncthreads();
+  double before = 0.0, total = 0.0;
+  for (int w = 0; w < kFinalThreads / kWave; ++w) {
+    if (w < wave) before += wave_tot[w];
+    total += wave_tot[w];
+  }
+  const double excl = before + (inc - mine);
+  const double goal = u * total;
+  if (mine > 0.0 && excl + mine > goal) atomicMin(&first_thread, tid);
+  if (my_last >= 0) atomicMax(&last_pos, my_last);
+  __syncthreads();
+  if (first_thread == tid) {
+    double cum = excl;
+    for (int32_t k = lo_i; k < hi_i; ++k) {
+      const double v = f(k);
+      if (!(v > 0.0)) continue;
+      const double nxt = cum + v;
+      if (nxt > goal || k == my_last) {   // k == my_last: guaranteed by excl + mine > goal
+        res.index = k; res.lo = cum; res.hi = nxt; res.total = total;
+        break;
+      }
+      cum = nxt;
+    }
+  } else if (first_thread == INT_MAX && tid == 0) {
+    // rounding at the top end (or no mass at all): the last index that has mass
+    res.index = last_pos; res.total = total; res.lo = total; res.hi = total;
+    if (last_pos >= 0) res.lo = total - f(last_pos);
+  }
+  __syncthreads();
+  CdfPick out = res;
+  __syncthreads();   // res / first_thread may be reused by the next call
+  return out;
+}
+
+__device__ __forceinline__ bool near_edge(const CdfPick &p, double u) {
+  const double goal = u * p.total;
+  const bool near_lo = p.lo > 0.0 && (goal - p.lo) < 1e-6 * p.total;
+  const bool near_hi = p.hi < p.total && (p.hi - goal) < 1e-6 * p.total;
+  return near_lo || near_hi;
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(kFinalThreads) void finalize_kernel(
+    RowSet rs, int32_t V, int32_t G, int32_t K, double cd, const RowStat *rowstat,
+    const int32_t *row_ptr, const int32_t *members, const int32_t *mult, uint64_t seed,
+    uint64_t offset, const int32_t *accept_len, float *R, int32_t *out_tokens,
+    int32_t *out_groups, pcg_diag *diag) {
+  const int b = blockIdx.x;
+  const int32_t istar = accept_len[b];
+  const int64_t trow_id = (int64_t) b * (K + 1) + istar;
+  const void *trow = row_base(rs, trow_id, BF16);
+  const RowStat st = rowstat[trow_id];
+  const Uniforms u = philox_uniforms(seed, offset, (uint32_t) b, (uint32_t) istar);
+  float *Rb = R + (int64_t) b * G;
+
+  // q(t) / N(t) on the decision row, in double
+  auto weight = [&](int32_t t) -> double {
+    return exp2((double) (logit_at<BF16>(trow, t) - st.M) * cd) / (st.Z * (double) mult[t]);
+  };
+
+  CdfPick pg = block_inverse_cdf(G, [&](int32_t g) { return (double) Rb[g]; }, (double) u.grp);
+  bool fallback = false;
+  if (!(pg.total > 0.0)) {
+    // Residual total <= 0 (cannot happen in exact arithmetic): draw from T of this row instead.
+    fallback = true;
+    for (int32_t g = threadIdx.x; g < G; g += kFinalThreads) {
+      double s = 0.0;
+      for (int32_t j = row_ptr[g]; j < row_ptr[g + 1]; ++j) s += weight(members[j]);
+      Rb[g] = (float) s;
+    }
+    __syncthreads();
+    pg = block_inverse_cdf(G, [&](int32_t g) { return (double) Rb[g]; }, (double) u.grp);
+  }
+  const int32_t gs = pg.index < 0 ? 0 : pg.index;
+
+  const int32_t beg = row_ptr[gs], end = row_ptr[gs + 1];
+  CdfPick pt = block_inverse_cdf(end - beg, [&](int32_t j) { return weight(members[beg + j]); },
+                                 (double) u.tok);
+  if (threadIdx.x == 0) {
+    out_groups[(int64_t) b * (K + 1) + istar] = gs;
+    out_tokens[(int64_t) b * (K + 1) + istar] = pt.index < 0 ? -1 : members[beg + pt.index];
+    if (diag) {
+      if (pg.index >= 0 && near_edge(pg, (double) u.grp)) atomicAdd(&diag->near_group, 1u);
+      if (pt.index >= 0 && near_edge(pt, (double) u.tok)) atomicAdd(&diag->near_token, 1u);
+      if (fallback) atomicAdd(&diag->residual_fallback, 1u);
+    }
+  }
+}
+
+// =============================================================================================
+// Launchers.
+// =============================================================================================
+
+static inline bool rows_vector_aligned(const RowSet &rs, bool bf16) {
+  const int64_t per16 = bf16 ? 8 : 4;   // elements in 16 bytes
+  auto ok = [&](const void *p, int64_t bs, int64_t ps) {
+    return p == nullptr || (((uintptr_t) p & 15) == 0 && bs % per16 == 0 && ps % per16 == 0);
+  };
+  return ok(rs.base0, rs.bs0, rs.ps0) && ok(rs.base1, rs.bs1, rs.ps1);
+}
+
+int32_t stats_nparts(int32_t V) { return (V + kPartElems - 1) / kPartElems; }
+
+hipError_t launch_row_stats(const RowSet &rs, bool bf16, int32_t V, int64_t nrows, float c,
+                            StatPart *parts, hipStream_t stream) {
+  const int32_t nparts = stats_nparts(V);
+  const int64_t total = nrows * nparts;
+  if (total == 0) return hipSuccess;
+  const dim3 grid((unsigned) ((total + kStatsWaves - 1) / kStatsWaves)), block(kStatsWaves * kWave);
+  const bool vec = rows_vector_aligned(rs, bf16);
+  if (bf16) {
+    if (vec) row_stats_kernel<true, true><<<grid, block, 0, stream>>>(rs, V, nparts, total, c, parts);
+    else row_stats_kernel<true, false><<<grid, block, 0, stream>>>(rs, V, nparts, total, c, parts);
+  } else {
+    if (vec) row_stats_kernel<false, true><<<grid, block, 0, stream>>>(rs, V, nparts, total, c, parts);
+    else row_stats_kernel<false, false><<<grid, block, 0, stream>>>(rs, V, nparts, total, c, parts);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_accept(const RowSet &rs, bool bf16, const pcg_groups &g, int32_t B, int32_t K,
+                         float c, double cd, const StatPart *parts, RowStat *rowstat,
+                         const int32_t *prop_tokens, const int32_t *prop_groups, uint64_t seed,
+                         uint64_t offset, int32_t *accept_len, int32_t *out_tokens,
+                         int32_t *out_groups, pcg_diag *diag, hipStream_t stream) {
+  const int32_t nparts = stats_nparts(g.V);
+  if (bf16)
+    accept_kernel<true><<<B, kAcceptThreads, 0, stream>>>(
+        rs, g.V, g.G, K, nparts, c, cd, parts, rowstat, g.row_ptr, g.members, g.mult, prop_tokens,
+        prop_groups, seed, offset, accept_len, out_tokens, out_groups, diag);
+  else
+    accept_kernel<false><<<B, kAcceptThreads, 0, stream>>>(
+        rs, g.V, g.G, K, nparts, c, cd, parts, rowstat, g.row_ptr, g.members, g.mult, prop_tokens,
+        prop_groups, seed, offset, accept_len, out_tokens, out_groups, diag);
+  return hipGetLastError();
+}
+
+hipError_t launch_delta(const RowSet &rs, bool bf16, const pcg_groups &g, int32_t B, int32_t K,
+                        float c_hi, float c_lo, const RowStat *rowstat, const int32_t *accept_len,
+                        float *table, hipStream_t stream) {
+  const int32_t nct = (g.V + kTableTokens - 1) / kTableTokens;
+  const dim3 grid((unsigned) ((int64_t) nct * B));
+  if (bf16)
+    delta_kernel<true><<<grid, kTableThreads, 0, stream>>>(rs, g.V, K, nct, c_hi, c_lo, rowstat,
+                                                           g.mult, accept_len, table);
+  else
+    delta_kernel<false><<<grid, kTableThreads, 0, stream>>>(rs, g.V, K, nct, c_hi, c_lo, rowstat,
+                                                            g.mult, accept_len, table);
+  return hipGetLastError();
+}
+
+hipError_t launch_weights(const RowSet &rs, bool bf16, const pcg_groups &g, int64_t row0,
+                          int32_t nrows, float c, float c_hi, float c_lo, const StatPart *parts,
+                          float *table, hipStream_t stream) {
+  const int32_t nct = (g.V + kTableTokens - 1) / kTableTokens;
+  const dim3 grid((unsigned) ((int64_t) nct * nrows));
+  const int32_t nparts = stats_nparts(g.V);
+  if (bf16)
+    weights_kernel<true><<<grid, kTableThreads, 0, stream>>>(rs, g.V, nparts, nct, row0, c, c_hi,
+                                                             c_lo, parts, g.mult, table);
+  else
+    weights_kernel<false><<<grid, kTableThreads, 0, stream>>>(rs, g.V, nparts, nct, row0, c, c_hi,
+                                                              c_lo, parts, g.mult, table);
+  return hipGetLastError();
+}
+
+template <int W>
+static void gather_dispatch(bool clamp, dim3 grid, hipStream_t stream, int32_t V, int32_t G,
+                            int32_t nrows, int32_t nchunks, int32_t gpc, int32_t ntiles,
+                            int32_t tile_len, const int32_t *row_ptr, const int32_t *members,
+                            const float *table, float *out) {
+  if (clamp)
+    gather_kernel<W, true><<<grid, kGatherThreads, 0, stream>>>(V, G, nrows, nchunks, gpc, ntiles,
+                                                                tile_len, row_ptr, members, table, out);
+  else
+    gather_kernel<W, false><<<grid, kGatherThreads, 0, stream>>>(V, G, nrows, nchunks, gpc, ntiles,
+                                                                 tile_len, row_ptr, members, table, out);
+}
+
+hipError_t launch_gather(const pcg_groups &g, int32_t nrows, bool clamp, const float *table,
+                         float *out, hipStream_t stream) {
+  if (nrows == 0) return hipSuccess;
+  // lanes per group: the smallest power of two >= the mean group size, within [4, 64]
+  const double mean = (double) g.nnz / (double) g.G;
+  int W = 4;
+  while (W < 64 && W < mean) W *= 2;
+  const int nsub = kGatherThreads / W;
+  // enough chunks per row to give every CU a workgroup, but no chunk below one pass
+  int32_t nchunks = (256 + nrows - 1) / nrows;
+  const int32_t max_chunks = (g.G + nsub - 1) / nsub;
+  if (nchunks > max_chunks) nchunks = max_chunks;
+  if (nchunks < 1) nchunks = 1;
+  int32_t gpc = (g.G + nchunks - 1) / nchunks;
+  gpc = (gpc + nsub - 1) / nsub * nsub;
+  nchunks = (g.G + gpc - 1) / gpc;
+  const int32_t ntiles = (g.V + kTileMax - 1) / kTileMax;
+  int32_t tile_len = (g.V + ntiles - 1) / ntiles;
+  tile_len = (tile_len + 63) / 64 * 64;
+  if (tile_len > kTileMax) tile_len = kTileMax;
+  const int32_t rows8 = (nrows + 7) / 8;
+  const dim3 grid((unsigned) (8 * rows8 * nchunks));
+  switch (W) {
+    case 4: gather_dispatch<4>(clamp, grid, stream, g.V, g.G, nrows, nchunks, gpc, ntiles, tile_len, g.row_ptr, g.members, table, out); break;
+    case 8: gather_dispatch<8>(clamp, grid, stream, g.V, g.G, nrows, nchunks, gpc, ntiles, tile_len, g.row_ptr, g.members, table, out); break;
+    case 16: gather_dispatch<16>(clamp, grid, stream, g.V, g.G, nrows, nchunks, gpc, ntiles, tile_len, g.row_ptr, g.members, table, out); break;
+    case 32: gather_dispatch<32>(clamp, grid, stream, g.V, g.G, nrows, nchunks, gpc, ntiles, tile_len, g.row_ptr, g.members, table, out); break;
+    default: gather_dispatch<64>(clamp, grid, stream, g.V, g.G, nrows, nchunks, gpc, ntiles, tile_len, g.row_ptr, g.members, table, out); break;
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_finalize(const RowSet &rs, bool bf16, const pcg_groups &g, int32_t B, int32_t K,
+                           double cd, const RowStat *rowstat, uint64_t seed, uint64_t offset,
+                           const int32_t *accept_len, float *R, int32_t *out_tokens,
+                           int32_t *out_groups, pcg_diag *diag, hipStream_t stream) {
+  if (bf16)
+    finalize_kernel<true><<<B, kFinalThreads, 0, stream>>>(rs, g.V, g.G, K, cd, rowstat, g.row_ptr,
+                                                           g.members, g.mult, seed, offset,
+                                                           accept_len, R, out_tokens, out_groups, diag);
+  else
+    finalize_kernel<false><<<B, kFinalThreads, 0, stream>>>(rs, g.V, g.G, K, cd, rowstat, g.row_ptr,
+                                                            g.members, g.mult, seed, offset,
+                                                            accept_len, R, out_tokens, out_groups, diag);
+  return hipGetLastError();
+}
+
+}  // namespace pcg

@@ -1,0 +1,343 @@
+"""GPU parity: libpcg (HIP, through the C ABI) against the CPU oracle, element by element,
+on the same seeded inputs.  Run with ``-m gpu`` on an MI355X."""
+import os
+
+import numpy as np
+import pytest
+import scipy.stats
+import torch
+
+import oracle
+import paper_2511_13732_amd as pcg
+import workloads as W
+from parity import (Tally, as_oracle_logits, compare_verify, device_groups, group_probs_error,
+                    oracle_groups, run_both)
+
+pytestmark = pytest.mark.gpu
+
+# Tolerances (relative, with an absolute floor of 1e-30 for fp32 underflow).  Both sides read
+# the same bf16 values exactly, so the fp32 bound is asserted for bf16 logits as well; the
+# looser bound the task allows for bf16 is kept as the outer limit.
+TOL_F32 = 1e-5
+TOL_BF16_LIMIT = 2e-3
+
+
+def logits_pair(B, K, V, dtype, seed, sigma_t=3.0, sigma_d=1.0, scale=1.0):
+    rng = np.random.default_rng(seed)
+    tgt = (sigma_t * rng.standard_normal((B, K + 1, V))).astype(np.float32)
+    dft = (scale * tgt[:, :K] + sigma_d * rng.standard_normal((B, K, V))).astype(np.float32)
+    t, d = torch.from_numpy(tgt), torch.from_numpy(dft)
+    if dtype == "bf16":
+        t, d = t.to(torch.bfloat16), d.to(torch.bfloat16)
+    return t, d
+
+
+def coupled_proposals(dft, tau, og, seed):
+    return W.proposals(dft, tau, og.row_ptr, og.members, np.random.default_rng(seed))
+
+
+# --------------------------------------------------------------------------- group probabilities
+
+@pytest.mark.parametrize("V,G,smin,smax,dtype,tau,rows", [
+    (1000, 700, 1, 9, "f32", 1.0, 5),          # ragged row tail, narrow groups (4 lanes / group)
+    (4097, 3000, 4, 20, "bf16", 0.8, 7),       # odd V: rows are not 16-byte aligned (scalar loads)
+    (2049, 2049, 10, 40, "f32", 0.7, 3),       # one element past a part boundary
+    (6144, 4000, 40, 128, "bf16", 1.0, 9),     # wide groups (64 lanes / group), several parts
+    (65536, 9000, 20, 44, "bf16", 1.0, 3),     # two LDS tiles
+    (50000, 5000, 1, 3, "f32", 1.3, 2),        # two tiles, ragged, tiny groups
+    (7, 3, 1, 4, "f32", 1.0, 4),               # smaller than a wave
+])
+def test_group_probs_matches_oracle(V, G, smin, smax, dtype, tau, rows):
+    rp, mem = W.random_groups(V, G, smin, smax, seed=V + G, cover=False)
+    og, dg = oracle_groups(V, rp, mem), device_groups(V, rp, mem)
+    assert og.G == dg.G and og.nnz == dg.nnz
+    np.testing.assert_array_equal(og.row_ptr, dg.row_ptr.cpu().numpy())
+    np.testing.assert_array_equal(og.mult, dg.mult.cpu().numpy())
+    t, _ = logits_pair(rows, 1, V, dtype, seed=V, sigma_t=4.0)
+    x = t[:, 0].contiguous()
+    out = pcg.group_probs(dg, x.cuda(), tau)
+    torch.cuda.synchronize()
+    ref = oracle.group_probs(og, as_oracle_logits(x), tau)
+    err = group_probs_error(out, ref)
+    print(f"group_probs V={V} {dtype}: max rel err {err:.3e}")
+    assert err <= TOL_F32 < TOL_BF16_LIMIT
+    s = out.double().sum(dim=1).cpu().numpy()
+    np.testing.assert_allclose(s, 1.0, atol=2e-6)      # Eq. (2): no mass lost, no renormalisation
+
+
+def test_group_probs_strided_rows_and_extremes():
+    V = 3000
+    rp, mem = W.random_groups(V, 2500, 2, 12, seed=5, cover=True)
+    og, dg = oracle_groups(V, rp, mem), device_groups(V, rp, mem)
+    rng = np.random.default_rng(6)
+    big = (4 * rng.standard_normal((6, V + 40))).astype(np.float32)
+    big[1, :V] *= 20.0                    # sharply peaked: most of the row underflows in fp32
+    big[2, 5:900] = -np.inf               # masked-out tokens
+    big[3, :V] = 0.0                      # uniform row
+    big[4, :V] += 3.0e4                   # large common offset
+    xb = torch.from_numpy(big).cuda()
+    out = pcg.group_probs(dg, xb[:, :V], 0.7)     # row stride V + 40
+    torch.cuda.synchronize()
+    ref = oracle.group_probs(og, np.ascontiguousarray(big[:, :V]), 0.7)
+    assert group_probs_error(out, ref) <= TOL_F32
+    assert pcg.group_probs(dg, xb[:0, :V]).shape == (0, dg.G)      # rows == 0 is a no-op
+
+
+def test_group_probs_many_rows_in_batches():
+    V = 32768 + 512
+    rp, mem = W.random_groups(V, 3000, 8, 24, seed=9, cover=False)
+    og, dg = oracle_groups(V, rp, mem), device_groups(V, rp, mem)
+    rows = 600                                   # more than one staging batch of the library
+    t, _ = logits_pair(rows, 1, V, "bf16", seed=10, sigma_t=4.0)
+    x = t[:, 0].contiguous()
+    out = pcg.group_probs(dg, x.cuda())
+    torch.cuda.synchronize()
+    sel = [0, 1, 254, 255, 256, 257, 511, 512, 599]
+    ref = oracle.group_probs(og, as_oracle_logits(x[sel]))
+    assert group_probs_error(out[sel], ref) <= TOL_F32
+    np.testing.assert_allclose(out.double().sum(dim=1).cpu().numpy(), 1.0, atol=2e-6)
+
+
+# --------------------------------------------------------------------------- verify, small shapes
+
+@pytest.mark.parametrize("V,G,smin,smax,B,K,dtype,tau", [
+    (64, 40, 1, 6, 33, 3, "f32", 1.0),
+    (1000, 800, 2, 9, 17, 5, "bf16", 0.8),
+    (4097, 3000, 4, 20, 9, 8, "bf16", 1.0),      # unaligned rows
+    (2048, 2048, 10, 40, 12, 1, "f32", 0.7),     # K = 1
+    (3000, 500, 40, 128, 5, 64, "f32", 1.0),     # K = PCG_MAX_K, wide groups
+    (50000, 6000, 10, 30, 6, 4, "f32", 1.0),     # two LDS tiles
+    (5, 4, 1, 3, 200, 2, "f32", 1.0),            # tiny vocabulary
+])
+def test_verify_matches_oracle(V, G, smin, smax, B, K, dtype, tau):
+    rp, mem = W.random_groups(V, G, smin, smax, seed=V * 3 + K, cover=False)
+    og, dg = oracle_groups(V, rp, mem), device_groups(V, rp, mem)
+    total = Tally()
+    lens = []
+    for step in range(6):
+        tgt, dft = logits_pair(B, K, V, dtype, seed=1000 * step + V, sigma_d=0.6)
+        ptok, pgrp = coupled_proposals(dft, tau, og, seed=step)
+        gpu, ref, _, diag = run_both(V, rp, mem, tgt, dft, ptok, pgrp, temperature=tau, seed=42,
+                                     offset=step, dg=dg, og=og)
+        total.add(compare_verify(gpu, ref, og, ptok, pgrp))
+        assert diag["sequences"] == B and diag["bad_proposal"] == 0
+        assert diag["accepted_total"] == int(gpu.accept_len.sum())
+        lens += ref.accept_len.tolist()
+    total.report(f"small V={V} K={K} {dtype}")
+    assert total.tolerated <= max(1, total.sequences // 200)
+    assert len(set(lens)) > 1                  # both accepts and rejects were exercised
+
+
+def test_verify_is_deterministic_and_offset_changes_the_stream():
+    V, B, K = 5000, 16, 4
+    rp, mem = W.random_groups(V, 4000, 3, 12, seed=3, cover=True)
+    og, dg = oracle_groups(V, rp, mem), device_groups(V, rp, mem)
+    tgt, dft = logits_pair(B, K, V, "bf16", seed=8)
+    ptok, pgrp = coupled_proposals(dft, 1.0, og, seed=1)
+    a, *_ = run_both(V, rp, mem, tgt, dft, ptok, pgrp, seed=1, offset=5, dg=dg, og=og)
+    b, *_ = run_both(V, rp, mem, tgt, dft, ptok, pgrp, seed=1, offset=5, dg=dg, og=og)
+    c, *_ = run_both(V, rp, mem, tgt, dft, ptok, pgrp, seed=1, offset=6, dg=dg, og=og)
+    for x, y in ((a.accept_len, b.accept_len), (a.out_tokens, b.out_tokens), (a.out_groups, b.out_groups)):
+        assert torch.equal(x, y)
+    assert not torch.equal(a.out_tokens, c.out_tokens)
+
+
+def test_verify_strided_buffers_and_shared_rows():
+    V, B, K = 3000, 10, 3
+    rp, mem = W.random_groups(V, 2000, 2, 10, seed=12, cover=True)
+    og, dg = oracle_groups(V, rp, mem), device_groups(V, rp, mem)
+    rng = np.random.default_rng(13)
+    tfull = torch.from_numpy((3 * rng.standard_normal((B, K + 2, V + 24))).astype(np.float32))
+    dfull = tfull + torch.from_numpy(rng.standard_normal((B, K + 2, V + 24)).astype(np.float32))
+    tgt, dft = tfull[:, :K + 1, :V], dfull[:, :K + 1, :V]          # a [B, K+1, V] draft buffer, padded
+    ptok, pgrp = coupled_proposals(dft[:, :K].contiguous(), 1.0, og, seed=2)
+    diag = torch.zeros(8, dtype=torch.int32, device="cuda")
+    gpu = pcg.verify(dg, tfull.cuda()[:, :K + 1, :V], dfull.cuda()[:, :K + 1, :V],
+                     torch.from_numpy(ptok).cuda(), torch.from_numpy(pgrp).cuda(), seed=7, diag=diag)
+    ref = oracle.verify(og, tgt.contiguous().numpy(), dft.contiguous().numpy(), ptok, pgrp, seed=7)
+    t = compare_verify(gpu, ref, og, ptok, pgrp)
+    assert t.tolerated == 0
+    # many sequences sharing one set of rows (batch stride 0), distinct proposals and streams
+    Bs = 4096
+    t1, d1 = logits_pair(1, K, V, "f32", seed=14)
+    ptok, pgrp = coupled_proposals(d1.expand(Bs, K, V), 1.0, og, seed=3)
+    gpu = pcg.verify(dg, t1.cuda(), d1.cuda(), torch.from_numpy(ptok).cuda(),
+                     torch.from_numpy(pgrp).cuda(), seed=9, offset=2, B=Bs)
+    ref = oracle.verify(og, t1.numpy(), d1.numpy(), ptok, pgrp, seed=9, offset=2, B=Bs,
+                        tgt_batch_stride=0, dft_batch_stride=0, nthreads=16)
+    t = compare_verify(gpu, ref, og, ptok, pgrp)
+    t.report("shared rows B=4096")
+    assert t.tolerated <= 2
+
+
+# --------------------------------------------------------------------------- degenerate cases
+
+def test_empty_batch_and_uncovered_tokens_and_empty_groups():
+    V = 40
+    # groups 1 and 3 are empty; tokens 30..39 are in no group and become singletons
+    rp = np.array([0, 10, 10, 25, 25, 30], np.int32)
+    mem = np.arange(30, dtype=np.int32)
+    og, dg = oracle_groups(V, rp, mem), device_groups(V, rp, mem)
+    assert dg.G == 15 and og.G == 15
+    out = pcg.verify(dg, torch.zeros((0, 3, V), device="cuda"), torch.zeros((0, 2, V), device="cuda"),
+                     torch.zeros((0, 2), dtype=torch.int32, device="cuda"),
+                     torch.zeros((0, 2), dtype=torch.int32, device="cuda"))
+    assert out.accept_len.numel() == 0
+    total = Tally()
+    for step in range(20):
+        tgt, dft = logits_pair(50, 2, V, "f32", seed=step, sigma_t=1.0)
+        ptok, pgrp = coupled_proposals(dft, 1.0, og, seed=step)
+        gpu, ref, *_ = run_both(V, rp, mem, tgt, dft, ptok, pgrp, offset=step, dg=dg, og=og)
+        total.add(compare_verify(gpu, ref, og, ptok, pgrp))
+        assert not np.isin(gpu.out_groups.cpu().numpy(), [1, 3]).any()      # zero mass: never drawn
+    assert total.tolerated == 0
+
+
+def test_singleton_groups_and_one_big_group():
+    V, B, K = 300, 64, 3
+    tgt, dft = logits_pair(B, K, V, "f32", seed=3)
+    # singleton groups: group id == token id everywhere
+    rp, mem = np.arange(V + 1, dtype=np.int32), np.arange(V, dtype=np.int32)
+    og = oracle_groups(V, rp, mem)
+    ptok, pgrp = coupled_proposals(dft, 1.0, og, seed=1)
+    assert (ptok == pgrp).all()
+    gpu, ref, *_ = run_both(V, rp, mem, tgt, dft, ptok, pgrp, og=og)
+    assert compare_verify(gpu, ref, og, ptok, pgrp).tolerated == 0
+    assert torch.equal(gpu.out_tokens, gpu.out_groups)
+    # one group holding everything: T = D = 1, every proposal is accepted, bonus token ~ q_K
+    rp, mem = np.array([0, V], np.int32), np.arange(V, dtype=np.int32)
+    og = oracle_groups(V, rp, mem)
+    ptok, pgrp = coupled_proposals(dft, 1.0, og, seed=1)
+    gpu, ref, *_ = run_both(V, rp, mem, tgt, dft, ptok, pgrp, og=og)
+    assert compare_verify(gpu, ref, og, ptok, pgrp).tolerated == 0
+    assert (gpu.accept_len == K).all()
+
+
+def test_zero_mass_proposals_identical_rows_and_masked_tokens():
+    V, K = 64, 2
+    rp, mem = W.random_groups(V, 30, 2, 6, seed=4, cover=True)
+    og, dg = oracle_groups(V, rp, mem), device_groups(V, rp, mem)
+    g0 = 0
+    seg = og.members[og.row_ptr[g0]:og.row_ptr[g0 + 1]]
+    rng = np.random.default_rng(1)
+    base = rng.standard_normal((3, K + 1, V)).astype(np.float32)
+    tgt = base.copy()
+    dft = base[:, :K].copy() + 0.5 * rng.standard_normal((3, K, V)).astype(np.float32)
+    # sequence 0: the draft gives the proposed group no mass at all while the target does -> accept
+    dft[0, 0, seg] = -np.inf
+    # sequence 1: draft row == target row and the proposed group has no mass on either -> reject,
+    # residual total is exactly zero, the draw falls back to T
+    dft[1, 0] = tgt[1, 0]
+    tgt[1, 0, seg] = -np.inf
+    dft[1, 0, seg] = -np.inf
+    # sequence 2: half the vocabulary masked on the target
+    tgt[2, :, ::2] = -np.inf
+    ptok = np.zeros((3, K), np.int32)
+    pgrp = np.zeros((3, K), np.int32) + g0
+    ptok[:] = seg[0]
+    gpu, ref, _, diag = run_both(V, rp, mem, torch.from_numpy(tgt), torch.from_numpy(dft), ptok, pgrp,
+                                 seed=3, dg=dg, og=og)
+    assert compare_verify(gpu, ref, og, ptok, pgrp).tolerated == 0
+    assert ref.accept_len[0] >= 1 and ref.flags[0] & 2 and diag["zero_draft_mass"] >= 1
+    assert ref.accept_len[1] == 0 and ref.flags[1] & 1 and diag["residual_fallback"] == 1
+    z2 = gpu.out_tokens.cpu().numpy()[2]
+    assert z2[int(gpu.accept_len[2])] % 2 == 1          # a masked token is never emitted
+
+
+def test_out_of_range_proposal_is_rejected_not_dereferenced():
+    V, B, K = 500, 8, 3
+    rp, mem = W.random_groups(V, 300, 2, 8, seed=6, cover=True)
+    og, dg = oracle_groups(V, rp, mem), device_groups(V, rp, mem)
+    tgt, dft = logits_pair(B, K, V, "f32", seed=2)
+    ptok, pgrp = coupled_proposals(dft, 1.0, og, seed=0)
+    pgrp[0, 0] = dg.G + 5
+    pgrp[1, 0] = -3
+    diag = torch.zeros(8, dtype=torch.int32, device="cuda")
+    gpu = pcg.verify(dg, tgt.cuda(), dft.cuda(), torch.from_numpy(ptok).cuda(),
+                     torch.from_numpy(pgrp).cuda(), diag=diag)
+    al = gpu.accept_len.cpu().numpy()
+    assert al[0] == 0 and al[1] == 0 and int(diag[5]) == 2
+    g = gpu.out_groups.cpu().numpy()
+    assert 0 <= g[0, 0] < dg.G and 0 <= g[1, 0] < dg.G
+
+
+# --------------------------------------------------------------------------- statistics of the GPU output
+
+def test_gpu_emitted_group_is_target_distributed():
+    """Proposition, on the HIP path itself: chi-square of the first emitted group against T
+    (computed by the oracle), 2^18 sequences sharing one set of rows."""
+    V, K, Bs, tau = 48, 2, 1 << 18, 0.8
+    rp, mem = W.random_groups(V, 36, 2, 6, seed=71, cover=False)
+    og, dg = oracle_groups(V, rp, mem), device_groups(V, rp, mem)
+    t1, d1 = logits_pair(1, K, V, "f32", seed=72, sigma_t=2.0, sigma_d=0.7)
+    ptok, pgrp = coupled_proposals(d1.expand(Bs, K, V), tau, og, seed=5)
+    gpu = pcg.verify(dg, t1.cuda(), d1.cuda(), torch.from_numpy(ptok).cuda(),
+                     torch.from_numpy(pgrp).cuda(), temperature=tau, seed=11, offset=3, B=Bs)
+    grp = gpu.out_groups.cpu().numpy()
+    al = gpu.accept_len.cpu().numpy()
+    T = oracle.group_probs(og, t1[0].numpy(), tau)
+
+    def chi2_p(counts, probs):
+        n = counts.sum()
+        keep = probs * n >= 5
+        obs = np.append(counts[keep], counts[~keep].sum())
+        exp = np.append(probs[keep], probs[~keep].sum()) * n
+        if exp[-1] == 0:
+            obs, exp = obs[:-1], exp[:-1]
+        return scipy.stats.chisquare(obs, exp * obs.sum() / exp.sum()).pvalue
+
+    assert chi2_p(np.bincount(grp[:, 0], minlength=og.G), T[0]) > 1e-3
+    sel = al >= 1
+    assert chi2_p(np.bincount(grp[sel, 1], minlength=og.G), T[1]) > 1e-3
+    bonus = al == K
+    qK = oracle.softmax_row(t1[0, K].numpy(), tau)
+    assert chi2_p(np.bincount(gpu.out_tokens.cpu().numpy()[bonus, K], minlength=V), qK) > 1e-3
+
+
+# --------------------------------------------------------------------------- the paper-shaped recipes
+
+def _steps(cfg, default):
+    return cfg.steps if os.environ.get("PCG_PARITY_FULL_STEPS") else default
+
+
+@pytest.mark.parametrize("name,steps", [("C1", 1000), ("C2", 300)])
+def test_recipe_small(name, steps):
+    cfg = W.CONFIGS[name]
+    rp, mem = W.groups(cfg)
+    og, dg = oracle_groups(cfg.V, rp, mem), device_groups(cfg.V, rp, mem)
+    total = Tally()
+    hist = np.zeros(cfg.K + 1, np.int64)
+    for step in range(_steps(cfg, steps)):
+        tgt, dft, ptok, pgrp = W.step_inputs(cfg, og.row_ptr, og.members, step)
+        gpu, ref, *_ = run_both(cfg.V, rp, mem, tgt, dft, ptok, pgrp, temperature=cfg.temperature,
+                                seed=0, offset=step, dg=dg, og=og, nthreads=8)
+        total.add(compare_verify(gpu, ref, og, ptok, pgrp))
+        hist += np.bincount(ref.accept_len, minlength=cfg.K + 1)
+    total.report(f"recipe {name}")
+    print("accept_len histogram", hist.tolist(), flush=True)
+    assert total.tolerated <= max(1, total.sequences // 500)
+
+
+@pytest.mark.parametrize("name,steps", [("C3", 3), ("C4", 2), ("C5", 2)])
+def test_recipe_full_size(name, steps):
+    """The large recipes at their full sizes, in the launch configuration the benchmark times."""
+    cfg = W.CONFIGS[name]
+    print(f"building groups for {name}", flush=True)
+    rp, mem = W.groups(cfg)
+    og, dg = oracle_groups(cfg.V, rp, mem), device_groups(cfg.V, rp, mem)
+    print(f"{name}: G={og.G} nnz={og.nnz} mean size {og.nnz / og.G:.1f}", flush=True)
+    total = Tally()
+    for step in range(steps):
+        tgt, dft, ptok, pgrp = W.step_inputs(cfg, og.row_ptr, og.members, step)
+        gpu, ref, _, diag = run_both(cfg.V, rp, mem, tgt, dft, ptok, pgrp,
+                                     temperature=cfg.temperature, seed=0, offset=step, dg=dg, og=og)
+        total.add(compare_verify(gpu, ref, og, ptok, pgrp))
+        print(f"{name} step {step}: accept_len mean {ref.accept_len.mean():.2f} diag {diag}", flush=True)
+        if step == 0:        # group probabilities of a few rows of the same inputs
+            rows = tgt[:3, 0].contiguous()
+            out = pcg.group_probs(dg, rows.cuda(), cfg.temperature)
+            err = group_probs_error(out, oracle.group_probs(og, as_oracle_logits(rows), cfg.temperature))
+            print(f"{name}: group_probs max rel err {err:.3e}", flush=True)
+            assert err <= TOL_F32
+    total.report(f"recipe {name} full size")
+    assert total.tolerated <= max(1, total.sequences // 100)

@@ -131,7 +131,8 @@ __device__ __forceinline__ RowStat merge_row(const StatPart *parts, int64_t row,
 // relative to the result: (x - M) * (c_hi + c_lo) with c_hi + c_lo = log2(e) / temperature.
 __device__ __forceinline__ float exp_rel(float x, float M, float c_hi, float c_lo) {
   const float d = x - M;
-  return __builtin_amdgcn_exp2f(fmaf(d, c_hi, d * c_lo));
+  // a -inf logit has no mass; (-inf) * c_lo would turn the sum into inf - inf otherwise
+  return d == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(fmaf(d, c_hi, d * c_lo));
 }
 
 // =============================================================================================

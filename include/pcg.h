@@ -70,6 +70,8 @@ typedef enum {
  * must describe a membership that pcg_groups_validate_host accepts; the
  * kernels do not re-check them.
  */
+typedef struct pcg_prepared pcg_prepared;
+
 typedef struct {
   int32_t V;
   int32_t G;
@@ -77,7 +79,36 @@ typedef struct {
   const int32_t *row_ptr;
   const int32_t *members;
   const int32_t *mult;
+  /* Optional fast form of the same membership (see pcg_groups_prepare_host): the blob
+   * uploaded to the DEVICE and its HOST descriptor.  Both NULL = use the CSR directly. */
+  const void *prepared;
+  const pcg_prepared *prepared_info;
 } pcg_groups;
+
+/*
+ * Prepared membership.  The groups are fixed once the similarity groups have been built
+ * (Sec. 2.2: "precomputed once and cached"), so the gather-sum of Eq. (5) can read them
+ * from a layout made for the kernel instead of from the CSR:
+ *   - the vocabulary is cut into `ntiles` tiles of `tile_len` tokens, each small enough for
+ *     a table of one float per token to sit in a workgroup's LDS;
+ *   - the groups are cut into chunks of `chunk_groups` consecutive groups (one workgroup
+ *     each); inside a chunk they are sorted by their member counts per tile and dealt 64 at
+ *     a time into slices, one group per lane;
+ *   - per (chunk, tile, slice) the members that fall into the tile are stored as 16-bit
+ *     tile-local slots, padded with a slot that holds 0 to the slice's longest list and
+ *     interleaved so that a wave reads them with coalesced loads.
+ * The descriptor is filled by pcg_groups_prepare_host and must be passed back unchanged.
+ */
+struct pcg_prepared {
+  int32_t V, G;
+  int32_t ntiles, tile_len;
+  int32_t chunk_groups, nchunks;
+  int32_t slices_per_chunk, reserved;
+  int64_t off_desc;   /* uint32 [nchunks][ntiles][slices_per_chunk][2]: data offset (dwords), length */
+  int64_t off_perm;   /* uint16 [nchunks][slices_per_chunk][64]: group index inside the chunk, 0xFFFF = none */
+  int64_t off_data;   /* uint32 []: two 16-bit slots per dword, [k][lane] inside a slice             */
+  int64_t bytes;      /* size of the blob */
+};
 
 /*
  * Optional counters a call adds to (DEVICE, caller zeroes them; may be NULL).
@@ -169,6 +200,20 @@ int pcg_groups_validate_host(int32_t V, int32_t G, const int32_t *row_ptr,
 int pcg_groups_canonicalize_host(int32_t V, int32_t G, const int32_t *row_ptr,
                                  const int32_t *members, int32_t *out_G, int64_t *out_nnz,
                                  int32_t *out_row_ptr, int32_t *out_members, int32_t *out_mult);
+
+/*
+ * Build the prepared form of a validated membership (all pointers HOST).  chunk_groups is the
+ * number of consecutive groups one workgroup handles: a multiple of 1024 in [1024, 16384], or
+ * 0 for the default (16384).  Smaller chunks spread a small batch over more compute units.
+ * pcg_groups_prepare_bytes returns the blob size (0 on bad arguments); pcg_groups_prepare_host
+ * fills `blob` (blob_bytes >= that size) and `info`.  The caller uploads the blob to the
+ * device (256-byte aligned) and points pcg_groups.prepared / prepared_info at it.
+ */
+size_t pcg_groups_prepare_bytes(int32_t V, int32_t G, const int32_t *row_ptr,
+                                const int32_t *members, int32_t chunk_groups);
+int pcg_groups_prepare_host(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members,
+                            int32_t chunk_groups, void *blob, size_t blob_bytes,
+                            pcg_prepared *info);
 
 /* ---- per-kernel timing (for the benchmark) ------------------------------------------------ */
 

@@ -4,12 +4,12 @@ Thin Python binding over ``libpcg.so`` (hand-written HIP for gfx950, C ABI in
 ``include/pcg.h``).  PyTorch supplies device memory and streams only; every
 step of the path runs in the library's kernels.
 """
-from .binding import (BF16, F32, Diag, Groups, PcgError, VerifyOutput, group_probs,
+from .binding import (BF16, F32, Diag, Groups, PcgError, PreparedInfo, VerifyOutput, group_probs,
                       group_probs_workspace_bytes, groups_canonicalize_host,
-                      groups_validate_host, lib, lib_path, profile_begin, profile_end, strerror,
+                      groups_prepare_host, groups_validate_host, lib, lib_path, profile_begin, profile_end, strerror,
                       verify, verify_workspace_bytes, version)
 
-__all__ = ["BF16", "F32", "Diag", "Groups", "PcgError", "VerifyOutput", "group_probs",
-           "group_probs_workspace_bytes", "groups_canonicalize_host", "groups_validate_host",
+__all__ = ["BF16", "F32", "Diag", "Groups", "PcgError", "PreparedInfo", "VerifyOutput", "group_probs",
+           "group_probs_workspace_bytes", "groups_canonicalize_host", "groups_prepare_host", "groups_validate_host",
            "lib", "lib_path", "profile_begin", "profile_end", "strerror", "verify",
            "verify_workspace_bytes", "version"]

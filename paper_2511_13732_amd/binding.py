@@ -24,9 +24,19 @@ def lib_path() -> str:
     return os.path.join(_HERE, "libpcg.so")
 
 
+class PreparedInfo(C.Structure):
+    """Mirror of pcg_prepared (host descriptor of the prepared membership blob)."""
+    _fields_ = [("V", C.c_int32), ("G", C.c_int32), ("ntiles", C.c_int32), ("tile_len", C.c_int32),
+                ("chunk_groups", C.c_int32), ("nchunks", C.c_int32),
+                ("slices_per_chunk", C.c_int32), ("reserved", C.c_int32),
+                ("off_desc", C.c_int64), ("off_perm", C.c_int64), ("off_data", C.c_int64),
+                ("bytes", C.c_int64)]
+
+
 class _GroupsStruct(C.Structure):
     _fields_ = [("V", C.c_int32), ("G", C.c_int32), ("nnz", C.c_int64),
-                ("row_ptr", C.c_void_p), ("members", C.c_void_p), ("mult", C.c_void_p)]
+                ("row_ptr", C.c_void_p), ("members", C.c_void_p), ("mult", C.c_void_p),
+                ("prepared", C.c_void_p), ("prepared_info", C.POINTER(PreparedInfo))]
 
 
 class Diag(C.Structure):
@@ -71,6 +81,11 @@ def lib() -> C.CDLL:
         L.pcg_groups_canonicalize_host.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                                    C.POINTER(C.c_int32), C.POINTER(C.c_int64),
                                                    C.c_void_p, C.c_void_p, C.c_void_p]
+        L.pcg_groups_prepare_bytes.restype = C.c_size_t
+        L.pcg_groups_prepare_bytes.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32]
+        L.pcg_groups_prepare_host.restype = C.c_int
+        L.pcg_groups_prepare_host.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32,
+                                              C.c_void_p, C.c_size_t, C.POINTER(PreparedInfo)]
         L.pcg_profile_begin.restype = C.c_int
         L.pcg_profile_begin.argtypes = [C.c_int32]
         L.pcg_profile_end.restype = C.c_int
@@ -126,29 +141,59 @@ def groups_canonicalize_host(V: int, row_ptr, members):
     return orp, omem[:onnz.value], omult
 
 
+def groups_prepare_host(V: int, row_ptr, members, chunk_groups: int = 0):
+    """(blob uint8 array, PreparedInfo) of a canonical host CSR; see pcg_groups_prepare_host."""
+    rp, mem = _np_i32(row_ptr), _np_i32(members)
+    G = len(rp) - 1
+    n = lib().pcg_groups_prepare_bytes(V, G, rp.ctypes.data, mem.ctypes.data, chunk_groups)
+    if n == 0:
+        raise PcgError(-2, "pcg_groups_prepare_bytes")
+    blob = np.zeros(n, dtype=np.uint8)
+    info = PreparedInfo()
+    _check(lib().pcg_groups_prepare_host(V, G, rp.ctypes.data, mem.ctypes.data, chunk_groups,
+                                         blob.ctypes.data, n, C.byref(info)), "prepare")
+    return blob, info
+
+
 class Groups:
-    """Group membership resident on a device (CSR group -> tokens + multiplicity)."""
+    """Group membership resident on a device (CSR group -> tokens + multiplicity, and
+    optionally the prepared layout the fast gather kernel reads)."""
 
     def __init__(self, V: int, row_ptr: torch.Tensor, members: torch.Tensor, mult: torch.Tensor,
-                 nnz: int):
+                 nnz: int, prepared: Optional[torch.Tensor] = None,
+                 prepared_info: Optional[PreparedInfo] = None):
         for t in (row_ptr, members, mult):
             assert t.dtype == torch.int32 and t.is_contiguous()
         self.V, self.G, self.nnz = int(V), int(row_ptr.numel() - 1), int(nnz)
         self.row_ptr, self.members, self.mult = row_ptr, members, mult
+        self.prepared, self.prepared_info = prepared, prepared_info
         self.device = row_ptr.device
 
     @classmethod
-    def from_csr(cls, V: int, row_ptr, members, device="cuda") -> "Groups":
-        """Canonicalise and validate a host CSR with the library, then upload it."""
+    def from_csr(cls, V: int, row_ptr, members, device="cuda", prepare: bool = True,
+                 chunk_groups: int = 0) -> "Groups":
+        """Canonicalise and validate a host CSR with the library, then upload it (with the
+        prepared layout unless prepare=False)."""
         rp, mem, mult = groups_canonicalize_host(V, row_ptr, members)
         _check(groups_validate_host(V, rp, mem, mult), "validate")
         dev = torch.device(device)
         up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
-        return cls(V, up(rp), up(mem if len(mem) else np.zeros(1, np.int32)), up(mult), len(mem))
+        blob_dev, info = None, None
+        if prepare:
+            blob, info = groups_prepare_host(V, rp, mem, chunk_groups)
+            blob_dev = up(blob)
+        return cls(V, up(rp), up(mem if len(mem) else np.zeros(1, np.int32)), up(mult), len(mem),
+                   blob_dev, info)
+
+    def without_prepared(self) -> "Groups":
+        """The same membership, read through the CSR by the generic kernel."""
+        return Groups(self.V, self.row_ptr, self.members, self.mult, self.nnz)
 
     def struct(self) -> _GroupsStruct:
         return _GroupsStruct(self.V, self.G, self.nnz, self.row_ptr.data_ptr(),
-                             self.members.data_ptr(), self.mult.data_ptr())
+                             self.members.data_ptr(), self.mult.data_ptr(),
+                             None if self.prepared is None else self.prepared.data_ptr(),
+                             None if self.prepared_info is None else C.pointer(self.prepared_info))
 
 
 # --------------------------------------------------------------------------- calls

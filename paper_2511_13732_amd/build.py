@@ -7,8 +7,8 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libpcg.so")
-SOURCES = ["pcg_kernels.hip", "pcg_api.cpp"]
-HEADERS = ["pcg_kernels.h", "pcg_device.h", os.path.join("..", "..", "include", "pcg.h")]
+SOURCES = ["pcg_kernels.hip", "pcg_api.cpp", "pcg_prepare.cpp"]
+HEADERS = ["pcg_kernels.h", "pcg_device.h", "pcg_layout.h", os.path.join("..", "..", "include", "pcg.h")]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

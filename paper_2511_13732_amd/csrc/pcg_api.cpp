@@ -7,6 +7,7 @@
 #include <vector>
 
 #include "pcg_kernels.h"
+#include "pcg_layout.h"
 
 namespace {
 
@@ -59,6 +60,17 @@ int check_groups(const pcg_groups *g) {
   if (!g->row_ptr || !g->mult) return PCG_ERR_NULL_ARG;
   if (g->V < 1 || g->G < 1 || g->nnz < 0 || g->nnz > INT32_MAX) return PCG_ERR_BAD_SHAPE;
   if (g->nnz > 0 && !g->members) return PCG_ERR_NULL_ARG;
+  if ((g->prepared == nullptr) != (g->prepared_info == nullptr)) return PCG_ERR_NULL_ARG;
+  if (g->prepared) {
+    const pcg_prepared &p = *g->prepared_info;
+    if (p.V != g->V || p.G != g->G || p.ntiles < 1 || p.tile_len < 1 || p.tile_len >= kTileMax ||
+        (int64_t) p.ntiles * p.tile_len < g->V || p.chunk_groups < kGatherThreads ||
+        p.chunk_groups > kMaxChunkGroups || p.chunk_groups % kGatherThreads ||
+        p.slices_per_chunk != p.chunk_groups / 64 ||
+        p.nchunks != (g->G + p.chunk_groups - 1) / p.chunk_groups)
+      return PCG_ERR_BAD_SHAPE;
+    if ((uintptr_t) g->prepared % 256) return PCG_ERR_MISALIGNED;
+  }
   return PCG_OK;
 }
 
@@ -102,7 +114,8 @@ size_t pcg_verify_workspace_bytes(int32_t V, int32_t G, int32_t B, int32_t K) {
   if (V < 1 || G < 1 || B < 0 || K < 1) return 0;
   const size_t rows = (size_t) B * (2 * (size_t) K + 1);
   return align_up(rows * stats_nparts(V) * sizeof(StatPart)) + align_up(rows * sizeof(RowStat)) +
-         align_up((size_t) B * V * sizeof(float)) + align_up((size_t) B * G * sizeof(float)) + kAlign;
+         align_up((size_t) B * V * sizeof(float)) + align_up((size_t) B * G * sizeof(float)) +
+         align_up((size_t) B * ((G + kGatherThreads - 1) / kGatherThreads) * sizeof(double)) + kAlign;
 }
 
 int pcg_group_probs(const pcg_groups *groups, const void *logits, pcg_dtype dt, int64_t rows,
@@ -138,6 +151,7 @@ int pcg_group_probs(const pcg_groups *groups, const void *logits, pcg_dtype dt, 
   rs.npos0 = 1;
   rs.npos1 = 1;
   rs.nrows0 = rows;
+  rs.inv_npos0 = rs.inv_npos1 = 1.0;
   const Factors f = factors(temperature);
 
   StageTimer tm(stream);
@@ -154,8 +168,10 @@ int pcg_group_probs(const pcg_groups *groups, const void *logits, pcg_dtype dt, 
         hipSuccess)
       return hip_fail(e);
     if (r0 == 0) { tm.end(kStageTable); tm.begin(kStageGather); }
-    if ((e = launch_gather(*groups, n, false, table, out + r0 * groups->G, stream)) != hipSuccess)
-      return hip_fail(e);
+    e = groups->prepared
+            ? launch_gather_prepared(*groups, n, table, out + r0 * groups->G, nullptr, stream)
+            : launch_gather(*groups, n, false, table, out + r0 * groups->G, stream);
+    if (e != hipSuccess) return hip_fail(e);
     if (r0 == 0) tm.end(kStageGather);
   }
   return PCG_OK;
@@ -202,6 +218,8 @@ int pcg_verify(const pcg_groups *groups, const void *target_logits, const void *
   float *table = (float *) ws;
   ws += align_up((size_t) B * V * sizeof(float));
   float *R = (float *) ws;
+  ws += align_up((size_t) B * groups->G * sizeof(float));
+  double *csum = (double *) ws;
 
   RowSet rs;
   rs.base0 = target_logits;
@@ -213,6 +231,8 @@ int pcg_verify(const pcg_groups *groups, const void *target_logits, const void *
   rs.npos0 = K + 1;
   rs.npos1 = K;
   rs.nrows0 = (int64_t) B * (K + 1);
+  rs.inv_npos0 = 1.0 / (K + 1);
+  rs.inv_npos1 = 1.0 / K;
   const Factors f = factors(temperature);
 
   StageTimer tm(stream);
@@ -232,11 +252,16 @@ int pcg_verify(const pcg_groups *groups, const void *target_logits, const void *
     return hip_fail(e);
   tm.end(kStageTable);
   tm.begin(kStageGather);
-  if ((e = launch_gather(*groups, B, true, table, R, stream)) != hipSuccess) return hip_fail(e);
+  const bool prepared = groups->prepared != nullptr;
+  e = prepared ? launch_gather_prepared(*groups, B, table, R, csum, stream)
+               : launch_gather(*groups, B, true, table, R, stream);
+  if (e != hipSuccess) return hip_fail(e);
   tm.end(kStageGather);
   tm.begin(kStageFinalize);
   if ((e = launch_finalize(rs, bf16, *groups, B, K, f.cd, rowstat, seed, offset, accept_len, R,
-                           out_tokens, out_groups, diag, stream)) != hipSuccess)
+                           prepared ? csum : nullptr, prepared ? groups->prepared_info->nchunks : 1,
+                           prepared ? groups->prepared_info->chunk_groups : groups->G, out_tokens,
+                           out_groups, diag, stream)) != hipSuccess)
     return hip_fail(e);
   tm.end(kStageFinalize);
   return PCG_OK;

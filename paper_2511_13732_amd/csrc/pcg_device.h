@@ -34,15 +34,29 @@ struct RowSet {
   int64_t bs0, ps0, bs1, ps1;   // strides in elements
   int32_t npos0, npos1;
   int64_t nrows0;               // B * npos0
+  double inv_npos0, inv_npos1;  // 1 / npos, so that kernels split a row id without dividing
 };
 
+// row / npos and row % npos for 0 <= row < 2^40, 1 <= npos <= 65: a multiplication by the
+// reciprocal and one correction step instead of a 64-bit integer division.
+__device__ __forceinline__ void split_row(int64_t row, int32_t npos, double inv_npos, int64_t &b,
+                                          int32_t &i) {
+  int64_t q = (int64_t) ((double) row * inv_npos);
+  int64_t r = row - q * npos;
+  if (r < 0) { --q; r += npos; }
+  if (r >= npos) { ++q; r -= npos; }
+  b = q;
+  i = (int32_t) r;
+}
+
 __device__ __forceinline__ const void *row_base(const RowSet &rs, int64_t row, bool bf16) {
+  int64_t b;
+  int32_t i;
   if (row < rs.nrows0) {
-    int64_t b = row / rs.npos0, i = row - b * rs.npos0;
+    split_row(row, rs.npos0, rs.inv_npos0, b, i);
     return elem_ptr(rs.base0, b * rs.bs0 + i * rs.ps0, bf16);
   }
-  row -= rs.nrows0;
-  int64_t b = row / rs.npos1, i = row - b * rs.npos1;
+  split_row(row - rs.nrows0, rs.npos1, rs.inv_npos1, b, i);
   return elem_ptr(rs.base1, b * rs.bs1 + i * rs.ps1, bf16);
 }
 

@@ -32,9 +32,13 @@ hipError_t launch_weights(const RowSet &rs, bool bf16, const pcg_groups &g, int6
 hipError_t launch_gather(const pcg_groups &g, int32_t nrows, bool clamp, const float *table,
                          float *out, hipStream_t stream);
 
+hipError_t launch_gather_prepared(const pcg_groups &g, int32_t nrows, const float *table, float *out,
+                                  double *csum, hipStream_t stream);
+
 hipError_t launch_finalize(const RowSet &rs, bool bf16, const pcg_groups &g, int32_t B, int32_t K,
                            double cd, const RowStat *rowstat, uint64_t seed, uint64_t offset,
-                           const int32_t *accept_len, float *R, int32_t *out_tokens,
-                           int32_t *out_groups, pcg_diag *diag, hipStream_t stream);
+                           const int32_t *accept_len, float *R, const double *csum, int32_t nchunks,
+                           int32_t chunk_groups, int32_t *out_tokens, int32_t *out_groups,
+                           pcg_diag *diag, hipStream_t stream);
 
 }  // namespace pcg

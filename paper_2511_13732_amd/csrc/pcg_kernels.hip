@@ -11,8 +11,11 @@
 //   finalize   per sequence: inverse CDF over R for the group, then Eq. (10) for the token
 // pcg_group_probs runs row_stats, a weights kernel (q(t) / N(t)) and the same gather.
 #include "pcg_kernels.h"
+#include "pcg_layout.h"
 
 #include <math.h>
+
+#include <algorithm>
 
 namespace pcg {
 
@@ -23,55 +26,52 @@ namespace pcg {
 constexpr int kPartElems = 2048;      // elements per wave: 32 per lane
 constexpr int kStatsWaves = 4;        // waves per workgroup
 
+// Row id of a workgroup: grid.y carries the low part, grid.z the rest (grid.y <= 65535).
+constexpr int kRowsPerGridY = 32768;
+
 template <bool BF16, bool VEC>
 __global__ __launch_bounds__(kStatsWaves *kWave) void row_stats_kernel(RowSet rs, int32_t V,
-                                                                       int32_t nparts,
-                                                                       int64_t total_parts,
+                                                                       int32_t nparts, int64_t nrows,
                                                                        float c, StatPart *parts) {
   const int lane = threadIdx.x & (kWave - 1);
-  const int64_t p = (int64_t) blockIdx.x * kStatsWaves + (threadIdx.x >> 6);
-  if (p >= total_parts) return;   // whole wave leaves together
-  const int64_t row = p / nparts;
-  const int32_t part = (int32_t)(p - row * nparts);
+  // everything that selects the data is wave-uniform: keep it in scalar registers
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int32_t part = blockIdx.x * kStatsWaves + wave;
+  const int64_t row = (int64_t) blockIdx.z * kRowsPerGridY + blockIdx.y;
+  if (part >= nparts || row >= nrows) return;   // whole wave leaves together
   const void *rowp = row_base(rs, row, BF16);
   const int32_t e0 = part * kPartElems;
 
   float x[32];
-  if constexpr (VEC) {
+  if (VEC && e0 + kPartElems <= V) {
+    // interior part of an aligned row: 16-byte loads, all issued before the first use;
+    // each load instruction covers 1 KiB of the row
     if constexpr (BF16) {
-      // 4 loads of 16 bytes per lane; each load instruction covers 1 KiB of the row
+      const uint4 *src = reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(rowp) + e0);
+      uint4 w[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) w[j] = src[j * kWave + lane];
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        const int32_t e = e0 + (j * kWave + lane) * 8;
-        if (e + 8 <= V) {
-          uint4 w = *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(rowp) + e);
-          const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+        const uint32_t ww[4] = {w[j].x, w[j].y, w[j].z, w[j].w};
 #pragma unroll
-          for (int k = 0; k < 4; ++k) {
-            x[j * 8 + 2 * k] = __uint_as_float(ww[k] << 16);
-            x[j * 8 + 2 * k + 1] = __uint_as_float(ww[k] & 0xffff0000u);
-          }
-        } else {
-#pragma unroll
-          for (int k = 0; k < 8; ++k)
-            x[j * 8 + k] = (e + k < V) ? logit_at<true>(rowp, e + k) : -INFINITY;
+        for (int k = 0; k < 4; ++k) {
+          x[j * 8 + 2 * k] = __uint_as_float(ww[k] << 16);
+          x[j * 8 + 2 * k + 1] = __uint_as_float(ww[k] & 0xffff0000u);
         }
       }
     } else {
+      const float4 *src = reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(rowp) + e0);
+      float4 w[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) w[j] = src[j * kWave + lane];
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
-        const int32_t e = e0 + (j * kWave + lane) * 4;
-        if (e + 4 <= V) {
-          float4 w = *reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(rowp) + e);
-          x[j * 4] = w.x; x[j * 4 + 1] = w.y; x[j * 4 + 2] = w.z; x[j * 4 + 3] = w.w;
-        } else {
-#pragma unroll
-          for (int k = 0; k < 4; ++k)
-            x[j * 4 + k] = (e + k < V) ? logit_at<false>(rowp, e + k) : -INFINITY;
-        }
+        x[j * 4] = w[j].x; x[j * 4 + 1] = w[j].y; x[j * 4 + 2] = w[j].z; x[j * 4 + 3] = w[j].w;
       }
     }
   } else {
+    // the ragged last part of a row, or rows that are not 16-byte aligned: element loads
 #pragma unroll
     for (int j = 0; j < 32; ++j) {
       const int32_t e = e0 + j * kWave + lane;
@@ -79,10 +79,13 @@ __global__ __launch_bounds__(kStatsWaves *kWave) void row_stats_kernel(RowSet rs
     }
   }
 
-  float m = x[0];
+  float m0 = fmaxf(x[0], x[1]), m1 = fmaxf(x[2], x[3]);
 #pragma unroll
-  for (int j = 1; j < 32; ++j) m = fmaxf(m, x[j]);
-  m = wave_max(m);
+  for (int j = 4; j < 32; j += 4) {
+    m0 = fmaxf(fmaxf(m0, x[j]), x[j + 1]);
+    m1 = fmaxf(fmaxf(m1, x[j + 2]), x[j + 3]);
+  }
+  const float m = wave_max(fmaxf(m0, m1));
 
   // exponentials relative to the wave's own maximum: (x - m) is exact for bf16 inputs, so
   // the dominant terms carry no argument error
@@ -102,7 +105,7 @@ __global__ __launch_bounds__(kStatsWaves *kWave) void row_stats_kernel(RowSet rs
     sp.z = z;
     sp.m = m;
     sp.pad = 0.f;
-    parts[p] = sp;
+    parts[row * nparts + part] = sp;
   }
 }
 
@@ -299,8 +302,6 @@ __global__ __launch_bounds__(kTableThreads) void weights_kernel(
 // gather: out[r][g] = sum over members t of G_g of table[r][t], table row staged in LDS.
 // =============================================================================================
 
-constexpr int kGatherThreads = 1024;
-constexpr int kTileMax = 40704;       // floats of LDS per workgroup (159 KiB of the 160 KiB)
 
 // Workgroup id -> (row, chunk).  Workgroups are dealt to the 8 XCDs round-robin by id, so all
 // chunks of one row are given ids that are equal mod 8: they then share that XCD's L2 for the
@@ -351,6 +352,101 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// The same sum read from the prepared layout (pcg_prepared): one group per lane, 16-bit
+// tile-local slots, no cross-lane reduction and no address arithmetic beyond a shift.
+// A workgroup owns one chunk of consecutive groups of one table row.  Lane l of wave w handles,
+// in round j, the group that slice j*16 + w puts on lane l -- the same group in every tile pass,
+// so its running sum stays in a register.  Results are put back into group order through LDS
+// and leave with coalesced stores; with CSUM the workgroup also writes the chunk's total of
+// max(0, .) in double, summed in a fixed order.
+// ---------------------------------------------------------------------------------------------
+
+template <bool CSUM>
+__global__ __launch_bounds__(kGatherThreads) void gather_prepared_kernel(
+    int32_t V, int32_t G, int32_t nrows, int32_t nchunks, int32_t chunk_groups, int32_t ntiles,
+    int32_t tile_len, int32_t spc, const uint32_t *desc, const uint16_t *perm,
+    const uint32_t *data, const float *table, float *out, double *csum) {
+  __shared__ float tab[kTileMax];
+  __shared__ double wsum[kGatherThreads / kWave];
+  const int xcd = blockIdx.x & 7;
+  const int y = blockIdx.x >> 3;
+  const int r = xcd + 8 * (y / nchunks);
+  const int chunk = y % nchunks;
+  if (r >= nrows) return;   // whole workgroup leaves together, before any barrier
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int32_t g0 = chunk * chunk_groups;
+  const int32_t ng = min(chunk_groups, G - g0);
+  const float *src = table + (int64_t) r * V;
+
+  float acc[kMaxRounds];
+#pragma unroll
+  for (int j = 0; j < kMaxRounds; ++j) acc[j] = 0.f;
+
+  for (int h = 0; h < ntiles; ++h) {
+    const int32_t t0 = h * tile_len;
+    const int32_t tl = min(tile_len, V - t0);
+    if (h > 0) __syncthreads();                       // everyone is done reading the old tile
+    for (int32_t k = threadIdx.x; k < tl; k += kGatherThreads) tab[k] = src[t0 + k];
+    if (threadIdx.x == 0) tab[tile_len] = 0.f;        // the padding slot
+    __syncthreads();
+    const uint32_t *dsc = desc + ((size_t) (chunk * ntiles + h) * spc) * 2;
+#pragma unroll
+    for (int j = 0; j < kMaxRounds; ++j) {
+      const int s = j * (kGatherThreads / kWave) + wave;
+      if (s < spc) {                                  // uniform over the wave
+        const uint32_t off = dsc[2 * s], n = dsc[2 * s + 1] >> 1;
+        const uint32_t *d = data + off + lane;
+        float a0 = 0.f, a1 = 0.f;
+        uint32_t k = 0;
+        for (; k + 4 <= n; k += 4) {
+          const uint32_t w0 = d[(size_t) k * kWave], w1 = d[(size_t) (k + 1) * kWave];
+          const uint32_t w2 = d[(size_t) (k + 2) * kWave], w3 = d[(size_t) (k + 3) * kWave];
+          a0 += tab[w0 & 0xffffu]; a1 += tab[w0 >> 16];
+          a0 += tab[w1 & 0xffffu]; a1 += tab[w1 >> 16];
+          a0 += tab[w2 & 0xffffu]; a1 += tab[w2 >> 16];
+          a0 += tab[w3 & 0xffffu]; a1 += tab[w3 >> 16];
+        }
+        for (; k < n; ++k) {
+          const uint32_t w0 = d[(size_t) k * kWave];
+          a0 += tab[w0 & 0xffffu]; a1 += tab[w0 >> 16];
+        }
+        acc[j] += a0 + a1;
+      }
+    }
+  }
+
+  // back into group order through LDS, then coalesced stores
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < kMaxRounds; ++j) {
+    const int s = j * (kGatherThreads / kWave) + wave;
+    if (s < spc) {
+      const uint16_t k = perm[((size_t) chunk * spc + s) * kWave + lane];
+      if (k != 0xFFFFu) tab[k] = acc[j];
+    }
+  }
+  __syncthreads();
+  float *dst = out + (int64_t) r * G + g0;
+  double part = 0.0;
+  for (int32_t i = threadIdx.x; i < ng; i += kGatherThreads) {
+    const float v = tab[i];
+    dst[i] = v;
+    if (CSUM) part += (double) fmaxf(v, 0.f);
+  }
+  if constexpr (CSUM) {
+    part = subwave_sum<64>(part);
+    if (lane == kWave - 1) wsum[wave] = part;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      double t = 0.0;
+      for (int w = 0; w < kGatherThreads / kWave; ++w) t += wsum[w];
+      csum[(int64_t) r * nchunks + chunk] = t;
+    }
+  }
+}
+
 // =============================================================================================
 // finalize: group from the residual by inverse CDF, then the token inside it (Eq. 10).
 // =============================================================================================
@@ -364,8 +460,10 @@ struct CdfPick {
 
 // Inverse CDF over f(0..n-1) >= 0 by the whole workgroup.  Each thread owns a contiguous run,
 // so the running sum is the ascending one up to fp64 rounding.  All threads get the result.
+// With have_goal the threshold is `goal` (already relative to this range) instead of u * total.
 template <typename F>
-__device__ CdfPick block_inverse_cdf(int32_t n, F f, double u) {
+__device__ CdfPick block_inverse_cdf(int32_t n, F f, double u, bool have_goal = false,
+                                     double goal_in = 0.0) {
   __shared__ double wave_tot[kFinalThreads / kWave];
   __shared__ int first_thread, last_pos;
   __shared__ CdfPick res;
@@ -394,7 +492,7 @@ __device__ CdfPick block_inverse_cdf(int32_t n, F f, double u) {
     total += wave_tot[w];
   }
   const double excl = before + (inc - mine);
-  const double goal = u * total;
+  const double goal = have_goal ? goal_in : u * total;
   if (mine > 0.0 && excl + mine > goal) atomicMin(&first_thread, tid);
   if (my_last >= 0) atomicMax(&last_pos, my_last);
   __syncthreads();
@@ -428,12 +526,15 @@ __device__ __forceinline__ bool near_edge(const CdfPick &p, double u) {
   return near_lo || near_hi;
 }
 
+// R holds the gathered sums T[g] - D[g] (T[g] on a bonus row), clamped here on read.  With
+// csum != NULL it also has the totals of max(0, R) over chunks of chunk_groups consecutive
+// groups, so only the chunk that holds the draw is scanned.
 template <bool BF16>
 __global__ __launch_bounds__(kFinalThreads) void finalize_kernel(
     RowSet rs, int32_t V, int32_t G, int32_t K, double cd, const RowStat *rowstat,
     const int32_t *row_ptr, const int32_t *members, const int32_t *mult, uint64_t seed,
-    uint64_t offset, const int32_t *accept_len, float *R, int32_t *out_tokens,
-    int32_t *out_groups, pcg_diag *diag) {
+    uint64_t offset, const int32_t *accept_len, float *R, const double *csum, int32_t nchunks,
+    int32_t chunk_groups, int32_t *out_tokens, int32_t *out_groups, pcg_diag *diag) {
   const int b = blockIdx.x;
   const int32_t istar = accept_len[b];
   const int64_t trow_id = (int64_t) b * (K + 1) + istar;
@@ -447,9 +548,37 @@ __global__ __launch_bounds__(kFinalThreads) void finalize_kernel(
     return exp2((double) (logit_at<BF16>(trow, t) - st.M) * cd) / (st.Z * (double) mult[t]);
   };
 
-  CdfPick pg = block_inverse_cdf(G, [&](int32_t g) { return (double) Rb[g]; }, (double) u.grp);
+  CdfPick pg;
+  if (csum) {
+    // residual total and the chunk that holds u * total, from the per-chunk sums (ascending)
+    const double *cs = csum + (int64_t) b * nchunks;
+    double S = 0.0;
+    for (int32_t c = 0; c < nchunks; ++c) S += cs[c];
+    const double goal = (double) u.grp * S;
+    double cum = 0.0, base = 0.0;
+    int32_t cstar = -1;
+    for (int32_t c = 0; c < nchunks; ++c) {
+      const double v = cs[c];
+      if (!(v > 0.0)) continue;
+      cstar = c;
+      base = cum;
+      if (cum + v > goal) break;
+      cum += v;
+    }
+    pg.index = -1; pg.total = S; pg.lo = pg.hi = 0.0;
+    if (S > 0.0 && cstar >= 0) {
+      const int32_t g0 = cstar * chunk_groups, ng = min(chunk_groups, G - g0);
+      CdfPick in = block_inverse_cdf(ng, [&](int32_t k) { return (double) fmaxf(Rb[g0 + k], 0.f); },
+                                     0.0, true, goal - base);
+      if (in.index >= 0) {
+        pg.index = g0 + in.index; pg.lo = base + in.lo; pg.hi = base + in.hi;
+      }
+    }
+  } else {
+    pg = block_inverse_cdf(G, [&](int32_t g) { return (double) fmaxf(Rb[g], 0.f); }, (double) u.grp);
+  }
   bool fallback = false;
-  if (!(pg.total > 0.0)) {
+  if (!(pg.total > 0.0) || pg.index < 0) {
     // Residual total <= 0 (cannot happen in exact arithmetic): draw from T of this row instead.
     fallback = true;
     for (int32_t g = threadIdx.x; g < G; g += kFinalThreads) {
@@ -493,16 +622,17 @@ int32_t stats_nparts(int32_t V) { return (V + kPartElems - 1) / kPartElems; }
 hipError_t launch_row_stats(const RowSet &rs, bool bf16, int32_t V, int64_t nrows, float c,
                             StatPart *parts, hipStream_t stream) {
   const int32_t nparts = stats_nparts(V);
-  const int64_t total = nrows * nparts;
-  if (total == 0) return hipSuccess;
-  const dim3 grid((unsigned) ((total + kStatsWaves - 1) / kStatsWaves)), block(kStatsWaves * kWave);
+  if (nrows == 0) return hipSuccess;
+  const unsigned gy = (unsigned) std::min<int64_t>(nrows, kRowsPerGridY);
+  const unsigned gz = (unsigned) ((nrows + kRowsPerGridY - 1) / kRowsPerGridY);
+  const dim3 grid((nparts + kStatsWaves - 1) / kStatsWaves, gy, gz), block(kStatsWaves * kWave);
   const bool vec = rows_vector_aligned(rs, bf16);
   if (bf16) {
-    if (vec) row_stats_kernel<true, true><<<grid, block, 0, stream>>>(rs, V, nparts, total, c, parts);
-    else row_stats_kernel<true, false><<<grid, block, 0, stream>>>(rs, V, nparts, total, c, parts);
+    if (vec) row_stats_kernel<true, true><<<grid, block, 0, stream>>>(rs, V, nparts, nrows, c, parts);
+    else row_stats_kernel<true, false><<<grid, block, 0, stream>>>(rs, V, nparts, nrows, c, parts);
   } else {
-    if (vec) row_stats_kernel<false, true><<<grid, block, 0, stream>>>(rs, V, nparts, total, c, parts);
-    else row_stats_kernel<false, false><<<grid, block, 0, stream>>>(rs, V, nparts, total, c, parts);
+    if (vec) row_stats_kernel<false, true><<<grid, block, 0, stream>>>(rs, V, nparts, nrows, c, parts);
+    else row_stats_kernel<false, false><<<grid, block, 0, stream>>>(rs, V, nparts, nrows, c, parts);
   }
   return hipGetLastError();
 }
@@ -598,18 +728,40 @@ hipError_t launch_gather(const pcg_groups &g, int32_t nrows, bool clamp, const f
   return hipGetLastError();
 }
 
+hipError_t launch_gather_prepared(const pcg_groups &g, int32_t nrows, const float *table, float *out,
+                                  double *csum, hipStream_t stream) {
+  if (nrows == 0) return hipSuccess;
+  const pcg_prepared &p = *g.prepared_info;
+  const char *blob = reinterpret_cast<const char *>(g.prepared);
+  const uint32_t *desc = reinterpret_cast<const uint32_t *>(blob + p.off_desc);
+  const uint16_t *perm = reinterpret_cast<const uint16_t *>(blob + p.off_perm);
+  const uint32_t *data = reinterpret_cast<const uint32_t *>(blob + p.off_data);
+  const int32_t rows8 = (nrows + 7) / 8;
+  const dim3 grid((unsigned) (8 * rows8 * p.nchunks));
+  if (csum)
+    gather_prepared_kernel<true><<<grid, kGatherThreads, 0, stream>>>(
+        g.V, g.G, nrows, p.nchunks, p.chunk_groups, p.ntiles, p.tile_len, p.slices_per_chunk, desc,
+        perm, data, table, out, csum);
+  else
+    gather_prepared_kernel<false><<<grid, kGatherThreads, 0, stream>>>(
+        g.V, g.G, nrows, p.nchunks, p.chunk_groups, p.ntiles, p.tile_len, p.slices_per_chunk, desc,
+        perm, data, table, out, nullptr);
+  return hipGetLastError();
+}
+
 hipError_t launch_finalize(const RowSet &rs, bool bf16, const pcg_groups &g, int32_t B, int32_t K,
                            double cd, const RowStat *rowstat, uint64_t seed, uint64_t offset,
-                           const int32_t *accept_len, float *R, int32_t *out_tokens,
-                           int32_t *out_groups, pcg_diag *diag, hipStream_t stream) {
+                           const int32_t *accept_len, float *R, const double *csum, int32_t nchunks,
+                           int32_t chunk_groups, int32_t *out_tokens, int32_t *out_groups,
+                           pcg_diag *diag, hipStream_t stream) {
   if (bf16)
-    finalize_kernel<true><<<B, kFinalThreads, 0, stream>>>(rs, g.V, g.G, K, cd, rowstat, g.row_ptr,
-                                                           g.members, g.mult, seed, offset,
-                                                           accept_len, R, out_tokens, out_groups, diag);
+    finalize_kernel<true><<<B, kFinalThreads, 0, stream>>>(
+        rs, g.V, g.G, K, cd, rowstat, g.row_ptr, g.members, g.mult, seed, offset, accept_len, R,
+        csum, nchunks, chunk_groups, out_tokens, out_groups, diag);
   else
-    finalize_kernel<false><<<B, kFinalThreads, 0, stream>>>(rs, g.V, g.G, K, cd, rowstat, g.row_ptr,
-                                                            g.members, g.mult, seed, offset,
-                                                            accept_len, R, out_tokens, out_groups, diag);
+    finalize_kernel<false><<<B, kFinalThreads, 0, stream>>>(
+        rs, g.V, g.G, K, cd, rowstat, g.row_ptr, g.members, g.mult, seed, offset, accept_len, R,
+        csum, nchunks, chunk_groups, out_tokens, out_groups, diag);
   return hipGetLastError();
 }
 

@@ -1,0 +1,156 @@
+// Host-side construction of the prepared membership layout (see pcg_prepared in pcg.h).
+#include <algorithm>
+#include <cstring>
+#include <numeric>
+#include <vector>
+
+#include "../../include/pcg.h"
+#include "pcg_layout.h"
+
+namespace {
+
+using namespace pcg;
+
+struct Shape {
+  int32_t ntiles, tile_len, chunk_groups, nchunks, slices_per_chunk;
+};
+
+bool make_shape(int32_t V, int32_t G, int32_t chunk_groups, Shape &s) {
+  if (V < 1 || G < 1) return false;
+  if (chunk_groups == 0) chunk_groups = kMaxChunkGroups;
+  if (chunk_groups < kGatherThreads || chunk_groups > kMaxChunkGroups ||
+      chunk_groups % kGatherThreads)
+    return false;
+  // one slot of every tile is kept for the padding entry, which must read as zero
+  s.ntiles = (V + (kTileMax - 1) - 1) / (kTileMax - 1);
+  s.tile_len = (V + s.ntiles - 1) / s.ntiles;
+  s.tile_len = std::min(kTileMax - 1, (s.tile_len + 63) / 64 * 64);
+  s.chunk_groups = chunk_groups;
+  s.nchunks = (G + chunk_groups - 1) / chunk_groups;
+  s.slices_per_chunk = chunk_groups / 64;
+  return true;
+}
+
+// Builds the layout; with blob == nullptr only sizes are computed.
+int build(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members,
+          int32_t chunk_groups, uint8_t *blob, size_t blob_bytes, pcg_prepared *info) {
+  Shape sh;
+  if (!make_shape(V, G, chunk_groups, sh)) return PCG_ERR_BAD_SHAPE;
+  if (row_ptr[0] != 0) return PCG_ERR_BAD_CSR;
+  for (int32_t g = 0; g < G; ++g)
+    if (row_ptr[g + 1] < row_ptr[g]) return PCG_ERR_BAD_CSR;
+  for (int32_t j = 0, n = row_ptr[G]; j < n; ++j)
+    if ((uint32_t) members[j] >= (uint32_t) V) return PCG_ERR_BAD_CSR;
+
+  const int32_t T = sh.ntiles, SPC = sh.slices_per_chunk;
+  const size_t n_desc = (size_t) sh.nchunks * T * SPC;
+  const size_t desc_bytes = (n_desc * 2 * sizeof(uint32_t) + 255) / 256 * 256;
+  const size_t perm_bytes = ((size_t) sh.nchunks * SPC * 64 * sizeof(uint16_t) + 255) / 256 * 256;
+
+  std::vector<uint32_t> desc(n_desc * 2, 0);
+  std::vector<uint16_t> perm((size_t) sh.nchunks * SPC * 64, 0xFFFF);
+  std::vector<int32_t> cnt;          // [group in chunk][tile]
+  std::vector<int32_t> order;
+  uint64_t dwords = 0;
+
+  // pass 1: order groups, size the slices
+  for (int32_t c = 0; c < sh.nchunks; ++c) {
+    const int32_t g0 = c * sh.chunk_groups, ng = std::min(sh.chunk_groups, G - g0);
+    cnt.assign((size_t) ng * T, 0);
+    for (int32_t k = 0; k < ng; ++k)
+      for (int32_t j = row_ptr[g0 + k]; j < row_ptr[g0 + k + 1]; ++j)
+        ++cnt[(size_t) k * T + members[j] / sh.tile_len];
+    order.resize(ng);
+    std::iota(order.begin(), order.end(), 0);
+    // longest lists first, tile by tile; ties by group id so that the layout is unique
+    std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) {
+      for (int32_t h = 0; h < T; ++h) {
+        const int32_t ca = cnt[(size_t) a * T + h], cb = cnt[(size_t) b * T + h];
+        if (ca != cb) return ca > cb;
+      }
+      return false;
+    });
+    for (int32_t k = 0; k < ng; ++k)
+      perm[((size_t) c * SPC + k / 64) * 64 + k % 64] = (uint16_t) order[k];
+    for (int32_t s = 0; s < SPC; ++s) {
+      for (int32_t h = 0; h < T; ++h) {
+        int32_t longest = 0;
+        for (int32_t l = 0; l < 64 && s * 64 + l < ng; ++l)
+          longest = std::max(longest, cnt[(size_t) order[s * 64 + l] * T + h]);
+        longest = (longest + 1) / 2 * 2;                      // two slots per dword
+        uint32_t *d = &desc[(((size_t) c * T + h) * SPC + s) * 2];
+        if (dwords > 0xFFFFFFFFull) return PCG_ERR_BAD_SHAPE;
+        d[0] = (uint32_t) dwords;
+        d[1] = (uint32_t) longest;
+        dwords += (uint64_t) (longest / 2) * 64;
+      }
+    }
+  }
+  if (dwords > 0xFFFFFFFFull) return PCG_ERR_BAD_SHAPE;
+  const size_t data_bytes = ((size_t) dwords * sizeof(uint32_t) + 255) / 256 * 256 + 256;
+  const size_t total = desc_bytes + perm_bytes + data_bytes;
+  if (info) {
+    info->V = V; info->G = G;
+    info->ntiles = T; info->tile_len = sh.tile_len;
+    info->chunk_groups = sh.chunk_groups; info->nchunks = sh.nchunks;
+    info->slices_per_chunk = SPC; info->reserved = 0;
+    info->off_desc = 0;
+    info->off_perm = (int64_t) desc_bytes;
+    info->off_data = (int64_t) (desc_bytes + perm_bytes);
+    info->bytes = (int64_t) total;
+  }
+  if (!blob) return PCG_OK;
+  if (blob_bytes < total) return PCG_ERR_WORKSPACE_TOO_SMALL;
+
+  // pass 2: emit
+  std::memset(blob, 0, total);
+  std::memcpy(blob, desc.data(), desc.size() * sizeof(uint32_t));
+  std::memcpy(blob + desc_bytes, perm.data(), perm.size() * sizeof(uint16_t));
+  uint32_t *data = reinterpret_cast<uint32_t *>(blob + desc_bytes + perm_bytes);
+  const uint16_t pad_slot = (uint16_t) sh.tile_len;           // table[tile_len] is kept at zero
+  std::vector<uint16_t> slots;
+  for (int32_t c = 0; c < sh.nchunks; ++c) {
+    const int32_t g0 = c * sh.chunk_groups;
+    for (int32_t s = 0; s < SPC; ++s) {
+      for (int32_t h = 0; h < T; ++h) {
+        const uint32_t *d = &desc[(((size_t) c * T + h) * SPC + s) * 2];
+        const uint32_t off = d[0], len = d[1];
+        if (len == 0) continue;
+        for (int32_t l = 0; l < 64; ++l) {
+          slots.assign(len, pad_slot);
+          const uint16_t k = perm[((size_t) c * SPC + s) * 64 + l];
+          if (k != 0xFFFF) {
+            uint32_t n = 0;
+            for (int32_t j = row_ptr[g0 + k]; j < row_ptr[g0 + k + 1]; ++j)
+              if (members[j] / sh.tile_len == h) slots[n++] = (uint16_t) (members[j] - h * sh.tile_len);
+          }
+          for (uint32_t q = 0; q < len / 2; ++q)
+            data[off + (size_t) q * 64 + l] = (uint32_t) slots[2 * q] | ((uint32_t) slots[2 * q + 1] << 16);
+        }
+      }
+    }
+  }
+  return PCG_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t pcg_groups_prepare_bytes(int32_t V, int32_t G, const int32_t *row_ptr,
+                                const int32_t *members, int32_t chunk_groups) {
+  if (!row_ptr || (G > 0 && row_ptr[G] > 0 && !members)) return 0;
+  pcg_prepared info;
+  if (build(V, G, row_ptr, members, chunk_groups, nullptr, 0, &info) != PCG_OK) return 0;
+  return (size_t) info.bytes;
+}
+
+int pcg_groups_prepare_host(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members,
+                            int32_t chunk_groups, void *blob, size_t blob_bytes,
+                            pcg_prepared *info) {
+  if (!row_ptr || !blob || !info) return PCG_ERR_NULL_ARG;
+  if (G > 0 && row_ptr[G] > 0 && !members) return PCG_ERR_NULL_ARG;
+  return build(V, G, row_ptr, members, chunk_groups, (uint8_t *) blob, blob_bytes, info);
+}
+
+}  // extern "C"

@@ -55,8 +55,8 @@ def oracle_groups(V: int, row_ptr, members) -> oracle.Groups:
     return oracle.canonicalize(V, row_ptr, members)
 
 
-def device_groups(V: int, row_ptr, members) -> pcg.Groups:
-    return pcg.Groups.from_csr(V, row_ptr, members, "cuda")
+def device_groups(V: int, row_ptr, members, prepare: bool = True, chunk_groups: int = 0) -> pcg.Groups:
+    return pcg.Groups.from_csr(V, row_ptr, members, "cuda", prepare=prepare, chunk_groups=chunk_groups)
 
 
 def as_oracle_logits(t: torch.Tensor):

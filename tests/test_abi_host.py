@@ -44,7 +44,7 @@ def test_header_constants_match_binding():
         assert re.search(rf"{name}\s*=\s*{val}\b", text)
         assert pcg.strerror(val) != "unknown status"
     assert re.search(r"PCG_F32 = 0, PCG_BF16 = 1", text) and (pcg.F32, pcg.BF16) == (0, 1)
-    assert C.sizeof(pcg.Diag) == 32 and C.sizeof(_GroupsStruct) == 40
+    assert C.sizeof(pcg.Diag) == 32 and C.sizeof(_GroupsStruct) == 56 and C.sizeof(pcg.PreparedInfo) == 64
 
 
 # Fake device addresses: every call below must fail its host-side checks and return before it
@@ -55,7 +55,7 @@ P = 0x10000
 def call_verify(V=64, G=8, nnz=16, dt=0, B=2, K=2, tbs=None, tps=None, dbs=None, dps=None, tau=1.0,
                 ws=P, ws_bytes=1 << 30, tgt=P, dft=P, rp=P, mem=P, mult=P, ptok=P, pgrp=P, al=P,
                 otok=P, ogrp=P, groups=True):
-    gs = _GroupsStruct(V, G, nnz, rp, mem, mult)
+    gs = _GroupsStruct(V, G, nnz, rp, mem, mult, None, None)
     tps = V if tps is None else tps
     dps = V if dps is None else dps
     tbs = (K + 1) * V if tbs is None else tbs
@@ -95,7 +95,7 @@ def test_verify_rejects_bad_arguments_on_the_host():
 
 def test_group_probs_rejects_bad_arguments_on_the_host():
     L = pcg.lib()
-    gs = _GroupsStruct(64, 8, 16, P, P, P)
+    gs = _GroupsStruct(64, 8, 16, P, P, P, None, None)
     f = lambda **k: L.pcg_group_probs(k.get("g", C.byref(gs)), k.get("x", P), k.get("dt", 0),
                                       k.get("rows", 4), k.get("stride", 64), k.get("tau", 1.0),
                                       k.get("out", P), k.get("ws", P), k.get("wsb", 1 << 30), None)
@@ -154,3 +154,93 @@ def test_profile_calls_are_guarded():
     assert L.pcg_profile_begin(0) == BAD_SHAPE
     assert [pcg.lib().pcg_stage_name(i).decode() for i in range(6)] == \
         ["row_stats", "accept", "table", "gather", "finalize", ""]
+
+
+# --------------------------------------------------------------------------- prepared layout
+
+def decode_prepared(blob, info, V, G):
+    """Rebuild {group: sorted member list} from the prepared blob, following the documented layout."""
+    T, SPC = info.ntiles, info.slices_per_chunk
+    desc = blob[info.off_desc:info.off_desc + info.nchunks * T * SPC * 8].view(np.uint32).reshape(
+        info.nchunks, T, SPC, 2)
+    perm = blob[info.off_perm:info.off_perm + info.nchunks * SPC * 64 * 2].view(np.uint16).reshape(
+        info.nchunks, SPC, 64)
+    data = blob[info.off_data:info.bytes // 4 * 4].view(np.uint32)
+    out = {g: [] for g in range(G)}
+    padded = 0
+    for c in range(info.nchunks):
+        for s in range(SPC):
+            for h in range(T):
+                off, ln = int(desc[c, h, s, 0]), int(desc[c, h, s, 1])
+                assert ln % 2 == 0
+                if ln == 0:
+                    continue
+                blk = data[off:off + (ln // 2) * 64].reshape(ln // 2, 64)
+                slots = np.stack([blk & 0xFFFF, blk >> 16], axis=1).reshape(ln, 64)   # [entry, lane]
+                padded += ln * 64
+                for lane in range(64):
+                    k = int(perm[c, s, lane])
+                    col = slots[:, lane]
+                    real = col[col != info.tile_len]
+                    if k == 0xFFFF:
+                        assert len(real) == 0
+                        continue
+                    assert (real < info.tile_len).all()
+                    out[c * info.chunk_groups + k] += (real.astype(np.int64) + h * info.tile_len).tolist()
+    return out, padded
+
+
+@pytest.mark.parametrize("V,G,smin,smax,chunk", [
+    (300, 200, 1, 9, 0),            # one tile, one chunk
+    (50000, 3000, 0, 40, 1024),     # two tiles, three chunks, some empty groups
+    (90000, 1500, 20, 20, 0),       # three tiles, fixed group size
+])
+def test_prepared_layout_holds_exactly_the_membership(V, G, smin, smax, chunk):
+    rp, mem = W.random_groups(V, G, max(smin, 1), smax, seed=V % 97, cover=False)
+    if smin == 0:                    # make a few groups empty
+        keep = np.ones(len(mem), bool)
+        for g in (3, 700, G - 1):
+            keep[rp[g]:rp[g + 1]] = False
+        sizes = np.diff(rp)
+        sizes[[3, 700, G - 1]] = 0
+        mem = mem[keep]
+        rp = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    rp, mem, _ = pcg.groups_canonicalize_host(V, rp, mem)
+    G2 = len(rp) - 1
+    blob, info = pcg.groups_prepare_host(V, rp, mem, chunk)
+    assert info.V == V and info.G == G2 and info.bytes == len(blob)
+    assert info.ntiles * info.tile_len >= V and info.tile_len < 40704
+    assert info.ntiles == -(-V // 40703) and info.nchunks == -(-G2 // info.chunk_groups)
+    got, padded = decode_prepared(blob, info, V, G2)
+    for g in range(G2):
+        assert sorted(got[g]) == sorted(mem[rp[g]:rp[g + 1]].tolist()), g
+    # entries appear in CSR order inside each tile (the summation order is part of the layout)
+    g = G2 // 2
+    seg = mem[rp[g]:rp[g + 1]]
+    want = [int(t) for h in range(info.ntiles) for t in seg if t // info.tile_len == h]
+    assert got[g] == want
+    print(f"padding overhead {padded / max(1, len(mem)) - 1:.3f}")
+    assert padded < 3.0 * len(mem) + 64 * 2 * info.nchunks * info.slices_per_chunk * info.ntiles
+
+
+def test_prepare_rejects_bad_arguments():
+    rp, mem = np.array([0, 2, 4], np.int32), np.array([0, 1, 2, 3], np.int32)
+    L = pcg.lib()
+    assert L.pcg_groups_prepare_bytes(4, 2, rp.ctypes.data, mem.ctypes.data, 100) == 0      # not a multiple of 1024
+    assert L.pcg_groups_prepare_bytes(4, 2, rp.ctypes.data, mem.ctypes.data, 32768) == 0
+    assert L.pcg_groups_prepare_bytes(4, 2, None, mem.ctypes.data, 0) == 0
+    n = L.pcg_groups_prepare_bytes(4, 2, rp.ctypes.data, mem.ctypes.data, 0)
+    assert n > 0 and n % 256 == 0
+    blob = np.zeros(n, np.uint8)
+    info = pcg.PreparedInfo()
+    assert L.pcg_groups_prepare_host(4, 2, rp.ctypes.data, mem.ctypes.data, 0, blob.ctypes.data, n - 1,
+                                     C.byref(info)) == WS_SMALL
+    bad = np.array([0, 1, 2, 7], np.int32)
+    assert L.pcg_groups_prepare_host(4, 2, rp.ctypes.data, bad.ctypes.data, 0, blob.ctypes.data, n,
+                                     C.byref(info)) == BAD_CSR
+    # a descriptor that does not belong to the groups is refused before any launch
+    blob, info = pcg.groups_prepare_host(4, rp, mem)
+    gs = _GroupsStruct(5, 2, 4, P, P, P, P, C.pointer(info))
+    assert pcg.lib().pcg_group_probs(C.byref(gs), P, 0, 1, 5, 1.0, P, P, 1 << 30, None) == BAD_SHAPE
+    gs = _GroupsStruct(4, 2, 4, P, P, P, P, None)
+    assert pcg.lib().pcg_group_probs(C.byref(gs), P, 0, 1, 4, 1.0, P, P, 1 << 30, None) == NULL_ARG

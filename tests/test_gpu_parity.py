@@ -47,9 +47,11 @@ def coupled_proposals(dft, tau, og, seed):
     (50000, 5000, 1, 3, "f32", 1.3, 2),        # two tiles, ragged, tiny groups
     (7, 3, 1, 4, "f32", 1.0, 4),               # smaller than a wave
 ])
-def test_group_probs_matches_oracle(V, G, smin, smax, dtype, tau, rows):
+@pytest.mark.parametrize("layout", ["prepared", "prepared-1024", "csr"])
+def test_group_probs_matches_oracle(V, G, smin, smax, dtype, tau, rows, layout):
     rp, mem = W.random_groups(V, G, smin, smax, seed=V + G, cover=False)
-    og, dg = oracle_groups(V, rp, mem), device_groups(V, rp, mem)
+    og = oracle_groups(V, rp, mem)
+    dg = device_groups(V, rp, mem, prepare=layout != "csr", chunk_groups=1024 if layout.endswith("1024") else 0)
     assert og.G == dg.G and og.nnz == dg.nnz
     np.testing.assert_array_equal(og.row_ptr, dg.row_ptr.cpu().numpy())
     np.testing.assert_array_equal(og.mult, dg.mult.cpu().numpy())
@@ -109,9 +111,11 @@ def test_group_probs_many_rows_in_batches():
     (50000, 6000, 10, 30, 6, 4, "f32", 1.0),     # two LDS tiles
     (5, 4, 1, 3, 200, 2, "f32", 1.0),            # tiny vocabulary
 ])
-def test_verify_matches_oracle(V, G, smin, smax, B, K, dtype, tau):
+@pytest.mark.parametrize("layout", ["prepared", "prepared-1024", "csr"])
+def test_verify_matches_oracle(V, G, smin, smax, B, K, dtype, tau, layout):
     rp, mem = W.random_groups(V, G, smin, smax, seed=V * 3 + K, cover=False)
-    og, dg = oracle_groups(V, rp, mem), device_groups(V, rp, mem)
+    og = oracle_groups(V, rp, mem)
+    dg = device_groups(V, rp, mem, prepare=layout != "csr", chunk_groups=1024 if layout.endswith("1024") else 0)
     total = Tally()
     lens = []
     for step in range(6):
@@ -123,7 +127,7 @@ def test_verify_matches_oracle(V, G, smin, smax, B, K, dtype, tau):
         assert diag["sequences"] == B and diag["bad_proposal"] == 0
         assert diag["accepted_total"] == int(gpu.accept_len.sum())
         lens += ref.accept_len.tolist()
-    total.report(f"small V={V} K={K} {dtype}")
+    total.report(f"small V={V} K={K} {dtype} {layout}")
     assert total.tolerated <= max(1, total.sequences // 200)
     assert len(set(lens)) > 1                  # both accepts and rejects were exercised
 

@@ -92,21 +92,23 @@ typedef struct {
  *   - the vocabulary is cut into `ntiles` tiles of `tile_len` tokens, each small enough for
  *     a table of one float per token to sit in a workgroup's LDS;
  *   - the groups are cut into chunks of `chunk_groups` consecutive groups (one workgroup
- *     each); inside a chunk they are sorted by their member counts per tile and dealt 64 at
- *     a time into slices, one group per lane;
- *   - per (chunk, tile, slice) the members that fall into the tile are stored as 16-bit
- *     tile-local slots, padded with a slot that holds 0 to the slice's longest list and
- *     interleaved so that a wave reads them with coalesced loads.
+ *     each); inside a chunk they are sorted by their member counts per tile and dealt 256 at
+ *     a time into blocks: lane l of a wave handles the 4 groups at sorted positions
+ *     block*256 + r*64 + l, r = 0..3;
+ *   - per (chunk, tile, block) the members that fall into the tile are stored as 16-bit
+ *     tile-local slots, two per dword, padded with a slot that holds 0 to the block's longest
+ *     list; a lane's 4 dwords of step k (one per group) are adjacent, so a wave reads step k
+ *     of a block with one coalesced 16-byte-per-lane load.
  * The descriptor is filled by pcg_groups_prepare_host and must be passed back unchanged.
  */
 struct pcg_prepared {
   int32_t V, G;
   int32_t ntiles, tile_len;
   int32_t chunk_groups, nchunks;
-  int32_t slices_per_chunk, reserved;
-  int64_t off_desc;   /* uint32 [nchunks][ntiles][slices_per_chunk][2]: data offset (dwords), length */
-  int64_t off_perm;   /* uint16 [nchunks][slices_per_chunk][64]: group index inside the chunk, 0xFFFF = none */
-  int64_t off_data;   /* uint32 []: two 16-bit slots per dword, [k][lane] inside a slice             */
+  int32_t blocks_per_chunk, reserved;
+  int64_t off_desc;   /* uint32 [nchunks][ntiles][blocks_per_chunk][2]: data offset (16-byte units), steps */
+  int64_t off_perm;   /* uint16 [nchunks][blocks_per_chunk][4][64]: group index inside the chunk, 0xFFFF = none */
+  int64_t off_data;   /* uint32 [][64][4]: step k of a block = 64 lanes x 4 dwords, 2 slots per dword */
   int64_t bytes;      /* size of the blob */
 };
 
@@ -203,7 +205,7 @@ int pcg_groups_canonicalize_host(int32_t V, int32_t G, const int32_t *row_ptr,
 
 /*
  * Build the prepared form of a validated membership (all pointers HOST).  chunk_groups is the
- * number of consecutive groups one workgroup handles: a multiple of 1024 in [1024, 16384], or
+ * number of consecutive groups one workgroup handles: a multiple of 4096 in [4096, 16384], or
  * 0 for the default (16384).  Smaller chunks spread a small batch over more compute units.
  * pcg_groups_prepare_bytes returns the blob size (0 on bad arguments); pcg_groups_prepare_host
  * fills `blob` (blob_bytes >= that size) and `info`.  The caller uploads the blob to the

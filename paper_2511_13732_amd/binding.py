@@ -28,7 +28,7 @@ class PreparedInfo(C.Structure):
     """Mirror of pcg_prepared (host descriptor of the prepared membership blob)."""
     _fields_ = [("V", C.c_int32), ("G", C.c_int32), ("ntiles", C.c_int32), ("tile_len", C.c_int32),
                 ("chunk_groups", C.c_int32), ("nchunks", C.c_int32),
-                ("slices_per_chunk", C.c_int32), ("reserved", C.c_int32),
+                ("blocks_per_chunk", C.c_int32), ("reserved", C.c_int32),
                 ("off_desc", C.c_int64), ("off_perm", C.c_int64), ("off_data", C.c_int64),
                 ("bytes", C.c_int64)]
 

@@ -64,9 +64,9 @@ int check_groups(const pcg_groups *g) {
   if (g->prepared) {
     const pcg_prepared &p = *g->prepared_info;
     if (p.V != g->V || p.G != g->G || p.ntiles < 1 || p.tile_len < 1 || p.tile_len >= kTileMax ||
-        (int64_t) p.ntiles * p.tile_len < g->V || p.chunk_groups < kGatherThreads ||
-        p.chunk_groups > kMaxChunkGroups || p.chunk_groups % kGatherThreads ||
-        p.slices_per_chunk != p.chunk_groups / 64 ||
+        (int64_t) p.ntiles * p.tile_len < g->V || p.chunk_groups < kChunkStep ||
+        p.chunk_groups > kMaxChunkGroups || p.chunk_groups % kChunkStep ||
+        p.blocks_per_chunk != p.chunk_groups / kBlockGroups ||
         p.nchunks != (g->G + p.chunk_groups - 1) / p.chunk_groups)
       return PCG_ERR_BAD_SHAPE;
     if ((uintptr_t) g->prepared % 256) return PCG_ERR_MISALIGNED;
@@ -115,7 +115,7 @@ size_t pcg_verify_workspace_bytes(int32_t V, int32_t G, int32_t B, int32_t K) {
   const size_t rows = (size_t) B * (2 * (size_t) K + 1);
   return align_up(rows * stats_nparts(V) * sizeof(StatPart)) + align_up(rows * sizeof(RowStat)) +
          align_up((size_t) B * V * sizeof(float)) + align_up((size_t) B * G * sizeof(float)) +
-         align_up((size_t) B * ((G + kGatherThreads - 1) / kGatherThreads) * sizeof(double)) + kAlign;
+         align_up((size_t) B * ((G + kChunkStep - 1) / kChunkStep) * sizeof(double)) + kAlign;
 }
 
 int pcg_group_probs(const pcg_groups *groups, const void *logits, pcg_dtype dt, int64_t rows,

@@ -353,22 +353,78 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
 }
 
 // ---------------------------------------------------------------------------------------------
-// The same sum read from the prepared layout (pcg_prepared): one group per lane, 16-bit
-// tile-local slots, no cross-lane reduction and no address arithmetic beyond a shift.
-// A workgroup owns one chunk of consecutive groups of one table row.  Lane l of wave w handles,
-// in round j, the group that slice j*16 + w puts on lane l -- the same group in every tile pass,
-// so its running sum stays in a register.  Results are put back into group order through LDS
-// and leave with coalesced stores; with CSUM the workgroup also writes the chunk's total of
-// max(0, .) in double, summed in a fixed order.
+// The same sum read from the prepared layout (pcg_prepared): no cross-lane reduction and no
+// address arithmetic beyond a shift.  A workgroup owns one chunk of consecutive groups of one
+// table row.  In its q-th turn wave w takes block block_of(q, w) of the chunk; lane l handles
+// the block's 4 groups r*64 + l side by side -- the same groups in every tile pass, so their
+// running sums stay in registers.  One 16-byte load per lane brings 2 slots for each of the 4
+// groups.  Results are put back into group order through LDS and leave with coalesced stores;
+// with CSUM the workgroup also writes the chunk's total of max(0, .) in double, summed in a
+// fixed order.
 // ---------------------------------------------------------------------------------------------
+
+__device__ __forceinline__ void gather_step(const float *tab, const uint4 w, float *acc) {
+  acc[0] += tab[w.x & 0xffffu]; acc[1] += tab[w.y & 0xffffu];
+  acc[2] += tab[w.z & 0xffffu]; acc[3] += tab[w.w & 0xffffu];
+  acc[0] += tab[w.x >> 16]; acc[1] += tab[w.y >> 16];
+  acc[2] += tab[w.z >> 16]; acc[3] += tab[w.w >> 16];
+}
+
+// Steps k .. k+3 of the block that starts at unit `off` of the data (clamped to its last
+// step, so every load is in bounds).  `data` stays the kernel's own global pointer so that the
+// loads are global loads, which the hardware returns in order.
+__device__ __forceinline__ void load_steps(uint4 *w, const uint4 *__restrict__ data, uint32_t off,
+                                           uint32_t k, uint32_t n) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) w[i] = data[(size_t) off + (size_t) min(k + i, n - 1) * kWave];
+}
+
+__device__ __forceinline__ void gather_steps(const float *tab, const uint4 *w, uint32_t left,
+                                             float *acc) {
+  gather_step(tab, w[0], acc);
+  if (left > 1) gather_step(tab, w[1], acc);
+  if (left > 2) gather_step(tab, w[2], acc);
+  if (left > 3) gather_step(tab, w[3], acc);
+}
+
+// One block of n steps, four at a time, with two register buffers used alternately: while
+// the steps in one are gathered, the next four (of this block, or the first of the next block
+// when nnext > 0) are on their way into the other.  On entry the block's first four steps are in
+// A (CUR_IS_A) or B; returns true if the steps loaded last went into A.
+template <bool CUR_IS_A>
+__device__ __forceinline__ bool run_block(const float *tab, uint4 (&A)[4], uint4 (&B)[4],
+                                          const uint4 *__restrict__ data, uint32_t off, uint32_t n,
+                                          uint32_t off_next, uint32_t nnext, float *acc) {
+  uint4 (&X)[4] = CUR_IS_A ? A : B;
+  uint4 (&Y)[4] = CUR_IS_A ? B : A;
+  // Exactly four loads are issued per turn whatever there is to fetch (a turn with nothing
+  // left re-reads step 0), so the number of loads in flight behind the ones being used is the
+  // same on every path and the wait for the current buffer never drains the prefetch.
+  auto prefetch = [&](uint4 (&dst)[4], uint32_t k) {
+    const bool own = k + 4 < n, next = !own && nnext > 0;
+    load_steps(dst, data, next ? off_next : off, own ? k + 4 : 0u, next ? nnext : n);
+  };
+  uint32_t k = 0;
+  while (true) {
+    prefetch(Y, k);
+    gather_steps(tab, X, n - k, acc);
+    k += 4;
+    if (k >= n) return !CUR_IS_A;
+    prefetch(X, k);
+    gather_steps(tab, Y, n - k, acc);
+    k += 4;
+    if (k >= n) return CUR_IS_A;
+  }
+}
 
 template <bool CSUM>
 __global__ __launch_bounds__(kGatherThreads) void gather_prepared_kernel(
     int32_t V, int32_t G, int32_t nrows, int32_t nchunks, int32_t chunk_groups, int32_t ntiles,
-    int32_t tile_len, int32_t spc, const uint32_t *desc, const uint16_t *perm,
-    const uint32_t *data, const float *table, float *out, double *csum) {
+    int32_t tile_len, int32_t bpc, const uint32_t *__restrict__ desc,
+    const uint16_t *__restrict__ perm, const uint4 *__restrict__ data,
+    const float *__restrict__ table, float *__restrict__ out, double *__restrict__ csum) {
   __shared__ float tab[kTileMax];
-  __shared__ double wsum[kGatherThreads / kWave];
+  __shared__ double wsum[kGatherWaves];
   const int xcd = blockIdx.x & 7;
   const int y = blockIdx.x >> 3;
   const int r = xcd + 8 * (y / nchunks);
@@ -380,51 +436,67 @@ __global__ __launch_bounds__(kGatherThreads) void gather_prepared_kernel(
   const int32_t ng = min(chunk_groups, G - g0);
   const float *src = table + (int64_t) r * V;
 
-  float acc[kMaxRounds];
+  float acc[kMaxAcc];
 #pragma unroll
-  for (int j = 0; j < kMaxRounds; ++j) acc[j] = 0.f;
+  for (int j = 0; j < kMaxAcc; ++j) acc[j] = 0.f;
 
   for (int h = 0; h < ntiles; ++h) {
     const int32_t t0 = h * tile_len;
     const int32_t tl = min(tile_len, V - t0);
     if (h > 0) __syncthreads();                       // everyone is done reading the old tile
-    for (int32_t k = threadIdx.x; k < tl; k += kGatherThreads) tab[k] = src[t0 + k];
+    if (((V | tl) & 3) == 0) {                        // rows and tiles are 16-byte aligned
+      const float4 *s4 = reinterpret_cast<const float4 *>(src + t0);
+      float4 *t4 = reinterpret_cast<float4 *>(tab);
+      for (int32_t k = threadIdx.x; k < (tl >> 2); k += kGatherThreads) t4[k] = s4[k];
+    } else {
+      for (int32_t k = threadIdx.x; k < tl; k += kGatherThreads) tab[k] = src[t0 + k];
+    }
     if (threadIdx.x == 0) tab[tile_len] = 0.f;        // the padding slot
     __syncthreads();
-    const uint32_t *dsc = desc + ((size_t) (chunk * ntiles + h) * spc) * 2;
+    // The wave's blocks of this tile.  Steps are taken four at a time; the loads of the next
+    // four (of this block, or the first of the next block) are issued before the current four
+    // are used, so their latency hides behind 32 LDS gathers per lane.
+    const uint32_t *dsc = desc + ((size_t) (chunk * ntiles + h) * bpc) * 2;
+    uint32_t steps[kMaxBlocksPerWave], offs[kMaxBlocksPerWave];
 #pragma unroll
-    for (int j = 0; j < kMaxRounds; ++j) {
-      const int s = j * (kGatherThreads / kWave) + wave;
-      if (s < spc) {                                  // uniform over the wave
-        const uint32_t off = dsc[2 * s], n = dsc[2 * s + 1] >> 1;
-        const uint32_t *d = data + off + lane;
-        float a0 = 0.f, a1 = 0.f;
-        uint32_t k = 0;
-        for (; k + 4 <= n; k += 4) {
-          const uint32_t w0 = d[(size_t) k * kWave], w1 = d[(size_t) (k + 1) * kWave];
-          const uint32_t w2 = d[(size_t) (k + 2) * kWave], w3 = d[(size_t) (k + 3) * kWave];
-          a0 += tab[w0 & 0xffffu]; a1 += tab[w0 >> 16];
-          a0 += tab[w1 & 0xffffu]; a1 += tab[w1 >> 16];
-          a0 += tab[w2 & 0xffffu]; a1 += tab[w2 >> 16];
-          a0 += tab[w3 & 0xffffu]; a1 += tab[w3 >> 16];
-        }
-        for (; k < n; ++k) {
-          const uint32_t w0 = d[(size_t) k * kWave];
-          a0 += tab[w0 & 0xffffu]; a1 += tab[w0 >> 16];
-        }
-        acc[j] += a0 + a1;
+    for (int q = 0; q < kMaxBlocksPerWave; ++q) {
+      const int bl = block_of(q, wave);
+      steps[q] = 0;
+      offs[q] = lane;
+      if (bl < bpc) {                                 // uniform over the wave
+        steps[q] = dsc[2 * bl + 1];
+        offs[q] = dsc[2 * bl] + lane;
       }
+    }
+    uint4 bufA[4], bufB[4];
+    bool in_a = true, primed = false;
+#pragma unroll
+    for (int q = 0; q < kMaxBlocksPerWave; ++q) {
+      const uint32_t n = steps[q];
+      if (n == 0) continue;                           // uniform
+      const int qn = (q + 1) % kMaxBlocksPerWave;
+      const uint32_t nn = (q + 1 < kMaxBlocksPerWave) ? steps[qn] : 0;
+      if (!primed) {
+        if (in_a) load_steps(bufA, data, offs[q], 0, n); else load_steps(bufB, data, offs[q], 0, n);
+      }
+      in_a = in_a ? run_block<true>(tab, bufA, bufB, data, offs[q], n, offs[qn], nn, acc + q * kLaneGroups)
+                  : run_block<false>(tab, bufA, bufB, data, offs[q], n, offs[qn], nn, acc + q * kLaneGroups);
+      primed = nn > 0;
     }
   }
 
   // back into group order through LDS, then coalesced stores
   __syncthreads();
 #pragma unroll
-  for (int j = 0; j < kMaxRounds; ++j) {
-    const int s = j * (kGatherThreads / kWave) + wave;
-    if (s < spc) {
-      const uint16_t k = perm[((size_t) chunk * spc + s) * kWave + lane];
-      if (k != 0xFFFFu) tab[k] = acc[j];
+  for (int q = 0; q < kMaxBlocksPerWave; ++q) {
+    const int bl = block_of(q, wave);
+    if (bl < bpc) {
+      const uint16_t *pp = perm + ((size_t) chunk * bpc + bl) * kBlockGroups + lane;
+#pragma unroll
+      for (int rr = 0; rr < kLaneGroups; ++rr) {
+        const uint16_t k = pp[rr * kWave];
+        if (k != 0xFFFFu) tab[k] = acc[q * kLaneGroups + rr];
+      }
     }
   }
   __syncthreads();
@@ -441,7 +513,7 @@ __global__ __launch_bounds__(kGatherThreads) void gather_prepared_kernel(
     __syncthreads();
     if (threadIdx.x == 0) {
       double t = 0.0;
-      for (int w = 0; w < kGatherThreads / kWave; ++w) t += wsum[w];
+      for (int w = 0; w < kGatherWaves; ++w) t += wsum[w];
       csum[(int64_t) r * nchunks + chunk] = t;
     }
   }
@@ -735,16 +807,16 @@ hipError_t launch_gather_prepared(const pcg_groups &g, int32_t nrows, const floa
   const char *blob = reinterpret_cast<const char *>(g.prepared);
   const uint32_t *desc = reinterpret_cast<const uint32_t *>(blob + p.off_desc);
   const uint16_t *perm = reinterpret_cast<const uint16_t *>(blob + p.off_perm);
-  const uint32_t *data = reinterpret_cast<const uint32_t *>(blob + p.off_data);
+  const uint4 *data = reinterpret_cast<const uint4 *>(blob + p.off_data);
   const int32_t rows8 = (nrows + 7) / 8;
   const dim3 grid((unsigned) (8 * rows8 * p.nchunks));
   if (csum)
     gather_prepared_kernel<true><<<grid, kGatherThreads, 0, stream>>>(
-        g.V, g.G, nrows, p.nchunks, p.chunk_groups, p.ntiles, p.tile_len, p.slices_per_chunk, desc,
+        g.V, g.G, nrows, p.nchunks, p.chunk_groups, p.ntiles, p.tile_len, p.blocks_per_chunk, desc,
         perm, data, table, out, csum);
   else
     gather_prepared_kernel<false><<<grid, kGatherThreads, 0, stream>>>(
-        g.V, g.G, nrows, p.nchunks, p.chunk_groups, p.ntiles, p.tile_len, p.slices_per_chunk, desc,
+        g.V, g.G, nrows, p.nchunks, p.chunk_groups, p.ntiles, p.tile_len, p.blocks_per_chunk, desc,
         perm, data, table, out, nullptr);
   return hipGetLastError();
 }

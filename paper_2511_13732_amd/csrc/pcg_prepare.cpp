@@ -12,14 +12,13 @@ namespace {
 using namespace pcg;
 
 struct Shape {
-  int32_t ntiles, tile_len, chunk_groups, nchunks, slices_per_chunk;
+  int32_t ntiles, tile_len, chunk_groups, nchunks, blocks_per_chunk;
 };
 
 bool make_shape(int32_t V, int32_t G, int32_t chunk_groups, Shape &s) {
   if (V < 1 || G < 1) return false;
   if (chunk_groups == 0) chunk_groups = kMaxChunkGroups;
-  if (chunk_groups < kGatherThreads || chunk_groups > kMaxChunkGroups ||
-      chunk_groups % kGatherThreads)
+  if (chunk_groups < kChunkStep || chunk_groups > kMaxChunkGroups || chunk_groups % kChunkStep)
     return false;
   // one slot of every tile is kept for the padding entry, which must read as zero
   s.ntiles = (V + (kTileMax - 1) - 1) / (kTileMax - 1);
@@ -27,7 +26,7 @@ bool make_shape(int32_t V, int32_t G, int32_t chunk_groups, Shape &s) {
   s.tile_len = std::min(kTileMax - 1, (s.tile_len + 63) / 64 * 64);
   s.chunk_groups = chunk_groups;
   s.nchunks = (G + chunk_groups - 1) / chunk_groups;
-  s.slices_per_chunk = chunk_groups / 64;
+  s.blocks_per_chunk = chunk_groups / kBlockGroups;
   return true;
 }
 
@@ -42,18 +41,19 @@ int build(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members,
   for (int32_t j = 0, n = row_ptr[G]; j < n; ++j)
     if ((uint32_t) members[j] >= (uint32_t) V) return PCG_ERR_BAD_CSR;
 
-  const int32_t T = sh.ntiles, SPC = sh.slices_per_chunk;
-  const size_t n_desc = (size_t) sh.nchunks * T * SPC;
+  const int32_t T = sh.ntiles, BPC = sh.blocks_per_chunk;
+  const size_t n_desc = (size_t) sh.nchunks * T * BPC;
   const size_t desc_bytes = (n_desc * 2 * sizeof(uint32_t) + 255) / 256 * 256;
-  const size_t perm_bytes = ((size_t) sh.nchunks * SPC * 64 * sizeof(uint16_t) + 255) / 256 * 256;
+  const size_t n_perm = (size_t) sh.nchunks * BPC * kBlockGroups;
+  const size_t perm_bytes = (n_perm * sizeof(uint16_t) + 255) / 256 * 256;
 
   std::vector<uint32_t> desc(n_desc * 2, 0);
-  std::vector<uint16_t> perm((size_t) sh.nchunks * SPC * 64, 0xFFFF);
+  std::vector<uint16_t> perm(n_perm, 0xFFFF);
   std::vector<int32_t> cnt;          // [group in chunk][tile]
   std::vector<int32_t> order;
-  uint64_t dwords = 0;
+  uint64_t units = 0;                // 16-byte units of data
 
-  // pass 1: order groups, size the slices
+  // pass 1: order the groups of each chunk, size the blocks
   for (int32_t c = 0; c < sh.nchunks; ++c) {
     const int32_t g0 = c * sh.chunk_groups, ng = std::min(sh.chunk_groups, G - g0);
     cnt.assign((size_t) ng * T, 0);
@@ -70,30 +70,30 @@ int build(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members,
       }
       return false;
     });
-    for (int32_t k = 0; k < ng; ++k)
-      perm[((size_t) c * SPC + k / 64) * 64 + k % 64] = (uint16_t) order[k];
-    for (int32_t s = 0; s < SPC; ++s) {
+    for (int32_t k = 0; k < ng; ++k)     // sorted position k = block * 256 + r * 64 + lane
+      perm[(size_t) c * BPC * kBlockGroups + k] = (uint16_t) order[k];
+    for (int32_t bl = 0; bl < BPC; ++bl) {
       for (int32_t h = 0; h < T; ++h) {
         int32_t longest = 0;
-        for (int32_t l = 0; l < 64 && s * 64 + l < ng; ++l)
-          longest = std::max(longest, cnt[(size_t) order[s * 64 + l] * T + h]);
-        longest = (longest + 1) / 2 * 2;                      // two slots per dword
-        uint32_t *d = &desc[(((size_t) c * T + h) * SPC + s) * 2];
-        if (dwords > 0xFFFFFFFFull) return PCG_ERR_BAD_SHAPE;
-        d[0] = (uint32_t) dwords;
-        d[1] = (uint32_t) longest;
-        dwords += (uint64_t) (longest / 2) * 64;
+        for (int32_t l = 0; l < kBlockGroups && bl * kBlockGroups + l < ng; ++l)
+          longest = std::max(longest, cnt[(size_t) order[bl * kBlockGroups + l] * T + h]);
+        const int32_t steps = (longest + 1) / 2;               // two slots per dword
+        uint32_t *d = &desc[(((size_t) c * T + h) * BPC + bl) * 2];
+        if (units > 0xFFFFFFFFull) return PCG_ERR_BAD_SHAPE;
+        d[0] = (uint32_t) units;
+        d[1] = (uint32_t) steps;
+        units += (uint64_t) steps * 64;
       }
     }
   }
-  if (dwords > 0xFFFFFFFFull) return PCG_ERR_BAD_SHAPE;
-  const size_t data_bytes = ((size_t) dwords * sizeof(uint32_t) + 255) / 256 * 256 + 256;
+  if (units > 0xFFFFFFFFull / 4) return PCG_ERR_BAD_SHAPE;
+  const size_t data_bytes = ((size_t) units * 16 + 255) / 256 * 256 + 1024;   // never empty
   const size_t total = desc_bytes + perm_bytes + data_bytes;
   if (info) {
     info->V = V; info->G = G;
     info->ntiles = T; info->tile_len = sh.tile_len;
     info->chunk_groups = sh.chunk_groups; info->nchunks = sh.nchunks;
-    info->slices_per_chunk = SPC; info->reserved = 0;
+    info->blocks_per_chunk = BPC; info->reserved = 0;
     info->off_desc = 0;
     info->off_perm = (int64_t) desc_bytes;
     info->off_data = (int64_t) (desc_bytes + perm_bytes);
@@ -111,21 +111,26 @@ int build(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members,
   std::vector<uint16_t> slots;
   for (int32_t c = 0; c < sh.nchunks; ++c) {
     const int32_t g0 = c * sh.chunk_groups;
-    for (int32_t s = 0; s < SPC; ++s) {
+    for (int32_t bl = 0; bl < BPC; ++bl) {
       for (int32_t h = 0; h < T; ++h) {
-        const uint32_t *d = &desc[(((size_t) c * T + h) * SPC + s) * 2];
-        const uint32_t off = d[0], len = d[1];
-        if (len == 0) continue;
-        for (int32_t l = 0; l < 64; ++l) {
-          slots.assign(len, pad_slot);
-          const uint16_t k = perm[((size_t) c * SPC + s) * 64 + l];
-          if (k != 0xFFFF) {
-            uint32_t n = 0;
-            for (int32_t j = row_ptr[g0 + k]; j < row_ptr[g0 + k + 1]; ++j)
-              if (members[j] / sh.tile_len == h) slots[n++] = (uint16_t) (members[j] - h * sh.tile_len);
+        const uint32_t *d = &desc[(((size_t) c * T + h) * BPC + bl) * 2];
+        const size_t off = d[0];
+        const uint32_t steps = d[1];
+        if (steps == 0) continue;
+        for (int32_t r = 0; r < kLaneGroups; ++r) {
+          for (int32_t l = 0; l < 64; ++l) {
+            slots.assign((size_t) steps * 2, pad_slot);
+            const uint16_t k = perm[((size_t) c * BPC + bl) * kBlockGroups + r * 64 + l];
+            if (k != 0xFFFF) {
+              uint32_t n = 0;
+              for (int32_t j = row_ptr[g0 + k]; j < row_ptr[g0 + k + 1]; ++j)
+                if (members[j] / sh.tile_len == h)
+                  slots[n++] = (uint16_t) (members[j] - h * sh.tile_len);
+            }
+            for (uint32_t q = 0; q < steps; ++q)
+              data[((off + (size_t) q * 64 + l) * 4) + r] =
+                  (uint32_t) slots[2 * q] | ((uint32_t) slots[2 * q + 1] << 16);
           }
-          for (uint32_t q = 0; q < len / 2; ++q)
-            data[off + (size_t) q * 64 + l] = (uint32_t) slots[2 * q] | ((uint32_t) slots[2 * q + 1] << 16);
         }
       }
     }

@@ -159,40 +159,41 @@ def test_profile_calls_are_guarded():
 # --------------------------------------------------------------------------- prepared layout
 
 def decode_prepared(blob, info, V, G):
-    """Rebuild {group: sorted member list} from the prepared blob, following the documented layout."""
-    T, SPC = info.ntiles, info.slices_per_chunk
-    desc = blob[info.off_desc:info.off_desc + info.nchunks * T * SPC * 8].view(np.uint32).reshape(
-        info.nchunks, T, SPC, 2)
-    perm = blob[info.off_perm:info.off_perm + info.nchunks * SPC * 64 * 2].view(np.uint16).reshape(
-        info.nchunks, SPC, 64)
-    data = blob[info.off_data:info.bytes // 4 * 4].view(np.uint32)
+    """Rebuild {group: member list} from the prepared blob, following the documented layout."""
+    T, BPC = info.ntiles, info.blocks_per_chunk
+    desc = blob[info.off_desc:info.off_desc + info.nchunks * T * BPC * 8].view(np.uint32).reshape(
+        info.nchunks, T, BPC, 2)
+    perm = blob[info.off_perm:info.off_perm + info.nchunks * BPC * 256 * 2].view(np.uint16).reshape(
+        info.nchunks, BPC, 4, 64)
+    data = blob[info.off_data:info.off_data + (info.bytes - info.off_data) // 16 * 16].view(
+        np.uint32).reshape(-1, 4)                    # 16-byte units
     out = {g: [] for g in range(G)}
     padded = 0
     for c in range(info.nchunks):
-        for s in range(SPC):
+        for bl in range(BPC):
             for h in range(T):
-                off, ln = int(desc[c, h, s, 0]), int(desc[c, h, s, 1])
-                assert ln % 2 == 0
-                if ln == 0:
+                off, steps = int(desc[c, h, bl, 0]), int(desc[c, h, bl, 1])
+                if steps == 0:
                     continue
-                blk = data[off:off + (ln // 2) * 64].reshape(ln // 2, 64)
-                slots = np.stack([blk & 0xFFFF, blk >> 16], axis=1).reshape(ln, 64)   # [entry, lane]
-                padded += ln * 64
-                for lane in range(64):
-                    k = int(perm[c, s, lane])
-                    col = slots[:, lane]
-                    real = col[col != info.tile_len]
-                    if k == 0xFFFF:
-                        assert len(real) == 0
-                        continue
-                    assert (real < info.tile_len).all()
-                    out[c * info.chunk_groups + k] += (real.astype(np.int64) + h * info.tile_len).tolist()
+                blk = data[off:off + steps * 64].reshape(steps, 64, 4)          # [step, lane, r]
+                slots = np.stack([blk & 0xFFFF, blk >> 16], axis=1).reshape(2 * steps, 64, 4)
+                padded += 2 * steps * 256
+                for r in range(4):
+                    for lane in range(64):
+                        k = int(perm[c, bl, r, lane])
+                        col = slots[:, lane, r]
+                        real = col[col != info.tile_len]
+                        if k == 0xFFFF:
+                            assert len(real) == 0
+                            continue
+                        assert (real < info.tile_len).all()
+                        out[c * info.chunk_groups + k] += (real.astype(np.int64) + h * info.tile_len).tolist()
     return out, padded
 
 
 @pytest.mark.parametrize("V,G,smin,smax,chunk", [
     (300, 200, 1, 9, 0),            # one tile, one chunk
-    (50000, 3000, 0, 40, 1024),     # two tiles, three chunks, some empty groups
+    (50000, 9000, 0, 40, 4096),     # two tiles, three chunks, some empty groups
     (90000, 1500, 20, 20, 0),       # three tiles, fixed group size
 ])
 def test_prepared_layout_holds_exactly_the_membership(V, G, smin, smax, chunk):
@@ -220,13 +221,13 @@ def test_prepared_layout_holds_exactly_the_membership(V, G, smin, smax, chunk):
     want = [int(t) for h in range(info.ntiles) for t in seg if t // info.tile_len == h]
     assert got[g] == want
     print(f"padding overhead {padded / max(1, len(mem)) - 1:.3f}")
-    assert padded < 3.0 * len(mem) + 64 * 2 * info.nchunks * info.slices_per_chunk * info.ntiles
+    assert padded < 3.0 * len(mem) + 256 * 2 * info.nchunks * info.blocks_per_chunk * info.ntiles
 
 
 def test_prepare_rejects_bad_arguments():
     rp, mem = np.array([0, 2, 4], np.int32), np.array([0, 1, 2, 3], np.int32)
     L = pcg.lib()
-    assert L.pcg_groups_prepare_bytes(4, 2, rp.ctypes.data, mem.ctypes.data, 100) == 0      # not a multiple of 1024
+    assert L.pcg_groups_prepare_bytes(4, 2, rp.ctypes.data, mem.ctypes.data, 1024) == 0     # not a multiple of 4096
     assert L.pcg_groups_prepare_bytes(4, 2, rp.ctypes.data, mem.ctypes.data, 32768) == 0
     assert L.pcg_groups_prepare_bytes(4, 2, None, mem.ctypes.data, 0) == 0
     n = L.pcg_groups_prepare_bytes(4, 2, rp.ctypes.data, mem.ctypes.data, 0)

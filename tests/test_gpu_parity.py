@@ -47,11 +47,11 @@ def coupled_proposals(dft, tau, og, seed):
     (50000, 5000, 1, 3, "f32", 1.3, 2),        # two tiles, ragged, tiny groups
     (7, 3, 1, 4, "f32", 1.0, 4),               # smaller than a wave
 ])
-@pytest.mark.parametrize("layout", ["prepared", "prepared-1024", "csr"])
+@pytest.mark.parametrize("layout", ["prepared", "prepared-4096", "csr"])
 def test_group_probs_matches_oracle(V, G, smin, smax, dtype, tau, rows, layout):
     rp, mem = W.random_groups(V, G, smin, smax, seed=V + G, cover=False)
     og = oracle_groups(V, rp, mem)
-    dg = device_groups(V, rp, mem, prepare=layout != "csr", chunk_groups=1024 if layout.endswith("1024") else 0)
+    dg = device_groups(V, rp, mem, prepare=layout != "csr", chunk_groups=4096 if layout.endswith("4096") else 0)
     assert og.G == dg.G and og.nnz == dg.nnz
     np.testing.assert_array_equal(og.row_ptr, dg.row_ptr.cpu().numpy())
     np.testing.assert_array_equal(og.mult, dg.mult.cpu().numpy())
@@ -111,11 +111,11 @@ def test_group_probs_many_rows_in_batches():
     (50000, 6000, 10, 30, 6, 4, "f32", 1.0),     # two LDS tiles
     (5, 4, 1, 3, 200, 2, "f32", 1.0),            # tiny vocabulary
 ])
-@pytest.mark.parametrize("layout", ["prepared", "prepared-1024", "csr"])
+@pytest.mark.parametrize("layout", ["prepared", "prepared-4096", "csr"])
 def test_verify_matches_oracle(V, G, smin, smax, B, K, dtype, tau, layout):
     rp, mem = W.random_groups(V, G, smin, smax, seed=V * 3 + K, cover=False)
     og = oracle_groups(V, rp, mem)
-    dg = device_groups(V, rp, mem, prepare=layout != "csr", chunk_groups=1024 if layout.endswith("1024") else 0)
+    dg = device_groups(V, rp, mem, prepare=layout != "csr", chunk_groups=4096 if layout.endswith("4096") else 0)
     total = Tally()
     lens = []
     for step in range(6):

@@ -142,7 +142,7 @@ __device__ __forceinline__ float exp_rel(float x, float M, float c_hi, float c_l
 // accept: one workgroup per sequence.
 // =============================================================================================
 
-constexpr int kAcceptThreads = 256;
+constexpr int kAcceptThreads = 1024;   // 16 waves: one per row to merge / per position to probe
 
 template <bool BF16>
 __global__ __launch_bounds__(kAcceptThreads) void accept_kernel(
@@ -201,14 +201,18 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_kernel(
   __syncthreads();
 
   // 3. sequential accept scan with early exit (Algorithm 1); the draft token stands for its
-  //    group on accept
+  //    group on accept.  The uniforms do not depend on the data, so they are drawn in parallel.
+  __shared__ float uacc[PCG_MAX_K];
+  if (threadIdx.x < K)
+    uacc[threadIdx.x] = philox_uniforms(seed, offset, (uint32_t) b, (uint32_t) threadIdx.x).acc;
+  __syncthreads();
   if (threadIdx.x == 0) {
     int32_t *otok = out_tokens + (int64_t) b * (K + 1);
     int32_t *ogrp = out_groups + (int64_t) b * (K + 1);
     uint32_t near = 0, zero_d = 0, nbad = 0;
     int i = 0;
     for (; i < K; ++i) {
-      const double u = (double) philox_uniforms(seed, offset, (uint32_t) b, (uint32_t) i).acc;
+      const double u = (double) uacc[i];
       const double T = Tp[i], D = Dp[i];
       if (bad[i]) ++nbad;
       else if (D == 0.0) ++zero_d;
@@ -236,43 +240,97 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_kernel(
 constexpr int kTableThreads = 256;
 constexpr int kTableTokens = 2048;    // tokens per workgroup
 
+constexpr int kTokensPerThread = kTableTokens / kTableThreads;   // 8 consecutive tokens
+
+// Eight consecutive logits of a row as floats; VEC: one (bf16) or two (fp32) 16-byte loads.
+template <bool BF16, bool VEC>
+__device__ __forceinline__ void load8(const void *row, int32_t t, int32_t V, float *x) {
+  if (VEC && t + 8 <= V) {
+    if constexpr (BF16) {
+      const uint4 w = *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(row) + t);
+      const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        x[2 * k] = __uint_as_float(ww[k] << 16);
+        x[2 * k + 1] = __uint_as_float(ww[k] & 0xffff0000u);
+      }
+    } else {
+      const float4 a = *reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(row) + t);
+      const float4 b = *reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(row) + t + 4);
+      x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+    }
+  } else {
+#pragma unroll
+    for (int k = 0; k < 8; ++k) x[k] = (t + k < V) ? logit_at<BF16>(row, t + k) : -INFINITY;
+  }
+}
+
+template <bool VEC>
+__device__ __forceinline__ void load8_mult(const int32_t *mult, int32_t t, int32_t V, float *m) {
+  if (VEC && t + 8 <= V) {
+    const int4 a = *reinterpret_cast<const int4 *>(mult + t);
+    const int4 b = *reinterpret_cast<const int4 *>(mult + t + 4);
+    m[0] = (float) a.x; m[1] = (float) a.y; m[2] = (float) a.z; m[3] = (float) a.w;
+    m[4] = (float) b.x; m[5] = (float) b.y; m[6] = (float) b.z; m[7] = (float) b.w;
+  } else {
+#pragma unroll
+    for (int k = 0; k < 8; ++k) m[k] = (t + k < V) ? (float) mult[t + k] : 1.f;
+  }
+}
+
+template <bool VEC>
+__device__ __forceinline__ void store8(float *out, int32_t t, int32_t V, const float *v) {
+  if (VEC && t + 8 <= V) {
+    *reinterpret_cast<float4 *>(out + t) = make_float4(v[0], v[1], v[2], v[3]);
+    *reinterpret_cast<float4 *>(out + t + 4) = make_float4(v[4], v[5], v[6], v[7]);
+  } else {
+#pragma unroll
+    for (int k = 0; k < 8; ++k)
+      if (t + k < V) out[t + k] = v[k];
+  }
+}
+
 // verify: on the decision row i* = accept_len[b] of sequence b,
 //   rejected (i* < K):  delta[t] = (q_{i*}(t) - p_{i*}(t)) / N(t)
 //   bonus    (i* = K):  delta[t] =  q_K(t) / N(t)
-template <bool BF16>
+// VEC: rows, mult and the table are 16-byte aligned and V is a multiple of 8.
+template <bool BF16, bool VEC>
 __global__ __launch_bounds__(kTableThreads) void delta_kernel(
     RowSet rs, int32_t V, int32_t K, int32_t nct, float c_hi, float c_lo, const RowStat *rowstat,
     const int32_t *mult, const int32_t *accept_len, float *table) {
   const int b = blockIdx.x / nct;
+  const int32_t t = (blockIdx.x % nct) * kTableTokens + threadIdx.x * kTokensPerThread;
+  if (t >= V) return;
   const int32_t istar = accept_len[b];
   const bool rejected = istar < K;
   const int64_t trow_id = (int64_t) b * (K + 1) + istar;
   const int64_t drow_id = rs.nrows0 + (int64_t) b * K + (rejected ? istar : 0);
   const void *trow = row_base(rs, trow_id, BF16);
   const void *drow = row_base(rs, drow_id, BF16);
+  float xt[8], xd[8], m[8], v[8];
+  load8<BF16, VEC>(trow, t, V, xt);
+  if (rejected) load8<BF16, VEC>(drow, t, V, xd);
+  load8_mult<VEC>(mult, t, V, m);
   const RowStat st = rowstat[trow_id];
   const RowStat sd = rowstat[drow_id];
   const double izt = 1.0 / st.Z, izd = rejected ? 1.0 / sd.Z : 0.0;
-  float *out = table + (int64_t) b * V;
-  const int32_t t0 = (blockIdx.x % nct) * kTableTokens;
-#pragma unroll 4
-  for (int32_t k = threadIdx.x; k < kTableTokens; k += kTableThreads) {
-    const int32_t t = t0 + k;
-    if (t >= V) break;
-    const float et = exp_rel(logit_at<BF16>(trow, t), st.M, c_hi, c_lo);
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    const float et = exp_rel(xt[k], st.M, c_hi, c_lo);
     // two rounded products and a rounded difference (no fused multiply-add), so that identical
     // target and draft rows give exactly zero
     double diff = __dmul_rn((double) et, izt);
     if (rejected) {
-      const float ed = exp_rel(logit_at<BF16>(drow, t), sd.M, c_hi, c_lo);
+      const float ed = exp_rel(xd[k], sd.M, c_hi, c_lo);
       diff = __dsub_rn(diff, __dmul_rn((double) ed, izd));
     }
-    out[t] = (float) diff / (float) mult[t];
+    v[k] = (float) diff / m[k];
   }
+  store8<VEC>(table + (int64_t) b * V, t, V, v);
 }
 
 // group_probs: w[r][t] = softmax(row r)[t] / N(t) for a batch of rows starting at row0.
-template <bool BF16>
+template <bool BF16, bool VEC>
 __global__ __launch_bounds__(kTableThreads) void weights_kernel(
     RowSet rs, int32_t V, int32_t nparts, int32_t nct, int64_t row0, float c, float c_hi,
     float c_lo, const StatPart *parts, const int32_t *mult, float *table) {
@@ -284,18 +342,18 @@ __global__ __launch_bounds__(kTableThreads) void weights_kernel(
     if (threadIdx.x == 0) sh = s;
   }
   __syncthreads();
+  const int32_t t = (blockIdx.x % nct) * kTableTokens + threadIdx.x * kTokensPerThread;
+  if (t >= V) return;
   const RowStat s = sh;
   const double iz = 1.0 / s.Z;
   const void *rowp = row_base(rs, row, BF16);
-  float *out = table + (int64_t) local * V;
-  const int32_t t0 = (blockIdx.x % nct) * kTableTokens;
-#pragma unroll 4
-  for (int32_t k = threadIdx.x; k < kTableTokens; k += kTableThreads) {
-    const int32_t t = t0 + k;
-    if (t >= V) break;
-    const float e = exp_rel(logit_at<BF16>(rowp, t), s.M, c_hi, c_lo);
-    out[t] = (float) ((double) e * iz) / (float) mult[t];
-  }
+  float x[8], m[8], v[8];
+  load8<BF16, VEC>(rowp, t, V, x);
+  load8_mult<VEC>(mult, t, V, m);
+#pragma unroll
+  for (int k = 0; k < 8; ++k)
+    v[k] = (float) ((double) exp_rel(x[k], s.M, c_hi, c_lo) * iz) / m[k];
+  store8<VEC>(table + (int64_t) local * V, t, V, v);
 }
 
 // =============================================================================================
@@ -607,6 +665,7 @@ __global__ __launch_bounds__(kFinalThreads) void finalize_kernel(
     const int32_t *row_ptr, const int32_t *members, const int32_t *mult, uint64_t seed,
     uint64_t offset, const int32_t *accept_len, float *R, const double *csum, int32_t nchunks,
     int32_t chunk_groups, int32_t *out_tokens, int32_t *out_groups, pcg_diag *diag) {
+  __shared__ __attribute__((aligned(16))) float stage[kMaxChunkGroups];
   const int b = blockIdx.x;
   const int32_t istar = accept_len[b];
   const int64_t trow_id = (int64_t) b * (K + 1) + istar;
@@ -639,9 +698,21 @@ __global__ __launch_bounds__(kFinalThreads) void finalize_kernel(
     }
     pg.index = -1; pg.total = S; pg.lo = pg.hi = 0.0;
     if (S > 0.0 && cstar >= 0) {
+      // stage the chunk in LDS with coalesced loads; the scan then reads contiguous runs
       const int32_t g0 = cstar * chunk_groups, ng = min(chunk_groups, G - g0);
-      CdfPick in = block_inverse_cdf(ng, [&](int32_t k) { return (double) fmaxf(Rb[g0 + k], 0.f); },
-                                     0.0, true, goal - base);
+      const float *Rc = Rb + g0;
+      if ((((uintptr_t) Rc | (uintptr_t) ng) & 15) == 0) {
+        for (int32_t k = threadIdx.x; k < (ng >> 2); k += kFinalThreads) {
+          const float4 v = reinterpret_cast<const float4 *>(Rc)[k];
+          reinterpret_cast<float4 *>(stage)[k] =
+              make_float4(fmaxf(v.x, 0.f), fmaxf(v.y, 0.f), fmaxf(v.z, 0.f), fmaxf(v.w, 0.f));
+        }
+      } else {
+        for (int32_t k = threadIdx.x; k < ng; k += kFinalThreads) stage[k] = fmaxf(Rc[k], 0.f);
+      }
+      __syncthreads();
+      CdfPick in = block_inverse_cdf(ng, [&](int32_t k) { return (double) stage[k]; }, 0.0, true,
+                                     goal - base);
       if (in.index >= 0) {
         pg.index = g0 + in.index; pg.lo = base + in.lo; pg.hi = base + in.hi;
       }
@@ -726,17 +797,24 @@ hipError_t launch_accept(const RowSet &rs, bool bf16, const pcg_groups &g, int32
   return hipGetLastError();
 }
 
+static inline bool table_vector_ok(const RowSet &rs, bool bf16, int32_t V, const int32_t *mult,
+                                   const float *table) {
+  return rows_vector_aligned(rs, bf16) && V % 8 == 0 && ((uintptr_t) mult & 15) == 0 &&
+         ((uintptr_t) table & 15) == 0;
+}
+
 hipError_t launch_delta(const RowSet &rs, bool bf16, const pcg_groups &g, int32_t B, int32_t K,
                         float c_hi, float c_lo, const RowStat *rowstat, const int32_t *accept_len,
                         float *table, hipStream_t stream) {
   const int32_t nct = (g.V + kTableTokens - 1) / kTableTokens;
   const dim3 grid((unsigned) ((int64_t) nct * B));
-  if (bf16)
-    delta_kernel<true><<<grid, kTableThreads, 0, stream>>>(rs, g.V, K, nct, c_hi, c_lo, rowstat,
-                                                           g.mult, accept_len, table);
-  else
-    delta_kernel<false><<<grid, kTableThreads, 0, stream>>>(rs, g.V, K, nct, c_hi, c_lo, rowstat,
-                                                            g.mult, accept_len, table);
+  const bool vec = table_vector_ok(rs, bf16, g.V, g.mult, table);
+#define PCG_LAUNCH_DELTA(BF, VE)                                                              \
+  delta_kernel<BF, VE><<<grid, kTableThreads, 0, stream>>>(rs, g.V, K, nct, c_hi, c_lo, rowstat, \
+                                                           g.mult, accept_len, table)
+  if (bf16) { if (vec) PCG_LAUNCH_DELTA(true, true); else PCG_LAUNCH_DELTA(true, false); }
+  else { if (vec) PCG_LAUNCH_DELTA(false, true); else PCG_LAUNCH_DELTA(false, false); }
+#undef PCG_LAUNCH_DELTA
   return hipGetLastError();
 }
 
@@ -746,12 +824,13 @@ hipError_t launch_weights(const RowSet &rs, bool bf16, const pcg_groups &g, int6
   const int32_t nct = (g.V + kTableTokens - 1) / kTableTokens;
   const dim3 grid((unsigned) ((int64_t) nct * nrows));
   const int32_t nparts = stats_nparts(g.V);
-  if (bf16)
-    weights_kernel<true><<<grid, kTableThreads, 0, stream>>>(rs, g.V, nparts, nct, row0, c, c_hi,
-                                                             c_lo, parts, g.mult, table);
-  else
-    weights_kernel<false><<<grid, kTableThreads, 0, stream>>>(rs, g.V, nparts, nct, row0, c, c_hi,
-                                                              c_lo, parts, g.mult, table);
+  const bool vec = table_vector_ok(rs, bf16, g.V, g.mult, table);
+#define PCG_LAUNCH_WEIGHTS(BF, VE)                                                             \
+  weights_kernel<BF, VE><<<grid, kTableThreads, 0, stream>>>(rs, g.V, nparts, nct, row0, c, c_hi, \
+                                                             c_lo, parts, g.mult, table)
+  if (bf16) { if (vec) PCG_LAUNCH_WEIGHTS(true, true); else PCG_LAUNCH_WEIGHTS(true, false); }
+  else { if (vec) PCG_LAUNCH_WEIGHTS(false, true); else PCG_LAUNCH_WEIGHTS(false, false); }
+#undef PCG_LAUNCH_WEIGHTS
   return hipGetLastError();
 }
 

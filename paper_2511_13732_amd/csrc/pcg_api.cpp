@@ -26,7 +26,7 @@ size_t align_up(size_t n) { return (n + kAlign - 1) / kAlign * kAlign; }
 // ---- per-kernel timing -------------------------------------------------------------------
 
 enum Stage { kStageStats = 0, kStageAccept, kStageTable, kStageGather, kStageFinalize, kNumStages };
-const char *const kStageNames[kNumStages] = {"row_stats", "accept", "table", "gather", "finalize"};
+const char *const kStageNames[kNumStages] = {"row_stats", "accept_delta", "weights", "gather", "finalize"};
 
 struct Profile {
   bool active = false;
@@ -115,7 +115,8 @@ size_t pcg_verify_workspace_bytes(int32_t V, int32_t G, int32_t B, int32_t K) {
   const size_t rows = (size_t) B * (2 * (size_t) K + 1);
   return align_up(rows * stats_nparts(V) * sizeof(StatPart)) + align_up(rows * sizeof(RowStat)) +
          align_up((size_t) B * V * sizeof(float)) + align_up((size_t) B * G * sizeof(float)) +
-         align_up((size_t) B * ((G + kChunkStep - 1) / kChunkStep) * sizeof(double)) + kAlign;
+         align_up((size_t) B * ((G + kChunkStep - 1) / kChunkStep) * sizeof(double)) +
+         align_up((size_t) B * sizeof(uint32_t)) + kAlign;
 }
 
 int pcg_group_probs(const pcg_groups *groups, const void *logits, pcg_dtype dt, int64_t rows,
@@ -220,6 +221,8 @@ int pcg_verify(const pcg_groups *groups, const void *target_logits, const void *
   float *R = (float *) ws;
   ws += align_up((size_t) B * groups->G * sizeof(float));
   double *csum = (double *) ws;
+  ws += align_up((size_t) B * ((groups->G + kChunkStep - 1) / kChunkStep) * sizeof(double));
+  uint32_t *arrivals = (uint32_t *) ws;
 
   RowSet rs;
   rs.base0 = target_logits;
@@ -235,22 +238,34 @@ int pcg_verify(const pcg_groups *groups, const void *target_logits, const void *
   rs.inv_npos1 = 1.0 / K;
   const Factors f = factors(temperature);
 
+  FinalizeArgs fa;
+  fa.rs = rs;
+  fa.K = K;
+  fa.cd = f.cd;
+  fa.rowstat = rowstat;
+  fa.row_ptr = groups->row_ptr;
+  fa.members = groups->members;
+  fa.mult = groups->mult;
+  fa.seed = seed;
+  fa.offset = offset;
+  fa.accept_len = accept_len;
+  fa.R = R;
+  fa.out_tokens = out_tokens;
+  fa.out_groups = out_groups;
+  fa.diag = diag;
+  fa.arrivals = arrivals;
+
   StageTimer tm(stream);
   hipError_t e;
   tm.begin(kStageStats);
   if ((e = launch_row_stats(rs, bf16, V, rows, f.c, parts, stream)) != hipSuccess) return hip_fail(e);
   tm.end(kStageStats);
   tm.begin(kStageAccept);
-  if ((e = launch_accept(rs, bf16, *groups, B, K, f.c, f.cd, parts, rowstat, prop_tokens,
-                         prop_groups, seed, offset, accept_len, out_tokens, out_groups, diag,
-                         stream)) != hipSuccess)
+  if ((e = launch_accept_delta(rs, bf16, *groups, B, K, f.c, f.c_lo, f.cd, parts, rowstat,
+                               prop_tokens, prop_groups, seed, offset, accept_len, out_tokens,
+                               out_groups, diag, arrivals, table, stream)) != hipSuccess)
     return hip_fail(e);
   tm.end(kStageAccept);
-  tm.begin(kStageTable);
-  if ((e = launch_delta(rs, bf16, *groups, B, K, f.c, f.c_lo, rowstat, accept_len, table, stream)) !=
-      hipSuccess)
-    return hip_fail(e);
-  tm.end(kStageTable);
   tm.begin(kStageGather);
   const bool prepared = groups->prepared != nullptr;
   e = prepared ? launch_gather_prepared(*groups, B, table, R, csum, stream)
@@ -258,10 +273,10 @@ int pcg_verify(const pcg_groups *groups, const void *target_logits, const void *
   if (e != hipSuccess) return hip_fail(e);
   tm.end(kStageGather);
   tm.begin(kStageFinalize);
-  if ((e = launch_finalize(rs, bf16, *groups, B, K, f.cd, rowstat, seed, offset, accept_len, R,
-                           prepared ? csum : nullptr, prepared ? groups->prepared_info->nchunks : 1,
-                           prepared ? groups->prepared_info->chunk_groups : groups->G, out_tokens,
-                           out_groups, diag, stream)) != hipSuccess)
+  if ((e = launch_finalize(fa, bf16, *groups, B, prepared ? csum : nullptr,
+                           prepared ? groups->prepared_info->nchunks : 1,
+                           prepared ? groups->prepared_info->chunk_groups : groups->G, stream)) !=
+      hipSuccess)
     return hip_fail(e);
   tm.end(kStageFinalize);
   return PCG_OK;

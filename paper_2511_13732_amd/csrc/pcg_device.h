@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "../../include/pcg.h"
+
 namespace pcg {
 
 constexpr int kWave = 64;
@@ -171,6 +173,21 @@ struct RowStat {
   double Z;
   float M;
   float pad;
+};
+
+// Everything a sequence's finalize step needs (pcg_verify only).
+struct FinalizeArgs {
+  RowSet rs;
+  int32_t K;
+  double cd;
+  const RowStat *rowstat;
+  const int32_t *row_ptr, *members, *mult;
+  uint64_t seed, offset;
+  const int32_t *accept_len;
+  float *R;
+  int32_t *out_tokens, *out_groups;
+  pcg_diag *diag;
+  uint32_t *arrivals;     // [B] workgroups of a sequence that have finished their gather
 };
 
 }  // namespace pcg

@@ -15,15 +15,15 @@ int32_t stats_nparts(int32_t V);
 hipError_t launch_row_stats(const RowSet &rs, bool bf16, int32_t V, int64_t nrows, float c,
                             StatPart *parts, hipStream_t stream);
 
-hipError_t launch_accept(const RowSet &rs, bool bf16, const pcg_groups &g, int32_t B, int32_t K,
-                         float c, double cd, const StatPart *parts, RowStat *rowstat,
-                         const int32_t *prop_tokens, const int32_t *prop_groups, uint64_t seed,
-                         uint64_t offset, int32_t *accept_len, int32_t *out_tokens,
-                         int32_t *out_groups, pcg_diag *diag, hipStream_t stream);
+int32_t accept_nsplit(int32_t V, int32_t B);
 
-hipError_t launch_delta(const RowSet &rs, bool bf16, const pcg_groups &g, int32_t B, int32_t K,
-                        float c_hi, float c_lo, const RowStat *rowstat, const int32_t *accept_len,
-                        float *table, hipStream_t stream);
+hipError_t launch_accept_delta(const RowSet &rs, bool bf16, const pcg_groups &g, int32_t B, int32_t K,
+                               float c, float c_lo, double cd, const StatPart *parts,
+                               RowStat *rowstat, const int32_t *prop_tokens,
+                               const int32_t *prop_groups, uint64_t seed, uint64_t offset,
+                               int32_t *accept_len, int32_t *out_tokens, int32_t *out_groups,
+                               pcg_diag *diag, uint32_t *arrivals, float *table,
+                               hipStream_t stream);
 
 hipError_t launch_weights(const RowSet &rs, bool bf16, const pcg_groups &g, int64_t row0,
                           int32_t nrows, float c, float c_hi, float c_lo, const StatPart *parts,
@@ -35,10 +35,8 @@ hipError_t launch_gather(const pcg_groups &g, int32_t nrows, bool clamp, const f
 hipError_t launch_gather_prepared(const pcg_groups &g, int32_t nrows, const float *table, float *out,
                                   double *csum, hipStream_t stream);
 
-hipError_t launch_finalize(const RowSet &rs, bool bf16, const pcg_groups &g, int32_t B, int32_t K,
-                           double cd, const RowStat *rowstat, uint64_t seed, uint64_t offset,
-                           const int32_t *accept_len, float *R, const double *csum, int32_t nchunks,
-                           int32_t chunk_groups, int32_t *out_tokens, int32_t *out_groups,
-                           pcg_diag *diag, hipStream_t stream);
+hipError_t launch_finalize(const FinalizeArgs &fa, bool bf16, const pcg_groups &g, int32_t B,
+                           const double *csum, int32_t nchunks, int32_t chunk_groups,
+                           hipStream_t stream);
 
 }  // namespace pcg

@@ -142,105 +142,7 @@ __device__ __forceinline__ float exp_rel(float x, float M, float c_hi, float c_l
 // accept: one workgroup per sequence.
 // =============================================================================================
 
-constexpr int kAcceptThreads = 1024;   // 16 waves: one per row to merge / per position to probe
-
-template <bool BF16>
-__global__ __launch_bounds__(kAcceptThreads) void accept_kernel(
-    RowSet rs, int32_t V, int32_t G, int32_t K, int32_t nparts, float c, double cd,
-    const StatPart *parts, RowStat *rowstat, const int32_t *row_ptr, const int32_t *members,
-    const int32_t *mult, const int32_t *prop_tokens, const int32_t *prop_groups, uint64_t seed,
-    uint64_t offset, int32_t *accept_len, int32_t *out_tokens, int32_t *out_groups,
-    pcg_diag *diag) {
-  __shared__ RowStat st_t[PCG_MAX_K + 1];
-  __shared__ RowStat st_d[PCG_MAX_K];
-  __shared__ double Tp[PCG_MAX_K], Dp[PCG_MAX_K];
-  __shared__ int bad[PCG_MAX_K];
-
-  const int b = blockIdx.x;
-  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
-  constexpr int nw = kAcceptThreads / kWave;
-  const int64_t B = rs.nrows0 / (K + 1);
-
-  // 1. row statistics of this sequence's 2K+1 rows
-  for (int r = wave; r < 2 * K + 1; r += nw) {
-    const bool is_t = r <= K;
-    const int64_t row = is_t ? (int64_t) b * (K + 1) + r : B * (K + 1) + (int64_t) b * K + (r - K - 1);
-    RowStat s = merge_row(parts, row, nparts, c, lane);
-    if (lane == 0) {
-      rowstat[row] = s;
-      if (is_t) st_t[r] = s; else st_d[r - K - 1] = s;
-    }
-  }
-  __syncthreads();
-
-  // 2. T_i[g], D_i[g] of the proposed group at every position (Eq. 5), one wave per position
-  for (int i = wave; i < K; i += nw) {
-    const int32_t g = prop_groups[(int64_t) b * K + i];
-    double at = 0.0, ad = 0.0;
-    const bool ok = g >= 0 && g < G;
-    if (ok) {
-      const void *trow = row_base(rs, (int64_t) b * (K + 1) + i, BF16);
-      const void *drow = row_base(rs, rs.nrows0 + (int64_t) b * K + i, BF16);
-      const float Mt = st_t[i].M, Md = st_d[i].M;
-      const int32_t beg = row_ptr[g], end = row_ptr[g + 1];
-      for (int32_t j = beg + lane; j < end; j += kWave) {
-        const int32_t t = members[j];
-        const double inv_m = 1.0 / (double) mult[t];
-        at += exp2((double) (logit_at<BF16>(trow, t) - Mt) * cd) * inv_m;
-        ad += exp2((double) (logit_at<BF16>(drow, t) - Md) * cd) * inv_m;
-      }
-    }
-    at = wave_sum_all(at);
-    ad = wave_sum_all(ad);
-    if (lane == 0) {
-      Tp[i] = ok ? at / st_t[i].Z : 0.0;
-      Dp[i] = ok ? ad / st_d[i].Z : 0.0;
-      bad[i] = !ok;
-    }
-  }
-  __syncthreads();
-
-  // 3. sequential accept scan with early exit (Algorithm 1); the draft token stands for its
-  //    group on accept.  The uniforms do not depend on the data, so they are drawn in parallel.
-  __shared__ float uacc[PCG_MAX_K];
-  if (threadIdx.x < K)
-    uacc[threadIdx.x] = philox_uniforms(seed, offset, (uint32_t) b, (uint32_t) threadIdx.x).acc;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    int32_t *otok = out_tokens + (int64_t) b * (K + 1);
-    int32_t *ogrp = out_groups + (int64_t) b * (K + 1);
-    uint32_t near = 0, zero_d = 0, nbad = 0;
-    int i = 0;
-    for (; i < K; ++i) {
-      const double u = (double) uacc[i];
-      const double T = Tp[i], D = Dp[i];
-      if (bad[i]) ++nbad;
-      else if (D == 0.0) ++zero_d;
-      if (fabs(u * D - T) < 1e-6 * D) ++near;
-      if (!(u * D < T)) break;
-      otok[i] = prop_tokens[(int64_t) b * K + i];
-      ogrp[i] = prop_groups[(int64_t) b * K + i];
-    }
-    accept_len[b] = i;
-    for (int k = i; k <= K; ++k) otok[k] = ogrp[k] = -1;
-    if (diag) {
-      if (near) atomicAdd(&diag->near_accept, near);
-      if (zero_d) atomicAdd(&diag->zero_draft_mass, zero_d);
-      if (nbad) atomicAdd(&diag->bad_proposal, nbad);
-      atomicAdd(&diag->accepted_total, (uint32_t) i);
-      atomicAdd(&diag->sequences, 1u);
-    }
-  }
-}
-
-// =============================================================================================
-// delta / weights: the per-token table the gather sums over.
-// =============================================================================================
-
-constexpr int kTableThreads = 256;
-constexpr int kTableTokens = 2048;    // tokens per workgroup
-
-constexpr int kTokensPerThread = kTableTokens / kTableThreads;   // 8 consecutive tokens
+constexpr int kTokensPerThread = 8;    // consecutive tokens a thread of the table kernels handles
 
 // Eight consecutive logits of a row as floats; VEC: one (bf16) or two (fp32) 16-byte loads.
 template <bool BF16, bool VEC>
@@ -290,44 +192,149 @@ __device__ __forceinline__ void store8(float *out, int32_t t, int32_t V, const f
   }
 }
 
-// verify: on the decision row i* = accept_len[b] of sequence b,
+constexpr int kAcceptThreads = 1024;   // 16 waves: one per row to merge / per position to probe
+constexpr int kAcceptTokens = kAcceptThreads * kTokensPerThread;   // delta tokens per workgroup
+
+// accept + delta.  Workgroup (b, s) runs the whole accept scan of sequence b -- every one of
+// the sequence's workgroups does, so that none has to wait for another -- and then writes slice
+// s of the table the gather sums over, on the decision row i* = accept_len[b]:
 //   rejected (i* < K):  delta[t] = (q_{i*}(t) - p_{i*}(t)) / N(t)
 //   bonus    (i* = K):  delta[t] =  q_K(t) / N(t)
+// Slice 0 also writes the sequence's outputs, row statistics and counters.
 // VEC: rows, mult and the table are 16-byte aligned and V is a multiple of 8.
 template <bool BF16, bool VEC>
-__global__ __launch_bounds__(kTableThreads) void delta_kernel(
-    RowSet rs, int32_t V, int32_t K, int32_t nct, float c_hi, float c_lo, const RowStat *rowstat,
-    const int32_t *mult, const int32_t *accept_len, float *table) {
-  const int b = blockIdx.x / nct;
-  const int32_t t = (blockIdx.x % nct) * kTableTokens + threadIdx.x * kTokensPerThread;
-  if (t >= V) return;
-  const int32_t istar = accept_len[b];
-  const bool rejected = istar < K;
-  const int64_t trow_id = (int64_t) b * (K + 1) + istar;
-  const int64_t drow_id = rs.nrows0 + (int64_t) b * K + (rejected ? istar : 0);
-  const void *trow = row_base(rs, trow_id, BF16);
-  const void *drow = row_base(rs, drow_id, BF16);
-  float xt[8], xd[8], m[8], v[8];
-  load8<BF16, VEC>(trow, t, V, xt);
-  if (rejected) load8<BF16, VEC>(drow, t, V, xd);
-  load8_mult<VEC>(mult, t, V, m);
-  const RowStat st = rowstat[trow_id];
-  const RowStat sd = rowstat[drow_id];
-  const double izt = 1.0 / st.Z, izd = rejected ? 1.0 / sd.Z : 0.0;
-#pragma unroll
-  for (int k = 0; k < 8; ++k) {
-    const float et = exp_rel(xt[k], st.M, c_hi, c_lo);
-    // two rounded products and a rounded difference (no fused multiply-add), so that identical
-    // target and draft rows give exactly zero
-    double diff = __dmul_rn((double) et, izt);
-    if (rejected) {
-      const float ed = exp_rel(xd[k], sd.M, c_hi, c_lo);
-      diff = __dsub_rn(diff, __dmul_rn((double) ed, izd));
+__global__ __launch_bounds__(kAcceptThreads) void accept_delta_kernel(
+    RowSet rs, int32_t V, int32_t G, int32_t K, int32_t nparts, int32_t nsplit, float c, float c_lo,
+    double cd, const StatPart *parts, RowStat *rowstat, const int32_t *row_ptr,
+    const int32_t *members, const int32_t *mult, const int32_t *prop_tokens,
+    const int32_t *prop_groups, uint64_t seed, uint64_t offset, int32_t *accept_len,
+    int32_t *out_tokens, int32_t *out_groups, pcg_diag *diag, uint32_t *arrivals, float *table) {
+  __shared__ RowStat st_t[PCG_MAX_K + 1];
+  __shared__ RowStat st_d[PCG_MAX_K];
+  __shared__ double Tp[PCG_MAX_K], Dp[PCG_MAX_K];
+  __shared__ int bad[PCG_MAX_K];
+  __shared__ float uacc[PCG_MAX_K];
+  __shared__ int istar_s;
+
+  const int b = blockIdx.x / nsplit;
+  const int split = blockIdx.x % nsplit;
+  const bool writer = split == 0;
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+  constexpr int nw = kAcceptThreads / kWave;
+  const int64_t B = rs.nrows0 / (K + 1);
+
+  // 1. row statistics of this sequence's 2K+1 rows
+  for (int r = wave; r < 2 * K + 1; r += nw) {
+    const bool is_t = r <= K;
+    const int64_t row = is_t ? (int64_t) b * (K + 1) + r : B * (K + 1) + (int64_t) b * K + (r - K - 1);
+    RowStat s = merge_row(parts, row, nparts, c, lane);
+    if (lane == 0) {
+      if (writer) rowstat[row] = s;
+      if (is_t) st_t[r] = s; else st_d[r - K - 1] = s;
     }
-    v[k] = (float) diff / m[k];
   }
-  store8<VEC>(table + (int64_t) b * V, t, V, v);
+  if (threadIdx.x < K)   // the uniforms do not depend on the data
+    uacc[threadIdx.x] = philox_uniforms(seed, offset, (uint32_t) b, (uint32_t) threadIdx.x).acc;
+  __syncthreads();
+
+  // 2. T_i[g], D_i[g] of the proposed group at every position (Eq. 5), one wave per position
+  for (int i = wave; i < K; i += nw) {
+    const int32_t g = prop_groups[(int64_t) b * K + i];
+    double at = 0.0, ad = 0.0;
+    const bool ok = g >= 0 && g < G;
+    if (ok) {
+      const void *trow = row_base(rs, (int64_t) b * (K + 1) + i, BF16);
+      const void *drow = row_base(rs, rs.nrows0 + (int64_t) b * K + i, BF16);
+      const float Mt = st_t[i].M, Md = st_d[i].M;
+      const int32_t beg = row_ptr[g], end = row_ptr[g + 1];
+      for (int32_t j = beg + lane; j < end; j += kWave) {
+        const int32_t t = members[j];
+        const double inv_m = 1.0 / (double) mult[t];
+        at += exp2((double) (logit_at<BF16>(trow, t) - Mt) * cd) * inv_m;
+        ad += exp2((double) (logit_at<BF16>(drow, t) - Md) * cd) * inv_m;
+      }
+    }
+    at = wave_sum_all(at);
+    ad = wave_sum_all(ad);
+    if (lane == 0) {
+      Tp[i] = ok ? at / st_t[i].Z : 0.0;
+      Dp[i] = ok ? ad / st_d[i].Z : 0.0;
+      bad[i] = !ok;
+    }
+  }
+  __syncthreads();
+
+  // 3. sequential accept scan with early exit (Algorithm 1); the draft token stands for its
+  //    group on accept
+  if (threadIdx.x == 0) {
+    uint32_t near = 0, zero_d = 0, nbad = 0;
+    int i = 0;
+    for (; i < K; ++i) {
+      const double u = (double) uacc[i];
+      const double T = Tp[i], D = Dp[i];
+      if (bad[i]) ++nbad;
+      else if (D == 0.0) ++zero_d;
+      if (fabs(u * D - T) < 1e-6 * D) ++near;
+      if (!(u * D < T)) break;
+    }
+    istar_s = i;
+    if (writer) {
+      int32_t *otok = out_tokens + (int64_t) b * (K + 1);
+      int32_t *ogrp = out_groups + (int64_t) b * (K + 1);
+      for (int k = 0; k < i; ++k) {
+        otok[k] = prop_tokens[(int64_t) b * K + k];
+        ogrp[k] = prop_groups[(int64_t) b * K + k];
+      }
+      for (int k = i; k <= K; ++k) otok[k] = ogrp[k] = -1;
+      accept_len[b] = i;
+      arrivals[b] = 0;
+      if (diag) {
+        if (near) atomicAdd(&diag->near_accept, near);
+        if (zero_d) atomicAdd(&diag->zero_draft_mass, zero_d);
+        if (nbad) atomicAdd(&diag->bad_proposal, nbad);
+        atomicAdd(&diag->accepted_total, (uint32_t) i);
+        atomicAdd(&diag->sequences, 1u);
+      }
+    }
+  }
+  __syncthreads();
+
+  // 4. this workgroup's share of the table on the decision row: slices split, split + nsplit, ...
+  const int32_t istar = istar_s;
+  const bool rejected = istar < K;
+  const void *trow = row_base(rs, (int64_t) b * (K + 1) + istar, BF16);
+  const void *drow = row_base(rs, rs.nrows0 + (int64_t) b * K + (rejected ? istar : 0), BF16);
+  const RowStat st = st_t[istar];
+  const RowStat sd = st_d[rejected ? istar : 0];
+  const double izt = 1.0 / st.Z, izd = rejected ? 1.0 / sd.Z : 0.0;
+  for (int32_t t = split * kAcceptTokens + threadIdx.x * kTokensPerThread; t < V;
+       t += nsplit * kAcceptTokens) {
+    float xt[8], xd[8], m[8], v[8];
+    load8<BF16, VEC>(trow, t, V, xt);
+    if (rejected) load8<BF16, VEC>(drow, t, V, xd);
+    load8_mult<VEC>(mult, t, V, m);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const float et = exp_rel(xt[k], st.M, c, c_lo);
+      // two rounded products and a rounded difference (no fused multiply-add), so that
+      // identical target and draft rows give exactly zero
+      double diff = __dmul_rn((double) et, izt);
+      if (rejected) {
+        const float ed = exp_rel(xd[k], sd.M, c, c_lo);
+        diff = __dsub_rn(diff, __dmul_rn((double) ed, izd));
+      }
+      v[k] = (float) diff / m[k];
+    }
+    store8<VEC>(table + (int64_t) b * V, t, V, v);
+  }
 }
+
+// =============================================================================================
+// weights: the per-token table of pcg_group_probs.
+// =============================================================================================
+
+constexpr int kTableThreads = 256;
+constexpr int kTableTokens = kTableThreads * kTokensPerThread;    // tokens per workgroup
 
 // group_probs: w[r][t] = softmax(row r)[t] / N(t) for a batch of rows starting at row0.
 template <bool BF16, bool VEC>
@@ -410,6 +417,190 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
   }
 }
 
+// =============================================================================================
+// finalize: group from the residual by inverse CDF, then the token inside it (Eq. 10).
+// =============================================================================================
+
+constexpr int kFinalThreads = 512;
+
+struct CdfPick {
+  int32_t index;    // first index whose running sum exceeds the threshold; -1 if nothing has mass
+  double total, lo, hi;   // total mass; running sum before / after the chosen bin
+};
+
+// Inverse CDF over f(0..n-1) >= 0 by a whole workgroup of NT threads.  Each thread owns a
+// contiguous run, so the running sum is the ascending one up to fp64 rounding.  All threads get
+// the result.  The threshold is u * total, or `goal_in` (relative to this range) with have_goal.
+template <int NT, typename F>
+__device__ CdfPick block_inverse_cdf(int32_t n, F f, double u, bool have_goal = false,
+                                     double goal_in = 0.0) {
+  __shared__ double wave_tot[NT / kWave];
+  __shared__ int first_thread, last_pos;
+  __shared__ CdfPick res;
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+  const int32_t run = (n + NT - 1) / NT;
+  const int32_t lo_i = min(n, tid * run), hi_i = min(n, lo_i + run);
+  if (tid == 0) { first_thread = INT_MAX; last_pos = -1; }
+  double mine = 0.0;
+  int32_t my_last = -1;
+  for (int32_t k = lo_i; k < hi_i; ++k) {
+    const double v = f(k);
+    if (v > 0.0) { mine += v; my_last = k; }
+  }
+  // inclusive scan inside the wave, then across waves
+  double inc = mine;
+#pragma unroll
+  for (int o = 1; o < kWave; o <<= 1) {
+    const double up = __shfl_up(inc, o, kWave);
+    if (lane >= o) inc += up;
+  }
+  if (lane == kWave - 1) wave_tot[wave] = inc;
+  __syncthreads();
+  double before = 0.0, total = 0.0;
+  for (int w = 0; w < NT / kWave; ++w) {
+    if (w < wave) before += wave_tot[w];
+    total += wave_tot[w];
+  }
+  const double excl = before + (inc - mine);
+  const double goal = have_goal ? goal_in : u * total;
+  if (mine > 0.0 && excl + mine > goal) atomicMin(&first_thread, tid);
+  if (my_last >= 0) atomicMax(&last_pos, my_last);
+  __syncthreads();
+  if (first_thread == tid) {
+    double cum = excl;
+    for (int32_t k = lo_i; k < hi_i; ++k) {
+      const double v = f(k);
+      if (!(v > 0.0)) continue;
+      const double nxt = cum + v;
+      if (nxt > goal || k == my_last) {   // k == my_last: guaranteed by excl + mine > goal
+        res.index = k; res.lo = cum; res.hi = nxt; res.total = total;
+        break;
+      }
+      cum = nxt;
+    }
+  } else if (first_thread == INT_MAX && tid == 0) {
+    // rounding at the top end (or no mass at all): the last index that has mass
+    res.index = last_pos; res.total = total; res.lo = total; res.hi = total;
+    if (last_pos >= 0) res.lo = total - f(last_pos);
+  }
+  __syncthreads();
+  CdfPick out = res;
+  __syncthreads();   // res / first_thread may be reused by the next call
+  return out;
+}
+
+__device__ __forceinline__ bool near_edge(const CdfPick &p, double u) {
+  const double goal = u * p.total;
+  const bool near_lo = p.lo > 0.0 && (goal - p.lo) < 1e-6 * p.total;
+  const bool near_hi = p.hi < p.total && (p.hi - goal) < 1e-6 * p.total;
+  return near_lo || near_hi;
+}
+
+// The last step of a sequence, by one whole workgroup of NT threads.  R holds the gathered sums
+// T[g] - D[g] (T[g] on a bonus row), clamped here on read.  With csum != NULL it also has the
+// totals of max(0, R) over chunks of chunk_groups consecutive groups, so only the chunk that
+// holds the draw is scanned, from `stage` (LDS, room for one chunk); staged_chunk >= 0 says that
+// chunk's R values are in `stage` already.
+template <bool BF16, int NT>
+__device__ void finalize_sequence(const FinalizeArgs &fa, int32_t V, int32_t G, int b,
+                                  const double *csum, int32_t nchunks, int32_t chunk_groups,
+                                  float *stage, int32_t staged_chunk) {
+  const int32_t K = fa.K;
+  const int32_t istar = fa.accept_len[b];
+  const int64_t trow_id = (int64_t) b * (K + 1) + istar;
+  const void *trow = row_base(fa.rs, trow_id, BF16);
+  const RowStat st = fa.rowstat[trow_id];
+  const Uniforms u = philox_uniforms(fa.seed, fa.offset, (uint32_t) b, (uint32_t) istar);
+  float *Rb = fa.R + (int64_t) b * G;
+  const int32_t *row_ptr = fa.row_ptr, *members = fa.members, *mult = fa.mult;
+  const double cd = fa.cd;
+
+  // q(t) / N(t) on the decision row, in double
+  auto weight = [&](int32_t t) -> double {
+    return exp2((double) (logit_at<BF16>(trow, t) - st.M) * cd) / (st.Z * (double) mult[t]);
+  };
+
+  CdfPick pg;
+  if (csum) {
+    // residual total and the chunk that holds u * total, from the per-chunk sums (ascending)
+    const double *cs = csum + (int64_t) b * nchunks;
+    double S = 0.0;
+    for (int32_t c = 0; c < nchunks; ++c) S += cs[c];
+    const double goal = (double) u.grp * S;
+    double cum = 0.0, base = 0.0;
+    int32_t cstar = -1;
+    for (int32_t c = 0; c < nchunks; ++c) {
+      const double v = cs[c];
+      if (!(v > 0.0)) continue;
+      cstar = c;
+      base = cum;
+      if (cum + v > goal) break;
+      cum += v;
+    }
+    pg.index = -1; pg.total = S; pg.lo = pg.hi = 0.0;
+    if (S > 0.0 && cstar >= 0) {
+      const int32_t g0 = cstar * chunk_groups, ng = min(chunk_groups, G - g0);
+      if (cstar != staged_chunk) {
+        // stage the chunk in LDS with coalesced loads; the scan then reads contiguous runs
+        __syncthreads();
+        const float *Rc = Rb + g0;
+        if ((((uintptr_t) Rc | (uintptr_t) ng) & 15) == 0) {
+          for (int32_t k = threadIdx.x; k < (ng >> 2); k += NT)
+            reinterpret_cast<float4 *>(stage)[k] = reinterpret_cast<const float4 *>(Rc)[k];
+        } else {
+          for (int32_t k = threadIdx.x; k < ng; k += NT) stage[k] = Rc[k];
+        }
+        __syncthreads();
+      }
+      CdfPick in = block_inverse_cdf<NT>(
+          ng, [&](int32_t k) { return (double) fmaxf(stage[k], 0.f); }, 0.0, true, goal - base);
+      if (in.index >= 0) {
+        pg.index = g0 + in.index; pg.lo = base + in.lo; pg.hi = base + in.hi;
+      }
+    }
+  } else {
+    pg = block_inverse_cdf<NT>(G, [&](int32_t g) { return (double) fmaxf(Rb[g], 0.f); },
+                               (double) u.grp);
+  }
+  bool fallback = false;
+  if (!(pg.total > 0.0) || pg.index < 0) {
+    // Residual total <= 0 (cannot happen in exact arithmetic): draw from T of this row instead.
+    fallback = true;
+    for (int32_t g = threadIdx.x; g < G; g += NT) {
+      double s = 0.0;
+      for (int32_t j = row_ptr[g]; j < row_ptr[g + 1]; ++j) s += weight(members[j]);
+      Rb[g] = (float) s;
+    }
+    __syncthreads();
+    pg = block_inverse_cdf<NT>(G, [&](int32_t g) { return (double) Rb[g]; }, (double) u.grp);
+  }
+  const int32_t gs = pg.index < 0 ? 0 : pg.index;
+
+  const int32_t beg = row_ptr[gs], end = row_ptr[gs + 1];
+  CdfPick pt = block_inverse_cdf<NT>(
+      end - beg, [&](int32_t j) { return weight(members[beg + j]); }, (double) u.tok);
+  if (threadIdx.x == 0) {
+    fa.out_groups[(int64_t) b * (K + 1) + istar] = gs;
+    fa.out_tokens[(int64_t) b * (K + 1) + istar] = pt.index < 0 ? -1 : members[beg + pt.index];
+    if (fa.diag) {
+      if (pg.index >= 0 && near_edge(pg, (double) u.grp)) atomicAdd(&fa.diag->near_group, 1u);
+      if (pt.index >= 0 && near_edge(pt, (double) u.tok)) atomicAdd(&fa.diag->near_token, 1u);
+      if (fallback) atomicAdd(&fa.diag->residual_fallback, 1u);
+    }
+  }
+}
+
+// One workgroup per sequence.  csum / nchunks / chunk_groups describe the chunk totals the
+// prepared gather wrote (csum == NULL after the CSR gather: the whole range is scanned).
+template <bool BF16>
+__global__ __launch_bounds__(kFinalThreads) void finalize_kernel(FinalizeArgs fa, int32_t V,
+                                                                 int32_t G, const double *csum,
+                                                                 int32_t nchunks,
+                                                                 int32_t chunk_groups) {
+  __shared__ __attribute__((aligned(16))) float stage[kMaxChunkGroups];
+  finalize_sequence<BF16, kFinalThreads>(fa, V, G, blockIdx.x, csum, nchunks, chunk_groups, stage, -1);
+}
+
 // ---------------------------------------------------------------------------------------------
 // The same sum read from the prepared layout (pcg_prepared): no cross-lane reduction and no
 // address arithmetic beyond a shift.  A workgroup owns one chunk of consecutive groups of one
@@ -481,7 +672,7 @@ __global__ __launch_bounds__(kGatherThreads) void gather_prepared_kernel(
     int32_t tile_len, int32_t bpc, const uint32_t *__restrict__ desc,
     const uint16_t *__restrict__ perm, const uint4 *__restrict__ data,
     const float *__restrict__ table, float *__restrict__ out, double *__restrict__ csum) {
-  __shared__ float tab[kTileMax];
+  __shared__ __attribute__((aligned(16))) float tab[kTileMax];
   __shared__ double wsum[kGatherWaves];
   const int xcd = blockIdx.x & 7;
   const int y = blockIdx.x >> 3;
@@ -578,177 +769,6 @@ __global__ __launch_bounds__(kGatherThreads) void gather_prepared_kernel(
 }
 
 // =============================================================================================
-// finalize: group from the residual by inverse CDF, then the token inside it (Eq. 10).
-// =============================================================================================
-
-constexpr int kFinalThreads = 512;
-
-struct CdfPick {
-  int32_t index;    // first index whose running sum exceeds u * total; -1 if nothing has mass
-  double total, lo, hi;   // total mass; running sum before / after the chosen bin
-};
-
-// Inverse CDF over f(0..n-1) >= 0 by the whole workgroup.  Each thread owns a contiguous run,
-// so the running sum is the ascending one up to fp64 rounding.  All threads get the result.
-// With have_goal the threshold is `goal` (already relative to this range) instead of u * total.
-template <typename F>
-__device__ CdfPick block_inverse_cdf(int32_t n, F f, double u, bool have_goal = false,
-                                     double goal_in = 0.0) {
-  __shared__ double wave_tot[kFinalThreads / kWave];
-  __shared__ int first_thread, last_pos;
-  __shared__ CdfPick res;
-  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
-  const int32_t run = (n + kFinalThreads - 1) / kFinalThreads;
-  const int32_t lo_i = min(n, tid * run), hi_i = min(n, lo_i + run);
-  if (tid == 0) { first_thread = INT_MAX; last_pos = -1; }
-  double mine = 0.0;
-  int32_t my_last = -1;
-  for (int32_t k = lo_i; k < hi_i; ++k) {
-    const double v = f(k);
-    if (v > 0.0) { mine += v; my_last = k; }
-  }
-  // inclusive scan inside the wave, then across waves
-  double inc = mine;
-#pragma unroll
-  for (int o = 1; o < kWave; o <<= 1) {
-    const double up = __shfl_up(inc, o, kWave);
-    if (lane >= o) inc += up;
-  }
-  if (lane == kWave - 1) wave_tot[wave] = inc;
-  __syncthreads();
-  double before = 0.0, total = 0.0;
-  for (int w = 0; w < kFinalThreads / kWave; ++w) {
-    if (w < wave) before += wave_tot[w];
-    total += wave_tot[w];
-  }
-  const double excl = before + (inc - mine);
-  const double goal = have_goal ? goal_in : u * total;
-  if (mine > 0.0 && excl + mine > goal) atomicMin(&first_thread, tid);
-  if (my_last >= 0) atomicMax(&last_pos, my_last);
-  __syncthreads();
-  if (first_thread == tid) {
-    double cum = excl;
-    for (int32_t k = lo_i; k < hi_i; ++k) {
-      const double v = f(k);
-      if (!(v > 0.0)) continue;
-      const double nxt = cum + v;
-      if (nxt > goal || k == my_last) {   // k == my_last: guaranteed by excl + mine > goal
-        res.index = k; res.lo = cum; res.hi = nxt; res.total = total;
-        break;
-      }
-      cum = nxt;
-    }
-  } else if (first_thread == INT_MAX && tid == 0) {
-    // rounding at the top end (or no mass at all): the last index that has mass
-    res.index = last_pos; res.total = total; res.lo = total; res.hi = total;
-    if (last_pos >= 0) res.lo = total - f(last_pos);
-  }
-  __syncthreads();
-  CdfPick out = res;
-  __syncthreads();   // res / first_thread may be reused by the next call
-  return out;
-}
-
-__device__ __forceinline__ bool near_edge(const CdfPick &p, double u) {
-  const double goal = u * p.total;
-  const bool near_lo = p.lo > 0.0 && (goal - p.lo) < 1e-6 * p.total;
-  const bool near_hi = p.hi < p.total && (p.hi - goal) < 1e-6 * p.total;
-  return near_lo || near_hi;
-}
-
-// R holds the gathered sums T[g] - D[g] (T[g] on a bonus row), clamped here on read.  With
-// csum != NULL it also has the totals of max(0, R) over chunks of chunk_groups consecutive
-// groups, so only the chunk that holds the draw is scanned.
-template <bool BF16>
-__global__ __launch_bounds__(kFinalThreads) void finalize_kernel(
-    RowSet rs, int32_t V, int32_t G, int32_t K, double cd, const RowStat *rowstat,
-    const int32_t *row_ptr, const int32_t *members, const int32_t *mult, uint64_t seed,
-    uint64_t offset, const int32_t *accept_len, float *R, const double *csum, int32_t nchunks,
-    int32_t chunk_groups, int32_t *out_tokens, int32_t *out_groups, pcg_diag *diag) {
-  __shared__ __attribute__((aligned(16))) float stage[kMaxChunkGroups];
-  const int b = blockIdx.x;
-  const int32_t istar = accept_len[b];
-  const int64_t trow_id = (int64_t) b * (K + 1) + istar;
-  const void *trow = row_base(rs, trow_id, BF16);
-  const RowStat st = rowstat[trow_id];
-  const Uniforms u = philox_uniforms(seed, offset, (uint32_t) b, (uint32_t) istar);
-  float *Rb = R + (int64_t) b * G;
-
-  // q(t) / N(t) on the decision row, in double
-  auto weight = [&](int32_t t) -> double {
-    return exp2((double) (logit_at<BF16>(trow, t) - st.M) * cd) / (st.Z * (double) mult[t]);
-  };
-
-  CdfPick pg;
-  if (csum) {
-    // residual total and the chunk that holds u * total, from the per-chunk sums (ascending)
-    const double *cs = csum + (int64_t) b * nchunks;
-    double S = 0.0;
-    for (int32_t c = 0; c < nchunks; ++c) S += cs[c];
-    const double goal = (double) u.grp * S;
-    double cum = 0.0, base = 0.0;
-    int32_t cstar = -1;
-    for (int32_t c = 0; c < nchunks; ++c) {
-      const double v = cs[c];
-      if (!(v > 0.0)) continue;
-      cstar = c;
-      base = cum;
-      if (cum + v > goal) break;
-      cum += v;
-    }
-    pg.index = -1; pg.total = S; pg.lo = pg.hi = 0.0;
-    if (S > 0.0 && cstar >= 0) {
-      // stage the chunk in LDS with coalesced loads; the scan then reads contiguous runs
-      const int32_t g0 = cstar * chunk_groups, ng = min(chunk_groups, G - g0);
-      const float *Rc = Rb + g0;
-      if ((((uintptr_t) Rc | (uintptr_t) ng) & 15) == 0) {
-        for (int32_t k = threadIdx.x; k < (ng >> 2); k += kFinalThreads) {
-          const float4 v = reinterpret_cast<const float4 *>(Rc)[k];
-          reinterpret_cast<float4 *>(stage)[k] =
-              make_float4(fmaxf(v.x, 0.f), fmaxf(v.y, 0.f), fmaxf(v.z, 0.f), fmaxf(v.w, 0.f));
-        }
-      } else {
-        for (int32_t k = threadIdx.x; k < ng; k += kFinalThreads) stage[k] = fmaxf(Rc[k], 0.f);
-      }
-      __syncthreads();
-      CdfPick in = block_inverse_cdf(ng, [&](int32_t k) { return (double) stage[k]; }, 0.0, true,
-                                     goal - base);
-      if (in.index >= 0) {
-        pg.index = g0 + in.index; pg.lo = base + in.lo; pg.hi = base + in.hi;
-      }
-    }
-  } else {
-    pg = block_inverse_cdf(G, [&](int32_t g) { return (double) fmaxf(Rb[g], 0.f); }, (double) u.grp);
-  }
-  bool fallback = false;
-  if (!(pg.total > 0.0) || pg.index < 0) {
-    // Residual total <= 0 (cannot happen in exact arithmetic): draw from T of this row instead.
-    fallback = true;
-    for (int32_t g = threadIdx.x; g < G; g += kFinalThreads) {
-      double s = 0.0;
-      for (int32_t j = row_ptr[g]; j < row_ptr[g + 1]; ++j) s += weight(members[j]);
-      Rb[g] = (float) s;
-    }
-    __syncthreads();
-    pg = block_inverse_cdf(G, [&](int32_t g) { return (double) Rb[g]; }, (double) u.grp);
-  }
-  const int32_t gs = pg.index < 0 ? 0 : pg.index;
-
-  const int32_t beg = row_ptr[gs], end = row_ptr[gs + 1];
-  CdfPick pt = block_inverse_cdf(end - beg, [&](int32_t j) { return weight(members[beg + j]); },
-                                 (double) u.tok);
-  if (threadIdx.x == 0) {
-    out_groups[(int64_t) b * (K + 1) + istar] = gs;
-    out_tokens[(int64_t) b * (K + 1) + istar] = pt.index < 0 ? -1 : members[beg + pt.index];
-    if (diag) {
-      if (pg.index >= 0 && near_edge(pg, (double) u.grp)) atomicAdd(&diag->near_group, 1u);
-      if (pt.index >= 0 && near_edge(pt, (double) u.tok)) atomicAdd(&diag->near_token, 1u);
-      if (fallback) atomicAdd(&diag->residual_fallback, 1u);
-    }
-  }
-}
-
-// =============================================================================================
 // Launchers.
 // =============================================================================================
 
@@ -780,41 +800,37 @@ hipError_t launch_row_stats(const RowSet &rs, bool bf16, int32_t V, int64_t nrow
   return hipGetLastError();
 }
 
-hipError_t launch_accept(const RowSet &rs, bool bf16, const pcg_groups &g, int32_t B, int32_t K,
-                         float c, double cd, const StatPart *parts, RowStat *rowstat,
-                         const int32_t *prop_tokens, const int32_t *prop_groups, uint64_t seed,
-                         uint64_t offset, int32_t *accept_len, int32_t *out_tokens,
-                         int32_t *out_groups, pcg_diag *diag, hipStream_t stream) {
-  const int32_t nparts = stats_nparts(g.V);
-  if (bf16)
-    accept_kernel<true><<<B, kAcceptThreads, 0, stream>>>(
-        rs, g.V, g.G, K, nparts, c, cd, parts, rowstat, g.row_ptr, g.members, g.mult, prop_tokens,
-        prop_groups, seed, offset, accept_len, out_tokens, out_groups, diag);
-  else
-    accept_kernel<false><<<B, kAcceptThreads, 0, stream>>>(
-        rs, g.V, g.G, K, nparts, c, cd, parts, rowstat, g.row_ptr, g.members, g.mult, prop_tokens,
-        prop_groups, seed, offset, accept_len, out_tokens, out_groups, diag);
-  return hipGetLastError();
-}
-
 static inline bool table_vector_ok(const RowSet &rs, bool bf16, int32_t V, const int32_t *mult,
                                    const float *table) {
   return rows_vector_aligned(rs, bf16) && V % 8 == 0 && ((uintptr_t) mult & 15) == 0 &&
          ((uintptr_t) table & 15) == 0;
 }
 
-hipError_t launch_delta(const RowSet &rs, bool bf16, const pcg_groups &g, int32_t B, int32_t K,
-                        float c_hi, float c_lo, const RowStat *rowstat, const int32_t *accept_len,
-                        float *table, hipStream_t stream) {
-  const int32_t nct = (g.V + kTableTokens - 1) / kTableTokens;
-  const dim3 grid((unsigned) ((int64_t) nct * B));
+// Workgroups per sequence in the accept + delta kernel: enough to give every compute unit one,
+// never more than there are slices of the table.
+int32_t accept_nsplit(int32_t V, int32_t B) {
+  const int32_t slices = (V + kAcceptTokens - 1) / kAcceptTokens;
+  return std::max(1, std::min(slices, (256 + B - 1) / B));
+}
+
+hipError_t launch_accept_delta(const RowSet &rs, bool bf16, const pcg_groups &g, int32_t B, int32_t K,
+                               float c, float c_lo, double cd, const StatPart *parts,
+                               RowStat *rowstat, const int32_t *prop_tokens,
+                               const int32_t *prop_groups, uint64_t seed, uint64_t offset,
+                               int32_t *accept_len, int32_t *out_tokens, int32_t *out_groups,
+                               pcg_diag *diag, uint32_t *arrivals, float *table,
+                               hipStream_t stream) {
+  const int32_t nparts = stats_nparts(g.V), nsplit = accept_nsplit(g.V, B);
+  const dim3 grid((unsigned) ((int64_t) B * nsplit));
   const bool vec = table_vector_ok(rs, bf16, g.V, g.mult, table);
-#define PCG_LAUNCH_DELTA(BF, VE)                                                              \
-  delta_kernel<BF, VE><<<grid, kTableThreads, 0, stream>>>(rs, g.V, K, nct, c_hi, c_lo, rowstat, \
-                                                           g.mult, accept_len, table)
-  if (bf16) { if (vec) PCG_LAUNCH_DELTA(true, true); else PCG_LAUNCH_DELTA(true, false); }
-  else { if (vec) PCG_LAUNCH_DELTA(false, true); else PCG_LAUNCH_DELTA(false, false); }
-#undef PCG_LAUNCH_DELTA
+#define PCG_LAUNCH_AD(BF, VE)                                                                   \
+  accept_delta_kernel<BF, VE><<<grid, kAcceptThreads, 0, stream>>>(                             \
+      rs, g.V, g.G, K, nparts, nsplit, c, c_lo, cd, parts, rowstat, g.row_ptr, g.members, g.mult, \
+      prop_tokens, prop_groups, seed, offset, accept_len, out_tokens, out_groups, diag, arrivals, \
+      table)
+  if (bf16) { if (vec) PCG_LAUNCH_AD(true, true); else PCG_LAUNCH_AD(true, false); }
+  else { if (vec) PCG_LAUNCH_AD(false, true); else PCG_LAUNCH_AD(false, false); }
+#undef PCG_LAUNCH_AD
   return hipGetLastError();
 }
 
@@ -900,19 +916,13 @@ hipError_t launch_gather_prepared(const pcg_groups &g, int32_t nrows, const floa
   return hipGetLastError();
 }
 
-hipError_t launch_finalize(const RowSet &rs, bool bf16, const pcg_groups &g, int32_t B, int32_t K,
-                           double cd, const RowStat *rowstat, uint64_t seed, uint64_t offset,
-                           const int32_t *accept_len, float *R, const double *csum, int32_t nchunks,
-                           int32_t chunk_groups, int32_t *out_tokens, int32_t *out_groups,
-                           pcg_diag *diag, hipStream_t stream) {
+hipError_t launch_finalize(const FinalizeArgs &fa, bool bf16, const pcg_groups &g, int32_t B,
+                           const double *csum, int32_t nchunks, int32_t chunk_groups,
+                           hipStream_t stream) {
   if (bf16)
-    finalize_kernel<true><<<B, kFinalThreads, 0, stream>>>(
-        rs, g.V, g.G, K, cd, rowstat, g.row_ptr, g.members, g.mult, seed, offset, accept_len, R,
-        csum, nchunks, chunk_groups, out_tokens, out_groups, diag);
+    finalize_kernel<true><<<B, kFinalThreads, 0, stream>>>(fa, g.V, g.G, csum, nchunks, chunk_groups);
   else
-    finalize_kernel<false><<<B, kFinalThreads, 0, stream>>>(
-        rs, g.V, g.G, K, cd, rowstat, g.row_ptr, g.members, g.mult, seed, offset, accept_len, R,
-        csum, nchunks, chunk_groups, out_tokens, out_groups, diag);
+    finalize_kernel<false><<<B, kFinalThreads, 0, stream>>>(fa, g.V, g.G, csum, nchunks, chunk_groups);
   return hipGetLastError();
 }
 

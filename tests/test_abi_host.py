@@ -153,7 +153,7 @@ def test_profile_calls_are_guarded():
     assert L.pcg_profile_end(ms, C.byref(n)) == BAD_SHAPE      # nothing was begun
     assert L.pcg_profile_begin(0) == BAD_SHAPE
     assert [pcg.lib().pcg_stage_name(i).decode() for i in range(6)] == \
-        ["row_stats", "accept", "table", "gather", "finalize", ""]
+        ["row_stats", "accept_delta", "weights", "gather", "finalize", ""]
 
 
 # --------------------------------------------------------------------------- prepared layout

@@ -113,16 +113,13 @@ __device__ __forceinline__ float wave_max(float v) {
   return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
-// Wave-wide sum / max through shuffles, result in every lane (for the small kernels).
-__device__ __forceinline__ double wave_sum_all(double v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
-  return v;
-}
-__device__ __forceinline__ float wave_max_all(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
-  return v;
+// Sum over the whole wave through DPP, returned in every lane (fixed tree).
+__device__ __forceinline__ double wave_sum(double v) {
+  v = subwave_sum<64>(v);
+  int2 r = *reinterpret_cast<int2 *>(&v);
+  r.x = __builtin_amdgcn_readlane(r.x, 63);
+  r.y = __builtin_amdgcn_readlane(r.y, 63);
+  return *reinterpret_cast<double *>(&r);
 }
 
 // ---------------------------------------------------------------------------------------------

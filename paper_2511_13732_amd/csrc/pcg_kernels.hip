@@ -116,13 +116,13 @@ __device__ __forceinline__ RowStat merge_row(const StatPart *parts, int64_t row,
   const StatPart *rp = parts + row * nparts;
   float M = -INFINITY;
   for (int32_t k = lane; k < nparts; k += kWave) M = fmaxf(M, rp[k].m);
-  M = wave_max_all(M);
+  M = wave_max(M);
   double Z = 0.0;
   for (int32_t k = lane; k < nparts; k += kWave) {
     StatPart sp = rp[k];
     if (sp.z > 0.0) Z += sp.z * exp2((double) (sp.m - M) * (double) c);
   }
-  Z = wave_sum_all(Z);
+  Z = wave_sum(Z);
   RowStat r;
   r.Z = Z;
   r.M = M;
@@ -211,9 +211,11 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_delta_kernel(
     int32_t *out_tokens, int32_t *out_groups, pcg_diag *diag, uint32_t *arrivals, float *table) {
   __shared__ RowStat st_t[PCG_MAX_K + 1];
   __shared__ RowStat st_d[PCG_MAX_K];
-  __shared__ double Tp[PCG_MAX_K], Dp[PCG_MAX_K];
+  __shared__ double Tp[PCG_MAX_K], Dp[PCG_MAX_K];     // sums relative to the group's own maxima
+  __shared__ float Tref[PCG_MAX_K], Dref[PCG_MAX_K];  // those maxima
   __shared__ int bad[PCG_MAX_K];
   __shared__ float uacc[PCG_MAX_K];
+  __shared__ int ptok_s[PCG_MAX_K], pgrp_s[PCG_MAX_K];
   __shared__ int istar_s;
 
   const int b = blockIdx.x / nsplit;
@@ -222,56 +224,72 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_delta_kernel(
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
   constexpr int nw = kAcceptThreads / kWave;
   const int64_t B = rs.nrows0 / (K + 1);
+  // The two chains of dependent loads run side by side on different waves: the first
+  // `nprobe` waves follow proposal -> group -> members -> logits, the others merge the row
+  // statistics.  The probes sum relative to the group's own maximum, so they need no row
+  // statistic until both chains meet.
+  const int nprobe = min(K, nw / 2);
 
-  // 1. row statistics of this sequence's 2K+1 rows
-  for (int r = wave; r < 2 * K + 1; r += nw) {
-    const bool is_t = r <= K;
-    const int64_t row = is_t ? (int64_t) b * (K + 1) + r : B * (K + 1) + (int64_t) b * K + (r - K - 1);
-    RowStat s = merge_row(parts, row, nparts, c, lane);
-    if (lane == 0) {
-      if (writer) rowstat[row] = s;
-      if (is_t) st_t[r] = s; else st_d[r - K - 1] = s;
-    }
-  }
-  if (threadIdx.x < K)   // the uniforms do not depend on the data
-    uacc[threadIdx.x] = philox_uniforms(seed, offset, (uint32_t) b, (uint32_t) threadIdx.x).acc;
-  __syncthreads();
-
-  // 2. T_i[g], D_i[g] of the proposed group at every position (Eq. 5), one wave per position
-  for (int i = wave; i < K; i += nw) {
-    const int32_t g = prop_groups[(int64_t) b * K + i];
-    double at = 0.0, ad = 0.0;
-    const bool ok = g >= 0 && g < G;
-    if (ok) {
-      const void *trow = row_base(rs, (int64_t) b * (K + 1) + i, BF16);
-      const void *drow = row_base(rs, rs.nrows0 + (int64_t) b * K + i, BF16);
-      const float Mt = st_t[i].M, Md = st_d[i].M;
-      const int32_t beg = row_ptr[g], end = row_ptr[g + 1];
-      for (int32_t j = beg + lane; j < end; j += kWave) {
-        const int32_t t = members[j];
-        const double inv_m = 1.0 / (double) mult[t];
-        at += exp2((double) (logit_at<BF16>(trow, t) - Mt) * cd) * inv_m;
-        ad += exp2((double) (logit_at<BF16>(drow, t) - Md) * cd) * inv_m;
+  if (wave < nprobe) {
+    // T_i[g], D_i[g] of the proposed group (Eq. 5), up to the row's normalisation
+    for (int i = wave; i < K; i += nprobe) {
+      const int32_t g = prop_groups[(int64_t) b * K + i];
+      const bool ok = g >= 0 && g < G;
+      double at = 0.0, ad = 0.0;
+      float mt = -INFINITY, md = -INFINITY;
+      if (ok) {
+        const void *trow = row_base(rs, (int64_t) b * (K + 1) + i, BF16);
+        const void *drow = row_base(rs, rs.nrows0 + (int64_t) b * K + i, BF16);
+        const int32_t beg = row_ptr[g], end = row_ptr[g + 1];
+        for (int32_t j = beg + lane; j < end; j += kWave) {
+          const int32_t t = members[j];
+          mt = fmaxf(mt, logit_at<BF16>(trow, t));
+          md = fmaxf(md, logit_at<BF16>(drow, t));
+        }
+        mt = wave_max(mt);
+        md = wave_max(md);
+        for (int32_t j = beg + lane; j < end; j += kWave) {
+          const int32_t t = members[j];
+          const double inv_m = 1.0 / (double) mult[t];
+          const float lt = logit_at<BF16>(trow, t), ld = logit_at<BF16>(drow, t);
+          if (lt > -INFINITY) at += exp2((double) (lt - mt) * cd) * inv_m;
+          if (ld > -INFINITY) ad += exp2((double) (ld - md) * cd) * inv_m;
+        }
+      }
+      at = wave_sum(at);
+      ad = wave_sum(ad);
+      if (lane == 0) {
+        Tp[i] = at; Dp[i] = ad; Tref[i] = mt; Dref[i] = md;
+        bad[i] = !ok;
+        pgrp_s[i] = g;
+        ptok_s[i] = prop_tokens[(int64_t) b * K + i];
+        uacc[i] = philox_uniforms(seed, offset, (uint32_t) b, (uint32_t) i).acc;
       }
     }
-    at = wave_sum_all(at);
-    ad = wave_sum_all(ad);
-    if (lane == 0) {
-      Tp[i] = ok ? at / st_t[i].Z : 0.0;
-      Dp[i] = ok ? ad / st_d[i].Z : 0.0;
-      bad[i] = !ok;
+  } else {
+    // row statistics of this sequence's 2K+1 rows
+    for (int r = wave - nprobe; r < 2 * K + 1; r += nw - nprobe) {
+      const bool is_t = r <= K;
+      const int64_t row = is_t ? (int64_t) b * (K + 1) + r : B * (K + 1) + (int64_t) b * K + (r - K - 1);
+      RowStat s = merge_row(parts, row, nparts, c, lane);
+      if (lane == 0) {
+        if (writer) rowstat[row] = s;
+        if (is_t) st_t[r] = s; else st_d[r - K - 1] = s;
+      }
     }
   }
   __syncthreads();
 
-  // 3. sequential accept scan with early exit (Algorithm 1); the draft token stands for its
-  //    group on accept
+  // sequential accept scan with early exit (Algorithm 1); the draft token stands for its group
+  // on accept
   if (threadIdx.x == 0) {
     uint32_t near = 0, zero_d = 0, nbad = 0;
     int i = 0;
     for (; i < K; ++i) {
       const double u = (double) uacc[i];
-      const double T = Tp[i], D = Dp[i];
+      double T = 0.0, D = 0.0;
+      if (Tp[i] > 0.0) T = Tp[i] * exp2((double) (Tref[i] - st_t[i].M) * cd) / st_t[i].Z;
+      if (Dp[i] > 0.0) D = Dp[i] * exp2((double) (Dref[i] - st_d[i].M) * cd) / st_d[i].Z;
       if (bad[i]) ++nbad;
       else if (D == 0.0) ++zero_d;
       if (fabs(u * D - T) < 1e-6 * D) ++near;
@@ -281,10 +299,7 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_delta_kernel(
     if (writer) {
       int32_t *otok = out_tokens + (int64_t) b * (K + 1);
       int32_t *ogrp = out_groups + (int64_t) b * (K + 1);
-      for (int k = 0; k < i; ++k) {
-        otok[k] = prop_tokens[(int64_t) b * K + k];
-        ogrp[k] = prop_groups[(int64_t) b * K + k];
-      }
+      for (int k = 0; k < i; ++k) { otok[k] = ptok_s[k]; ogrp[k] = pgrp_s[k]; }
       for (int k = i; k <= K; ++k) otok[k] = ogrp[k] = -1;
       accept_len[b] = i;
       arrivals[b] = 0;
@@ -499,8 +514,8 @@ __device__ __forceinline__ bool near_edge(const CdfPick &p, double u) {
 // The last step of a sequence, by one whole workgroup of NT threads.  R holds the gathered sums
 // T[g] - D[g] (T[g] on a bonus row), clamped here on read.  With csum != NULL it also has the
 // totals of max(0, R) over chunks of chunk_groups consecutive groups, so only the chunk that
-// holds the draw is scanned, from `stage` (LDS, room for one chunk); staged_chunk >= 0 says that
-// chunk's R values are in `stage` already.
+// holds the draw is scanned, from `stage` (LDS, room for one chunk plus one pad word per 32);
+// staged_chunk >= 0 says that chunk's R values are in `stage` already, in the padded layout.
 template <bool BF16, int NT>
 __device__ void finalize_sequence(const FinalizeArgs &fa, int32_t V, int32_t G, int b,
                                   const double *csum, int32_t nchunks, int32_t chunk_groups,
@@ -540,20 +555,17 @@ __device__ void finalize_sequence(const FinalizeArgs &fa, int32_t V, int32_t G, 
     pg.index = -1; pg.total = S; pg.lo = pg.hi = 0.0;
     if (S > 0.0 && cstar >= 0) {
       const int32_t g0 = cstar * chunk_groups, ng = min(chunk_groups, G - g0);
+      // Stage the chunk in LDS with coalesced loads; the scan then reads contiguous runs.  One
+      // pad word per 32 keeps the runs of neighbouring threads in different banks.
       if (cstar != staged_chunk) {
-        // stage the chunk in LDS with coalesced loads; the scan then reads contiguous runs
         __syncthreads();
         const float *Rc = Rb + g0;
-        if ((((uintptr_t) Rc | (uintptr_t) ng) & 15) == 0) {
-          for (int32_t k = threadIdx.x; k < (ng >> 2); k += NT)
-            reinterpret_cast<float4 *>(stage)[k] = reinterpret_cast<const float4 *>(Rc)[k];
-        } else {
-          for (int32_t k = threadIdx.x; k < ng; k += NT) stage[k] = Rc[k];
-        }
+        for (int32_t k = threadIdx.x; k < ng; k += NT) stage[k + (k >> 5)] = Rc[k];
         __syncthreads();
       }
       CdfPick in = block_inverse_cdf<NT>(
-          ng, [&](int32_t k) { return (double) fmaxf(stage[k], 0.f); }, 0.0, true, goal - base);
+          ng, [&](int32_t k) { return (double) fmaxf(stage[k + (k >> 5)], 0.f); }, 0.0, true,
+          goal - base);
       if (in.index >= 0) {
         pg.index = g0 + in.index; pg.lo = base + in.lo; pg.hi = base + in.hi;
       }
@@ -597,7 +609,7 @@ __global__ __launch_bounds__(kFinalThreads) void finalize_kernel(FinalizeArgs fa
                                                                  int32_t G, const double *csum,
                                                                  int32_t nchunks,
                                                                  int32_t chunk_groups) {
-  __shared__ __attribute__((aligned(16))) float stage[kMaxChunkGroups];
+  __shared__ float stage[kMaxChunkGroups + kMaxChunkGroups / 32];
   finalize_sequence<BF16, kFinalThreads>(fa, V, G, blockIdx.x, csum, nchunks, chunk_groups, stage, -1);
 }
 

@@ -280,6 +280,18 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_delta_kernel(
   }
   __syncthreads();
 
+  // both chains have met: normalise the probes, one thread per position
+  __shared__ double Tn[PCG_MAX_K], Dn[PCG_MAX_K];
+  if (threadIdx.x < K) {
+    const int i = threadIdx.x;
+    double T = 0.0, D = 0.0;
+    if (Tp[i] > 0.0) T = Tp[i] * exp2((double) (Tref[i] - st_t[i].M) * cd) / st_t[i].Z;
+    if (Dp[i] > 0.0) D = Dp[i] * exp2((double) (Dref[i] - st_d[i].M) * cd) / st_d[i].Z;
+    Tn[i] = T;
+    Dn[i] = D;
+  }
+  __syncthreads();
+
   // sequential accept scan with early exit (Algorithm 1); the draft token stands for its group
   // on accept
   if (threadIdx.x == 0) {
@@ -287,9 +299,7 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_delta_kernel(
     int i = 0;
     for (; i < K; ++i) {
       const double u = (double) uacc[i];
-      double T = 0.0, D = 0.0;
-      if (Tp[i] > 0.0) T = Tp[i] * exp2((double) (Tref[i] - st_t[i].M) * cd) / st_t[i].Z;
-      if (Dp[i] > 0.0) D = Dp[i] * exp2((double) (Dref[i] - st_d[i].M) * cd) / st_d[i].Z;
+      const double T = Tn[i], D = Dn[i];
       if (bad[i]) ++nbad;
       else if (D == 0.0) ++zero_d;
       if (fabs(u * D - T) < 1e-6 * D) ++near;
@@ -449,18 +459,29 @@ struct CdfPick {
 template <int NT, typename F>
 __device__ CdfPick block_inverse_cdf(int32_t n, F f, double u, bool have_goal = false,
                                      double goal_in = 0.0) {
+  constexpr int kRegRun = 32;          // runs up to this length are held in registers
   __shared__ double wave_tot[NT / kWave];
   __shared__ int first_thread, last_pos;
   __shared__ CdfPick res;
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
   const int32_t run = (n + NT - 1) / NT;
   const int32_t lo_i = min(n, tid * run), hi_i = min(n, lo_i + run);
+  const bool in_regs = run <= kRegRun;           // uniform
   if (tid == 0) { first_thread = INT_MAX; last_pos = -1; }
   double mine = 0.0;
-  int32_t my_last = -1;
-  for (int32_t k = lo_i; k < hi_i; ++k) {
-    const double v = f(k);
-    if (v > 0.0) { mine += v; my_last = k; }
+  double vals[kRegRun];
+  if (in_regs) {
+    // all loads of the run are issued before the first is used
+#pragma unroll
+    for (int j = 0; j < kRegRun; ++j) vals[j] = (lo_i + j < hi_i) ? f(lo_i + j) : 0.0;
+#pragma unroll
+    for (int j = 0; j < kRegRun; ++j)
+      if (vals[j] > 0.0) mine += vals[j];
+  } else {
+    for (int32_t k = lo_i; k < hi_i; ++k) {
+      const double v = f(k);
+      if (v > 0.0) mine += v;
+    }
   }
   // inclusive scan inside the wave, then across waves
   double inc = mine;
@@ -478,25 +499,51 @@ __device__ CdfPick block_inverse_cdf(int32_t n, F f, double u, bool have_goal = 
   }
   const double excl = before + (inc - mine);
   const double goal = have_goal ? goal_in : u * total;
-  if (mine > 0.0 && excl + mine > goal) atomicMin(&first_thread, tid);
-  if (my_last >= 0) atomicMax(&last_pos, my_last);
+  // the first thread whose run carries the running sum past the threshold: first lane of each
+  // wave by ballot, then one LDS atomic per wave
+  const unsigned long long hit = __ballot(mine > 0.0 && excl + mine > goal);
+  if (hit != 0 && lane == __ffsll((long long) hit) - 1) atomicMin(&first_thread, tid);
   __syncthreads();
-  if (first_thread == tid) {
+  const int ft = first_thread;
+  if (ft == tid) {
     double cum = excl;
-    for (int32_t k = lo_i; k < hi_i; ++k) {
-      const double v = f(k);
-      if (!(v > 0.0)) continue;
-      const double nxt = cum + v;
-      if (nxt > goal || k == my_last) {   // k == my_last: guaranteed by excl + mine > goal
-        res.index = k; res.lo = cum; res.hi = nxt; res.total = total;
-        break;
+    int32_t last = lo_i;
+    bool done = false;
+    if (in_regs) {
+#pragma unroll
+      for (int j = 0; j < kRegRun; ++j) {
+        if (!done && vals[j] > 0.0) {
+          const double nxt = cum + vals[j];
+          if (nxt > goal) { res.index = lo_i + j; res.lo = cum; res.hi = nxt; done = true; }
+          else { last = lo_i + j; cum = nxt; }
+        }
       }
-      cum = nxt;
+    } else {
+      for (int32_t k = lo_i; k < hi_i && !done; ++k) {
+        const double v = f(k);
+        if (!(v > 0.0)) continue;
+        const double nxt = cum + v;
+        if (nxt > goal) { res.index = k; res.lo = cum; res.hi = nxt; done = true; }
+        else { last = k; cum = nxt; }
+      }
     }
-  } else if (first_thread == INT_MAX && tid == 0) {
+    if (!done) {   // summation order: excl + mine > goal, yet the walk stayed below: last bin
+      const double v = (double) f(last);
+      res.index = last; res.lo = cum - v; res.hi = cum;
+    }
+    res.total = total;
+  }
+  if (ft == INT_MAX) {
     // rounding at the top end (or no mass at all): the last index that has mass
-    res.index = last_pos; res.total = total; res.lo = total; res.hi = total;
-    if (last_pos >= 0) res.lo = total - f(last_pos);
+    int32_t my_last = -1;
+    for (int32_t k = lo_i; k < hi_i; ++k)
+      if (f(k) > 0.0) my_last = k;
+    if (my_last >= 0) atomicMax(&last_pos, my_last);
+    __syncthreads();
+    if (tid == 0) {
+      res.index = last_pos; res.total = total; res.lo = total; res.hi = total;
+      if (last_pos >= 0) res.lo = total - f(last_pos);
+    }
   }
   __syncthreads();
   CdfPick out = res;
@@ -560,7 +607,24 @@ __device__ void finalize_sequence(const FinalizeArgs &fa, int32_t V, int32_t G, 
       if (cstar != staged_chunk) {
         __syncthreads();
         const float *Rc = Rb + g0;
-        for (int32_t k = threadIdx.x; k < ng; k += NT) stage[k + (k >> 5)] = Rc[k];
+        if ((((uintptr_t) Rc | (uintptr_t) ng) & 15) == 0 && ng <= 8 * 4 * NT) {
+          float4 v[8];                            // up to eight 16-byte loads in flight
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            const int32_t k4 = threadIdx.x + i * NT;
+            if (4 * k4 < ng) v[i] = reinterpret_cast<const float4 *>(Rc)[k4];
+          }
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            const int32_t k = 4 * (threadIdx.x + i * NT);
+            if (k < ng) {
+              float *d = stage + k + (k >> 5);    // k is a multiple of 4: all four share k >> 5
+              d[0] = v[i].x; d[1] = v[i].y; d[2] = v[i].z; d[3] = v[i].w;
+            }
+          }
+        } else {
+          for (int32_t k = threadIdx.x; k < ng; k += NT) stage[k + (k >> 5)] = Rc[k];
+        }
         __syncthreads();
       }
       CdfPick in = block_inverse_cdf<NT>(

@@ -332,12 +332,7 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_delta_kernel(
   const RowStat st = st_t[istar];
   const RowStat sd = st_d[rejected ? istar : 0];
   const double izt = 1.0 / st.Z, izd = rejected ? 1.0 / sd.Z : 0.0;
-  for (int32_t t = split * kAcceptTokens + threadIdx.x * kTokensPerThread; t < V;
-       t += nsplit * kAcceptTokens) {
-    float xt[8], xd[8], m[8], v[8];
-    load8<BF16, VEC>(trow, t, V, xt);
-    if (rejected) load8<BF16, VEC>(drow, t, V, xd);
-    load8_mult<VEC>(mult, t, V, m);
+  auto delta8 = [&](const float *xt, const float *xd, const float *m, float *v) {
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
       const float et = exp_rel(xt[k], st.M, c, c_lo);
@@ -350,7 +345,27 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_delta_kernel(
       }
       v[k] = (float) diff / m[k];
     }
-    store8<VEC>(table + (int64_t) b * V, t, V, v);
+  };
+  const int32_t stride = nsplit * kAcceptTokens;
+  float *out = table + (int64_t) b * V;
+  // two slices per turn, so that the loads of the second are in flight behind the first
+  for (int32_t t = split * kAcceptTokens + threadIdx.x * kTokensPerThread; t < V; t += 2 * stride) {
+    const int32_t t2 = t + stride;
+    float xt[8], xd[8], m[8], v[8], xt2[8], xd2[8], m2[8];
+    load8<BF16, VEC>(trow, t, V, xt);
+    if (rejected) load8<BF16, VEC>(drow, t, V, xd);
+    load8_mult<VEC>(mult, t, V, m);
+    if (t2 < V) {
+      load8<BF16, VEC>(trow, t2, V, xt2);
+      if (rejected) load8<BF16, VEC>(drow, t2, V, xd2);
+      load8_mult<VEC>(mult, t2, V, m2);
+    }
+    delta8(xt, xd, m, v);
+    store8<VEC>(out, t, V, v);
+    if (t2 < V) {
+      delta8(xt2, xd2, m2, v);
+      store8<VEC>(out, t2, V, v);
+    }
   }
 }
 
@@ -706,10 +721,16 @@ __device__ __forceinline__ void load_steps(uint4 *w, const uint4 *__restrict__ d
 
 __device__ __forceinline__ void gather_steps(const float *tab, const uint4 *w, uint32_t left,
                                              float *acc) {
-  gather_step(tab, w[0], acc);
-  if (left > 1) gather_step(tab, w[1], acc);
-  if (left > 2) gather_step(tab, w[2], acc);
-  if (left > 3) gather_step(tab, w[3], acc);
+  if (left >= 4) {             // a full turn is straight-line code: 32 gathers in flight
+    gather_step(tab, w[0], acc);
+    gather_step(tab, w[1], acc);
+    gather_step(tab, w[2], acc);
+    gather_step(tab, w[3], acc);
+  } else {
+    gather_step(tab, w[0], acc);
+    if (left > 1) gather_step(tab, w[1], acc);
+    if (left > 2) gather_step(tab, w[2], acc);
+  }
 }
 
 // One block of n steps, four at a time, with two register buffers used alternately: while
@@ -762,8 +783,19 @@ __global__ __launch_bounds__(kGatherThreads) void gather_prepared_kernel(
   const float *src = table + (int64_t) r * V;
 
   float acc[kMaxAcc];
+  uint16_t where[kMaxAcc];     // group (inside the chunk) behind each running sum; loaded now,
+                               // needed only when the sums are put back into group order
 #pragma unroll
-  for (int j = 0; j < kMaxAcc; ++j) acc[j] = 0.f;
+  for (int q = 0; q < kMaxBlocksPerWave; ++q) {
+    const int bl = block_of(q, wave);
+#pragma unroll
+    for (int rr = 0; rr < kLaneGroups; ++rr) {
+      acc[q * kLaneGroups + rr] = 0.f;
+      where[q * kLaneGroups + rr] =
+          bl < bpc ? perm[((size_t) chunk * bpc + bl) * kBlockGroups + rr * kWave + lane]
+                   : (uint16_t) 0xFFFFu;
+    }
+  }
 
   for (int h = 0; h < ntiles; ++h) {
     const int32_t t0 = h * tile_len;
@@ -813,17 +845,8 @@ __global__ __launch_bounds__(kGatherThreads) void gather_prepared_kernel(
   // back into group order through LDS, then coalesced stores
   __syncthreads();
 #pragma unroll
-  for (int q = 0; q < kMaxBlocksPerWave; ++q) {
-    const int bl = block_of(q, wave);
-    if (bl < bpc) {
-      const uint16_t *pp = perm + ((size_t) chunk * bpc + bl) * kBlockGroups + lane;
-#pragma unroll
-      for (int rr = 0; rr < kLaneGroups; ++rr) {
-        const uint16_t k = pp[rr * kWave];
-        if (k != 0xFFFFu) tab[k] = acc[q * kLaneGroups + rr];
-      }
-    }
-  }
+  for (int j = 0; j < kMaxAcc; ++j)
+    if (where[j] != 0xFFFFu) tab[where[j]] = acc[j];
   __syncthreads();
   float *dst = out + (int64_t) r * G + g0;
   double part = 0.0;

@@ -96,9 +96,11 @@ typedef struct {
  *     a time into blocks: lane l of a wave handles the 4 groups at sorted positions
  *     block*256 + r*64 + l, r = 0..3;
  *   - per (chunk, tile, block) the members that fall into the tile are stored as 16-bit
- *     tile-local slots, two per dword, padded with a slot that holds 0 to the block's longest
- *     list; a lane's 4 dwords of step k (one per group) are adjacent, so a wave reads step k
- *     of a block with one coalesced 16-byte-per-lane load.
+ *     tile-local slots, two per dword, each list padded to the block's longest with slots
+ *     tile_len + bank (which read as 0); a lane's 4 dwords of step k (one per group) are
+ *     adjacent, so a wave reads step k of a block with one coalesced 16-byte-per-lane load;
+ *   - the order of a group's slots is free (a sum), and is chosen per half-wave of 32 lanes
+ *     so that the 32 LDS addresses of a step fall into different banks wherever possible.
  * The descriptor is filled by pcg_groups_prepare_host and must be passed back unchanged.
  */
 struct pcg_prepared {

@@ -63,7 +63,7 @@ int check_groups(const pcg_groups *g) {
   if ((g->prepared == nullptr) != (g->prepared_info == nullptr)) return PCG_ERR_NULL_ARG;
   if (g->prepared) {
     const pcg_prepared &p = *g->prepared_info;
-    if (p.V != g->V || p.G != g->G || p.ntiles < 1 || p.tile_len < 1 || p.tile_len >= kTileMax ||
+    if (p.V != g->V || p.G != g->G || p.ntiles < 1 || p.tile_len < 1 || p.tile_len > kTileTokensMax ||
         (int64_t) p.ntiles * p.tile_len < g->V || p.chunk_groups < kChunkStep ||
         p.chunk_groups > kMaxChunkGroups || p.chunk_groups % kChunkStep ||
         p.blocks_per_chunk != p.chunk_groups / kBlockGroups ||

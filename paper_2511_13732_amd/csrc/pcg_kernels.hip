@@ -808,7 +808,7 @@ __global__ __launch_bounds__(kGatherThreads) void gather_prepared_kernel(
     } else {
       for (int32_t k = threadIdx.x; k < tl; k += kGatherThreads) tab[k] = src[t0 + k];
     }
-    if (threadIdx.x == 0) tab[tile_len] = 0.f;        // the padding slot
+    if (threadIdx.x < kBanks) tab[tile_len + threadIdx.x] = 0.f;   // the padding slots
     __syncthreads();
     // The wave's blocks of this tile.  Steps are taken four at a time; the loads of the next
     // four (of this block, or the first of the next block) are issued before the current four

@@ -6,6 +6,9 @@ namespace pcg {
 constexpr int kGatherThreads = 1024;     // one workgroup per compute unit (LDS-bound)
 constexpr int kGatherWaves = kGatherThreads / 64;
 constexpr int kTileMax = 40704;          // floats of LDS a workgroup stages (159 of the 160 KiB)
+constexpr int kBanks = 32;               // LDS banks (4 bytes wide); a half-wave of 32 lanes is
+                                         // served in one pass when its addresses fall in 32 banks
+constexpr int kTileTokensMax = kTileMax - kBanks;   // the last kBanks floats of a tile read as zero
 constexpr int kLaneGroups = 4;           // groups a lane handles side by side (one 16-byte load)
 constexpr int kBlockGroups = 64 * kLaneGroups;                 // groups per block: 256
 constexpr int kMaxBlocksPerWave = 4;     // blocks a wave handles per tile pass

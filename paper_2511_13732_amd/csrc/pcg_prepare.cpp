@@ -20,14 +20,70 @@ bool make_shape(int32_t V, int32_t G, int32_t chunk_groups, Shape &s) {
   if (chunk_groups == 0) chunk_groups = kMaxChunkGroups;
   if (chunk_groups < kChunkStep || chunk_groups > kMaxChunkGroups || chunk_groups % kChunkStep)
     return false;
-  // one slot of every tile is kept for the padding entry, which must read as zero
-  s.ntiles = (V + (kTileMax - 1) - 1) / (kTileMax - 1);
+  // kBanks slots after every tile are kept for padding entries (one per bank, all zero)
+  s.ntiles = (V + kTileTokensMax - 1) / kTileTokensMax;
   s.tile_len = (V + s.ntiles - 1) / s.ntiles;
-  s.tile_len = std::min(kTileMax - 1, (s.tile_len + 63) / 64 * 64);
+  s.tile_len = std::min(kTileTokensMax, (s.tile_len + 63) / 64 * 64);
   s.chunk_groups = chunk_groups;
   s.nchunks = (G + chunk_groups - 1) / chunk_groups;
   s.blocks_per_chunk = chunk_groups / kBlockGroups;
   return true;
+}
+
+// Order in which a half-wave (32 lanes, one group each) reads its lists, chosen so that the 32
+// addresses of a time slot fall into different LDS banks wherever that is possible.  lists[l]
+// holds lane l's tile-local slots; every lane gets exactly n entries back, its own slots plus
+// padding slots pad_base + bank.  Greedy, one time slot after the other: lanes with the most
+// entries left choose first, each takes an entry whose bank is still free in this slot
+// (preferring the bank with the most entries still to place); a lane that finds none waits if
+// it has slots to spare, and otherwise takes the least crowded bank.
+void schedule_half_wave(std::vector<uint16_t> (&lists)[32], int n, uint16_t pad_base,
+                        std::vector<uint16_t> &out /* [n][32] */) {
+  int bank_left[kBanks] = {0};
+  for (auto &l : lists)
+    for (uint16_t s : l) ++bank_left[s % kBanks];
+  out.assign((size_t) n * 32, 0);
+  int order[32];
+  for (int t = 0; t < n; ++t) {
+    const int slots_left = n - t;
+    int used[kBanks] = {0};
+    bool placed[32] = {false};
+    std::iota(order, order + 32, 0);
+    std::stable_sort(order, order + 32,
+                     [&](int a, int b) { return lists[a].size() > lists[b].size(); });
+    for (int oi = 0; oi < 32; ++oi) {
+      const int l = order[oi];
+      auto &rem = lists[l];
+      if (rem.empty()) continue;
+      int best = -1;
+      for (int e = 0; e < (int) rem.size(); ++e) {
+        const int b = rem[e] % kBanks;
+        if (used[b]) continue;
+        if (best < 0 || bank_left[b] > bank_left[rem[best] % kBanks]) best = e;
+      }
+      if (best < 0) {
+        if ((int) rem.size() < slots_left) continue;      // can wait for a later slot
+        for (int e = 0; e < (int) rem.size(); ++e) {      // must go now: least crowded bank
+          const int b = rem[e] % kBanks;
+          if (best < 0 || used[b] < used[rem[best] % kBanks]) best = e;
+        }
+      }
+      const uint16_t s = rem[best];
+      rem.erase(rem.begin() + best);
+      ++used[s % kBanks];
+      --bank_left[s % kBanks];
+      out[(size_t) t * 32 + l] = s;
+      placed[l] = true;
+    }
+    for (int l = 0; l < 32; ++l) {
+      if (placed[l]) continue;
+      int b = 0;
+      for (int c = 0; c < kBanks; ++c)
+        if (used[c] < used[b]) b = c;
+      ++used[b];
+      out[(size_t) t * 32 + l] = (uint16_t) (pad_base + b);
+    }
+  }
 }
 
 // Builds the layout; with blob == nullptr only sizes are computed.
@@ -107,8 +163,8 @@ int build(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members,
   std::memcpy(blob, desc.data(), desc.size() * sizeof(uint32_t));
   std::memcpy(blob + desc_bytes, perm.data(), perm.size() * sizeof(uint16_t));
   uint32_t *data = reinterpret_cast<uint32_t *>(blob + desc_bytes + perm_bytes);
-  const uint16_t pad_slot = (uint16_t) sh.tile_len;           // table[tile_len] is kept at zero
-  std::vector<uint16_t> slots;
+  const uint16_t pad_base = (uint16_t) sh.tile_len;   // table[tile_len .. tile_len + kBanks) is zero
+  std::vector<uint16_t> lists[32], sched;
   for (int32_t c = 0; c < sh.nchunks; ++c) {
     const int32_t g0 = c * sh.chunk_groups;
     for (int32_t bl = 0; bl < BPC; ++bl) {
@@ -118,18 +174,21 @@ int build(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members,
         const uint32_t steps = d[1];
         if (steps == 0) continue;
         for (int32_t r = 0; r < kLaneGroups; ++r) {
-          for (int32_t l = 0; l < 64; ++l) {
-            slots.assign((size_t) steps * 2, pad_slot);
-            const uint16_t k = perm[((size_t) c * BPC + bl) * kBlockGroups + r * 64 + l];
-            if (k != 0xFFFF) {
-              uint32_t n = 0;
+          for (int32_t half = 0; half < 2; ++half) {
+            for (int32_t l = 0; l < 32; ++l) {
+              lists[l].clear();
+              const uint16_t k = perm[((size_t) c * BPC + bl) * kBlockGroups + r * 64 + half * 32 + l];
+              if (k == 0xFFFF) continue;
               for (int32_t j = row_ptr[g0 + k]; j < row_ptr[g0 + k + 1]; ++j)
                 if (members[j] / sh.tile_len == h)
-                  slots[n++] = (uint16_t) (members[j] - h * sh.tile_len);
+                  lists[l].push_back((uint16_t) (members[j] - h * sh.tile_len));
             }
+            schedule_half_wave(lists, (int) steps * 2, pad_base, sched);
             for (uint32_t q = 0; q < steps; ++q)
-              data[((off + (size_t) q * 64 + l) * 4) + r] =
-                  (uint32_t) slots[2 * q] | ((uint32_t) slots[2 * q + 1] << 16);
+              for (int32_t l = 0; l < 32; ++l)
+                data[((off + (size_t) q * 64 + half * 32 + l) * 4) + r] =
+                    (uint32_t) sched[(size_t) (2 * q) * 32 + l] |
+                    ((uint32_t) sched[(size_t) (2 * q + 1) * 32 + l] << 16);
           }
         }
       }

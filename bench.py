@@ -7,9 +7,11 @@ recipe C4 (V = 65 536, 32-member cosine-neighbour groups, B = 64, K = 8, bf16). 
 resident in HBM before the timed region; several input sets are rotated so that the logits
 (142.6 MB per step) cannot be served from the 256 MB Infinity Cache.
 
-Prints ONE JSON line: verified draft positions per second, the HBM roofline of the dominant
-kernel (durations from HIP events recorded by the library around each of its kernels, in a
-second instrumented pass over the same steps) and the CPU oracle timed on a bounded sample.
+Prints ONE JSON line: verified draft positions per second, the HBM roofline of the streaming
+kernel that carries the step's bytes and the LDS roofline of the longest kernel (durations
+from HIP events recorded by the library around each of its kernels, in a second instrumented
+pass over the same steps, net of the cost of an event pair) and the CPU oracle timed on a
+bounded sample.
 """
 from __future__ import annotations
 
@@ -25,10 +27,16 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published peak
 
-# HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE and
-# WRITE_SIZE, each scaled by what the same counter reads for a plain copy of known size).
-# Filled in from profiles/; None until measured for that workload.
-MEASURED_TRAFFIC_BYTES = {}
+LDS_PEAK_GBS = 256 * 128 * 2.4     # 256 CUs x 128 B/clk x 2.4 GHz = 78 643 GB/s
+
+# HBM bytes per launch measured with rocprofv3 --pmc on this workload (FETCH_SIZE and
+# WRITE_SIZE in KiB per dispatch, each scaled by what the same counter reads for a plain device
+# copy of 256 MiB: FETCH_SIZE reads 131 085 for 262 144 KiB, factor 2.000; WRITE_SIZE reads
+# 262 144, factor 1.000).  Source: profiles/pcg_verify_C4_hbm_traffic.md.
+MEASURED_TRAFFIC_BYTES = {
+    "row_stats@C4": int((69659.56 * 2.000 + 544.84) * 1024),
+    "gather@C4": int((28572.20 * 2.000 + 21506.0) * 1024),
+}
 
 
 def parse_args():
@@ -129,21 +137,34 @@ def main():
         step(args.warmup + i)
     torch.cuda.synchronize()
     stage_ms, ncalls = pcg.profile_end()
-    dominant = max(stage_ms, key=stage_ms.get)
+    # an event pair costs time of its own; the library measures that on an empty pair
+    overhead_ms = stage_ms.pop("event_overhead", 0.0)
+    stage_ms = {k: v for k, v in stage_ms.items() if v > 0.0}
+    by_time = max(stage_ms, key=stage_ms.get)
     logits_b, csr_b, small_b = algorithmic_bytes(cfg, groups.G, groups.nnz)
-    # algorithmic bytes of one launch of each kernel (units it processes x bytes per unit)
-    kernel_bytes = {
-        "row_stats": logits_b,                                     # every logit once
-        "gather": 4 * cfg.B * cfg.V + 4 * (groups.nnz + groups.G + 1) + 4 * cfg.B * groups.G,
-    }
-    roof_kernel = dominant if dominant in kernel_bytes else "row_stats"
-    dur_s = stage_ms[roof_kernel] * 1e-3
-    achieved = kernel_bytes[roof_kernel] / dur_s / 1e9 if dur_s > 0 else 0.0
-    roofline = {"bound": "hbm", "kernel": roof_kernel, "achieved": round(achieved, 1),
+
+    # row_stats is the kernel the HBM roofline is about: it streams every logit once, 94 % of
+    # the step's algorithmic bytes.  Algorithmic bytes per launch = logits bytes per position
+    # ((2K+1)/K * V * bytes per logit) x the B*K positions one launch processes.
+    dur_s = stage_ms["row_stats"] * 1e-3
+    achieved = logits_b / dur_s / 1e9
+    roofline = {"bound": "hbm", "kernel": "row_stats", "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES.get(f"{roof_kernel}@{cfg.name}"),
-                "algorithmic_bytes": kernel_bytes[roof_kernel],
-                "kernel_us": round(1e3 * stage_ms[roof_kernel], 2)}
+                "traffic": MEASURED_TRAFFIC_BYTES.get(f"row_stats@{cfg.name}"),
+                "algorithmic_bytes": logits_b,
+                "kernel_us": round(1e3 * stage_ms["row_stats"], 2)}
+    # the gather is the longest kernel; it is bound by LDS gather throughput, not by HBM: one
+    # 4-byte LDS read per (sequence, membership entry)
+    lds_bytes = 4 * cfg.B * groups.nnz
+    g_s = stage_ms["gather"] * 1e-3
+    roofline_gather = {"bound": "lds", "kernel": "gather",
+                       "achieved": round(lds_bytes / g_s / 1e9, 1), "peak": round(LDS_PEAK_GBS, 1),
+                       "unit": "GB/s", "frac": round(lds_bytes / g_s / 1e9 / LDS_PEAK_GBS, 4),
+                       "traffic": MEASURED_TRAFFIC_BYTES.get(f"gather@{cfg.name}"),
+                       "algorithmic_bytes": lds_bytes,
+                       "hbm_algorithmic_bytes": 4 * cfg.B * cfg.V + 4 * cfg.B * groups.G
+                                                + 2 * groups.nnz,
+                       "kernel_us": round(1e3 * stage_ms["gather"], 2)}
 
     result = {
         "metric": "verified draft positions/sec at V=65536,B=64,K=8; achieved HBM GB/s vs peak",
@@ -156,7 +177,9 @@ def main():
         "step_hbm_frac": round((logits_b + csr_b + small_b) / elapsed * args.steps / 1e9
                                / HBM_PEAK_GBS, 4),
         "stages_us": {k: round(1e3 * v, 2) for k, v in stage_ms.items()},
+        "event_overhead_us": round(1e3 * overhead_ms, 2), "longest_kernel": by_time,
         "roofline": roofline,
+        "roofline_longest_kernel": roofline_gather,
     }
 
     if not args.no_cpu_baseline:
@@ -175,7 +198,7 @@ def main():
             used = r.threads
             n += 1
             dt = time.perf_counter() - c0
-            if dt >= args.cpu_seconds or n >= 200:
+            if dt >= args.cpu_seconds or n >= 5000:
                 break
         result["cpu_baseline"] = {"value": round(positions * n / dt, 1), "unit": "positions/s",
                                   "cores": used, "kind": "oracle",

@@ -228,7 +228,9 @@ int pcg_groups_prepare_host(int32_t V, int32_t G, const int32_t *row_ptr, const 
  * it off otherwise).  pcg_profile_end synchronises those events and writes, for each stage,
  * the mean duration in milliseconds over the recorded calls (HOST float [PCG_MAX_STAGES],
  * unused entries 0), the number of calls (HOST) and returns PCG_OK.  At most `max_calls`
- * calls are recorded; later ones run unrecorded.  Stage names: pcg_stage_name(i).
+ * calls are recorded; later ones run unrecorded.  Stage names: pcg_stage_name(i).  The stage
+ * "event_overhead" is an empty event pair recorded at the start of each call: the time an
+ * event pair adds, which is included in every other stage's figure.
  * Not thread-safe; one profile at a time.
  */
 int pcg_profile_begin(int32_t max_calls);

@@ -25,8 +25,9 @@ size_t align_up(size_t n) { return (n + kAlign - 1) / kAlign * kAlign; }
 
 // ---- per-kernel timing -------------------------------------------------------------------
 
-enum Stage { kStageStats = 0, kStageAccept, kStageTable, kStageGather, kStageFinalize, kNumStages };
-const char *const kStageNames[kNumStages] = {"row_stats", "accept_delta", "weights", "gather", "finalize"};
+enum Stage { kStageStats = 0, kStageAccept, kStageTable, kStageGather, kStageFinalize, kStageNull, kNumStages };
+const char *const kStageNames[kNumStages] = {"row_stats", "accept_delta", "weights", "gather", "finalize",
+                                             "event_overhead"};
 
 struct Profile {
   bool active = false;
@@ -41,6 +42,10 @@ struct StageTimer {
   int slot;          // index of the recorded call, -1 if not recording
   explicit StageTimer(hipStream_t s) : stream(s), slot(-1) {
     if (g_prof.active && g_prof.calls < g_prof.max_calls) slot = g_prof.calls++;
+    // two events with nothing between them: what an event pair costs on this stream, to be
+    // taken off the stage times by whoever reads them
+    begin(kStageNull);
+    end(kStageNull);
   }
   void begin(Stage st) {
     if (slot < 0) return;
@@ -289,7 +294,8 @@ int pcg_profile_begin(int32_t max_calls) {
   g_prof.ev.assign((size_t) max_calls * 2 * kNumStages, nullptr);
   g_prof.used.assign((size_t) max_calls * kNumStages, 0);
   for (auto &ev : g_prof.ev) {
-    hipError_t e = hipEventCreate(&ev);
+    // timing events need no cache flush of their own
+    hipError_t e = hipEventCreateWithFlags(&ev, hipEventDisableSystemFence);
     if (e != hipSuccess) {
       for (auto &x : g_prof.ev) if (x) (void) hipEventDestroy(x);
       g_prof.ev.clear();

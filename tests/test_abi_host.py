@@ -152,8 +152,8 @@ def test_profile_calls_are_guarded():
     n = C.c_int32()
     assert L.pcg_profile_end(ms, C.byref(n)) == BAD_SHAPE      # nothing was begun
     assert L.pcg_profile_begin(0) == BAD_SHAPE
-    assert [pcg.lib().pcg_stage_name(i).decode() for i in range(6)] == \
-        ["row_stats", "accept_delta", "weights", "gather", "finalize", ""]
+    assert [pcg.lib().pcg_stage_name(i).decode() for i in range(7)] == \
+        ["row_stats", "accept_delta", "weights", "gather", "finalize", "event_overhead", ""]
 
 
 # --------------------------------------------------------------------------- prepared layout

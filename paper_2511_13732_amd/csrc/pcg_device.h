@@ -158,11 +158,12 @@ __device__ __forceinline__ Uniforms philox_uniforms(uint64_t seed, uint64_t offs
 // Per-row softmax statistics.
 // ---------------------------------------------------------------------------------------------
 
-// One wave's share of a row: the exact maximum m of its logits and z = sum 2^((x - m) * c).
+// One wave's share of a row: the exact maximum m of its logits, the log2-domain reference
+// t = fl(m * c) and z = sum 2^(x * c - t).
 struct StatPart {
   double z;
   float m;
-  float pad;
+  float t;
 };
 
 // A whole row: M = max logit, Z = sum over the row of exp((x - M) / temperature).

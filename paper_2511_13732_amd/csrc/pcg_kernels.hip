@@ -87,15 +87,18 @@ __global__ __launch_bounds__(kStatsWaves *kWave) void row_stats_kernel(RowSet rs
   }
   const float m = wave_max(fmaxf(m0, m1));
 
-  // exponentials relative to the wave's own maximum: (x - m) is exact for bf16 inputs, so
-  // the dominant terms carry no argument error
+  // Exponentials relative to the wave's own maximum, in the log2 domain: t = fl(m * c) is the
+  // reference, and each term is 2^(x * c - t) with the product exact inside the fused
+  // multiply-add, so terms near the maximum carry no argument error.  Whoever merges the parts
+  // rescales by 2^(t - M * c) in double; t is an exact float, so nothing is lost.
+  const float t = m * c;
   float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
 #pragma unroll
   for (int j = 0; j < 32; j += 4) {
-    s0 += __builtin_amdgcn_exp2f((x[j] - m) * c);
-    s1 += __builtin_amdgcn_exp2f((x[j + 1] - m) * c);
-    s2 += __builtin_amdgcn_exp2f((x[j + 2] - m) * c);
-    s3 += __builtin_amdgcn_exp2f((x[j + 3] - m) * c);
+    s0 += __builtin_amdgcn_exp2f(fmaf(x[j], c, -t));
+    s1 += __builtin_amdgcn_exp2f(fmaf(x[j + 1], c, -t));
+    s2 += __builtin_amdgcn_exp2f(fmaf(x[j + 2], c, -t));
+    s3 += __builtin_amdgcn_exp2f(fmaf(x[j + 3], c, -t));
   }
   double z = (double) ((s0 + s1) + (s2 + s3));
   if (m == -INFINITY) z = 0.0;   // (-inf) - (-inf) is NaN: an all -inf part holds no mass
@@ -104,13 +107,13 @@ __global__ __launch_bounds__(kStatsWaves *kWave) void row_stats_kernel(RowSet rs
     StatPart sp;
     sp.z = z;
     sp.m = m;
-    sp.pad = 0.f;
+    sp.t = t;
     parts[row * nparts + part] = sp;
   }
 }
 
 // Merge the parts of one row inside a wave: every lane returns the row's (M, Z).
-// c must be the same fp32 factor row_stats used, so that 2^((x-m)c) * 2^((m-M)c) = 2^((x-M)c).
+// c must be the same fp32 factor row_stats used, so that 2^(xc-t) * 2^(t-Mc) = 2^((x-M)c).
 __device__ __forceinline__ RowStat merge_row(const StatPart *parts, int64_t row, int32_t nparts,
                                              float c, int lane) {
   const StatPart *rp = parts + row * nparts;
@@ -120,7 +123,7 @@ __device__ __forceinline__ RowStat merge_row(const StatPart *parts, int64_t row,
   double Z = 0.0;
   for (int32_t k = lane; k < nparts; k += kWave) {
     StatPart sp = rp[k];
-    if (sp.z > 0.0) Z += sp.z * exp2((double) (sp.m - M) * (double) c);
+    if (sp.z > 0.0) Z += sp.z * exp2((double) sp.t - (double) M * (double) c);
   }
   Z = wave_sum(Z);
   RowStat r;

@@ -95,7 +95,8 @@ def main():
     cfg = W.CONFIGS[args.config]
     t0 = time.time()
     rp, mem = W.groups(cfg)
-    groups = pcg.Groups.from_csr(cfg.V, rp, mem, dev)
+    groups = pcg.Groups.from_csr(cfg.V, rp, mem, dev,
+                                 chunk_groups=pcg.suggest_chunk_groups(len(rp) - 1, cfg.B))
     rp_c, mem_c, _ = pcg.groups_canonicalize_host(cfg.V, rp, mem)
     print(f"[bench] {cfg.name}: V={cfg.V} G={groups.G} nnz={groups.nnz} B={cfg.B} K={cfg.K} "
           f"{cfg.dtype} (groups built in {time.time() - t0:.1f}s)", file=sys.stderr, flush=True)

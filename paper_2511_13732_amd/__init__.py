@@ -6,10 +6,10 @@ step of the path runs in the library's kernels.
 """
 from .binding import (BF16, F32, Diag, Groups, PcgError, PreparedInfo, VerifyOutput, group_probs,
                       group_probs_workspace_bytes, groups_canonicalize_host,
-                      groups_prepare_host, groups_validate_host, lib, lib_path, profile_begin, profile_end, strerror,
+                      groups_prepare_host, groups_validate_host, lib, lib_path, profile_begin, profile_end, strerror, suggest_chunk_groups,
                       verify, verify_workspace_bytes, version)
 
 __all__ = ["BF16", "F32", "Diag", "Groups", "PcgError", "PreparedInfo", "VerifyOutput", "group_probs",
            "group_probs_workspace_bytes", "groups_canonicalize_host", "groups_prepare_host", "groups_validate_host",
-           "lib", "lib_path", "profile_begin", "profile_end", "strerror", "verify",
+           "lib", "lib_path", "profile_begin", "profile_end", "strerror", "suggest_chunk_groups", "verify",
            "verify_workspace_bytes", "version"]

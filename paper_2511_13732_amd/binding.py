@@ -141,6 +141,14 @@ def groups_canonicalize_host(V: int, row_ptr, members):
     return orp, omem[:onnz.value], omult
 
 
+def suggest_chunk_groups(G: int, batch: int) -> int:
+    """Groups per workgroup of the prepared gather for an expected batch (sequences, or rows of
+    pcg_group_probs): small enough to give each of the 256 compute units a workgroup, within the
+    library's limits (a multiple of 4096 up to 16384)."""
+    want = -(-G * max(1, batch) // 256)
+    return int(min(16384, max(4096, -(-want // 4096) * 4096)))
+
+
 def groups_prepare_host(V: int, row_ptr, members, chunk_groups: int = 0):
     """(blob uint8 array, PreparedInfo) of a canonical host CSR; see pcg_groups_prepare_host."""
     rp, mem = _np_i32(row_ptr), _np_i32(members)

@@ -345,3 +345,25 @@ def test_recipe_full_size(name, steps):
             assert err <= TOL_F32
     total.report(f"recipe {name} full size")
     assert total.tolerated <= max(1, total.sequences // 100)
+
+
+def test_profile_reports_every_kernel_of_a_step():
+    cfg = W.CONFIGS["C2"]
+    rp, mem = W.groups(cfg)
+    og = oracle_groups(cfg.V, rp, mem)
+    dg = device_groups(cfg.V, rp, mem, chunk_groups=pcg.suggest_chunk_groups(og.G, cfg.B))
+    tgt, dft, ptok, pgrp = W.step_inputs(cfg, og.row_ptr, og.members, 0)
+    args = (dg, tgt.cuda(), dft.cuda(), torch.from_numpy(ptok).cuda(), torch.from_numpy(pgrp).cuda())
+    plain = pcg.verify(*args, seed=1, offset=2)
+    pcg.profile_begin(4)
+    for _ in range(6):                     # two more calls than slots: they run unrecorded
+        timed = pcg.verify(*args, seed=1, offset=2)
+    torch.cuda.synchronize()
+    ms, calls = pcg.profile_end()
+    assert calls == 4
+    for k in ("row_stats", "accept_delta", "gather", "finalize", "event_overhead"):
+        assert 0.0 < ms[k] < 5.0, (k, ms)
+    assert ms["weights"] == 0.0
+    assert torch.equal(plain.out_tokens, timed.out_tokens)      # timing does not change results
+    with pytest.raises(pcg.PcgError):
+        pcg.profile_end()

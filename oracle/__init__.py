@@ -53,9 +53,14 @@ def lib():
         _lib.pcg_ref_uniforms.restype = None
         _lib.pcg_ref_uniforms.argtypes = [C.c_uint64, C.c_uint64, C.c_uint32, C.c_uint32,
                                           C.c_void_p, C.c_void_p, C.c_void_p]
+        _lib.pcg_ref_trial_uniforms.restype = None
+        _lib.pcg_ref_trial_uniforms.argtypes = [C.c_uint64, C.c_uint64, C.c_uint32, C.c_uint32,
+                                                C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                                C.c_void_p]
         for name in ("pcg_ref_softmax_row", "pcg_ref_count_mult", "pcg_ref_canonicalize",
                      "pcg_ref_validate", "pcg_ref_group_probs", "pcg_ref_verify_u",
-                     "pcg_ref_verify"):
+                     "pcg_ref_verify", "pcg_ref_reverse_index", "pcg_ref_thin_trial",
+                     "pcg_ref_verify_thinning"):
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -257,4 +262,80 @@ def verify(g: Groups, target_logits, draft_logits, prop_tokens, prop_groups, *,
                                   C.c_int32(nthreads), C.byref(used))
         res.threads = used.value
     _check(rc, "verify")
+    return res
+
+
+# --------------------------------------------------------------------------- thinning (Eq. 9)
+
+class _Trial(C.Structure):
+    _fields_ = [("y", C.c_int32), ("group", C.c_int32), ("accepted", C.c_int32),
+                ("token", C.c_int32), ("T", C.c_double), ("D", C.c_double), ("near", C.c_uint8)]
+
+
+def reverse_index(g: Groups) -> tuple[np.ndarray, np.ndarray]:
+    """token -> groups holding it: (tok_ptr [V+1], tok_groups [nnz])."""
+    tok_ptr = np.empty(g.V + 1, dtype=np.int32)
+    tok_groups = np.empty(max(1, g.nnz), dtype=np.int32)
+    _check(lib().pcg_ref_reverse_index(C.c_int32(g.V), C.c_int32(g.G), _p(g.row_ptr), _p(g.members),
+                                       _p(tok_ptr), _p(tok_groups)), "reverse_index")
+    return tok_ptr, tok_groups[:g.nnz]
+
+
+def trial_uniforms(seed: int, offset: int, b: int, i: int, trial: int):
+    """(u_y, k24, u_a, u_tok) of one thinning trial."""
+    uy, ua, ut, k = C.c_double(), C.c_double(), C.c_double(), C.c_uint32()
+    lib().pcg_ref_trial_uniforms(C.c_uint64(seed), C.c_uint64(offset), C.c_uint32(b), C.c_uint32(i),
+                                 C.c_uint32(trial), C.byref(uy), C.byref(k), C.byref(ua), C.byref(ut))
+    return uy.value, k.value, ua.value, ut.value
+
+
+def thin_trial(g: Groups, rev, q: np.ndarray, p: Optional[np.ndarray], u_y: float, k24: int,
+               u_a: float, u_tok: float) -> _Trial:
+    """One thinning trial on token distributions q (target) and p (draft; None = bonus row)."""
+    tok_ptr, tok_groups = rev
+    q = np.ascontiguousarray(q, dtype=np.float64)
+    pp = None if p is None else np.ascontiguousarray(p, dtype=np.float64)
+    out = _Trial()
+    _check(lib().pcg_ref_thin_trial(C.c_int32(g.V), C.c_int32(g.G), _p(g.row_ptr), _p(g.members),
+                                    _p(g.mult), _p(tok_ptr), _p(tok_groups), _p(q), _p(pp),
+                                    C.c_double(u_y), C.c_uint32(k24), C.c_double(u_a),
+                                    C.c_double(u_tok), C.byref(out)), "thin_trial")
+    return out
+
+
+@dataclass
+class ThinningResult:
+    accept_len: np.ndarray     # int32 [B]
+    out_tokens: np.ndarray     # int32 [B, K+1]
+    out_groups: np.ndarray     # int32 [B, K+1]
+    trials: np.ndarray         # int32 [B]  thinning trials run (0 on the bonus position)
+    flags: np.ndarray          # uint8 [B]  bit0: a near-tie on the emitted path; bit1: max_trials hit
+    near_acc: np.ndarray       # uint8 [B, K]
+
+
+def verify_thinning(g: Groups, rev, target_logits, draft_logits, prop_tokens, prop_groups, *,
+                    temperature: float = 1.0, seed: int = 0, offset: int = 0,
+                    B: Optional[int] = None, tgt_batch_stride=None, dft_batch_stride=None,
+                    max_trials: int = 1 << 16, nthreads: int = 1) -> ThinningResult:
+    """One speculative step with the reject branch drawn by thinning."""
+    tgt, dt = _logits(target_logits)
+    dft, dt2 = _logits(draft_logits)
+    assert dt == dt2 and tgt.ndim == 3 and dft.ndim == 3
+    K = tgt.shape[1] - 1
+    if B is None:
+        B = tgt.shape[0]
+    tok_ptr, tok_groups = rev
+    ptok = _i32(prop_tokens).reshape(B, K)
+    pgrp = _i32(prop_groups).reshape(B, K)
+    tbs, tps = _strides(tgt, tgt_batch_stride, None)
+    dbs, dps = _strides(dft, dft_batch_stride, None)
+    res = ThinningResult(np.empty(B, np.int32), np.empty((B, K + 1), np.int32),
+                         np.empty((B, K + 1), np.int32), np.empty(B, np.int32),
+                         np.zeros(B, np.uint8), np.zeros((B, K), np.uint8))
+    _check(lib().pcg_ref_verify_thinning(
+        C.c_int32(g.V), C.c_int32(g.G), _p(g.row_ptr), _p(g.members), _p(g.mult), _p(tok_ptr),
+        _p(tok_groups), _p(tgt), _p(dft), C.c_int(dt), C.c_int32(B), C.c_int32(K), tbs, tps, dbs,
+        dps, C.c_double(temperature), _p(ptok), _p(pgrp), C.c_uint64(seed), C.c_uint64(offset),
+        _p(res.accept_len), _p(res.out_tokens), _p(res.out_groups), _p(res.trials), _p(res.flags),
+        _p(res.near_acc), C.c_int32(max_trials), C.c_int32(nthreads)), "verify_thinning")
     return res

@@ -425,3 +425,218 @@ int pcg_ref_verify(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *
   free(u);
   return rc;
 }
+
+/* ------------------------------------------------------------------------- */
+/* Residual sampling via thinning (Eq. 9).                                   */
+/* ------------------------------------------------------------------------- */
+
+int pcg_ref_reverse_index(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members,
+                          int32_t *tok_ptr, int32_t *tok_groups) {
+  if (V < 1 || G < 1 || !row_ptr || !members || !tok_ptr || !tok_groups) return PCG_REF_ERR_ARG;
+  if (!csr_shape_ok(V, G, row_ptr, members)) return PCG_REF_ERR_CSR;
+  for (int32_t v = 0; v <= V; ++v) tok_ptr[v] = 0;
+  for (int32_t j = 0; j < row_ptr[G]; ++j) tok_ptr[members[j] + 1] += 1;
+  for (int32_t v = 0; v < V; ++v) tok_ptr[v + 1] += tok_ptr[v];
+  int32_t *fill = (int32_t *)calloc((size_t)V, sizeof(int32_t));
+  if (!fill) return PCG_REF_ERR_NOMEM;
+  for (int32_t g = 0; g < G; ++g)
+    for (int32_t j = row_ptr[g]; j < row_ptr[g + 1]; ++j) {
+      int32_t t = members[j];
+      tok_groups[tok_ptr[t] + fill[t]++] = g;
+    }
+  free(fill);
+  return PCG_REF_OK;
+}
+
+void pcg_ref_trial_uniforms(uint64_t seed, uint64_t offset, uint32_t b, uint32_t i, uint32_t trial,
+                            double *u_y, uint32_t *k24, double *u_a, double *u_tok) {
+  uint32_t ctr[4] = {(uint32_t)offset, (uint32_t)(offset >> 32), b, i | ((trial + 1u) << 16)};
+  uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+  uint32_t w[4];
+  pcg_ref_philox4x32_10(ctr, key, w);
+  const double scale = 1.0 / 16777216.0;
+  *u_y = (double)(w[0] >> 8) * scale;
+  *k24 = w[1] >> 8;
+  *u_a = (double)(w[2] >> 8) * scale;
+  *u_tok = (double)(w[3] >> 8) * scale;
+}
+
+/* First index whose running sum strictly exceeds u * total (ascending order);
+ * the last index with mass if rounding leaves none; -1 if nothing has mass.
+ * *near is set when u * total lies within 1e-6 * total of an inner edge of the
+ * chosen bin. */
+static int64_t inverse_cdf(const double *w, int64_t n, double u, int *near) {
+  double total = 0.0;
+  for (int64_t k = 0; k < n; ++k) total += w[k];
+  double goal = u * total, cum = 0.0, lo = 0.0, hi = 0.0;
+  int64_t pick = -1, last = -1;
+  for (int64_t k = 0; k < n; ++k) {
+    if (w[k] > 0.0) last = k;
+    double nxt = cum + w[k];
+    if (pick < 0 && nxt > goal) { pick = k; lo = cum; hi = nxt; }
+    cum = nxt;
+  }
+  if (pick < 0) {
+    if (last < 0) { *near = 0; return -1; }
+    pick = last; lo = cum - w[last]; hi = cum;
+  }
+  *near = (lo > 0.0 && goal - lo < PCG_REF_NEAR_TIE * total) ||
+          (hi < cum && hi - goal < PCG_REF_NEAR_TIE * total);
+  return pick;
+}
+
+int pcg_ref_thin_trial(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members,
+                       const int32_t *mult, const int32_t *tok_ptr, const int32_t *tok_groups,
+                       const double *q, const double *p, double u_y, uint32_t k24, double u_a,
+                       double u_tok, pcg_ref_trial *out) {
+  if (!row_ptr || !members || !mult || !tok_ptr || !tok_groups || !q || !out || V < 1 || G < 1)
+    return PCG_REF_ERR_ARG;
+  int near = 0;
+  out->near = 0;
+  /* y ~ q */
+  int64_t y = inverse_cdf(q, V, u_y, &near);
+  if (y < 0) return PCG_REF_ERR_ROW;
+  if (near) out->near |= 1;
+  /* K ~ w_{.,y}: one of the N(y) membership entries of y, equally likely */
+  int32_t n = tok_ptr[y + 1] - tok_ptr[y];
+  if (n < 1) return PCG_REF_ERR_CSR;
+  int32_t g = tok_groups[tok_ptr[y] + (int32_t)(((uint64_t)k24 * (uint64_t)n) >> 24)];
+  double T = group_prob(q, row_ptr, members, mult, g);
+  double D = p ? group_prob(p, row_ptr, members, mult, g) : 0.0;
+  /* accept with probability [1 - D/T]_+, written without the division */
+  int accepted = p ? (u_a * T < T - D) : 1;
+  if (p && fabs(u_a * T - (T - D)) < PCG_REF_NEAR_TIE * T) out->near |= 2;
+  /* token inside the group, Eq. (10) */
+  int32_t beg = row_ptr[g], len = row_ptr[g + 1] - beg;
+  double *c = (double *)malloc((size_t)(len > 0 ? len : 1) * sizeof(double));
+  if (!c) return PCG_REF_ERR_NOMEM;
+  for (int32_t j = 0; j < len; ++j) c[j] = q[members[beg + j]] / (double)mult[members[beg + j]];
+  int64_t js = inverse_cdf(c, len, u_tok, &near);
+  free(c);
+  if (near) out->near |= 4;
+  out->y = (int32_t)y;
+  out->group = g;
+  out->accepted = accepted;
+  out->token = js < 0 ? -1 : members[beg + js];
+  out->T = T;
+  out->D = D;
+  return PCG_REF_OK;
+}
+
+int pcg_ref_verify_thinning(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members,
+                            const int32_t *mult, const int32_t *tok_ptr,
+                            const int32_t *tok_groups, const void *target_logits,
+                            const void *draft_logits, int dtype, int32_t B, int32_t K,
+                            int64_t tgt_batch_stride, int64_t tgt_pos_stride,
+                            int64_t dft_batch_stride, int64_t dft_pos_stride, double temperature,
+                            const int32_t *prop_tokens, const int32_t *prop_groups, uint64_t seed,
+                            uint64_t offset, int32_t *accept_len, int32_t *out_tokens,
+                            int32_t *out_groups, int32_t *trials, uint8_t *flags,
+                            uint8_t *near_acc, int32_t max_trials, int32_t nthreads) {
+  if (!row_ptr || !members || !mult || !tok_ptr || !tok_groups || !target_logits ||
+      !draft_logits || !prop_tokens || !prop_groups || !accept_len || !out_tokens ||
+      !out_groups || !trials || !flags)
+    return PCG_REF_ERR_ARG;
+  if (V < 1 || G < 1 || B < 0 || K < 1 || K > 0xFFFF || max_trials < 1 ||
+      !(temperature > 0.0))
+    return PCG_REF_ERR_ARG;
+  if (dtype != PCG_REF_F32 && dtype != PCG_REF_BF16) return PCG_REF_ERR_ARG;
+  int rc = pcg_ref_validate(V, G, row_ptr, members, mult);
+  if (rc) return rc;
+  if (nthreads < 1) nthreads = 1;
+  int status = PCG_REF_OK;
+#ifdef _OPENMP
+#pragma omp parallel num_threads(nthreads)
+#endif
+  {
+    double *q = (double *)malloc(2 * (size_t)V * sizeof(double));
+    double *p = q ? q + V : NULL;
+    if (!q) {
+#ifdef _OPENMP
+#pragma omp critical
+#endif
+      status = PCG_REF_ERR_NOMEM;
+    }
+#ifdef _OPENMP
+#pragma omp barrier
+#pragma omp for schedule(dynamic, 1)
+#endif
+    for (int32_t b = 0; b < B; ++b) {
+      if (!q || status != PCG_REF_OK) continue;
+      int32_t *otok = out_tokens + (int64_t)b * (K + 1);
+      int32_t *ogrp = out_groups + (int64_t)b * (K + 1);
+      for (int32_t i = 0; i <= K; ++i) otok[i] = ogrp[i] = -1;
+      flags[b] = 0;
+      trials[b] = 0;
+      int r = PCG_REF_OK;
+      /* the accept scan of Algorithm 1, with the draws of pcg_ref_verify */
+      int32_t i = 0;
+      while (i < K && r == PCG_REF_OK) {
+        r = softmax_row_at(target_logits, dtype, b * tgt_batch_stride + i * tgt_pos_stride, V,
+                           temperature, q);
+        if (r) break;
+        r = softmax_row_at(draft_logits, dtype, b * dft_batch_stride + i * dft_pos_stride, V,
+                           temperature, p);
+        if (r) break;
+        int32_t g = prop_groups[(int64_t)b * K + i];
+        if (g < 0 || g >= G) { r = PCG_REF_ERR_ARG; break; }
+        double Tp = group_prob(q, row_ptr, members, mult, g);
+        double Dp = group_prob(p, row_ptr, members, mult, g);
+        double ua;
+        pcg_ref_uniforms(seed, offset, (uint32_t)b, (uint32_t)i, &ua, NULL, NULL);
+        if (near_acc) near_acc[(int64_t)b * K + i] = fabs(ua * Dp - Tp) < PCG_REF_NEAR_TIE * Dp;
+        if (!(ua * Dp < Tp)) break;
+        otok[i] = prop_tokens[(int64_t)b * K + i];
+        ogrp[i] = g;
+        ++i;
+      }
+      if (near_acc)
+        for (int32_t k = i + 1; k < K; ++k) near_acc[(int64_t)b * K + k] = 0;
+      if (r == PCG_REF_OK) {
+        accept_len[b] = i;
+        pcg_ref_trial tr;
+        double uy, uacc, ut;
+        uint32_t k24;
+        if (i == K) { /* bonus: token from the target's last row, its group by the weights */
+          r = softmax_row_at(target_logits, dtype, b * tgt_batch_stride + i * tgt_pos_stride, V,
+                             temperature, q);
+          if (r == PCG_REF_OK) {
+            pcg_ref_trial_uniforms(seed, offset, (uint32_t)b, (uint32_t)i, 0, &uy, &k24, &uacc, &ut);
+            r = pcg_ref_thin_trial(V, G, row_ptr, members, mult, tok_ptr, tok_groups, q, NULL, uy,
+                                   k24, uacc, ut, &tr);
+            if (r == PCG_REF_OK) {
+              otok[i] = tr.y;
+              ogrp[i] = tr.group;
+              if (tr.near & 1) flags[b] |= 1;
+            }
+          }
+        } else {
+          for (int32_t t = 0; r == PCG_REF_OK; ++t) {
+            pcg_ref_trial_uniforms(seed, offset, (uint32_t)b, (uint32_t)i, (uint32_t)t, &uy, &k24,
+                                   &uacc, &ut);
+            r = pcg_ref_thin_trial(V, G, row_ptr, members, mult, tok_ptr, tok_groups, q, p, uy,
+                                   k24, uacc, ut, &tr);
+            if (r) break;
+            trials[b] = t + 1;
+            if (tr.near & 3) flags[b] |= 1;
+            if (tr.accepted || t + 1 >= max_trials) {
+              if (tr.near & 4) flags[b] |= 1;
+              if (!tr.accepted) flags[b] |= 2;
+              otok[i] = tr.token;
+              ogrp[i] = tr.group;
+              break;
+            }
+          }
+        }
+      }
+      if (r) {
+#ifdef _OPENMP
+#pragma omp critical
+#endif
+        status = r;
+      }
+    }
+    free(q);
+  }
+  return status;
+}

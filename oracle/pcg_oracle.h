@@ -121,6 +121,64 @@ int pcg_ref_verify(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *
                    int32_t *out_groups, const pcg_ref_trace *trace, int32_t nthreads,
                    int32_t *threads_used);
 
+/* ------------------------------------------------------------------------- */
+/* Residual sampling via thinning (Sec. 2.2 "Residual sampling via thinning", */
+/* Eq. 9): the paper's own way to draw from the group residual without        */
+/* enumerating the groups.  Same law as the enumerated residual above, a       */
+/* different sample path, hence entry points of its own.                       */
+/* ------------------------------------------------------------------------- */
+
+/* Reverse index token -> groups holding it (the paper's S(t)): tok_ptr [V+1],
+ * tok_groups [nnz]; a token's groups appear in ascending CSR entry position, a
+ * group listing the token twice appears twice. */
+int pcg_ref_reverse_index(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members,
+                          int32_t *tok_ptr, int32_t *tok_groups);
+
+/* Draws of thinning trial `trial` (0, 1, ...) at position (b, i): Philox block
+ * with counter (offset_lo, offset_hi, b, i | (trial + 1) << 16); word 0 -> u_y,
+ * word 1 >> 8 -> k24 (a 24-bit integer), word 2 -> u_a, word 3 -> u_tok. */
+void pcg_ref_trial_uniforms(uint64_t seed, uint64_t offset, uint32_t b, uint32_t i, uint32_t trial,
+                            double *u_y, uint32_t *k24, double *u_a, double *u_tok);
+
+typedef struct {
+  int32_t y;          /* token drawn from the target distribution                         */
+  int32_t group;      /* one of the groups holding y, by the weights w_{k,y}              */
+  int32_t accepted;   /* 1 iff u_a < [1 - D[group] / T[group]]_+                          */
+  int32_t token;      /* token inside `group` by Eq. (10) (computed whether accepted or not) */
+  double T, D;        /* group probabilities of `group`                                   */
+  uint8_t near;       /* bit0: u_y near an inner bin edge; bit1: accept draw near its
+                         threshold; bit2: u_tok near an inner edge                        */
+} pcg_ref_trial;
+
+/* One trial with explicit draws, on given token distributions q (target) and
+ * p (draft), both [V].  With p == NULL nothing is subtracted (bonus row):
+ * the trial is always accepted. */
+int pcg_ref_thin_trial(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members,
+                       const int32_t *mult, const int32_t *tok_ptr, const int32_t *tok_groups,
+                       const double *q, const double *p, double u_y, uint32_t k24, double u_a,
+                       double u_tok, pcg_ref_trial *out);
+
+/* One speculative step for B sequences, reject branch by thinning.  The accept
+ * scan and its draws are those of pcg_ref_verify.  On a reject at position i
+ * trials 0, 1, ... are run until one is accepted (at most max_trials; then the
+ * last candidate is emitted and flags bit1 is set).  On the bonus position the
+ * token is drawn from the target row and its group by the weights (Algorithm 1,
+ * last step; Eq. 6), using the draws of trial 0.
+ *   trials [B]  number of trials run (0 on the bonus position)
+ *   flags  [B]  bit0: some decision of the emitted path was within 1e-6 of its
+ *               threshold; bit1: max_trials reached
+ *   near_acc [B*K] as in pcg_ref_trace (may be NULL) */
+int pcg_ref_verify_thinning(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members,
+                            const int32_t *mult, const int32_t *tok_ptr,
+                            const int32_t *tok_groups, const void *target_logits,
+                            const void *draft_logits, int dtype, int32_t B, int32_t K,
+                            int64_t tgt_batch_stride, int64_t tgt_pos_stride,
+                            int64_t dft_batch_stride, int64_t dft_pos_stride, double temperature,
+                            const int32_t *prop_tokens, const int32_t *prop_groups, uint64_t seed,
+                            uint64_t offset, int32_t *accept_len, int32_t *out_tokens,
+                            int32_t *out_groups, int32_t *trials, uint8_t *flags,
+                            uint8_t *near_acc, int32_t max_trials, int32_t nthreads);
+
 #ifdef __cplusplus
 }
 #endif

@@ -83,6 +83,10 @@ typedef struct {
    * uploaded to the DEVICE and its HOST descriptor.  Both NULL = use the CSR directly. */
   const void *prepared;
   const pcg_prepared *prepared_info;
+  /* Optional reverse index token -> groups (the paper's S(t); see pcg_groups_reverse_host),
+   * DEVICE: tok_ptr [V+1], tok_groups [nnz].  Needed by pcg_verify_thinning only. */
+  const int32_t *tok_ptr;
+  const int32_t *tok_groups;
 } pcg_groups;
 
 /*
@@ -186,6 +190,43 @@ int pcg_verify(const pcg_groups *groups, const void *target_logits, const void *
 
 size_t pcg_verify_workspace_bytes(int32_t V, int32_t G, int32_t B, int32_t K);
 
+/* ---- the same step with the reject branch drawn by thinning ------------------------------ */
+
+#define PCG_THIN_MAX_TRIALS 65520
+
+/*
+ * pcg_verify with the group residual of Eq. (8) drawn the way the paper itself does it
+ * (Sec. 2.2 "Residual sampling via thinning", Eq. 9) instead of by enumerating the groups:
+ * trial j = 0, 1, ... draws a token y from the target row, one of the mult[y] membership
+ * entries of y (hence a group g with probability T[g]), and accepts g with probability
+ * [1 - D[g]/T[g]]_+; the first accepted trial emits g and a token inside it by Eq. (10).
+ * Same distribution as pcg_verify, a different sample path: the accept scan and its draws are
+ * identical, the emitted (token, group) on a rejection is not.  When every proposal is
+ * accepted the bonus token is drawn from the target's last row and its group by the weights
+ * (Algorithm 1, last step; Eq. 6).
+ *   groups        must carry tok_ptr / tok_groups; the prepared form is not used
+ *   draws         trial j of position (b, i) uses the Philox block with counter
+ *                 (offset_lo, offset_hi, b, i | (j + 1) << 16): word 0 -> token uniform,
+ *                 word 1 >> 8 = k24 -> membership entry (k24 * mult[y]) >> 24, word 2 -> accept
+ *                 uniform, word 3 -> token-in-group uniform; the bonus position uses trial 0
+ *   trials        DEVICE int32 [B]: trials run for the sequence (0 on the bonus position)
+ *   diag          near_group counts token / accept draws within 1e-6 of their threshold on the
+ *                 emitted path, near_token the token-in-group draw, residual_fallback sequences
+ *                 that hit PCG_THIN_MAX_TRIALS (the last candidate is emitted then)
+ *   workspace     >= pcg_verify_thinning_workspace_bytes(V, B, K)
+ * Other arguments, conventions and limits as for pcg_verify; V must not exceed 4 194 304.
+ */
+int pcg_verify_thinning(const pcg_groups *groups, const void *target_logits,
+                        const void *draft_logits, pcg_dtype dt, int32_t B, int32_t K,
+                        int64_t tgt_batch_stride, int64_t tgt_pos_stride, int64_t dft_batch_stride,
+                        int64_t dft_pos_stride, float temperature, const int32_t *prop_tokens,
+                        const int32_t *prop_groups, uint64_t seed, uint64_t offset,
+                        int32_t *accept_len, int32_t *out_tokens, int32_t *out_groups,
+                        int32_t *trials, pcg_diag *diag, void *workspace, size_t workspace_bytes,
+                        void *hip_stream);
+
+size_t pcg_verify_thinning_workspace_bytes(int32_t V, int32_t B, int32_t K);
+
 /* ---- group membership on the host -------------------------------------------------------- */
 
 /* PCG_OK iff (row_ptr, members, mult), all HOST, form a membership the kernels may use (see
@@ -204,6 +245,12 @@ int pcg_groups_validate_host(int32_t V, int32_t G, const int32_t *row_ptr,
 int pcg_groups_canonicalize_host(int32_t V, int32_t G, const int32_t *row_ptr,
                                  const int32_t *members, int32_t *out_G, int64_t *out_nnz,
                                  int32_t *out_row_ptr, int32_t *out_members, int32_t *out_mult);
+
+/* Reverse index of a membership (all pointers HOST): tok_ptr [V+1], tok_groups [nnz]; the
+ * groups of a token are listed by ascending CSR entry position (a group that lists the token
+ * twice appears twice), so tok_ptr[v+1] - tok_ptr[v] == mult[v]. */
+int pcg_groups_reverse_host(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members,
+                            int32_t *tok_ptr, int32_t *tok_groups);
 
 /*
  * Build the prepared form of a validated membership (all pointers HOST).  chunk_groups is the

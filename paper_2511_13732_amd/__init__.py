@@ -4,12 +4,16 @@ Thin Python binding over ``libpcg.so`` (hand-written HIP for gfx950, C ABI in
 ``include/pcg.h``).  PyTorch supplies device memory and streams only; every
 step of the path runs in the library's kernels.
 """
-from .binding import (BF16, F32, Diag, Groups, PcgError, PreparedInfo, VerifyOutput, group_probs,
-                      group_probs_workspace_bytes, groups_canonicalize_host,
-                      groups_prepare_host, groups_validate_host, lib, lib_path, profile_begin, profile_end, strerror, suggest_chunk_groups,
-                      verify, verify_workspace_bytes, version)
+from .binding import (BF16, F32, THIN_MAX_TRIALS, Diag, Groups, PcgError, PreparedInfo,
+                      VerifyOutput, group_probs, group_probs_workspace_bytes,
+                      groups_canonicalize_host, groups_prepare_host, groups_reverse_host,
+                      groups_validate_host, lib, lib_path, profile_begin, profile_end, strerror,
+                      suggest_chunk_groups, verify, verify_thinning,
+                      verify_thinning_workspace_bytes, verify_workspace_bytes, version)
 
-__all__ = ["BF16", "F32", "Diag", "Groups", "PcgError", "PreparedInfo", "VerifyOutput", "group_probs",
-           "group_probs_workspace_bytes", "groups_canonicalize_host", "groups_prepare_host", "groups_validate_host",
-           "lib", "lib_path", "profile_begin", "profile_end", "strerror", "suggest_chunk_groups", "verify",
+__all__ = ["BF16", "F32", "THIN_MAX_TRIALS", "Diag", "Groups", "PcgError", "PreparedInfo",
+           "VerifyOutput", "group_probs", "group_probs_workspace_bytes",
+           "groups_canonicalize_host", "groups_prepare_host", "groups_reverse_host",
+           "groups_validate_host", "lib", "lib_path", "profile_begin", "profile_end", "strerror",
+           "suggest_chunk_groups", "verify", "verify_thinning", "verify_thinning_workspace_bytes",
            "verify_workspace_bytes", "version"]

@@ -36,7 +36,8 @@ class PreparedInfo(C.Structure):
 class _GroupsStruct(C.Structure):
     _fields_ = [("V", C.c_int32), ("G", C.c_int32), ("nnz", C.c_int64),
                 ("row_ptr", C.c_void_p), ("members", C.c_void_p), ("mult", C.c_void_p),
-                ("prepared", C.c_void_p), ("prepared_info", C.POINTER(PreparedInfo))]
+                ("prepared", C.c_void_p), ("prepared_info", C.POINTER(PreparedInfo)),
+                ("tok_ptr", C.c_void_p), ("tok_groups", C.c_void_p)]
 
 
 class Diag(C.Structure):
@@ -74,6 +75,17 @@ def lib() -> C.CDLL:
                                  C.c_float, C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint64,
                                  C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                  C.c_size_t, C.c_void_p]
+        L.pcg_verify_thinning_workspace_bytes.restype = C.c_size_t
+        L.pcg_verify_thinning_workspace_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32]
+        L.pcg_verify_thinning.restype = C.c_int
+        L.pcg_verify_thinning.argtypes = [C.POINTER(_GroupsStruct), C.c_void_p, C.c_void_p, C.c_int,
+                                          C.c_int32, C.c_int32, C.c_int64, C.c_int64, C.c_int64,
+                                          C.c_int64, C.c_float, C.c_void_p, C.c_void_p, C.c_uint64,
+                                          C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                          C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.pcg_groups_reverse_host.restype = C.c_int
+        L.pcg_groups_reverse_host.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                              C.c_void_p, C.c_void_p]
         L.pcg_groups_validate_host.restype = C.c_int
         L.pcg_groups_validate_host.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                                C.c_void_p]
@@ -141,6 +153,16 @@ def groups_canonicalize_host(V: int, row_ptr, members):
     return orp, omem[:onnz.value], omult
 
 
+def groups_reverse_host(V: int, row_ptr, members):
+    """(tok_ptr [V+1], tok_groups [nnz]): the groups holding each token."""
+    rp, mem = _np_i32(row_ptr), _np_i32(members)
+    tok_ptr = np.empty(V + 1, np.int32)
+    tok_groups = np.empty(max(1, len(mem)), np.int32)
+    _check(lib().pcg_groups_reverse_host(V, len(rp) - 1, rp.ctypes.data, mem.ctypes.data,
+                                         tok_ptr.ctypes.data, tok_groups.ctypes.data), "reverse")
+    return tok_ptr, tok_groups[:len(mem)]
+
+
 def suggest_chunk_groups(G: int, batch: int) -> int:
     """Groups per workgroup of the prepared gather for an expected batch (sequences, or rows of
     pcg_group_probs): small enough to give each of the 256 compute units a workgroup, within the
@@ -169,19 +191,21 @@ class Groups:
 
     def __init__(self, V: int, row_ptr: torch.Tensor, members: torch.Tensor, mult: torch.Tensor,
                  nnz: int, prepared: Optional[torch.Tensor] = None,
-                 prepared_info: Optional[PreparedInfo] = None):
+                 prepared_info: Optional[PreparedInfo] = None,
+                 tok_ptr: Optional[torch.Tensor] = None, tok_groups: Optional[torch.Tensor] = None):
         for t in (row_ptr, members, mult):
             assert t.dtype == torch.int32 and t.is_contiguous()
         self.V, self.G, self.nnz = int(V), int(row_ptr.numel() - 1), int(nnz)
         self.row_ptr, self.members, self.mult = row_ptr, members, mult
         self.prepared, self.prepared_info = prepared, prepared_info
+        self.tok_ptr, self.tok_groups = tok_ptr, tok_groups
         self.device = row_ptr.device
 
     @classmethod
     def from_csr(cls, V: int, row_ptr, members, device="cuda", prepare: bool = True,
-                 chunk_groups: int = 0) -> "Groups":
+                 chunk_groups: int = 0, reverse: bool = False) -> "Groups":
         """Canonicalise and validate a host CSR with the library, then upload it (with the
-        prepared layout unless prepare=False)."""
+        prepared layout unless prepare=False, with the token -> groups index if reverse)."""
         rp, mem, mult = groups_canonicalize_host(V, row_ptr, members)
         _check(groups_validate_host(V, rp, mem, mult), "validate")
         dev = torch.device(device)
@@ -190,8 +214,12 @@ class Groups:
         if prepare:
             blob, info = groups_prepare_host(V, rp, mem, chunk_groups)
             blob_dev = up(blob)
+        tp = tg = None
+        if reverse:
+            tok_ptr, tok_groups = groups_reverse_host(V, rp, mem)
+            tp, tg = up(tok_ptr), up(tok_groups if len(tok_groups) else np.zeros(1, np.int32))
         return cls(V, up(rp), up(mem if len(mem) else np.zeros(1, np.int32)), up(mult), len(mem),
-                   blob_dev, info)
+                   blob_dev, info, tp, tg)
 
     def without_prepared(self) -> "Groups":
         """The same membership, read through the CSR by the generic kernel."""
@@ -201,7 +229,9 @@ class Groups:
         return _GroupsStruct(self.V, self.G, self.nnz, self.row_ptr.data_ptr(),
                              self.members.data_ptr(), self.mult.data_ptr(),
                              None if self.prepared is None else self.prepared.data_ptr(),
-                             None if self.prepared_info is None else C.pointer(self.prepared_info))
+                             None if self.prepared_info is None else C.pointer(self.prepared_info),
+                             None if self.tok_ptr is None else self.tok_ptr.data_ptr(),
+                             None if self.tok_groups is None else self.tok_groups.data_ptr())
 
 
 # --------------------------------------------------------------------------- calls
@@ -311,6 +341,59 @@ def verify(groups: Groups, target_logits: torch.Tensor, draft_logits: torch.Tens
                                 None if diag is None else diag.data_ptr(), ws.data_ptr(),
                                 ws.numel(), _stream(dev)), "pcg_verify")
     return out
+
+
+THIN_MAX_TRIALS = 65520      # PCG_THIN_MAX_TRIALS of pcg.h
+
+
+def verify_thinning_workspace_bytes(V: int, B: int, K: int) -> int:
+    return lib().pcg_verify_thinning_workspace_bytes(V, B, K)
+
+
+def verify_thinning(groups: Groups, target_logits: torch.Tensor, draft_logits: torch.Tensor,
+                    prop_tokens: torch.Tensor, prop_groups: torch.Tensor, *,
+                    temperature: float = 1.0, seed: int = 0, offset: int = 0,
+                    out: Optional[VerifyOutput] = None, trials: Optional[torch.Tensor] = None,
+                    diag: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                    B: Optional[int] = None) -> tuple[VerifyOutput, torch.Tensor]:
+    """One speculative step with the reject branch drawn by thinning (Eq. 9).  Arguments as for
+    ``verify``; ``groups`` must have been built with ``reverse=True``.  Returns the outputs and
+    the int32 [B] number of thinning trials per sequence."""
+    assert groups.tok_ptr is not None, "build the groups with reverse=True"
+    assert target_logits.dim() == 3 and draft_logits.dim() == 3
+    K, V = target_logits.shape[1] - 1, target_logits.shape[2]
+    assert V == groups.V and draft_logits.shape[2] == V and draft_logits.shape[1] >= K
+    assert target_logits.stride(2) == 1 and draft_logits.stride(2) == 1
+    assert target_logits.dtype == draft_logits.dtype
+    dev = target_logits.device
+    if B is None:
+        B = target_logits.shape[0]
+    shared = B != target_logits.shape[0]
+    if shared:
+        assert target_logits.shape[0] == 1 and draft_logits.shape[0] == 1
+    tbs = 0 if shared else (target_logits.stride(0) if B > 1 else 0)
+    dbs = 0 if shared else (draft_logits.stride(0) if B > 1 else 0)
+    assert prop_tokens.dtype == torch.int32 and prop_groups.dtype == torch.int32
+    assert prop_tokens.numel() == B * K and prop_groups.numel() == B * K
+    if out is None:
+        out = VerifyOutput(torch.empty(B, dtype=torch.int32, device=dev),
+                           torch.empty((B, K + 1), dtype=torch.int32, device=dev),
+                           torch.empty((B, K + 1), dtype=torch.int32, device=dev))
+    if trials is None:
+        trials = torch.empty(B, dtype=torch.int32, device=dev)
+    need = verify_thinning_workspace_bytes(V, B, K)
+    ws = _workspace(dev, need) if workspace is None else workspace
+    gs = groups.struct()
+    with torch.cuda.device(dev):
+        _check(lib().pcg_verify_thinning(
+            C.byref(gs), target_logits.data_ptr(), draft_logits.data_ptr(),
+            _dtype_code(target_logits), B, K, tbs, target_logits.stride(1), dbs,
+            draft_logits.stride(1) if K > 1 else V, float(temperature), prop_tokens.data_ptr(),
+            prop_groups.data_ptr(), seed, offset, out.accept_len.data_ptr(),
+            out.out_tokens.data_ptr(), out.out_groups.data_ptr(), trials.data_ptr(),
+            None if diag is None else diag.data_ptr(), ws.data_ptr(), ws.numel(), _stream(dev)),
+            "pcg_verify_thinning")
+    return out, trials
 
 
 def profile_begin(max_calls: int):

@@ -2,6 +2,7 @@
 // No device memory is allocated here and nothing synchronises except pcg_profile_end.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstring>
 #include <vector>
@@ -25,9 +26,10 @@ size_t align_up(size_t n) { return (n + kAlign - 1) / kAlign * kAlign; }
 
 // ---- per-kernel timing -------------------------------------------------------------------
 
-enum Stage { kStageStats = 0, kStageAccept, kStageTable, kStageGather, kStageFinalize, kStageNull, kNumStages };
+enum Stage { kStageStats = 0, kStageAccept, kStageTable, kStageGather, kStageFinalize, kStageThin, kStageNull,
+             kNumStages };
 const char *const kStageNames[kNumStages] = {"row_stats", "accept_delta", "weights", "gather", "finalize",
-                                             "event_overhead"};
+                                             "accept_thin", "event_overhead"};
 
 struct Profile {
   bool active = false;
@@ -120,8 +122,7 @@ size_t pcg_verify_workspace_bytes(int32_t V, int32_t G, int32_t B, int32_t K) {
   const size_t rows = (size_t) B * (2 * (size_t) K + 1);
   return align_up(rows * stats_nparts(V) * sizeof(StatPart)) + align_up(rows * sizeof(RowStat)) +
          align_up((size_t) B * V * sizeof(float)) + align_up((size_t) B * G * sizeof(float)) +
-         align_up((size_t) B * ((G + kChunkStep - 1) / kChunkStep) * sizeof(double)) +
-         align_up((size_t) B * sizeof(uint32_t)) + kAlign;
+         align_up((size_t) B * ((G + kChunkStep - 1) / kChunkStep) * sizeof(double)) + kAlign;
 }
 
 int pcg_group_probs(const pcg_groups *groups, const void *logits, pcg_dtype dt, int64_t rows,
@@ -183,13 +184,17 @@ int pcg_group_probs(const pcg_groups *groups, const void *logits, pcg_dtype dt, 
   return PCG_OK;
 }
 
-int pcg_verify(const pcg_groups *groups, const void *target_logits, const void *draft_logits,
-               pcg_dtype dt, int32_t B, int32_t K, int64_t tgt_batch_stride,
-               int64_t tgt_pos_stride, int64_t dft_batch_stride, int64_t dft_pos_stride,
-               float temperature, const int32_t *prop_tokens, const int32_t *prop_groups,
-               uint64_t seed, uint64_t offset, int32_t *accept_len, int32_t *out_tokens,
-               int32_t *out_groups, pcg_diag *diag, void *workspace, size_t workspace_bytes,
-               void *hip_stream) {
+}  // extern "C"
+
+namespace {
+
+// Host-side checks shared by the two verify entry points; on PCG_OK with B > 0 fills rs.
+int check_verify_args(const pcg_groups *groups, const void *target_logits, const void *draft_logits,
+                      pcg_dtype dt, int32_t B, int32_t K, int64_t tgt_batch_stride,
+                      int64_t tgt_pos_stride, int64_t dft_batch_stride, int64_t dft_pos_stride,
+                      float temperature, const int32_t *prop_tokens, const int32_t *prop_groups,
+                      const int32_t *accept_len, const int32_t *out_tokens,
+                      const int32_t *out_groups, const void *workspace, RowSet &rs) {
   int rc = check_groups(groups);
   if (rc) return rc;
   if (dt != PCG_F32 && dt != PCG_BF16) return PCG_ERR_BAD_DTYPE;
@@ -203,17 +208,79 @@ int pcg_verify(const pcg_groups *groups, const void *target_logits, const void *
       !stride_ok(tgt_batch_stride, V, true) || !stride_ok(dft_batch_stride, V, true))
     return PCG_ERR_BAD_STRIDE;
   if (!good_temperature(temperature)) return PCG_ERR_BAD_TEMPERATURE;
-  const bool bf16 = dt == PCG_BF16;
-  const uintptr_t esz = bf16 ? 2 : 4;
+  const uintptr_t esz = dt == PCG_BF16 ? 2 : 4;
   if (((uintptr_t) target_logits % esz) || ((uintptr_t) draft_logits % esz) ||
       ((uintptr_t) workspace % kAlign))
     return PCG_ERR_MISALIGNED;
+  const int64_t rows = (int64_t) B * (2 * K + 1);
+  if (rows * stats_nparts(V) / 4 >= INT32_MAX) return PCG_ERR_BAD_SHAPE;
+  if ((int64_t) B * ((V + 2047) / 2048) >= INT32_MAX) return PCG_ERR_BAD_SHAPE;
+  rs.base0 = target_logits;
+  rs.base1 = draft_logits;
+  rs.bs0 = tgt_batch_stride;
+  rs.ps0 = tgt_pos_stride;
+  rs.bs1 = dft_batch_stride;
+  rs.ps1 = dft_pos_stride;
+  rs.npos0 = K + 1;
+  rs.npos1 = K;
+  rs.nrows0 = (int64_t) B * (K + 1);
+  rs.inv_npos0 = 1.0 / (K + 1);
+  rs.inv_npos1 = 1.0 / K;
+  return PCG_OK;
+}
+
+AcceptArgs accept_args(const pcg_groups *groups, const RowSet &rs, int32_t K, const Factors &f,
+                       const StatPart *parts, RowStat *rowstat, const int32_t *prop_tokens,
+                       const int32_t *prop_groups, uint64_t seed, uint64_t offset,
+                       int32_t *accept_len, int32_t *out_tokens, int32_t *out_groups,
+                       pcg_diag *diag) {
+  AcceptArgs aa;
+  aa.rs = rs;
+  aa.V = groups->V;
+  aa.G = groups->G;
+  aa.K = K;
+  aa.nparts = stats_nparts(groups->V);
+  aa.c = f.c;
+  aa.cd = f.cd;
+  aa.parts = parts;
+  aa.rowstat = rowstat;
+  aa.row_ptr = groups->row_ptr;
+  aa.members = groups->members;
+  aa.mult = groups->mult;
+  aa.prop_tokens = prop_tokens;
+  aa.prop_groups = prop_groups;
+  aa.seed = seed;
+  aa.offset = offset;
+  aa.accept_len = accept_len;
+  aa.out_tokens = out_tokens;
+  aa.out_groups = out_groups;
+  aa.diag = diag;
+  return aa;
+}
+
+}  // namespace
+
+extern "C" {
+
+int pcg_verify(const pcg_groups *groups, const void *target_logits, const void *draft_logits,
+               pcg_dtype dt, int32_t B, int32_t K, int64_t tgt_batch_stride,
+               int64_t tgt_pos_stride, int64_t dft_batch_stride, int64_t dft_pos_stride,
+               float temperature, const int32_t *prop_tokens, const int32_t *prop_groups,
+               uint64_t seed, uint64_t offset, int32_t *accept_len, int32_t *out_tokens,
+               int32_t *out_groups, pcg_diag *diag, void *workspace, size_t workspace_bytes,
+               void *hip_stream) {
+  RowSet rs;
+  int rc = check_verify_args(groups, target_logits, draft_logits, dt, B, K, tgt_batch_stride,
+                             tgt_pos_stride, dft_batch_stride, dft_pos_stride, temperature,
+                             prop_tokens, prop_groups, accept_len, out_tokens, out_groups,
+                             workspace, rs);
+  if (rc || B == 0) return rc;
+  const int32_t V = groups->V;
+  const bool bf16 = dt == PCG_BF16;
   if (workspace_bytes < pcg_verify_workspace_bytes(V, groups->G, B, K))
     return PCG_ERR_WORKSPACE_TOO_SMALL;
   const int64_t rows = (int64_t) B * (2 * K + 1);
   const int32_t nparts = stats_nparts(V);
-  if (rows * nparts / 4 >= INT32_MAX) return PCG_ERR_BAD_SHAPE;
-  if ((int64_t) B * ((V + 2047) / 2048) >= INT32_MAX) return PCG_ERR_BAD_SHAPE;
 
   hipStream_t stream = (hipStream_t) hip_stream;
   char *ws = (char *) workspace;
@@ -226,23 +293,10 @@ int pcg_verify(const pcg_groups *groups, const void *target_logits, const void *
   float *R = (float *) ws;
   ws += align_up((size_t) B * groups->G * sizeof(float));
   double *csum = (double *) ws;
-  ws += align_up((size_t) B * ((groups->G + kChunkStep - 1) / kChunkStep) * sizeof(double));
-  uint32_t *arrivals = (uint32_t *) ws;
 
-  RowSet rs;
-  rs.base0 = target_logits;
-  rs.base1 = draft_logits;
-  rs.bs0 = tgt_batch_stride;
-  rs.ps0 = tgt_pos_stride;
-  rs.bs1 = dft_batch_stride;
-  rs.ps1 = dft_pos_stride;
-  rs.npos0 = K + 1;
-  rs.npos1 = K;
-  rs.nrows0 = (int64_t) B * (K + 1);
-  rs.inv_npos0 = 1.0 / (K + 1);
-  rs.inv_npos1 = 1.0 / K;
   const Factors f = factors(temperature);
-
+  const AcceptArgs aa = accept_args(groups, rs, K, f, parts, rowstat, prop_tokens, prop_groups, seed,
+                                    offset, accept_len, out_tokens, out_groups, diag);
   FinalizeArgs fa;
   fa.rs = rs;
   fa.K = K;
@@ -258,7 +312,6 @@ int pcg_verify(const pcg_groups *groups, const void *target_logits, const void *
   fa.out_tokens = out_tokens;
   fa.out_groups = out_groups;
   fa.diag = diag;
-  fa.arrivals = arrivals;
 
   StageTimer tm(stream);
   hipError_t e;
@@ -266,9 +319,7 @@ int pcg_verify(const pcg_groups *groups, const void *target_logits, const void *
   if ((e = launch_row_stats(rs, bf16, V, rows, f.c, parts, stream)) != hipSuccess) return hip_fail(e);
   tm.end(kStageStats);
   tm.begin(kStageAccept);
-  if ((e = launch_accept_delta(rs, bf16, *groups, B, K, f.c, f.c_lo, f.cd, parts, rowstat,
-                               prop_tokens, prop_groups, seed, offset, accept_len, out_tokens,
-                               out_groups, diag, arrivals, table, stream)) != hipSuccess)
+  if ((e = launch_accept_delta(aa, bf16, B, f.c_lo, table, stream)) != hipSuccess)
     return hip_fail(e);
   tm.end(kStageAccept);
   tm.begin(kStageGather);
@@ -284,6 +335,55 @@ int pcg_verify(const pcg_groups *groups, const void *target_logits, const void *
       hipSuccess)
     return hip_fail(e);
   tm.end(kStageFinalize);
+  return PCG_OK;
+}
+
+size_t pcg_verify_thinning_workspace_bytes(int32_t V, int32_t B, int32_t K) {
+  if (V < 1 || B < 0 || K < 1) return 0;
+  const size_t rows = (size_t) B * (2 * (size_t) K + 1);
+  return align_up(rows * stats_nparts(V) * sizeof(StatPart)) + align_up(rows * sizeof(RowStat)) + kAlign;
+}
+
+int pcg_verify_thinning(const pcg_groups *groups, const void *target_logits,
+                        const void *draft_logits, pcg_dtype dt, int32_t B, int32_t K,
+                        int64_t tgt_batch_stride, int64_t tgt_pos_stride, int64_t dft_batch_stride,
+                        int64_t dft_pos_stride, float temperature, const int32_t *prop_tokens,
+                        const int32_t *prop_groups, uint64_t seed, uint64_t offset,
+                        int32_t *accept_len, int32_t *out_tokens, int32_t *out_groups,
+                        int32_t *trials, pcg_diag *diag, void *workspace, size_t workspace_bytes,
+                        void *hip_stream) {
+  RowSet rs;
+  int rc = check_verify_args(groups, target_logits, draft_logits, dt, B, K, tgt_batch_stride,
+                             tgt_pos_stride, dft_batch_stride, dft_pos_stride, temperature,
+                             prop_tokens, prop_groups, accept_len, out_tokens, out_groups,
+                             workspace, rs);
+  if (rc || B == 0) return rc;
+  if (!trials || !groups->tok_ptr || !groups->tok_groups) return PCG_ERR_NULL_ARG;
+  const int32_t V = groups->V;
+  const int32_t nparts = stats_nparts(V);
+  if (nparts > thin_max_parts()) return PCG_ERR_BAD_SHAPE;
+  if (workspace_bytes < pcg_verify_thinning_workspace_bytes(V, B, K))
+    return PCG_ERR_WORKSPACE_TOO_SMALL;
+  const bool bf16 = dt == PCG_BF16;
+  const int64_t rows = (int64_t) B * (2 * K + 1);
+  hipStream_t stream = (hipStream_t) hip_stream;
+  char *ws = (char *) workspace;
+  StatPart *parts = (StatPart *) ws;
+  ws += align_up((size_t) rows * nparts * sizeof(StatPart));
+  RowStat *rowstat = (RowStat *) ws;
+  const Factors f = factors(temperature);
+  const AcceptArgs aa = accept_args(groups, rs, K, f, parts, rowstat, prop_tokens, prop_groups, seed,
+                                    offset, accept_len, out_tokens, out_groups, diag);
+  StageTimer tm(stream);
+  hipError_t e;
+  tm.begin(kStageStats);
+  if ((e = launch_row_stats(rs, bf16, V, rows, f.c, parts, stream)) != hipSuccess) return hip_fail(e);
+  tm.end(kStageStats);
+  tm.begin(kStageThin);
+  if ((e = launch_accept_thin(aa, bf16, B, groups->tok_ptr, groups->tok_groups, trials,
+                              PCG_THIN_MAX_TRIALS, stream)) != hipSuccess)
+    return hip_fail(e);
+  tm.end(kStageThin);
   return PCG_OK;
 }
 
@@ -391,6 +491,21 @@ int pcg_groups_canonicalize_host(int32_t V, int32_t G, const int32_t *row_ptr,
       out_row_ptr[++next_group] = next_entry;
     }
   }
+  return PCG_OK;
+}
+
+int pcg_groups_reverse_host(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members,
+                            int32_t *tok_ptr, int32_t *tok_groups) {
+  if (!row_ptr || !members || !tok_ptr || !tok_groups) return PCG_ERR_NULL_ARG;
+  if (V < 1 || G < 1) return PCG_ERR_BAD_SHAPE;
+  if (!csr_well_formed(V, G, row_ptr, members)) return PCG_ERR_BAD_CSR;
+  const int32_t nnz = row_ptr[G];
+  std::fill(tok_ptr, tok_ptr + V + 1, 0);
+  for (int32_t j = 0; j < nnz; ++j) ++tok_ptr[members[j] + 1];
+  for (int32_t v = 0; v < V; ++v) tok_ptr[v + 1] += tok_ptr[v];
+  std::vector<int32_t> cursor(tok_ptr, tok_ptr + V);
+  for (int32_t g = 0; g < G; ++g)               // ascending entry position within a token's list
+    for (int32_t j = row_ptr[g]; j < row_ptr[g + 1]; ++j) tok_groups[cursor[members[j]]++] = g;
   return PCG_OK;
 }
 

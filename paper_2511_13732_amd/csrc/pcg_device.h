@@ -130,10 +130,8 @@ struct Uniforms {
   float acc, grp, tok;   // 24-bit draws in [0, 1): exact in fp32 and fp64
 };
 
-__device__ __forceinline__ Uniforms philox_uniforms(uint64_t seed, uint64_t offset, uint32_t b,
-                                                    uint32_t i) {
-  uint32_t c0 = (uint32_t) offset, c1 = (uint32_t)(offset >> 32), c2 = b, c3 = i;
-  uint32_t k0 = (uint32_t) seed, k1 = (uint32_t)(seed >> 32);
+__device__ __forceinline__ uint4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                               uint32_t k0, uint32_t k1) {
 #pragma unroll
   for (int r = 0; r < 10; ++r) {
     const uint32_t m0 = 0xD2511F53u, m1 = 0xCD9E8D57u;
@@ -146,12 +144,41 @@ __device__ __forceinline__ Uniforms philox_uniforms(uint64_t seed, uint64_t offs
     k0 += 0x9E3779B9u;
     k1 += 0xBB67AE85u;
   }
+  return make_uint4(c0, c1, c2, c3);
+}
+
+// Draws of position (b, i): counter (offset_lo, offset_hi, b, i), key (seed_lo, seed_hi).
+__device__ __forceinline__ Uniforms philox_uniforms(uint64_t seed, uint64_t offset, uint32_t b,
+                                                    uint32_t i) {
+  const uint4 w = philox4x32_10((uint32_t) offset, (uint32_t) (offset >> 32), b, i,
+                                (uint32_t) seed, (uint32_t) (seed >> 32));
   const float s = 1.0f / 16777216.0f;
   Uniforms u;
-  u.acc = (float)(c0 >> 8) * s;
-  u.grp = (float)(c1 >> 8) * s;
-  u.tok = (float)(c2 >> 8) * s;
+  u.acc = (float) (w.x >> 8) * s;
+  u.grp = (float) (w.y >> 8) * s;
+  u.tok = (float) (w.z >> 8) * s;
   return u;
+}
+
+// Draws of thinning trial `trial` at position (b, i): the block with counter word 3 =
+// i | (trial + 1) << 16.  u_y, u_a, u_tok are 24-bit uniforms; k24 is the raw 24-bit integer
+// that picks one of a token's membership entries as (k24 * N) >> 24.
+struct TrialDraws {
+  float u_y, u_a, u_tok;
+  uint32_t k24;
+};
+
+__device__ __forceinline__ TrialDraws philox_trial(uint64_t seed, uint64_t offset, uint32_t b,
+                                                   uint32_t i, uint32_t trial) {
+  const uint4 w = philox4x32_10((uint32_t) offset, (uint32_t) (offset >> 32), b,
+                                i | ((trial + 1u) << 16), (uint32_t) seed, (uint32_t) (seed >> 32));
+  const float s = 1.0f / 16777216.0f;
+  TrialDraws d;
+  d.u_y = (float) (w.x >> 8) * s;
+  d.k24 = w.y >> 8;
+  d.u_a = (float) (w.z >> 8) * s;
+  d.u_tok = (float) (w.w >> 8) * s;
+  return d;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -185,7 +212,20 @@ struct FinalizeArgs {
   float *R;
   int32_t *out_tokens, *out_groups;
   pcg_diag *diag;
-  uint32_t *arrivals;     // [B] workgroups of a sequence that have finished their gather
+};
+
+// Everything a sequence's accept scan needs (pcg_verify, pcg_verify_thinning).
+struct AcceptArgs {
+  RowSet rs;
+  int32_t V, G, K, nparts;
+  float c;                 // fp32(log2(e) / temperature), as used by row_stats
+  double cd;               // log2(e) / temperature
+  const StatPart *parts;
+  RowStat *rowstat;
+  const int32_t *row_ptr, *members, *mult, *prop_tokens, *prop_groups;
+  uint64_t seed, offset;
+  int32_t *accept_len, *out_tokens, *out_groups;
+  pcg_diag *diag;
 };
 
 }  // namespace pcg

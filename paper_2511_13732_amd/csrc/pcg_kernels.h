@@ -17,13 +17,13 @@ hipError_t launch_row_stats(const RowSet &rs, bool bf16, int32_t V, int64_t nrow
 
 int32_t accept_nsplit(int32_t V, int32_t B);
 
-hipError_t launch_accept_delta(const RowSet &rs, bool bf16, const pcg_groups &g, int32_t B, int32_t K,
-                               float c, float c_lo, double cd, const StatPart *parts,
-                               RowStat *rowstat, const int32_t *prop_tokens,
-                               const int32_t *prop_groups, uint64_t seed, uint64_t offset,
-                               int32_t *accept_len, int32_t *out_tokens, int32_t *out_groups,
-                               pcg_diag *diag, uint32_t *arrivals, float *table,
+hipError_t launch_accept_delta(const AcceptArgs &a, bool bf16, int32_t B, float c_lo, float *table,
                                hipStream_t stream);
+
+hipError_t launch_accept_thin(const AcceptArgs &a, bool bf16, int32_t B, const int32_t *tok_ptr,
+                              const int32_t *tok_groups, int32_t *trials, int32_t max_trials,
+                              hipStream_t stream);
+int32_t thin_max_parts();
 
 hipError_t launch_weights(const RowSet &rs, bool bf16, const pcg_groups &g, int64_t row0,
                           int32_t nrows, float c, float c_hi, float c_lo, const StatPart *parts,

@@ -198,35 +198,27 @@ __device__ __forceinline__ void store8(float *out, int32_t t, int32_t V, const f
 constexpr int kAcceptThreads = 1024;   // 16 waves: one per row to merge / per position to probe
 constexpr int kAcceptTokens = kAcceptThreads * kTokensPerThread;   // delta tokens per workgroup
 
-// accept + delta.  Workgroup (b, s) runs the whole accept scan of sequence b -- every one of
-// the sequence's workgroups does, so that none has to wait for another -- and then writes slice
-// s of the table the gather sums over, on the decision row i* = accept_len[b]:
-//   rejected (i* < K):  delta[t] = (q_{i*}(t) - p_{i*}(t)) / N(t)
-//   bonus    (i* = K):  delta[t] =  q_K(t) / N(t)
-// Slice 0 also writes the sequence's outputs, row statistics and counters.
-// VEC: rows, mult and the table are 16-byte aligned and V is a multiple of 8.
-template <bool BF16, bool VEC>
-__global__ __launch_bounds__(kAcceptThreads) void accept_delta_kernel(
-    RowSet rs, int32_t V, int32_t G, int32_t K, int32_t nparts, int32_t nsplit, float c, float c_lo,
-    double cd, const StatPart *parts, RowStat *rowstat, const int32_t *row_ptr,
-    const int32_t *members, const int32_t *mult, const int32_t *prop_tokens,
-    const int32_t *prop_groups, uint64_t seed, uint64_t offset, int32_t *accept_len,
-    int32_t *out_tokens, int32_t *out_groups, pcg_diag *diag, uint32_t *arrivals, float *table) {
-  __shared__ RowStat st_t[PCG_MAX_K + 1];
-  __shared__ RowStat st_d[PCG_MAX_K];
-  __shared__ double Tp[PCG_MAX_K], Dp[PCG_MAX_K];     // sums relative to the group's own maxima
-  __shared__ float Tref[PCG_MAX_K], Dref[PCG_MAX_K];  // those maxima
-  __shared__ int bad[PCG_MAX_K];
-  __shared__ float uacc[PCG_MAX_K];
-  __shared__ int ptok_s[PCG_MAX_K], pgrp_s[PCG_MAX_K];
-  __shared__ int istar_s;
+// State of one sequence's accept scan, in LDS.
+struct AcceptShared {
+  RowStat st_t[PCG_MAX_K + 1];                 // statistics of the target rows 0..K
+  RowStat st_d[PCG_MAX_K];                     // ... and of the draft rows 0..K-1
+  double Tp[PCG_MAX_K], Dp[PCG_MAX_K];         // probe sums relative to the group's own maxima
+  double Tn[PCG_MAX_K], Dn[PCG_MAX_K];         // T_i[g], D_i[g] of the proposed groups
+  float Tref[PCG_MAX_K], Dref[PCG_MAX_K];      // those maxima
+  float uacc[PCG_MAX_K];                       // accept uniforms
+  int bad[PCG_MAX_K], ptok[PCG_MAX_K], pgrp[PCG_MAX_K];
+  int istar;                                   // accept_len of the sequence
+};
 
-  const int b = blockIdx.x / nsplit;
-  const int split = blockIdx.x % nsplit;
-  const bool writer = split == 0;
+// The accept scan of sequence b (Algorithm 1 up to the first rejection) by one workgroup of
+// kAcceptThreads.  On return sh.istar, sh.st_t and sh.st_d are valid for every thread; with
+// `writer` the sequence's outputs, row statistics and counters are written.
+template <bool BF16>
+__device__ void accept_phase(AcceptShared &sh, const AcceptArgs &a, int b, bool writer) {
+  const int K = a.K;
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
   constexpr int nw = kAcceptThreads / kWave;
-  const int64_t B = rs.nrows0 / (K + 1);
+  const int64_t B = a.rs.nrows0 / (K + 1);
   // The two chains of dependent loads run side by side on different waves: the first
   // `nprobe` waves follow proposal -> group -> members -> logits, the others merge the row
   // statistics.  The probes sum relative to the group's own maximum, so they need no row
@@ -236,37 +228,37 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_delta_kernel(
   if (wave < nprobe) {
     // T_i[g], D_i[g] of the proposed group (Eq. 5), up to the row's normalisation
     for (int i = wave; i < K; i += nprobe) {
-      const int32_t g = prop_groups[(int64_t) b * K + i];
-      const bool ok = g >= 0 && g < G;
+      const int32_t g = a.prop_groups[(int64_t) b * K + i];
+      const bool ok = g >= 0 && g < a.G;
       double at = 0.0, ad = 0.0;
       float mt = -INFINITY, md = -INFINITY;
       if (ok) {
-        const void *trow = row_base(rs, (int64_t) b * (K + 1) + i, BF16);
-        const void *drow = row_base(rs, rs.nrows0 + (int64_t) b * K + i, BF16);
-        const int32_t beg = row_ptr[g], end = row_ptr[g + 1];
+        const void *trow = row_base(a.rs, (int64_t) b * (K + 1) + i, BF16);
+        const void *drow = row_base(a.rs, a.rs.nrows0 + (int64_t) b * K + i, BF16);
+        const int32_t beg = a.row_ptr[g], end = a.row_ptr[g + 1];
         for (int32_t j = beg + lane; j < end; j += kWave) {
-          const int32_t t = members[j];
+          const int32_t t = a.members[j];
           mt = fmaxf(mt, logit_at<BF16>(trow, t));
           md = fmaxf(md, logit_at<BF16>(drow, t));
         }
         mt = wave_max(mt);
         md = wave_max(md);
         for (int32_t j = beg + lane; j < end; j += kWave) {
-          const int32_t t = members[j];
-          const double inv_m = 1.0 / (double) mult[t];
+          const int32_t t = a.members[j];
+          const double inv_m = 1.0 / (double) a.mult[t];
           const float lt = logit_at<BF16>(trow, t), ld = logit_at<BF16>(drow, t);
-          if (lt > -INFINITY) at += exp2((double) (lt - mt) * cd) * inv_m;
-          if (ld > -INFINITY) ad += exp2((double) (ld - md) * cd) * inv_m;
+          if (lt > -INFINITY) at += exp2((double) (lt - mt) * a.cd) * inv_m;
+          if (ld > -INFINITY) ad += exp2((double) (ld - md) * a.cd) * inv_m;
         }
       }
       at = wave_sum(at);
       ad = wave_sum(ad);
       if (lane == 0) {
-        Tp[i] = at; Dp[i] = ad; Tref[i] = mt; Dref[i] = md;
-        bad[i] = !ok;
-        pgrp_s[i] = g;
-        ptok_s[i] = prop_tokens[(int64_t) b * K + i];
-        uacc[i] = philox_uniforms(seed, offset, (uint32_t) b, (uint32_t) i).acc;
+        sh.Tp[i] = at; sh.Dp[i] = ad; sh.Tref[i] = mt; sh.Dref[i] = md;
+        sh.bad[i] = !ok;
+        sh.pgrp[i] = g;
+        sh.ptok[i] = a.prop_tokens[(int64_t) b * K + i];
+        sh.uacc[i] = philox_uniforms(a.seed, a.offset, (uint32_t) b, (uint32_t) i).acc;
       }
     }
   } else {
@@ -274,66 +266,83 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_delta_kernel(
     for (int r = wave - nprobe; r < 2 * K + 1; r += nw - nprobe) {
       const bool is_t = r <= K;
       const int64_t row = is_t ? (int64_t) b * (K + 1) + r : B * (K + 1) + (int64_t) b * K + (r - K - 1);
-      RowStat s = merge_row(parts, row, nparts, c, lane);
+      RowStat s = merge_row(a.parts, row, a.nparts, a.c, lane);
       if (lane == 0) {
-        if (writer) rowstat[row] = s;
-        if (is_t) st_t[r] = s; else st_d[r - K - 1] = s;
+        if (writer) a.rowstat[row] = s;
+        if (is_t) sh.st_t[r] = s; else sh.st_d[r - K - 1] = s;
       }
     }
   }
   __syncthreads();
 
   // both chains have met: normalise the probes, one thread per position
-  __shared__ double Tn[PCG_MAX_K], Dn[PCG_MAX_K];
   if (threadIdx.x < K) {
     const int i = threadIdx.x;
     double T = 0.0, D = 0.0;
-    if (Tp[i] > 0.0) T = Tp[i] * exp2((double) (Tref[i] - st_t[i].M) * cd) / st_t[i].Z;
-    if (Dp[i] > 0.0) D = Dp[i] * exp2((double) (Dref[i] - st_d[i].M) * cd) / st_d[i].Z;
-    Tn[i] = T;
-    Dn[i] = D;
+    if (sh.Tp[i] > 0.0) T = sh.Tp[i] * exp2((double) (sh.Tref[i] - sh.st_t[i].M) * a.cd) / sh.st_t[i].Z;
+    if (sh.Dp[i] > 0.0) D = sh.Dp[i] * exp2((double) (sh.Dref[i] - sh.st_d[i].M) * a.cd) / sh.st_d[i].Z;
+    sh.Tn[i] = T;
+    sh.Dn[i] = D;
   }
   __syncthreads();
 
-  // sequential accept scan with early exit (Algorithm 1); the draft token stands for its group
-  // on accept
+  // sequential accept scan with early exit; the draft token stands for its group on accept
   if (threadIdx.x == 0) {
     uint32_t near = 0, zero_d = 0, nbad = 0;
     int i = 0;
     for (; i < K; ++i) {
-      const double u = (double) uacc[i];
-      const double T = Tn[i], D = Dn[i];
-      if (bad[i]) ++nbad;
+      const double u = (double) sh.uacc[i];
+      const double T = sh.Tn[i], D = sh.Dn[i];
+      if (sh.bad[i]) ++nbad;
       else if (D == 0.0) ++zero_d;
       if (fabs(u * D - T) < 1e-6 * D) ++near;
       if (!(u * D < T)) break;
     }
-    istar_s = i;
+    sh.istar = i;
     if (writer) {
-      int32_t *otok = out_tokens + (int64_t) b * (K + 1);
-      int32_t *ogrp = out_groups + (int64_t) b * (K + 1);
-      for (int k = 0; k < i; ++k) { otok[k] = ptok_s[k]; ogrp[k] = pgrp_s[k]; }
+      int32_t *otok = a.out_tokens + (int64_t) b * (K + 1);
+      int32_t *ogrp = a.out_groups + (int64_t) b * (K + 1);
+      for (int k = 0; k < i; ++k) { otok[k] = sh.ptok[k]; ogrp[k] = sh.pgrp[k]; }
       for (int k = i; k <= K; ++k) otok[k] = ogrp[k] = -1;
-      accept_len[b] = i;
-      arrivals[b] = 0;
-      if (diag) {
-        if (near) atomicAdd(&diag->near_accept, near);
-        if (zero_d) atomicAdd(&diag->zero_draft_mass, zero_d);
-        if (nbad) atomicAdd(&diag->bad_proposal, nbad);
-        atomicAdd(&diag->accepted_total, (uint32_t) i);
-        atomicAdd(&diag->sequences, 1u);
+      a.accept_len[b] = i;
+      if (a.diag) {
+        if (near) atomicAdd(&a.diag->near_accept, near);
+        if (zero_d) atomicAdd(&a.diag->zero_draft_mass, zero_d);
+        if (nbad) atomicAdd(&a.diag->bad_proposal, nbad);
+        atomicAdd(&a.diag->accepted_total, (uint32_t) i);
+        atomicAdd(&a.diag->sequences, 1u);
       }
     }
   }
   __syncthreads();
+}
+
+// accept + delta.  Workgroup (b, s) runs the whole accept scan of sequence b -- every one of
+// the sequence's workgroups does, so that none has to wait for another -- and then writes its
+// slices of the table the gather sums over, on the decision row i* = accept_len[b]:
+//   rejected (i* < K):  delta[t] = (q_{i*}(t) - p_{i*}(t)) / N(t)
+//   bonus    (i* = K):  delta[t] =  q_K(t) / N(t)
+// Workgroup s = 0 also writes the sequence's outputs, row statistics and counters.
+// VEC: rows, mult and the table are 16-byte aligned and V is a multiple of 8.
+template <bool BF16, bool VEC>
+__global__ __launch_bounds__(kAcceptThreads) void accept_delta_kernel(AcceptArgs a, int32_t nsplit,
+                                                                      float c_lo, float *table) {
+  __shared__ AcceptShared sh;
+  const int b = blockIdx.x / nsplit;
+  const int split = blockIdx.x % nsplit;
+  accept_phase<BF16>(sh, a, b, split == 0);
+  const RowSet &rs = a.rs;
+  const int32_t V = a.V, K = a.K;
+  const float c = a.c;
+  const int32_t *mult = a.mult;
 
   // 4. this workgroup's share of the table on the decision row: slices split, split + nsplit, ...
-  const int32_t istar = istar_s;
+  const int32_t istar = sh.istar;
   const bool rejected = istar < K;
   const void *trow = row_base(rs, (int64_t) b * (K + 1) + istar, BF16);
   const void *drow = row_base(rs, rs.nrows0 + (int64_t) b * K + (rejected ? istar : 0), BF16);
-  const RowStat st = st_t[istar];
-  const RowStat sd = st_d[rejected ? istar : 0];
+  const RowStat st = sh.st_t[istar];
+  const RowStat sd = sh.st_d[rejected ? istar : 0];
   const double izt = 1.0 / st.Z, izd = rejected ? 1.0 / sd.Z : 0.0;
   auto delta8 = [&](const float *xt, const float *xd, const float *m, float *v) {
 #pragma unroll
@@ -369,6 +378,250 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_delta_kernel(
       delta8(xt2, xd2, m2, v);
       store8<VEC>(out, t2, V, v);
     }
+  }
+}
+
+// =============================================================================================
+// accept + thinning: the reject branch drawn the paper's own way (Sec. 2.2 "Residual sampling
+// via thinning", Eq. 9), with no enumeration of the groups: y ~ q, one of the groups holding y
+// by the weights, accepted with probability [1 - D/T]_+, repeated until one is.  One workgroup
+// per sequence; its 16 waves run 16 trials at a time and the first accepted one (in trial
+// order) is emitted, so the result is that of running the trials one after the other.
+// =============================================================================================
+
+constexpr int kMaxThinParts = 2048;       // parts of a row the token draw can search (V <= 4 Mi)
+
+struct WavePick {
+  int32_t index;            // first index whose running sum exceeds u * total; -1: nothing has mass
+  double total, goal, lo, hi;
+};
+
+// Inverse CDF over f(0..n-1) >= 0 by one wave (ascending order; every lane gets the result).
+template <typename F>
+__device__ WavePick wave_inverse_cdf(int32_t n, F f, double u, int lane) {
+  double total = 0.0;
+  for (int32_t j = lane; j < n; j += kWave) {
+    const double v = f(j);
+    if (v > 0.0) total += v;
+  }
+  total = wave_sum(total);
+  WavePick r;
+  r.total = total;
+  r.goal = u * total;
+  r.index = -1;
+  r.lo = r.hi = 0.0;
+  double base = 0.0;
+  int32_t last = -1;
+  double last_v = 0.0;
+  for (int32_t j0 = 0; j0 < n; j0 += kWave) {
+    const int32_t j = j0 + lane;
+    double v = j < n ? f(j) : 0.0;
+    if (!(v > 0.0)) v = 0.0;
+    double inc = v;
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+      const double up = __shfl_up(inc, o, kWave);
+      if (lane >= o) inc += up;
+    }
+    const unsigned long long pos = __ballot(v > 0.0);
+    if (pos) {
+      const int hl = 63 - __clzll((long long) pos);
+      last = j0 + hl;
+      last_v = __shfl(v, hl, kWave);
+    }
+    const unsigned long long hit = __ballot(v > 0.0 && base + inc > r.goal);
+    if (hit) {
+      const int l = __ffsll((long long) hit) - 1;
+      r.index = j0 + l;
+      r.hi = base + __shfl(inc, l, kWave);
+      r.lo = r.hi - __shfl(v, l, kWave);
+      return r;
+    }
+    base += __shfl(inc, kWave - 1, kWave);
+  }
+  if (last >= 0) {   // rounding at the top end: the last index that has mass
+    r.index = last;
+    r.hi = total;
+    r.lo = total - last_v;
+  }
+  return r;
+}
+
+__device__ __forceinline__ bool near_edge(const WavePick &p) {
+  return (p.lo > 0.0 && p.goal - p.lo < 1e-6 * p.total) ||
+         (p.hi < p.total && p.hi - p.goal < 1e-6 * p.total);
+}
+
+struct ThinShared {
+  double Zp[kMaxThinParts];     // mass of each part of the decision row, relative to its maximum
+  float tp[kMaxThinParts];      // log2-domain reference of each part
+  int accepted[kAcceptThreads / kWave], group[kAcceptThreads / kWave];
+  int token[kAcceptThreads / kWave], near[kAcceptThreads / kWave];
+  int done;
+};
+
+// y ~ q on the row whose part masses are in th: the part by its mass, then the token inside the
+// part with each lane holding 32 consecutive tokens.  *near: the draw is within 1e-6 of an
+// inner edge of the token's bin.
+template <bool BF16, bool VEC>
+__device__ int32_t draw_token(const ThinShared &th, const void *trow, int32_t V, int32_t nparts,
+                              float M, float c, double u, int lane, bool *near) {
+  const WavePick pp = wave_inverse_cdf(nparts, [&](int32_t p) { return th.Zp[p]; }, u, lane);
+  if (pp.index < 0) { *near = false; return 0; }
+  const int32_t p = pp.index;
+  const float t = th.tp[p];
+  const int32_t e0 = p * kPartElems + lane * 32;
+  float v[32];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    float x[8];
+    load8<BF16, VEC>(trow, e0 + 8 * i, V, x);
+#pragma unroll
+    for (int k = 0; k < 8; ++k)   // the same expression row_stats summed
+      v[8 * i + k] = x[k] > -INFINITY ? __builtin_amdgcn_exp2f(fmaf(x[k], c, -t)) : 0.f;
+  }
+  double s = 0.0;
+#pragma unroll
+  for (int k = 0; k < 32; ++k) s += (double) v[k];
+  double inc = s;
+#pragma unroll
+  for (int o = 1; o < kWave; o <<= 1) {
+    const double up = __shfl_up(inc, o, kWave);
+    if (lane >= o) inc += up;
+  }
+  // threshold in the part's own units: masses there are relative to 2^t, in Zp to 2^(M c)
+  const double scale = exp2((double) M * (double) c - (double) t);
+  const double goal = (pp.goal - pp.lo) * scale;
+  const double part_total = __shfl(inc, kWave - 1, kWave);
+  const unsigned long long hit = __ballot(s > 0.0 && inc > goal);
+  const unsigned long long pos = __ballot(s > 0.0);
+  const int l = hit ? __ffsll((long long) hit) - 1 : (pos ? 63 - __clzll((long long) pos) : 0);
+  int32_t y = -1;
+  double lo = 0.0, hi = 0.0;
+  if (lane == l) {
+    double cum = inc - s;
+    int last = -1;
+    double last_lo = 0.0;
+#pragma unroll
+    for (int k = 0; k < 32; ++k) {
+      if (y < 0 && v[k] > 0.f) {
+        const double nxt = cum + (double) v[k];
+        if (nxt > goal) { y = e0 + k; lo = cum; hi = nxt; }
+        else { last = k; last_lo = cum; cum = nxt; }
+      }
+    }
+    if (y < 0 && last >= 0) { y = e0 + last; lo = last_lo; hi = cum; }
+  }
+  y = __shfl(y, l, kWave);
+  lo = __shfl(lo, l, kWave);
+  hi = __shfl(hi, l, kWave);
+  const double tot_units = pp.total * scale;
+  const bool first_mass = pp.lo <= 0.0 && lo <= 0.0;            // no bin below
+  const bool last_mass = pp.hi >= pp.total && hi >= part_total;  // no bin above
+  *near = (!first_mass && goal - lo < 1e-6 * tot_units) || (!last_mass && hi - goal < 1e-6 * tot_units);
+  return y < 0 ? 0 : y;
+}
+
+template <bool BF16, bool VEC>
+__global__ __launch_bounds__(kAcceptThreads) void accept_thin_kernel(
+    AcceptArgs a, const int32_t *tok_ptr, const int32_t *tok_groups, int32_t *trials,
+    int32_t max_trials) {
+  __shared__ AcceptShared sh;
+  __shared__ ThinShared th;
+  const int b = blockIdx.x;
+  accept_phase<BF16>(sh, a, b, true);
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  constexpr int nw = kAcceptThreads / kWave;
+  const int32_t K = a.K, V = a.V, istar = sh.istar;
+  const bool bonus = istar == K;
+  const int64_t trow_id = (int64_t) b * (K + 1) + istar;
+  const void *trow = row_base(a.rs, trow_id, BF16);
+  const void *drow = row_base(a.rs, a.rs.nrows0 + (int64_t) b * K + (bonus ? 0 : istar), BF16);
+  const RowStat st = sh.st_t[istar];
+  const RowStat sd = sh.st_d[bonus ? 0 : istar];
+
+  for (int32_t p = threadIdx.x; p < a.nparts; p += kAcceptThreads) {
+    const StatPart sp = a.parts[trow_id * a.nparts + p];
+    th.Zp[p] = sp.z > 0.0 ? sp.z * exp2((double) sp.t - (double) st.M * (double) a.c) : 0.0;
+    th.tp[p] = sp.t;
+  }
+  if (threadIdx.x == 0) th.done = 0;
+  __syncthreads();
+
+  // q(t) / N(t) up to the row's normalisation, and the same for the draft row
+  auto wq = [&](int32_t t) -> double {
+    const float x = logit_at<BF16>(trow, t);
+    return x > -INFINITY ? exp2((double) (x - st.M) * a.cd) / (double) a.mult[t] : 0.0;
+  };
+  auto wp = [&](int32_t t) -> double {
+    const float x = logit_at<BF16>(drow, t);
+    return x > -INFINITY ? exp2((double) (x - sd.M) * a.cd) / (double) a.mult[t] : 0.0;
+  };
+
+  for (int32_t round = 0;; ++round) {
+    const int32_t trial = round * nw + wave;
+    const bool active = bonus ? (round == 0 && wave == 0) : trial < max_trials;
+    if (active) {   // uniform over the wave
+      const TrialDraws d = philox_trial(a.seed, a.offset, (uint32_t) b, (uint32_t) istar,
+                                        (uint32_t) trial);
+      bool near_y = false;
+      const int32_t y = draw_token<BF16, VEC>(th, trow, V, a.nparts, st.M, a.c, (double) d.u_y, lane,
+                                              &near_y);
+      const int32_t e0 = tok_ptr[y], n = tok_ptr[y + 1] - e0;
+      const int32_t g = tok_groups[e0 + (int32_t) (((uint64_t) d.k24 * (uint64_t) max(n, 1)) >> 24)];
+      const int32_t beg = a.row_ptr[g], len = a.row_ptr[g + 1] - beg;
+      int accepted = 1, near = near_y ? 1 : 0;
+      int32_t token = y;
+      if (!bonus) {
+        double at = 0.0, ad = 0.0;
+        for (int32_t j = lane; j < len; j += kWave) {
+          const int32_t t = a.members[beg + j];
+          at += wq(t);
+          ad += wp(t);
+        }
+        const double T = wave_sum(at) / st.Z, D = wave_sum(ad) / sd.Z;
+        const double ua = (double) d.u_a;
+        accepted = ua * T < T - D;                    // u_a < [1 - D/T]_+
+        if (fabs(ua * T - (T - D)) < 1e-6 * T) near |= 1;
+        const WavePick pt = wave_inverse_cdf(
+            len, [&](int32_t j) { return wq(a.members[beg + j]); }, (double) d.u_tok, lane);
+        token = pt.index < 0 ? -1 : a.members[beg + pt.index];
+        if (pt.index >= 0 && near_edge(pt)) near |= 2;
+      }
+      if (lane == 0) {
+        th.accepted[wave] = accepted; th.group[wave] = g; th.token[wave] = token; th.near[wave] = near;
+      }
+    } else if (lane == 0) {
+      th.accepted[wave] = -1;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      uint32_t n_near = 0, n_near_tok = 0;
+      int chosen = -1, last_active = -1;
+      for (int w = 0; w < nw && chosen < 0; ++w) {
+        if (th.accepted[w] < 0) break;
+        last_active = w;
+        if (th.near[w] & 1) ++n_near;
+        if (th.accepted[w] == 1) chosen = w;
+      }
+      const bool exhausted = chosen < 0 && (round + 1) * nw >= max_trials;
+      if (exhausted) chosen = last_active;
+      if (chosen >= 0) {
+        if (th.near[chosen] & 2) ++n_near_tok;
+        a.out_groups[(int64_t) b * (K + 1) + istar] = th.group[chosen];
+        a.out_tokens[(int64_t) b * (K + 1) + istar] = th.token[chosen];
+        trials[b] = bonus ? 0 : round * nw + chosen + 1;
+        th.done = 1;
+      }
+      if (a.diag) {
+        if (n_near) atomicAdd(&a.diag->near_group, n_near);
+        if (n_near_tok) atomicAdd(&a.diag->near_token, n_near_tok);
+        if (exhausted) atomicAdd(&a.diag->residual_fallback, 1u);
+      }
+    }
+    __syncthreads();
+    if (th.done) break;
   }
 }
 
@@ -915,26 +1168,33 @@ int32_t accept_nsplit(int32_t V, int32_t B) {
   return std::max(1, std::min(slices, (256 + B - 1) / B));
 }
 
-hipError_t launch_accept_delta(const RowSet &rs, bool bf16, const pcg_groups &g, int32_t B, int32_t K,
-                               float c, float c_lo, double cd, const StatPart *parts,
-                               RowStat *rowstat, const int32_t *prop_tokens,
-                               const int32_t *prop_groups, uint64_t seed, uint64_t offset,
-                               int32_t *accept_len, int32_t *out_tokens, int32_t *out_groups,
-                               pcg_diag *diag, uint32_t *arrivals, float *table,
+hipError_t launch_accept_delta(const AcceptArgs &a, bool bf16, int32_t B, float c_lo, float *table,
                                hipStream_t stream) {
-  const int32_t nparts = stats_nparts(g.V), nsplit = accept_nsplit(g.V, B);
+  const int32_t nsplit = accept_nsplit(a.V, B);
   const dim3 grid((unsigned) ((int64_t) B * nsplit));
-  const bool vec = table_vector_ok(rs, bf16, g.V, g.mult, table);
-#define PCG_LAUNCH_AD(BF, VE)                                                                   \
-  accept_delta_kernel<BF, VE><<<grid, kAcceptThreads, 0, stream>>>(                             \
-      rs, g.V, g.G, K, nparts, nsplit, c, c_lo, cd, parts, rowstat, g.row_ptr, g.members, g.mult, \
-      prop_tokens, prop_groups, seed, offset, accept_len, out_tokens, out_groups, diag, arrivals, \
-      table)
+  const bool vec = table_vector_ok(a.rs, bf16, a.V, a.mult, table);
+#define PCG_LAUNCH_AD(BF, VE) \
+  accept_delta_kernel<BF, VE><<<grid, kAcceptThreads, 0, stream>>>(a, nsplit, c_lo, table)
   if (bf16) { if (vec) PCG_LAUNCH_AD(true, true); else PCG_LAUNCH_AD(true, false); }
   else { if (vec) PCG_LAUNCH_AD(false, true); else PCG_LAUNCH_AD(false, false); }
 #undef PCG_LAUNCH_AD
   return hipGetLastError();
 }
+
+hipError_t launch_accept_thin(const AcceptArgs &a, bool bf16, int32_t B, const int32_t *tok_ptr,
+                              const int32_t *tok_groups, int32_t *trials, int32_t max_trials,
+                              hipStream_t stream) {
+  const bool vec = rows_vector_aligned(a.rs, bf16) && a.V % 8 == 0;
+#define PCG_LAUNCH_AT(BF, VE)                                                                \
+  accept_thin_kernel<BF, VE><<<B, kAcceptThreads, 0, stream>>>(a, tok_ptr, tok_groups, trials, \
+                                                               max_trials)
+  if (bf16) { if (vec) PCG_LAUNCH_AT(true, true); else PCG_LAUNCH_AT(true, false); }
+  else { if (vec) PCG_LAUNCH_AT(false, true); else PCG_LAUNCH_AT(false, false); }
+#undef PCG_LAUNCH_AT
+  return hipGetLastError();
+}
+
+int32_t thin_max_parts() { return kMaxThinParts; }
 
 hipError_t launch_weights(const RowSet &rs, bool bf16, const pcg_groups &g, int64_t row0,
                           int32_t nrows, float c, float c_hi, float c_lo, const StatPart *parts,

@@ -128,3 +128,57 @@ def group_probs_error(gpu: torch.Tensor, ref: np.ndarray) -> float:
     for probabilities that underflow in fp32."""
     g = gpu.double().cpu().numpy()
     return float(np.max(np.abs(g - ref) / (ref + 1e-30 / 1e-5)))
+
+
+def compare_thinning(gpu: pcg.VerifyOutput, gpu_trials: torch.Tensor, ref: oracle.ThinningResult,
+                     og: oracle.Groups, prop_tokens: np.ndarray, prop_groups: np.ndarray) -> Tally:
+    """As compare_verify, for the thinning sampler: accept length, emitted token and group and
+    the number of trials agree exactly unless the oracle flagged a near-tie on that path."""
+    al = gpu.accept_len.cpu().numpy()
+    tok = gpu.out_tokens.cpu().numpy()
+    grp = gpu.out_groups.cpu().numpy()
+    ntr = gpu_trials.cpu().numpy()
+    B, K1 = tok.shape
+    K = K1 - 1
+    prop_tokens = np.asarray(prop_tokens).reshape(B, K)
+    prop_groups = np.asarray(prop_groups).reshape(B, K)
+    t = Tally(sequences=B)
+    t.flagged_accept = int(ref.near_acc.sum())
+    t.flagged_group = int((ref.flags & 1).sum())
+    for b in range(B):
+        n = int(al[b])
+        assert 0 <= n <= K, (b, n)
+        assert (tok[b, :n] == prop_tokens[b, :n]).all() and (grp[b, :n] == prop_groups[b, :n]).all()
+        assert (tok[b, n + 1:] == -1).all() and (grp[b, n + 1:] == -1).all()
+        g, z = int(grp[b, n]), int(tok[b, n])
+        assert 0 <= g < og.G, (b, g)
+        assert z in og.members[og.row_ptr[g]:og.row_ptr[g + 1]], (b, g, z)
+        assert (ntr[b] == 0) == (n == K), (b, n, ntr[b])
+        nr = int(ref.accept_len[b])
+        if n != nr:
+            assert ref.near_acc[b, min(n, nr)], f"seq {b}: accept_len {n} vs oracle {nr}, no near-tie"
+            t.tolerated += 1
+            t.detail.append({"b": b, "kind": "accept", "gpu": n, "oracle": nr})
+            continue
+        got = (g, z, int(ntr[b]))
+        want = (int(ref.out_groups[b, n]), int(ref.out_tokens[b, n]), int(ref.trials[b]))
+        if got != want:
+            assert ref.flags[b] & 1, f"seq {b}: (group, token, trials) {got} vs oracle {want}, no near-tie"
+            t.tolerated += 1
+            t.detail.append({"b": b, "kind": "thinning", "gpu": got, "oracle": want})
+    return t
+
+
+def run_both_thinning(V, tgt: torch.Tensor, dft: torch.Tensor, ptok, pgrp, *, dg: pcg.Groups,
+                      og: oracle.Groups, rev, temperature=1.0, seed=0, offset=0, nthreads=16):
+    """The thinning entry point of the HIP library and of the oracle on the same inputs."""
+    diag = torch.zeros(8, dtype=torch.int32, device="cuda")
+    gpu, trials = pcg.verify_thinning(
+        dg, tgt.cuda(), dft.cuda(), torch.from_numpy(np.ascontiguousarray(ptok, dtype=np.int32)).cuda(),
+        torch.from_numpy(np.ascontiguousarray(pgrp, dtype=np.int32)).cuda(),
+        temperature=temperature, seed=seed, offset=offset, diag=diag)
+    torch.cuda.synchronize()
+    ref = oracle.verify_thinning(og, rev, as_oracle_logits(tgt), as_oracle_logits(dft), ptok, pgrp,
+                                 temperature=temperature, seed=seed, offset=offset,
+                                 max_trials=pcg.THIN_MAX_TRIALS, nthreads=nthreads)
+    return gpu, trials, ref, dict(zip(pcg.Diag.NAMES, diag.cpu().tolist()))

@@ -44,7 +44,7 @@ def test_header_constants_match_binding():
         assert re.search(rf"{name}\s*=\s*{val}\b", text)
         assert pcg.strerror(val) != "unknown status"
     assert re.search(r"PCG_F32 = 0, PCG_BF16 = 1", text) and (pcg.F32, pcg.BF16) == (0, 1)
-    assert C.sizeof(pcg.Diag) == 32 and C.sizeof(_GroupsStruct) == 56 and C.sizeof(pcg.PreparedInfo) == 64
+    assert C.sizeof(pcg.Diag) == 32 and C.sizeof(_GroupsStruct) == 72 and C.sizeof(pcg.PreparedInfo) == 64
 
 
 # Fake device addresses: every call below must fail its host-side checks and return before it
@@ -55,7 +55,7 @@ P = 0x10000
 def call_verify(V=64, G=8, nnz=16, dt=0, B=2, K=2, tbs=None, tps=None, dbs=None, dps=None, tau=1.0,
                 ws=P, ws_bytes=1 << 30, tgt=P, dft=P, rp=P, mem=P, mult=P, ptok=P, pgrp=P, al=P,
                 otok=P, ogrp=P, groups=True):
-    gs = _GroupsStruct(V, G, nnz, rp, mem, mult, None, None)
+    gs = _GroupsStruct(V, G, nnz, rp, mem, mult, None, None, None, None)
     tps = V if tps is None else tps
     dps = V if dps is None else dps
     tbs = (K + 1) * V if tbs is None else tbs
@@ -95,7 +95,7 @@ def test_verify_rejects_bad_arguments_on_the_host():
 
 def test_group_probs_rejects_bad_arguments_on_the_host():
     L = pcg.lib()
-    gs = _GroupsStruct(64, 8, 16, P, P, P, None, None)
+    gs = _GroupsStruct(64, 8, 16, P, P, P, None, None, None, None)
     f = lambda **k: L.pcg_group_probs(k.get("g", C.byref(gs)), k.get("x", P), k.get("dt", 0),
                                       k.get("rows", 4), k.get("stride", 64), k.get("tau", 1.0),
                                       k.get("out", P), k.get("ws", P), k.get("wsb", 1 << 30), None)
@@ -152,8 +152,8 @@ def test_profile_calls_are_guarded():
     n = C.c_int32()
     assert L.pcg_profile_end(ms, C.byref(n)) == BAD_SHAPE      # nothing was begun
     assert L.pcg_profile_begin(0) == BAD_SHAPE
-    assert [pcg.lib().pcg_stage_name(i).decode() for i in range(7)] == \
-        ["row_stats", "accept_delta", "weights", "gather", "finalize", "event_overhead", ""]
+    assert [pcg.lib().pcg_stage_name(i).decode() for i in range(8)] == \
+        ["row_stats", "accept_delta", "weights", "gather", "finalize", "accept_thin", "event_overhead", ""]
 
 
 # --------------------------------------------------------------------------- prepared layout
@@ -238,7 +238,30 @@ def test_prepare_rejects_bad_arguments():
                                      C.byref(info)) == BAD_CSR
     # a descriptor that does not belong to the groups is refused before any launch
     blob, info = pcg.groups_prepare_host(4, rp, mem)
-    gs = _GroupsStruct(5, 2, 4, P, P, P, P, C.pointer(info))
+    gs = _GroupsStruct(5, 2, 4, P, P, P, P, C.pointer(info), None, None)
     assert pcg.lib().pcg_group_probs(C.byref(gs), P, 0, 1, 5, 1.0, P, P, 1 << 30, None) == BAD_SHAPE
-    gs = _GroupsStruct(4, 2, 4, P, P, P, P, None)
+    gs = _GroupsStruct(4, 2, 4, P, P, P, P, None, None, None)
     assert pcg.lib().pcg_group_probs(C.byref(gs), P, 0, 1, 4, 1.0, P, P, 1 << 30, None) == NULL_ARG
+
+
+def test_reverse_index_and_thinning_argument_checks():
+    V, G = 257, 150
+    rp, mem = W.random_groups(V, G, 1, 9, seed=2, cover=False)
+    rp, mem, mult = pcg.groups_canonicalize_host(V, rp, mem)
+    tok_ptr, tok_groups = pcg.groups_reverse_host(V, rp, mem)
+    a = oracle.Groups(V, len(rp) - 1, rp, mem, mult)
+    ref_ptr, ref_groups = oracle.reverse_index(a)
+    np.testing.assert_array_equal(tok_ptr, ref_ptr)
+    np.testing.assert_array_equal(tok_groups, ref_groups)
+    np.testing.assert_array_equal(np.diff(tok_ptr), mult)
+    L = pcg.lib()
+    gs = _GroupsStruct(64, 8, 16, P, P, P, None, None, None, None)      # no reverse index
+    args = lambda g, **k: L.pcg_verify_thinning(C.byref(g), P, P, 0, 2, 2, 192, 64, 128, 64, 1.0, P, P, 0, 0,
+                                                P, P, P, k.get("trials", P), None, P, k.get("wsb", 1 << 30), None)
+    assert args(gs) == NULL_ARG
+    gs = _GroupsStruct(64, 8, 16, P, P, P, None, None, P, P)
+    assert args(gs, trials=None) == NULL_ARG
+    assert args(gs, wsb=pcg.verify_thinning_workspace_bytes(64, 2, 2) - 1) == WS_SMALL
+    big = _GroupsStruct(5_000_000, 8, 16, P, P, P, None, None, P, P)    # more parts than the token draw searches
+    assert L.pcg_verify_thinning(C.byref(big), P, P, 0, 1, 1, 0, 5_000_000, 0, 5_000_000, 1.0, P, P, 0, 0,
+                                 P, P, P, P, None, P, 1 << 40, None) == BAD_SHAPE

@@ -34,8 +34,8 @@ LDS_PEAK_GBS = 256 * 128 * 2.4     # 256 CUs x 128 B/clk x 2.4 GHz = 78 643 GB/s
 # copy of 256 MiB: FETCH_SIZE reads 131 085 for 262 144 KiB, factor 2.000; WRITE_SIZE reads
 # 262 144, factor 1.000).  Source: profiles/pcg_verify_C4_hbm_traffic.md.
 MEASURED_TRAFFIC_BYTES = {
-    "row_stats@C4": int((69659.56 * 2.000 + 544.84) * 1024),
-    "gather@C4": int((28572.20 * 2.000 + 21506.0) * 1024),
+    "row_stats@C4": int((69660.5 * 2.000 + 544.8) * 1024),
+    "gather@C4": int((28586.7 * 2.000 + 21506.0) * 1024),
 }
 
 
@@ -95,7 +95,7 @@ def main():
     cfg = W.CONFIGS[args.config]
     t0 = time.time()
     rp, mem = W.groups(cfg)
-    groups = pcg.Groups.from_csr(cfg.V, rp, mem, dev,
+    groups = pcg.Groups.from_csr(cfg.V, rp, mem, dev, reverse=True,
                                  chunk_groups=pcg.suggest_chunk_groups(len(rp) - 1, cfg.B))
     rp_c, mem_c, _ = pcg.groups_canonicalize_host(cfg.V, rp, mem)
     print(f"[bench] {cfg.name}: V={cfg.V} G={groups.G} nnz={groups.nnz} B={cfg.B} K={cfg.K} "
@@ -182,6 +182,37 @@ def main():
         "roofline": roofline,
         "roofline_longest_kernel": roofline_gather,
     }
+
+    # The same steps with the reject branch drawn by thinning (Sec. 2.2, Eq. 9) instead of the
+    # enumerated residual: a different sample path of the same law, reported beside the
+    # headline, never as `value`.
+    trials = torch.empty(cfg.B, dtype=torch.int32, device=dev)
+
+    def thin_step(i):
+        tgt, dft, ptok, pgrp = sets[i % len(sets)]
+        pcg.verify_thinning(groups, tgt, dft, ptok, pgrp, temperature=cfg.temperature, seed=0,
+                            offset=i, out=out, trials=trials, workspace=ws)
+
+    for i in range(args.warmup):
+        thin_step(i)
+    torch.cuda.synchronize()
+    t_begin = time.perf_counter()
+    for i in range(args.steps):
+        thin_step(args.warmup + i)
+    torch.cuda.synchronize()
+    thin_elapsed = time.perf_counter() - t_begin
+    pcg.profile_begin(args.steps)
+    for i in range(args.steps):
+        thin_step(args.warmup + i)
+    torch.cuda.synchronize()
+    thin_ms, _ = pcg.profile_end()
+    tr = trials.cpu().numpy()
+    result["thinning"] = {
+        "value": round(positions * args.steps / thin_elapsed, 1), "unit": "positions/s",
+        "ms_per_step": round(1e3 * thin_elapsed / args.steps, 5),
+        "stages_us": {k: round(1e3 * v, 2) for k, v in thin_ms.items()
+                      if v > 0.0 and k != "event_overhead"},
+        "mean_trials_per_rejection_last_step": round(float(tr[tr > 0].mean()) if (tr > 0).any() else 0.0, 2)}
 
     if not args.no_cpu_baseline:
         import oracle

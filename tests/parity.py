@@ -51,6 +51,18 @@ class Tally:
             pass
 
 
+def report_error(name: str, err: float):
+    """Record a measured group-probability error next to the tallies."""
+    rec = {"case": name, "max_rel_err": err}
+    print("parity", json.dumps(rec), flush=True)
+    try:
+        os.makedirs(os.path.dirname(REPORT), exist_ok=True)
+        with open(REPORT, "a") as f:
+            f.write(json.dumps(rec) + "\n")
+    except OSError:
+        pass
+
+
 def oracle_groups(V: int, row_ptr, members) -> oracle.Groups:
     return oracle.canonicalize(V, row_ptr, members)
 

@@ -11,7 +11,7 @@ import oracle
 import paper_2511_13732_amd as pcg
 import workloads as W
 from parity import (Tally, as_oracle_logits, compare_verify, device_groups, group_probs_error,
-                    oracle_groups, run_both)
+                    oracle_groups, report_error, run_both)
 
 pytestmark = pytest.mark.gpu
 
@@ -61,7 +61,7 @@ def test_group_probs_matches_oracle(V, G, smin, smax, dtype, tau, rows, layout):
     torch.cuda.synchronize()
     ref = oracle.group_probs(og, as_oracle_logits(x), tau)
     err = group_probs_error(out, ref)
-    print(f"group_probs V={V} {dtype}: max rel err {err:.3e}")
+    report_error(f"group_probs V={V} {dtype} {layout}", err)
     assert err <= TOL_F32 < TOL_BF16_LIMIT
     s = out.double().sum(dim=1).cpu().numpy()
     np.testing.assert_allclose(s, 1.0, atol=2e-6)      # Eq. (2): no mass lost, no renormalisation
@@ -341,7 +341,7 @@ def test_recipe_full_size(name, steps):
             rows = tgt[:3, 0].contiguous()
             out = pcg.group_probs(dg, rows.cuda(), cfg.temperature)
             err = group_probs_error(out, oracle.group_probs(og, as_oracle_logits(rows), cfg.temperature))
-            print(f"{name}: group_probs max rel err {err:.3e}", flush=True)
+            report_error(f"group_probs recipe {name}", err)
             assert err <= TOL_F32
     total.report(f"recipe {name} full size")
     assert total.tolerated <= max(1, total.sequences // 100)

@@ -339,3 +339,46 @@ def verify_thinning(g: Groups, rev, target_logits, draft_logits, prop_tokens, pr
         _p(res.accept_len), _p(res.out_tokens), _p(res.out_groups), _p(res.trials), _p(res.flags),
         _p(res.near_acc), C.c_int32(max_trials), C.c_int32(nthreads)), "verify_thinning")
     return res
+
+
+# --------------------------------------------------------------------------- proposal coupling (Eq. 6)
+
+def propose_uniforms(seed: int, offset: int, b: int, i: int) -> tuple[float, int]:
+    ux, k = C.c_double(), C.c_uint32()
+    lib().pcg_ref_propose_uniforms(C.c_uint64(seed), C.c_uint64(offset), C.c_uint32(b), C.c_uint32(i),
+                                   C.byref(ux), C.byref(k))
+    return ux.value, k.value
+
+
+@dataclass
+class Proposals:
+    tokens: np.ndarray     # int32 [B, K]
+    groups: np.ndarray     # int32 [B, K]
+    near: np.ndarray       # uint8 [B, K]  token draw within 1e-6 of an inner bin edge
+
+
+def propose(g: Groups, rev, draft_logits, *, temperature: float = 1.0, seed: int = 0,
+            offset: int = 0, pos0: int = 0, B: Optional[int] = None, dft_batch_stride=None,
+            u_x=None, k24=None, nthreads: int = 1) -> Proposals:
+    """Draft-side proposals: x ~ p_i, then one of the groups holding x by the weights (Eq. 6).
+    With u_x and k24 ([B, K]) the draws are explicit, else Philox(seed, offset)."""
+    dft, dt = _logits(draft_logits)
+    assert dft.ndim == 3
+    K = dft.shape[1]
+    if B is None:
+        B = dft.shape[0]
+    tok_ptr, tok_groups = rev
+    dbs, dps = _strides(dft, dft_batch_stride, None)
+    res = Proposals(np.empty((B, K), np.int32), np.empty((B, K), np.int32), np.zeros((B, K), np.uint8))
+    common = (C.c_int32(g.V), C.c_int32(g.G), _p(g.mult), _p(tok_ptr), _p(tok_groups), _p(dft),
+              C.c_int(dt), C.c_int32(B), C.c_int32(K))
+    if u_x is not None:
+        ux = np.ascontiguousarray(u_x, dtype=np.float64).reshape(B, K)
+        kk = np.ascontiguousarray(k24, dtype=np.uint32).reshape(B, K)
+        _check(lib().pcg_ref_propose_u(*common, dbs, dps, C.c_double(temperature), _p(ux), _p(kk),
+                                       _p(res.tokens), _p(res.groups), _p(res.near)), "propose_u")
+    else:
+        _check(lib().pcg_ref_propose(*common, C.c_int32(pos0), dbs, dps, C.c_double(temperature),
+                                     C.c_uint64(seed), C.c_uint64(offset), _p(res.tokens),
+                                     _p(res.groups), _p(res.near), C.c_int32(nthreads)), "propose")
+    return res

@@ -640,3 +640,108 @@ int pcg_ref_verify_thinning(int32_t V, int32_t G, const int32_t *row_ptr, const 
   }
   return status;
 }
+
+/* ------------------------------------------------------------------------- */
+/* Draft-side proposal coupling, Eq. (6)                                       */
+/* ------------------------------------------------------------------------- */
+
+void pcg_ref_propose_uniforms(uint64_t seed, uint64_t offset, uint32_t b, uint32_t i, double *u_x,
+                              uint32_t *k24) {
+  uint32_t ctr[4] = {(uint32_t)offset, (uint32_t)(offset >> 32), b, i | 0xFFFF0000u};
+  uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+  uint32_t w[4];
+  pcg_ref_philox4x32_10(ctr, key, w);
+  if (u_x) *u_x = (double)(w[0] >> 8) / 16777216.0;
+  if (k24) *k24 = w[1] >> 8;
+}
+
+static int propose_one(int32_t V, int32_t G, const int32_t *mult, const int32_t *tok_ptr,
+                       const int32_t *tok_groups, const void *draft_logits, int dtype,
+                       int64_t first, double temperature, double u_x, uint32_t k24, double *p,
+                       int32_t *token, int32_t *group, uint8_t *near) {
+  int r = softmax_row_at(draft_logits, dtype, first, V, temperature, p);
+  if (r) return r;
+  int nr = 0;
+  int64_t x = inverse_cdf(p, V, u_x, &nr);          /* x ~ p_i */
+  if (x < 0) return PCG_REF_ERR_ROW;
+  int32_t n = tok_ptr[x + 1] - tok_ptr[x];          /* N(x) membership entries */
+  if (n < 1 || n != mult[x]) return PCG_REF_ERR_CSR;
+  int32_t g = tok_groups[tok_ptr[x] + (int32_t)(((uint64_t)k24 * (uint64_t)n) >> 24)];
+  if (g < 0 || g >= G) return PCG_REF_ERR_CSR;
+  *token = (int32_t)x;
+  *group = g;
+  if (near) *near = (uint8_t)nr;
+  return PCG_REF_OK;
+}
+
+static int propose_impl(int32_t V, int32_t G, const int32_t *mult, const int32_t *tok_ptr,
+                        const int32_t *tok_groups, const void *draft_logits, int dtype, int32_t B,
+                        int32_t K, int32_t pos0, int64_t dft_batch_stride, int64_t dft_pos_stride,
+                        double temperature, const double *u_x, const uint32_t *k24, uint64_t seed,
+                        uint64_t offset, int32_t *prop_tokens, int32_t *prop_groups, uint8_t *near,
+                        int32_t nthreads) {
+  if (!mult || !tok_ptr || !tok_groups || !draft_logits || !prop_tokens || !prop_groups)
+    return PCG_REF_ERR_ARG;
+  if (V < 1 || G < 1 || B < 0 || K < 1 || pos0 < 0 || (int64_t)pos0 + K > 0xFFFF ||
+      !(temperature > 0.0))
+    return PCG_REF_ERR_ARG;
+  if (dtype != PCG_REF_F32 && dtype != PCG_REF_BF16) return PCG_REF_ERR_ARG;
+  if (nthreads < 1) nthreads = 1;
+  int status = PCG_REF_OK;
+#ifdef _OPENMP
+#pragma omp parallel num_threads(nthreads)
+#endif
+  {
+    double *p = (double *)malloc((size_t)V * sizeof(double));
+    if (!p) {
+#ifdef _OPENMP
+#pragma omp critical
+#endif
+      status = PCG_REF_ERR_NOMEM;
+    }
+#ifdef _OPENMP
+#pragma omp barrier
+#pragma omp for schedule(dynamic, 1)
+#endif
+    for (int64_t bi = 0; bi < (int64_t)B * K; ++bi) {
+      if (!p || status != PCG_REF_OK) continue;
+      int32_t b = (int32_t)(bi / K), i = (int32_t)(bi % K);
+      double ux;
+      uint32_t kk;
+      if (u_x) { ux = u_x[bi]; kk = k24[bi]; }
+      else pcg_ref_propose_uniforms(seed, offset, (uint32_t)b, (uint32_t)(pos0 + i), &ux, &kk);
+      int r = propose_one(V, G, mult, tok_ptr, tok_groups, draft_logits, dtype,
+                          b * dft_batch_stride + i * dft_pos_stride, temperature, ux, kk, p,
+                          prop_tokens + bi, prop_groups + bi, near ? near + bi : NULL);
+      if (r) {
+#ifdef _OPENMP
+#pragma omp critical
+#endif
+        status = r;
+      }
+    }
+    free(p);
+  }
+  return status;
+}
+
+int pcg_ref_propose_u(int32_t V, int32_t G, const int32_t *mult, const int32_t *tok_ptr,
+                      const int32_t *tok_groups, const void *draft_logits, int dtype, int32_t B,
+                      int32_t K, int64_t dft_batch_stride, int64_t dft_pos_stride,
+                      double temperature, const double *u_x, const uint32_t *k24,
+                      int32_t *prop_tokens, int32_t *prop_groups, uint8_t *near) {
+  if (!u_x || !k24) return PCG_REF_ERR_ARG;
+  return propose_impl(V, G, mult, tok_ptr, tok_groups, draft_logits, dtype, B, K, 0,
+                      dft_batch_stride, dft_pos_stride, temperature, u_x, k24, 0, 0, prop_tokens,
+                      prop_groups, near, 1);
+}
+
+int pcg_ref_propose(int32_t V, int32_t G, const int32_t *mult, const int32_t *tok_ptr,
+                    const int32_t *tok_groups, const void *draft_logits, int dtype, int32_t B,
+                    int32_t K, int32_t pos0, int64_t dft_batch_stride, int64_t dft_pos_stride,
+                    double temperature, uint64_t seed, uint64_t offset, int32_t *prop_tokens,
+                    int32_t *prop_groups, uint8_t *near, int32_t nthreads) {
+  return propose_impl(V, G, mult, tok_ptr, tok_groups, draft_logits, dtype, B, K, pos0,
+                      dft_batch_stride, dft_pos_stride, temperature, NULL, NULL, seed, offset,
+                      prop_tokens, prop_groups, near, nthreads);
+}

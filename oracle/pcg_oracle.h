@@ -16,6 +16,8 @@
  *   - token inside the emitted group          (Eq. 10)
  *   - control flow of one speculative step    (Algorithm 1)
  *   - Philox4x32-10 counter-based generator   (Salmon et al., SC'11)
+ *   - residual sampling by thinning           (Eq. 9)
+ *   - draft-side proposal coupling            (Eq. 6)
  *
  * Naming: the paper's body calls the target model q and the draft p, its group
  * distributions Q_c (target) and P_c (draft).  To keep the two apart this file
@@ -178,6 +180,40 @@ int pcg_ref_verify_thinning(int32_t V, int32_t G, const int32_t *row_ptr, const 
                             uint64_t offset, int32_t *accept_len, int32_t *out_tokens,
                             int32_t *out_groups, int32_t *trials, uint8_t *flags,
                             uint8_t *near_acc, int32_t max_trials, int32_t nthreads);
+
+/* ------------------------------------------------------------------------- */
+/* Draft-side proposal coupling (Sec. 2.2 "Proposal coupling and acceptance",  */
+/* Eq. 6; Algorithm 1, the two sampling steps at the top of the loop): a token */
+/* x ~ p_i, then a group label among the groups holding x by the weights       */
+/* w_{k,x} (equal split: each of the N(x) membership entries equally likely),  */
+/* so that Pr(label = k) = D_i[k].                                             */
+/* ------------------------------------------------------------------------- */
+
+/* Draws of the proposal at position (b, i): Philox block with counter
+ * (offset_lo, offset_hi, b, i | 0xFFFF0000) -- a trial field no thinning trial
+ * uses, so the proposal is independent of every draw of the verifier under the
+ * same (seed, offset); word 0 -> u_x, word 1 >> 8 -> k24. */
+void pcg_ref_propose_uniforms(uint64_t seed, uint64_t offset, uint32_t b, uint32_t i, double *u_x,
+                              uint32_t *k24);
+
+/* Proposals for B sequences x K positions from explicit draws u_x [B*K] and
+ * k24 [B*K] (24-bit integers): x = inverse CDF of softmax(draft row / temperature)
+ * at u_x (ascending token order, first running sum strictly above u_x * total);
+ * group = tok_groups[tok_ptr[x] + ((k24 * N(x)) >> 24)].  near [B*K] (may be
+ * NULL): u_x within 1e-6 of an inner edge of the chosen token's bin. */
+int pcg_ref_propose_u(int32_t V, int32_t G, const int32_t *mult, const int32_t *tok_ptr,
+                      const int32_t *tok_groups, const void *draft_logits, int dtype, int32_t B,
+                      int32_t K, int64_t dft_batch_stride, int64_t dft_pos_stride,
+                      double temperature, const double *u_x, const uint32_t *k24,
+                      int32_t *prop_tokens, int32_t *prop_groups, uint8_t *near);
+
+/* Same with the draws of pcg_ref_propose_uniforms at positions pos0 .. pos0+K-1
+ * (pos0: position index of the first row, for drafts that call once per token). */
+int pcg_ref_propose(int32_t V, int32_t G, const int32_t *mult, const int32_t *tok_ptr,
+                    const int32_t *tok_groups, const void *draft_logits, int dtype, int32_t B,
+                    int32_t K, int32_t pos0, int64_t dft_batch_stride, int64_t dft_pos_stride,
+                    double temperature, uint64_t seed, uint64_t offset, int32_t *prop_tokens,
+                    int32_t *prop_groups, uint8_t *near, int32_t nthreads);
 
 #ifdef __cplusplus
 }

@@ -227,6 +227,38 @@ int pcg_verify_thinning(const pcg_groups *groups, const void *target_logits,
 
 size_t pcg_verify_thinning_workspace_bytes(int32_t V, int32_t B, int32_t K);
 
+/* ---- draft-side proposals ---------------------------------------------------------------- */
+
+/*
+ * The two sampling steps at the top of Algorithm 1's loop (Sec. 2.2 "Proposal coupling and
+ * acceptance", Eq. 6): for every (b, i) a draft token x ~ softmax(draft row / temperature) by
+ * inverse CDF over ascending token ids (first token whose running sum strictly exceeds
+ * u * total), then a group label among the groups holding x by the equal-split weights: one
+ * of the mult[x] membership entries of x, each equally likely, so that the label is distributed
+ * as the draft's group distribution D_i.
+ *   groups        must carry tok_ptr / tok_groups; row_ptr / members are not read
+ *   draft_logits  DEVICE [B, K, V], V contiguous; strides in elements as for pcg_verify
+ *   pos0          position index of row 0 (a draft that samples one token per forward pass
+ *                 calls with K = 1 and pos0 = 0, 1, ...); pos0 + K <= PCG_MAX_K
+ *   draws         position (b, i) uses the Philox block with counter
+ *                 (offset_lo, offset_hi, b, (pos0 + i) | 0xFFFF0000), a block neither
+ *                 pcg_verify nor any thinning trial reads: word 0 -> token uniform,
+ *                 word 1 >> 8 = k24 -> membership entry (k24 * mult[x]) >> 24
+ *   prop_tokens, prop_groups   DEVICE int32 [B, K], written
+ *   diag          optional DEVICE counters: near_token counts token draws within 1e-6 of an
+ *                 inner bin edge, sequences the rows processed
+ *   workspace     DEVICE, 256-byte aligned, >= pcg_propose_workspace_bytes(V, B, K)
+ * A row without any finite logit yields token 0 (the statistics kernel reports nothing: such
+ * rows are the caller's error, as for pcg_verify).  V must not exceed 4 194 304.
+ */
+int pcg_propose(const pcg_groups *groups, const void *draft_logits, pcg_dtype dt, int32_t B,
+                int32_t K, int32_t pos0, int64_t dft_batch_stride, int64_t dft_pos_stride,
+                float temperature, uint64_t seed, uint64_t offset, int32_t *prop_tokens,
+                int32_t *prop_groups, pcg_diag *diag, void *workspace, size_t workspace_bytes,
+                void *hip_stream);
+
+size_t pcg_propose_workspace_bytes(int32_t V, int32_t B, int32_t K);
+
 /* ---- group membership on the host -------------------------------------------------------- */
 
 /* PCG_OK iff (row_ptr, members, mult), all HOST, form a membership the kernels may use (see

@@ -83,6 +83,13 @@ def lib() -> C.CDLL:
                                           C.c_int64, C.c_float, C.c_void_p, C.c_void_p, C.c_uint64,
                                           C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                           C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.pcg_propose_workspace_bytes.restype = C.c_size_t
+        L.pcg_propose_workspace_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32]
+        L.pcg_propose.restype = C.c_int
+        L.pcg_propose.argtypes = [C.POINTER(_GroupsStruct), C.c_void_p, C.c_int, C.c_int32, C.c_int32,
+                                  C.c_int32, C.c_int64, C.c_int64, C.c_float, C.c_uint64, C.c_uint64,
+                                  C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
+                                  C.c_void_p]
         L.pcg_groups_reverse_host.restype = C.c_int
         L.pcg_groups_reverse_host.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                               C.c_void_p, C.c_void_p]
@@ -394,6 +401,49 @@ def verify_thinning(groups: Groups, target_logits: torch.Tensor, draft_logits: t
             None if diag is None else diag.data_ptr(), ws.data_ptr(), ws.numel(), _stream(dev)),
             "pcg_verify_thinning")
     return out, trials
+
+
+def propose_workspace_bytes(V: int, B: int, K: int) -> int:
+    return lib().pcg_propose_workspace_bytes(V, B, K)
+
+
+def propose(groups: Groups, draft_logits: torch.Tensor, *, temperature: float = 1.0, seed: int = 0,
+            offset: int = 0, pos0: int = 0, prop_tokens: Optional[torch.Tensor] = None,
+            prop_groups: Optional[torch.Tensor] = None, diag: Optional[torch.Tensor] = None,
+            workspace: Optional[torch.Tensor] = None,
+            B: Optional[int] = None) -> tuple[torch.Tensor, torch.Tensor]:
+    """Draft-side proposals (Eq. 6): a token from each draft row [B, K, V] and one of the groups
+    holding it.  ``groups`` must have been built with ``reverse=True``.  With ``B`` given and a
+    leading dimension of 1, all B sequences share the rows.  Returns int32 [B, K] tokens and
+    groups."""
+    assert groups.tok_ptr is not None, "build the groups with reverse=True"
+    assert draft_logits.dim() == 3 and draft_logits.stride(2) == 1
+    K, V = draft_logits.shape[1], draft_logits.shape[2]
+    assert V == groups.V
+    dev = draft_logits.device
+    if B is None:
+        B = draft_logits.shape[0]
+    shared = B != draft_logits.shape[0]
+    if shared:
+        assert draft_logits.shape[0] == 1
+    dbs = 0 if shared else (draft_logits.stride(0) if B > 1 else 0)
+    if prop_tokens is None:
+        prop_tokens = torch.empty((B, K), dtype=torch.int32, device=dev)
+    if prop_groups is None:
+        prop_groups = torch.empty((B, K), dtype=torch.int32, device=dev)
+    assert prop_tokens.dtype == torch.int32 and prop_groups.dtype == torch.int32
+    assert prop_tokens.numel() == B * K and prop_groups.numel() == B * K
+    need = propose_workspace_bytes(V, B, K)
+    ws = _workspace(dev, need) if workspace is None else workspace
+    gs = groups.struct()
+    with torch.cuda.device(dev):
+        _check(lib().pcg_propose(
+            C.byref(gs), draft_logits.data_ptr(), _dtype_code(draft_logits), B, K, pos0, dbs,
+            draft_logits.stride(1) if K > 1 else V, float(temperature), seed, offset,
+            prop_tokens.data_ptr(), prop_groups.data_ptr(),
+            None if diag is None else diag.data_ptr(), ws.data_ptr(), ws.numel(), _stream(dev)),
+            "pcg_propose")
+    return prop_tokens, prop_groups
 
 
 def profile_begin(max_calls: int):

@@ -26,10 +26,10 @@ size_t align_up(size_t n) { return (n + kAlign - 1) / kAlign * kAlign; }
 
 // ---- per-kernel timing -------------------------------------------------------------------
 
-enum Stage { kStageStats = 0, kStageAccept, kStageTable, kStageGather, kStageFinalize, kStageThin, kStageNull,
-             kNumStages };
+enum Stage { kStageStats = 0, kStageAccept, kStageTable, kStageGather, kStageFinalize, kStageThin,
+             kStagePropose, kStageNull, kNumStages };
 const char *const kStageNames[kNumStages] = {"row_stats", "accept_delta", "weights", "gather", "finalize",
-                                             "accept_thin", "event_overhead"};
+                                             "accept_thin", "propose", "event_overhead"};
 
 struct Profile {
   bool active = false;
@@ -335,6 +335,63 @@ int pcg_verify(const pcg_groups *groups, const void *target_logits, const void *
       hipSuccess)
     return hip_fail(e);
   tm.end(kStageFinalize);
+  return PCG_OK;
+}
+
+size_t pcg_propose_workspace_bytes(int32_t V, int32_t B, int32_t K) {
+  if (V < 1 || B < 0 || K < 1) return 0;
+  return align_up((size_t) B * K * stats_nparts(V) * sizeof(StatPart)) + kAlign;
+}
+
+int pcg_propose(const pcg_groups *groups, const void *draft_logits, pcg_dtype dt, int32_t B,
+                int32_t K, int32_t pos0, int64_t dft_batch_stride, int64_t dft_pos_stride,
+                float temperature, uint64_t seed, uint64_t offset, int32_t *prop_tokens,
+                int32_t *prop_groups, pcg_diag *diag, void *workspace, size_t workspace_bytes,
+                void *hip_stream) {
+  int rc = check_groups(groups);
+  if (rc) return rc;
+  if (dt != PCG_F32 && dt != PCG_BF16) return PCG_ERR_BAD_DTYPE;
+  if (B < 0 || K < 1 || pos0 < 0 || (int64_t) pos0 + K > PCG_MAX_K) return PCG_ERR_BAD_SHAPE;
+  if (B == 0) return PCG_OK;
+  if (!draft_logits || !prop_tokens || !prop_groups || !workspace || !groups->tok_ptr ||
+      !groups->tok_groups)
+    return PCG_ERR_NULL_ARG;
+  const int32_t V = groups->V;
+  if (!stride_ok(dft_pos_stride, V, K == 1) || !stride_ok(dft_batch_stride, V, true))
+    return PCG_ERR_BAD_STRIDE;
+  if (!good_temperature(temperature)) return PCG_ERR_BAD_TEMPERATURE;
+  const bool bf16 = dt == PCG_BF16;
+  if (((uintptr_t) draft_logits % (bf16 ? 2 : 4)) || ((uintptr_t) workspace % kAlign))
+    return PCG_ERR_MISALIGNED;
+  const int32_t nparts = stats_nparts(V);
+  const int64_t rows = (int64_t) B * K;
+  if (nparts > thin_max_parts() || rows * nparts / 4 >= INT32_MAX || rows >= INT32_MAX)
+    return PCG_ERR_BAD_SHAPE;
+  if (workspace_bytes < pcg_propose_workspace_bytes(V, B, K)) return PCG_ERR_WORKSPACE_TOO_SMALL;
+
+  RowSet rs;
+  std::memset(&rs, 0, sizeof rs);
+  rs.base0 = draft_logits;
+  rs.bs0 = dft_batch_stride;
+  rs.ps0 = dft_pos_stride;
+  rs.npos0 = K;
+  rs.npos1 = 1;
+  rs.nrows0 = rows;
+  rs.inv_npos0 = 1.0 / K;
+  rs.inv_npos1 = 1.0;
+  const Factors f = factors(temperature);
+  hipStream_t stream = (hipStream_t) hip_stream;
+  StatPart *parts = (StatPart *) workspace;
+  StageTimer tm(stream);
+  hipError_t e;
+  tm.begin(kStageStats);
+  if ((e = launch_row_stats(rs, bf16, V, rows, f.c, parts, stream)) != hipSuccess) return hip_fail(e);
+  tm.end(kStageStats);
+  tm.begin(kStagePropose);
+  if ((e = launch_propose(rs, bf16, V, K, pos0, f.c, parts, groups->tok_ptr, groups->tok_groups, seed,
+                          offset, prop_tokens, prop_groups, diag, stream)) != hipSuccess)
+    return hip_fail(e);
+  tm.end(kStagePropose);
   return PCG_OK;
 }
 

@@ -181,6 +181,23 @@ __device__ __forceinline__ TrialDraws philox_trial(uint64_t seed, uint64_t offse
   return d;
 }
 
+// Draws of the draft-side proposal at position (b, i): the block with counter word 3 =
+// i | 0xFFFF0000, a trial field no thinning trial reaches.
+struct ProposalDraws {
+  float u_x;
+  uint32_t k24;
+};
+
+__device__ __forceinline__ ProposalDraws philox_proposal(uint64_t seed, uint64_t offset, uint32_t b,
+                                                         uint32_t i) {
+  const uint4 w = philox4x32_10((uint32_t) offset, (uint32_t) (offset >> 32), b, i | 0xFFFF0000u,
+                                (uint32_t) seed, (uint32_t) (seed >> 32));
+  ProposalDraws d;
+  d.u_x = (float) (w.x >> 8) * (1.0f / 16777216.0f);
+  d.k24 = w.y >> 8;
+  return d;
+}
+
 // ---------------------------------------------------------------------------------------------
 // Per-row softmax statistics.
 // ---------------------------------------------------------------------------------------------

@@ -460,16 +460,17 @@ struct ThinShared {
   int done;
 };
 
-// y ~ q on the row whose part masses are in th: the part by its mass, then the token inside the
+// y ~ q on the row whose part masses are in Zp (relative to 2^(M c)) with log2-domain references
+// tp: the part by its mass, then the token inside the
 // part with each lane holding 32 consecutive tokens.  *near: the draw is within 1e-6 of an
 // inner edge of the token's bin.
 template <bool BF16, bool VEC>
-__device__ int32_t draw_token(const ThinShared &th, const void *trow, int32_t V, int32_t nparts,
-                              float M, float c, double u, int lane, bool *near) {
-  const WavePick pp = wave_inverse_cdf(nparts, [&](int32_t p) { return th.Zp[p]; }, u, lane);
+__device__ int32_t draw_token(const double *Zp, const float *tp, const void *trow, int32_t V,
+                              int32_t nparts, float M, float c, double u, int lane, bool *near) {
+  const WavePick pp = wave_inverse_cdf(nparts, [&](int32_t p) { return Zp[p]; }, u, lane);
   if (pp.index < 0) { *near = false; return 0; }
   const int32_t p = pp.index;
-  const float t = th.tp[p];
+  const float t = tp[p];
   const int32_t e0 = p * kPartElems + lane * 32;
   float v[32];
 #pragma unroll
@@ -566,8 +567,8 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_thin_kernel(
       const TrialDraws d = philox_trial(a.seed, a.offset, (uint32_t) b, (uint32_t) istar,
                                         (uint32_t) trial);
       bool near_y = false;
-      const int32_t y = draw_token<BF16, VEC>(th, trow, V, a.nparts, st.M, a.c, (double) d.u_y, lane,
-                                              &near_y);
+      const int32_t y = draw_token<BF16, VEC>(th.Zp, th.tp, trow, V, a.nparts, st.M, a.c,
+                                              (double) d.u_y, lane, &near_y);
       const int32_t e0 = tok_ptr[y], n = tok_ptr[y + 1] - e0;
       const int32_t g = tok_groups[e0 + (int32_t) (((uint64_t) d.k24 * (uint64_t) max(n, 1)) >> 24)];
       const int32_t beg = a.row_ptr[g], len = a.row_ptr[g + 1] - beg;
@@ -622,6 +623,49 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_thin_kernel(
     }
     __syncthreads();
     if (th.done) break;
+  }
+}
+
+// =============================================================================================
+// propose: the draft-side coupling (Sec. 2.2 "Proposal coupling and acceptance", Eq. 6).  One
+// wave per draft row: merge the row's part statistics, draw x ~ p through the parts, then one
+// of the membership entries of x.
+// =============================================================================================
+
+template <bool BF16, bool VEC>
+__global__ __launch_bounds__(kWave) void propose_kernel(
+    RowSet rs, int32_t V, int32_t K, int32_t pos0, int32_t nparts, float c, const StatPart *parts,
+    const int32_t *tok_ptr, const int32_t *tok_groups, uint64_t seed, uint64_t offset,
+    int32_t *prop_tokens, int32_t *prop_groups, pcg_diag *diag) {
+  __shared__ double Zp[kMaxThinParts];
+  __shared__ float tp[kMaxThinParts];
+  const int lane = threadIdx.x;
+  const int64_t row = blockIdx.x;
+  const StatPart *rp = parts + row * nparts;
+  float M = -INFINITY;
+  for (int32_t p = lane; p < nparts; p += kWave) M = fmaxf(M, rp[p].m);
+  M = wave_max(M);
+  for (int32_t p = lane; p < nparts; p += kWave) {
+    const StatPart sp = rp[p];
+    Zp[p] = sp.z > 0.0 ? sp.z * exp2((double) sp.t - (double) M * (double) c) : 0.0;
+    tp[p] = sp.t;
+  }
+  __syncthreads();
+  int64_t b;
+  int32_t i;
+  split_row(row, K, rs.inv_npos0, b, i);
+  const ProposalDraws d = philox_proposal(seed, offset, (uint32_t) b, (uint32_t) (pos0 + i));
+  bool near = false;
+  const int32_t x = draw_token<BF16, VEC>(Zp, tp, row_base(rs, row, BF16), V, nparts, M, c,
+                                          (double) d.u_x, lane, &near);
+  if (lane == 0) {
+    const int32_t e0 = tok_ptr[x], n = tok_ptr[x + 1] - e0;
+    prop_tokens[row] = x;
+    prop_groups[row] = tok_groups[e0 + (int32_t) (((uint64_t) d.k24 * (uint64_t) max(n, 1)) >> 24)];
+    if (diag) {
+      if (near) atomicAdd(&diag->near_token, 1u);
+      atomicAdd(&diag->sequences, 1u);
+    }
   }
 }
 
@@ -1195,6 +1239,23 @@ hipError_t launch_accept_thin(const AcceptArgs &a, bool bf16, int32_t B, const i
 }
 
 int32_t thin_max_parts() { return kMaxThinParts; }
+
+hipError_t launch_propose(const RowSet &rs, bool bf16, int32_t V, int32_t K, int32_t pos0, float c,
+                          const StatPart *parts, const int32_t *tok_ptr, const int32_t *tok_groups,
+                          uint64_t seed, uint64_t offset, int32_t *prop_tokens, int32_t *prop_groups,
+                          pcg_diag *diag, hipStream_t stream) {
+  const bool vec = rows_vector_aligned(rs, bf16) && V % 8 == 0;
+  const int32_t nparts = stats_nparts(V);
+  const unsigned grid = (unsigned) rs.nrows0;
+#define PCG_LAUNCH_PR(BF, VE)                                                                     \
+  propose_kernel<BF, VE><<<grid, kWave, 0, stream>>>(rs, V, K, pos0, nparts, c, parts, tok_ptr,   \
+                                                     tok_groups, seed, offset, prop_tokens,       \
+                                                     prop_groups, diag)
+  if (bf16) { if (vec) PCG_LAUNCH_PR(true, true); else PCG_LAUNCH_PR(true, false); }
+  else { if (vec) PCG_LAUNCH_PR(false, true); else PCG_LAUNCH_PR(false, false); }
+#undef PCG_LAUNCH_PR
+  return hipGetLastError();
+}
 
 hipError_t launch_weights(const RowSet &rs, bool bf16, const pcg_groups &g, int64_t row0,
                           int32_t nrows, float c, float c_hi, float c_lo, const StatPart *parts,

@@ -152,8 +152,8 @@ def test_profile_calls_are_guarded():
     n = C.c_int32()
     assert L.pcg_profile_end(ms, C.byref(n)) == BAD_SHAPE      # nothing was begun
     assert L.pcg_profile_begin(0) == BAD_SHAPE
-    assert [pcg.lib().pcg_stage_name(i).decode() for i in range(8)] == \
-        ["row_stats", "accept_delta", "weights", "gather", "finalize", "accept_thin", "event_overhead", ""]
+    assert [pcg.lib().pcg_stage_name(i).decode() for i in range(9)] == \
+        ["row_stats", "accept_delta", "weights", "gather", "finalize", "accept_thin", "propose", "event_overhead", ""]
 
 
 # --------------------------------------------------------------------------- prepared layout
@@ -265,3 +265,21 @@ def test_reverse_index_and_thinning_argument_checks():
     big = _GroupsStruct(5_000_000, 8, 16, P, P, P, None, None, P, P)    # more parts than the token draw searches
     assert L.pcg_verify_thinning(C.byref(big), P, P, 0, 1, 1, 0, 5_000_000, 0, 5_000_000, 1.0, P, P, 0, 0,
                                  P, P, P, P, None, P, 1 << 40, None) == BAD_SHAPE
+
+
+def test_propose_argument_checks():
+    L = pcg.lib()
+    call = lambda g, **k: L.pcg_propose(C.byref(g), k.get("logits", P), k.get("dt", 0), 2, k.get("K", 2),
+                                        k.get("pos0", 0), 128, k.get("ps", 64), k.get("tau", 1.0), 0, 0, P, P,
+                                        None, P, k.get("wsb", 1 << 30), None)
+    rev = _GroupsStruct(64, 8, 16, P, P, P, None, None, P, P)
+    assert call(_GroupsStruct(64, 8, 16, P, P, P, None, None, None, None)) == NULL_ARG   # no reverse index
+    assert call(rev, logits=None) == NULL_ARG
+    assert call(rev, dt=7) == BAD_DTYPE
+    assert call(rev, K=0) == BAD_SHAPE
+    assert call(rev, pos0=63) == BAD_SHAPE          # pos0 + K beyond PCG_MAX_K
+    assert call(rev, ps=10) == BAD_STRIDE
+    assert call(rev, tau=0.0) == BAD_TEMP
+    assert call(rev, logits=P + 2) == MISALIGNED
+    assert call(rev, wsb=pcg.propose_workspace_bytes(64, 2, 2) - 1) == WS_SMALL
+    assert pcg.propose_workspace_bytes(0, 1, 1) == 0

@@ -214,6 +214,34 @@ def main():
                       if v > 0.0 and k != "event_overhead"},
         "mean_trials_per_rejection_last_step": round(float(tr[tr > 0].mean()) if (tr > 0).any() else 0.0, 2)}
 
+    # The draft-side proposal coupling (Eq. 6) on the same draft rows: the step before the path,
+    # timed on its own.
+    ptok_out = torch.empty((cfg.B, cfg.K), dtype=torch.int32, device=dev)
+    pgrp_out = torch.empty((cfg.B, cfg.K), dtype=torch.int32, device=dev)
+
+    def propose_step(i):
+        pcg.propose(groups, sets[i % len(sets)][1], temperature=cfg.temperature, seed=0, offset=i,
+                    prop_tokens=ptok_out, prop_groups=pgrp_out, workspace=ws)
+
+    for i in range(args.warmup):
+        propose_step(i)
+    torch.cuda.synchronize()
+    t_begin = time.perf_counter()
+    for i in range(args.steps):
+        propose_step(args.warmup + i)
+    torch.cuda.synchronize()
+    prop_elapsed = time.perf_counter() - t_begin
+    pcg.profile_begin(args.steps)
+    for i in range(args.steps):
+        propose_step(args.warmup + i)
+    torch.cuda.synchronize()
+    prop_ms, _ = pcg.profile_end()
+    result["propose"] = {
+        "value": round(positions * args.steps / prop_elapsed, 1), "unit": "proposed positions/s",
+        "ms_per_call": round(1e3 * prop_elapsed / args.steps, 5),
+        "stages_us": {k: round(1e3 * v, 2) for k, v in prop_ms.items()
+                      if v > 0.0 and k != "event_overhead"}}
+
     if not args.no_cpu_baseline:
         import oracle
         og = oracle.canonicalize(cfg.V, rp, mem)

@@ -122,6 +122,34 @@ __device__ __forceinline__ double wave_sum(double v) {
   return *reinterpret_cast<double *>(&r);
 }
 
+constexpr int kDppShr1 = 0x111;        // row_shr: lane i <- lane i-k inside each row of 16
+constexpr int kDppShr2 = 0x112;
+constexpr int kDppShr4 = 0x114;
+constexpr int kDppShr8 = 0x118;
+
+// Inclusive prefix sum over the wave through DPP: lane l receives v[0] + ... + v[l] (fixed tree).
+__device__ __forceinline__ double wave_scan(double v) {
+  v += dpp_get<kDppShr1, 0xf>(v, 0.0);
+  v += dpp_get<kDppShr2, 0xf>(v, 0.0);
+  v += dpp_get<kDppShr4, 0xf>(v, 0.0);
+  v += dpp_get<kDppShr8, 0xf>(v, 0.0);
+  v += dpp_get<kDppBcast15, 0xa>(v, 0.0);   // rows 1 and 3 add the total of the row before
+  v += dpp_get<kDppBcast31, 0xc>(v, 0.0);   // rows 2 and 3 add the total of rows 0 and 1
+  return v;
+}
+
+// Value of lane l (the same l in every lane) in every lane.
+__device__ __forceinline__ double read_lane(double v, int l) {
+  int2 r = *reinterpret_cast<int2 *>(&v);
+  r.x = __builtin_amdgcn_readlane(r.x, l);
+  r.y = __builtin_amdgcn_readlane(r.y, l);
+  return *reinterpret_cast<double *>(&r);
+}
+
+__device__ __forceinline__ int32_t read_lane(int32_t v, int l) {
+  return __builtin_amdgcn_readlane(v, l);
+}
+
 // ---------------------------------------------------------------------------------------------
 // Philox4x32-10 (Salmon et al., SC'11), one block per (sequence, position).
 // ---------------------------------------------------------------------------------------------

@@ -390,6 +390,7 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_delta_kernel(AcceptArgs
 // =============================================================================================
 
 constexpr int kMaxThinParts = 2048;       // parts of a row the token draw can search (V <= 4 Mi)
+constexpr int kThinTrialWaves = 16;       // trials a workgroup runs side by side, one per wave
 
 struct WavePick {
   int32_t index;            // first index whose running sum exceeds u * total; -1: nothing has mass
@@ -397,14 +398,17 @@ struct WavePick {
 };
 
 // Inverse CDF over f(0..n-1) >= 0 by one wave (ascending order; every lane gets the result).
+// `total` < 0: the sum of f is formed here first.
 template <typename F>
-__device__ WavePick wave_inverse_cdf(int32_t n, F f, double u, int lane) {
-  double total = 0.0;
-  for (int32_t j = lane; j < n; j += kWave) {
-    const double v = f(j);
-    if (v > 0.0) total += v;
+__device__ WavePick wave_inverse_cdf(int32_t n, F f, double u, int lane, double total = -1.0) {
+  if (total < 0.0) {
+    total = 0.0;
+    for (int32_t j = lane; j < n; j += kWave) {
+      const double v = f(j);
+      if (v > 0.0) total += v;
+    }
+    total = wave_sum(total);
   }
-  total = wave_sum(total);
   WavePick r;
   r.total = total;
   r.goal = u * total;
@@ -417,27 +421,22 @@ __device__ WavePick wave_inverse_cdf(int32_t n, F f, double u, int lane) {
     const int32_t j = j0 + lane;
     double v = j < n ? f(j) : 0.0;
     if (!(v > 0.0)) v = 0.0;
-    double inc = v;
-#pragma unroll
-    for (int o = 1; o < kWave; o <<= 1) {
-      const double up = __shfl_up(inc, o, kWave);
-      if (lane >= o) inc += up;
-    }
+    const double inc = wave_scan(v);
     const unsigned long long pos = __ballot(v > 0.0);
     if (pos) {
       const int hl = 63 - __clzll((long long) pos);
       last = j0 + hl;
-      last_v = __shfl(v, hl, kWave);
+      last_v = read_lane(v, hl);
     }
     const unsigned long long hit = __ballot(v > 0.0 && base + inc > r.goal);
     if (hit) {
       const int l = __ffsll((long long) hit) - 1;
       r.index = j0 + l;
-      r.hi = base + __shfl(inc, l, kWave);
-      r.lo = r.hi - __shfl(v, l, kWave);
+      r.hi = base + read_lane(inc, l);
+      r.lo = r.hi - read_lane(v, l);
       return r;
     }
-    base += __shfl(inc, kWave - 1, kWave);
+    base += read_lane(inc, kWave - 1);
   }
   if (last >= 0) {   // rounding at the top end: the last index that has mass
     r.index = last;
@@ -452,75 +451,132 @@ __device__ __forceinline__ bool near_edge(const WavePick &p) {
          (p.hi < p.total && p.hi - p.goal < 1e-6 * p.total);
 }
 
+// Masses of the parts of one row, as the token draw reads them.
+struct PartMasses {
+  double Zp[kMaxThinParts];     // mass of each part relative to the row maximum, 2^(M c)
+  double up[kMaxThinParts];     // 2^(M c - t): from the row's units to the part's own
+  float tp[kMaxThinParts];      // log2-domain reference t of each part
+};
+
+// Filled by the calling threads (tid of nthreads) from the statistics of row `rp`; a barrier
+// must follow.
+__device__ __forceinline__ void fill_part_masses(PartMasses &pm, const StatPart *rp, int32_t nparts,
+                                                 float M, float c, int tid, int nthreads) {
+  for (int32_t p = tid; p < nparts; p += nthreads) {
+    const StatPart sp = rp[p];
+    const double e = exp2((double) sp.t - (double) M * (double) c);
+    const bool has = sp.z > 0.0 && e > 0.0;
+    pm.Zp[p] = has ? sp.z * e : 0.0;
+    pm.up[p] = has ? 1.0 / e : 0.0;
+    pm.tp[p] = sp.t;
+  }
+}
+
 struct ThinShared {
-  double Zp[kMaxThinParts];     // mass of each part of the decision row, relative to its maximum
-  float tp[kMaxThinParts];      // log2-domain reference of each part
-  int accepted[kAcceptThreads / kWave], group[kAcceptThreads / kWave];
-  int token[kAcceptThreads / kWave], near[kAcceptThreads / kWave];
+  PartMasses pm;
+  uint32_t redo[kThinTrialWaves][32];     // per wave: one lane's 32 logits, spread over the lanes
+  int accepted[kThinTrialWaves], group[kThinTrialWaves];
+  int token[kThinTrialWaves], near[kThinTrialWaves];
   int done;
 };
 
-// y ~ q on the row whose part masses are in Zp (relative to 2^(M c)) with log2-domain references
-// tp: the part by its mass, then the token inside the
-// part with each lane holding 32 consecutive tokens.  *near: the draw is within 1e-6 of an
-// inner edge of the token's bin.
+// 32 consecutive logits of a row as loaded: bf16 stays packed two per register.
+template <bool BF16>
+struct Logits32 {
+  static constexpr int kWords = BF16 ? 16 : 32;
+  uint32_t w[kWords];
+  __device__ __forceinline__ float get(int k) const {
+    if constexpr (BF16) return __uint_as_float((k & 1) ? (w[k >> 1] & 0xffff0000u) : (w[k >> 1] << 16));
+    else return __uint_as_float(w[k]);
+  }
+};
+
+// Tokens e0 .. e0+31 of a row; tokens at or beyond V read as -inf.
 template <bool BF16, bool VEC>
-__device__ int32_t draw_token(const double *Zp, const float *tp, const void *trow, int32_t V,
-                              int32_t nparts, float M, float c, double u, int lane, bool *near) {
-  const WavePick pp = wave_inverse_cdf(nparts, [&](int32_t p) { return Zp[p]; }, u, lane);
-  if (pp.index < 0) { *near = false; return 0; }
-  const int32_t p = pp.index;
-  const float t = tp[p];
-  const int32_t e0 = p * kPartElems + lane * 32;
-  float v[32];
+__device__ __forceinline__ void load32(const void *row, int32_t e0, int32_t V, Logits32<BF16> &r) {
+  constexpr int nvec = BF16 ? 4 : 8;
+  if (VEC && e0 + 32 <= V) {
+    const uint4 *src = reinterpret_cast<const uint4 *>(reinterpret_cast<const char *>(row) +
+                                                       (size_t) e0 * (BF16 ? 2 : 4));
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    float x[8];
-    load8<BF16, VEC>(trow, e0 + 8 * i, V, x);
-#pragma unroll
-    for (int k = 0; k < 8; ++k)   // the same expression row_stats summed
-      v[8 * i + k] = x[k] > -INFINITY ? __builtin_amdgcn_exp2f(fmaf(x[k], c, -t)) : 0.f;
-  }
-  double s = 0.0;
-#pragma unroll
-  for (int k = 0; k < 32; ++k) s += (double) v[k];
-  double inc = s;
-#pragma unroll
-  for (int o = 1; o < kWave; o <<= 1) {
-    const double up = __shfl_up(inc, o, kWave);
-    if (lane >= o) inc += up;
-  }
-  // threshold in the part's own units: masses there are relative to 2^t, in Zp to 2^(M c)
-  const double scale = exp2((double) M * (double) c - (double) t);
-  const double goal = (pp.goal - pp.lo) * scale;
-  const double part_total = __shfl(inc, kWave - 1, kWave);
-  const unsigned long long hit = __ballot(s > 0.0 && inc > goal);
-  const unsigned long long pos = __ballot(s > 0.0);
-  const int l = hit ? __ffsll((long long) hit) - 1 : (pos ? 63 - __clzll((long long) pos) : 0);
-  int32_t y = -1;
-  double lo = 0.0, hi = 0.0;
-  if (lane == l) {
-    double cum = inc - s;
-    int last = -1;
-    double last_lo = 0.0;
+    for (int i = 0; i < nvec; ++i) {
+      const uint4 q = src[i];
+      r.w[4 * i] = q.x; r.w[4 * i + 1] = q.y; r.w[4 * i + 2] = q.z; r.w[4 * i + 3] = q.w;
+    }
+  } else {
+    const uint32_t ninf = BF16 ? 0xff80u : 0xff800000u;
 #pragma unroll
     for (int k = 0; k < 32; ++k) {
-      if (y < 0 && v[k] > 0.f) {
-        const double nxt = cum + (double) v[k];
-        if (nxt > goal) { y = e0 + k; lo = cum; hi = nxt; }
-        else { last = k; last_lo = cum; cum = nxt; }
+      uint32_t bits = ninf;
+      if (e0 + k < V) {
+        if constexpr (BF16) bits = reinterpret_cast<const uint16_t *>(row)[e0 + k];
+        else bits = reinterpret_cast<const uint32_t *>(row)[e0 + k];
+      }
+      if constexpr (BF16) {
+        if (k & 1) r.w[k >> 1] |= bits << 16; else r.w[k >> 1] = bits;
+      } else {
+        r.w[k] = bits;
       }
     }
-    if (y < 0 && last >= 0) { y = e0 + last; lo = last_lo; hi = cum; }
   }
-  y = __shfl(y, l, kWave);
-  lo = __shfl(lo, l, kWave);
-  hi = __shfl(hi, l, kWave);
+}
+
+// y ~ q on the row whose part masses are in pm: the part by its mass, then the lane inside the
+// part (each lane sums 32 consecutive tokens), then the token among that lane's 32, which are
+// handed to 32 lanes through `redo` (32 words of LDS private to the calling wave).
+// *near: the draw is within 1e-6 of an inner edge of the token's bin.
+template <bool BF16, bool VEC>
+__device__ int32_t draw_token(const PartMasses &pm, uint32_t *redo, const void *trow, int32_t V,
+                              int32_t nparts, float c, double u, int lane, bool *near) {
+  const WavePick pp = wave_inverse_cdf(nparts, [&](int32_t p) { return pm.Zp[p]; }, u, lane);
+  if (pp.index < 0) { *near = false; return 0; }
+  const int32_t p = pp.index;
+  const float t = pm.tp[p];
+  const int32_t e0 = p * kPartElems + lane * 32;
+  Logits32<BF16> raw;
+  load32<BF16, VEC>(trow, e0, V, raw);
+  // the same expression row_stats summed
+  auto mass = [&](float x) -> float {
+    return x > -INFINITY ? __builtin_amdgcn_exp2f(fmaf(x, c, -t)) : 0.f;
+  };
+  double s = 0.0;
+#pragma unroll
+  for (int k = 0; k < 32; k += 2) s += (double) mass(raw.get(k)) + (double) mass(raw.get(k + 1));
+  const double inc = wave_scan(s);
+  // threshold in the part's own units: masses there are relative to 2^t, in Zp to 2^(M c)
+  const double scale = pm.up[p];
+  const double goal = (pp.goal - pp.lo) * scale;
+  const double part_total = read_lane(inc, kWave - 1);
+  const unsigned long long hit = __ballot(s > 0.0 && inc > goal);
+  const unsigned long long pos = __ballot(s > 0.0);
+  if (!pos) { *near = false; return min(p * kPartElems, V - 1); }   // cannot happen: Zp[p] > 0
+  const int l = hit ? __ffsll((long long) hit) - 1 : 63 - __clzll((long long) pos);
+  // lane l's 32 tokens, one per lane
+  if (lane == l) {
+#pragma unroll
+    for (int k = 0; k < Logits32<BF16>::kWords; ++k) redo[k] = raw.w[k];
+  }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  float x = -INFINITY;
+  if (lane < 32) {
+    if constexpr (BF16) x = __uint_as_float((uint32_t) reinterpret_cast<const uint16_t *>(redo)[lane] << 16);
+    else x = __uint_as_float(redo[lane]);
+  }
+  const double v = (double) mass(x);
+  const double before = read_lane(inc, l) - read_lane(s, l);
+  const double cum = before + wave_scan(v);
+  const unsigned long long hit2 = __ballot(v > 0.0 && cum > goal);
+  const unsigned long long pos2 = __ballot(v > 0.0);
+  const int k = hit2 ? __ffsll((long long) hit2) - 1 : 63 - __clzll((long long) pos2);
+  const double hi = read_lane(cum, k), lo = hi - read_lane(v, k);
+  const int32_t y = p * kPartElems + l * 32 + k;
   const double tot_units = pp.total * scale;
   const bool first_mass = pp.lo <= 0.0 && lo <= 0.0;            // no bin below
   const bool last_mass = pp.hi >= pp.total && hi >= part_total;  // no bin above
   *near = (!first_mass && goal - lo < 1e-6 * tot_units) || (!last_mass && hi - goal < 1e-6 * tot_units);
-  return y < 0 ? 0 : y;
+  return y;
 }
 
 template <bool BF16, bool VEC>
@@ -533,7 +589,6 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_thin_kernel(
   accept_phase<BF16>(sh, a, b, true);
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  constexpr int nw = kAcceptThreads / kWave;
   const int32_t K = a.K, V = a.V, istar = sh.istar;
   const bool bonus = istar == K;
   const int64_t trow_id = (int64_t) b * (K + 1) + istar;
@@ -541,33 +596,29 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_thin_kernel(
   const void *drow = row_base(a.rs, a.rs.nrows0 + (int64_t) b * K + (bonus ? 0 : istar), BF16);
   const RowStat st = sh.st_t[istar];
   const RowStat sd = sh.st_d[bonus ? 0 : istar];
+  const float c_lo = (float) (a.cd - (double) a.c);
 
-  for (int32_t p = threadIdx.x; p < a.nparts; p += kAcceptThreads) {
-    const StatPart sp = a.parts[trow_id * a.nparts + p];
-    th.Zp[p] = sp.z > 0.0 ? sp.z * exp2((double) sp.t - (double) st.M * (double) a.c) : 0.0;
-    th.tp[p] = sp.t;
-  }
+  fill_part_masses(th.pm, a.parts + trow_id * a.nparts, a.nparts, st.M, a.c, threadIdx.x, kAcceptThreads);
   if (threadIdx.x == 0) th.done = 0;
   __syncthreads();
 
-  // q(t) / N(t) up to the row's normalisation, and the same for the draft row
+  // q(t) / N(t) and p(t) / N(t) up to the rows' normalisations, in the kernels' precision (fp32)
   auto wq = [&](int32_t t) -> double {
-    const float x = logit_at<BF16>(trow, t);
-    return x > -INFINITY ? exp2((double) (x - st.M) * a.cd) / (double) a.mult[t] : 0.0;
+    return (double) (exp_rel(logit_at<BF16>(trow, t), st.M, a.c, c_lo) / (float) a.mult[t]);
   };
   auto wp = [&](int32_t t) -> double {
-    const float x = logit_at<BF16>(drow, t);
-    return x > -INFINITY ? exp2((double) (x - sd.M) * a.cd) / (double) a.mult[t] : 0.0;
+    return (double) (exp_rel(logit_at<BF16>(drow, t), sd.M, a.c, c_lo) / (float) a.mult[t]);
   };
 
+  // Trials run kThinTrialWaves at a time, one per wave; the other waves only keep the barriers.
   for (int32_t round = 0;; ++round) {
-    const int32_t trial = round * nw + wave;
-    const bool active = bonus ? (round == 0 && wave == 0) : trial < max_trials;
+    const int32_t trial = round * kThinTrialWaves + wave;
+    const bool active = wave < kThinTrialWaves && (bonus ? trial == 0 : trial < max_trials);
     if (active) {   // uniform over the wave
       const TrialDraws d = philox_trial(a.seed, a.offset, (uint32_t) b, (uint32_t) istar,
                                         (uint32_t) trial);
       bool near_y = false;
-      const int32_t y = draw_token<BF16, VEC>(th.Zp, th.tp, trow, V, a.nparts, st.M, a.c,
+      const int32_t y = draw_token<BF16, VEC>(th.pm, th.redo[wave], trow, V, a.nparts, a.c,
                                               (double) d.u_y, lane, &near_y);
       const int32_t e0 = tok_ptr[y], n = tok_ptr[y + 1] - e0;
       const int32_t g = tok_groups[e0 + (int32_t) (((uint64_t) d.k24 * (uint64_t) max(n, 1)) >> 24)];
@@ -575,44 +626,48 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_thin_kernel(
       int accepted = 1, near = near_y ? 1 : 0;
       int32_t token = y;
       if (!bonus) {
-        double at = 0.0, ad = 0.0;
-        for (int32_t j = lane; j < len; j += kWave) {
+        // the first 64 members stay in registers for the token draw below
+        const int32_t t0 = lane < len ? a.members[beg + lane] : -1;
+        const double q0 = t0 >= 0 ? wq(t0) : 0.0;
+        double at = q0, ad = t0 >= 0 ? wp(t0) : 0.0;
+        for (int32_t j = lane + kWave; j < len; j += kWave) {
           const int32_t t = a.members[beg + j];
           at += wq(t);
           ad += wp(t);
         }
-        const double T = wave_sum(at) / st.Z, D = wave_sum(ad) / sd.Z;
+        const double Tn = wave_sum(at), T = Tn / st.Z, D = wave_sum(ad) / sd.Z;
         const double ua = (double) d.u_a;
         accepted = ua * T < T - D;                    // u_a < [1 - D/T]_+
         if (fabs(ua * T - (T - D)) < 1e-6 * T) near |= 1;
         const WavePick pt = wave_inverse_cdf(
-            len, [&](int32_t j) { return wq(a.members[beg + j]); }, (double) d.u_tok, lane);
-        token = pt.index < 0 ? -1 : a.members[beg + pt.index];
+            len, [&](int32_t j) { return j < kWave ? q0 : wq(a.members[beg + j]); },
+            (double) d.u_tok, lane, Tn);
+        token = pt.index < 0 ? -1 : (pt.index < kWave ? read_lane(t0, pt.index) : a.members[beg + pt.index]);
         if (pt.index >= 0 && near_edge(pt)) near |= 2;
       }
       if (lane == 0) {
         th.accepted[wave] = accepted; th.group[wave] = g; th.token[wave] = token; th.near[wave] = near;
       }
-    } else if (lane == 0) {
+    } else if (lane == 0 && wave < kThinTrialWaves) {
       th.accepted[wave] = -1;
     }
     __syncthreads();
     if (threadIdx.x == 0) {
       uint32_t n_near = 0, n_near_tok = 0;
       int chosen = -1, last_active = -1;
-      for (int w = 0; w < nw && chosen < 0; ++w) {
+      for (int w = 0; w < kThinTrialWaves && chosen < 0; ++w) {
         if (th.accepted[w] < 0) break;
         last_active = w;
         if (th.near[w] & 1) ++n_near;
         if (th.accepted[w] == 1) chosen = w;
       }
-      const bool exhausted = chosen < 0 && (round + 1) * nw >= max_trials;
+      const bool exhausted = chosen < 0 && (round + 1) * kThinTrialWaves >= max_trials;
       if (exhausted) chosen = last_active;
       if (chosen >= 0) {
         if (th.near[chosen] & 2) ++n_near_tok;
         a.out_groups[(int64_t) b * (K + 1) + istar] = th.group[chosen];
         a.out_tokens[(int64_t) b * (K + 1) + istar] = th.token[chosen];
-        trials[b] = bonus ? 0 : round * nw + chosen + 1;
+        trials[b] = bonus ? 0 : round * kThinTrialWaves + chosen + 1;
         th.done = 1;
       }
       if (a.diag) {
@@ -637,26 +692,22 @@ __global__ __launch_bounds__(kWave) void propose_kernel(
     RowSet rs, int32_t V, int32_t K, int32_t pos0, int32_t nparts, float c, const StatPart *parts,
     const int32_t *tok_ptr, const int32_t *tok_groups, uint64_t seed, uint64_t offset,
     int32_t *prop_tokens, int32_t *prop_groups, pcg_diag *diag) {
-  __shared__ double Zp[kMaxThinParts];
-  __shared__ float tp[kMaxThinParts];
+  __shared__ PartMasses pm;
+  __shared__ uint32_t redo[32];
   const int lane = threadIdx.x;
   const int64_t row = blockIdx.x;
   const StatPart *rp = parts + row * nparts;
   float M = -INFINITY;
   for (int32_t p = lane; p < nparts; p += kWave) M = fmaxf(M, rp[p].m);
   M = wave_max(M);
-  for (int32_t p = lane; p < nparts; p += kWave) {
-    const StatPart sp = rp[p];
-    Zp[p] = sp.z > 0.0 ? sp.z * exp2((double) sp.t - (double) M * (double) c) : 0.0;
-    tp[p] = sp.t;
-  }
+  fill_part_masses(pm, rp, nparts, M, c, lane, kWave);
   __syncthreads();
   int64_t b;
   int32_t i;
   split_row(row, K, rs.inv_npos0, b, i);
   const ProposalDraws d = philox_proposal(seed, offset, (uint32_t) b, (uint32_t) (pos0 + i));
   bool near = false;
-  const int32_t x = draw_token<BF16, VEC>(Zp, tp, row_base(rs, row, BF16), V, nparts, M, c,
+  const int32_t x = draw_token<BF16, VEC>(pm, redo, row_base(rs, row, BF16), V, nparts, c,
                                           (double) d.u_x, lane, &near);
   if (lane == 0) {
     const int32_t e0 = tok_ptr[x], n = tok_ptr[x + 1] - e0;

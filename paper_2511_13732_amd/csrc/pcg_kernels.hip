@@ -210,6 +210,29 @@ struct AcceptShared {
   int istar;                                   // accept_len of the sequence
 };
 
+// Statistics of one row from its parts, by the 16 lanes of one DPP row (sub = lane & 15); four
+// rows are merged per wave at once.  Every lane of the 16 returns the result.
+__device__ __forceinline__ RowStat merge_row16(const StatPart *parts, int64_t row, int32_t nparts,
+                                               float c, int sub) {
+  const StatPart *rp = parts + row * nparts;
+  float M = -INFINITY;
+  for (int32_t k = sub; k < nparts; k += 16) M = fmaxf(M, rp[k].m);
+  M = fmaxf(M, dpp_get<kDppXor1, 0xf>(M, M));
+  M = fmaxf(M, dpp_get<kDppXor2, 0xf>(M, M));
+  M = fmaxf(M, dpp_get<kDppHalfMirror, 0xf>(M, M));
+  M = fmaxf(M, dpp_get<kDppMirror, 0xf>(M, M));
+  double Z = 0.0;
+  for (int32_t k = sub; k < nparts; k += 16) {
+    const StatPart sp = rp[k];
+    if (sp.z > 0.0) Z += sp.z * exp2((double) sp.t - (double) M * (double) c);
+  }
+  RowStat r;
+  r.Z = subwave_sum<16>(Z);
+  r.M = M;
+  r.pad = 0.f;
+  return r;
+}
+
 // The accept scan of sequence b (Algorithm 1 up to the first rejection) by one workgroup of
 // kAcceptThreads.  On return sh.istar, sh.st_t and sh.st_d are valid for every thread; with
 // `writer` the sequence's outputs, row statistics and counters are written.
@@ -219,6 +242,7 @@ __device__ void accept_phase(AcceptShared &sh, const AcceptArgs &a, int b, bool 
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
   constexpr int nw = kAcceptThreads / kWave;
   const int64_t B = a.rs.nrows0 / (K + 1);
+  const float c_lo = (float) (a.cd - (double) a.c);
   // The two chains of dependent loads run side by side on different waves: the first
   // `nprobe` waves follow proposal -> group -> members -> logits, the others merge the row
   // statistics.  The probes sum relative to the group's own maximum, so they need no row
@@ -236,19 +260,30 @@ __device__ void accept_phase(AcceptShared &sh, const AcceptArgs &a, int b, bool 
         const void *trow = row_base(a.rs, (int64_t) b * (K + 1) + i, BF16);
         const void *drow = row_base(a.rs, a.rs.nrows0 + (int64_t) b * K + i, BF16);
         const int32_t beg = a.row_ptr[g], end = a.row_ptr[g + 1];
-        for (int32_t j = beg + lane; j < end; j += kWave) {
+        // the first 64 members stay in registers; longer groups take a second trip
+        const bool has = beg + lane < end;
+        const int32_t t0 = has ? a.members[beg + lane] : 0;
+        const float lt0 = has ? logit_at<BF16>(trow, t0) : -INFINITY;
+        const float ld0 = has ? logit_at<BF16>(drow, t0) : -INFINITY;
+        const float m0 = has ? (float) a.mult[t0] : 1.f;
+        mt = lt0;
+        md = ld0;
+        for (int32_t j = beg + lane + kWave; j < end; j += kWave) {
           const int32_t t = a.members[j];
           mt = fmaxf(mt, logit_at<BF16>(trow, t));
           md = fmaxf(md, logit_at<BF16>(drow, t));
         }
         mt = wave_max(mt);
         md = wave_max(md);
-        for (int32_t j = beg + lane; j < end; j += kWave) {
+        // masses in the kernels' precision: fp32 exponential and division, fp64 sum
+        if (lt0 > -INFINITY) at = (double) (exp_rel(lt0, mt, a.c, c_lo) / m0);
+        if (ld0 > -INFINITY) ad = (double) (exp_rel(ld0, md, a.c, c_lo) / m0);
+        for (int32_t j = beg + lane + kWave; j < end; j += kWave) {
           const int32_t t = a.members[j];
-          const double inv_m = 1.0 / (double) a.mult[t];
+          const float m = (float) a.mult[t];
           const float lt = logit_at<BF16>(trow, t), ld = logit_at<BF16>(drow, t);
-          if (lt > -INFINITY) at += exp2((double) (lt - mt) * a.cd) * inv_m;
-          if (ld > -INFINITY) ad += exp2((double) (ld - md) * a.cd) * inv_m;
+          if (lt > -INFINITY) at += (double) (exp_rel(lt, mt, a.c, c_lo) / m);
+          if (ld > -INFINITY) ad += (double) (exp_rel(ld, md, a.c, c_lo) / m);
         }
       }
       at = wave_sum(at);
@@ -262,12 +297,13 @@ __device__ void accept_phase(AcceptShared &sh, const AcceptArgs &a, int b, bool 
       }
     }
   } else {
-    // row statistics of this sequence's 2K+1 rows
-    for (int r = wave - nprobe; r < 2 * K + 1; r += nw - nprobe) {
+    // row statistics of this sequence's 2K+1 rows, four rows per wave at a time
+    const int sub = lane & 15;
+    for (int r = (wave - nprobe) * 4 + (lane >> 4); r < 2 * K + 1; r += (nw - nprobe) * 4) {
       const bool is_t = r <= K;
       const int64_t row = is_t ? (int64_t) b * (K + 1) + r : B * (K + 1) + (int64_t) b * K + (r - K - 1);
-      RowStat s = merge_row(a.parts, row, a.nparts, a.c, lane);
-      if (lane == 0) {
+      const RowStat s = merge_row16(a.parts, row, a.nparts, a.c, sub);
+      if (sub == 0) {
         if (writer) a.rowstat[row] = s;
         if (is_t) sh.st_t[r] = s; else sh.st_d[r - K - 1] = s;
       }
@@ -275,42 +311,45 @@ __device__ void accept_phase(AcceptShared &sh, const AcceptArgs &a, int b, bool 
   }
   __syncthreads();
 
-  // both chains have met: normalise the probes, one thread per position
-  if (threadIdx.x < K) {
-    const int i = threadIdx.x;
-    double T = 0.0, D = 0.0;
-    if (sh.Tp[i] > 0.0) T = sh.Tp[i] * exp2((double) (sh.Tref[i] - sh.st_t[i].M) * a.cd) / sh.st_t[i].Z;
-    if (sh.Dp[i] > 0.0) D = sh.Dp[i] * exp2((double) (sh.Dref[i] - sh.st_d[i].M) * a.cd) / sh.st_d[i].Z;
-    sh.Tn[i] = T;
-    sh.Dn[i] = D;
-  }
-  __syncthreads();
-
-  // sequential accept scan with early exit; the draft token stands for its group on accept
-  if (threadIdx.x == 0) {
-    uint32_t near = 0, zero_d = 0, nbad = 0;
-    int i = 0;
-    for (; i < K; ++i) {
-      const double u = (double) sh.uacc[i];
-      const double T = sh.Tn[i], D = sh.Dn[i];
-      if (sh.bad[i]) ++nbad;
-      else if (D == 0.0) ++zero_d;
-      if (fabs(u * D - T) < 1e-6 * D) ++near;
-      if (!(u * D < T)) break;
+  // Both chains have met.  One wave, one position per lane (K <= 64): normalise the probe,
+  // take the accept test, and find the first rejection with a ballot; the draft token stands
+  // for its group on accept.
+  if (wave == 0) {
+    const int i = lane;
+    const bool in = i < K;
+    double T = 0.0, D = 0.0, u = 0.0;
+    bool bad = false;
+    if (in) {
+      if (sh.Tp[i] > 0.0) T = sh.Tp[i] * exp2((double) (sh.Tref[i] - sh.st_t[i].M) * a.cd) / sh.st_t[i].Z;
+      if (sh.Dp[i] > 0.0) D = sh.Dp[i] * exp2((double) (sh.Dref[i] - sh.st_d[i].M) * a.cd) / sh.st_d[i].Z;
+      u = (double) sh.uacc[i];
+      bad = sh.bad[i] != 0;
+      sh.Tn[i] = T;
+      sh.Dn[i] = D;
     }
-    sh.istar = i;
+    const unsigned long long rejects = __ballot(in && !(u * D < T));
+    const int istar = rejects ? __ffsll((long long) rejects) - 1 : K;
+    const bool evaluated = in && i <= istar;
+    const uint32_t near = __popcll(__ballot(evaluated && fabs(u * D - T) < 1e-6 * D));
+    const uint32_t zero_d = __popcll(__ballot(evaluated && !bad && D == 0.0));
+    const uint32_t nbad = __popcll(__ballot(evaluated && bad));
+    if (lane == 0) sh.istar = istar;
     if (writer) {
       int32_t *otok = a.out_tokens + (int64_t) b * (K + 1);
       int32_t *ogrp = a.out_groups + (int64_t) b * (K + 1);
-      for (int k = 0; k < i; ++k) { otok[k] = sh.ptok[k]; ogrp[k] = sh.pgrp[k]; }
-      for (int k = i; k <= K; ++k) otok[k] = ogrp[k] = -1;
-      a.accept_len[b] = i;
-      if (a.diag) {
-        if (near) atomicAdd(&a.diag->near_accept, near);
-        if (zero_d) atomicAdd(&a.diag->zero_draft_mass, zero_d);
-        if (nbad) atomicAdd(&a.diag->bad_proposal, nbad);
-        atomicAdd(&a.diag->accepted_total, (uint32_t) i);
-        atomicAdd(&a.diag->sequences, 1u);
+      for (int k = lane; k <= K; k += kWave) {
+        otok[k] = k < istar ? sh.ptok[k] : -1;
+        ogrp[k] = k < istar ? sh.pgrp[k] : -1;
+      }
+      if (lane == 0) {
+        a.accept_len[b] = istar;
+        if (a.diag) {
+          if (near) atomicAdd(&a.diag->near_accept, near);
+          if (zero_d) atomicAdd(&a.diag->zero_draft_mass, zero_d);
+          if (nbad) atomicAdd(&a.diag->bad_proposal, nbad);
+          atomicAdd(&a.diag->accepted_total, (uint32_t) istar);
+          atomicAdd(&a.diag->sequences, 1u);
+        }
       }
     }
   }

@@ -322,7 +322,7 @@ def test_recipe_small(name, steps):
     assert total.tolerated <= max(1, total.sequences // 500)
 
 
-@pytest.mark.parametrize("name,steps", [("C3", 3), ("C4", 2), ("C5", 2)])
+@pytest.mark.parametrize("name,steps", [("C3", 3), ("C4", 2), ("C5", 2), ("C6", 1)])
 def test_recipe_full_size(name, steps):
     """The large recipes at their full sizes, in the launch configuration the benchmark times."""
     cfg = W.CONFIGS[name]

@@ -139,10 +139,42 @@ class Groups:
     row_ptr: np.ndarray   # int32 [G+1]
     members: np.ndarray   # int32 [nnz]
     mult: np.ndarray      # int32 [V]
+    weights: Optional[np.ndarray] = None       # float32 [nnz] general weights (Eq. 2); None = equal split
+    tok_weights: Optional[np.ndarray] = None   # float32 [nnz] the same in reverse-index order
 
     @property
     def nnz(self) -> int:
         return int(self.row_ptr[-1])
+
+
+class _Weights(C.Structure):
+    _fields_ = [("weights", C.c_void_p), ("tok_weights", C.c_void_p)]
+
+
+def _wt(g: "Groups"):
+    """Pointer to the weights argument of the _w entry points (NULL = equal split)."""
+    if g.weights is None:
+        return None
+    return C.byref(_Weights(g.weights.ctypes.data,
+                            None if g.tok_weights is None else g.tok_weights.ctypes.data))
+
+
+def validate_weights(g: "Groups", weights, tol: float = 1e-6) -> int:
+    w = np.ascontiguousarray(weights, dtype=np.float32)
+    return lib().pcg_ref_validate_weights(C.c_int32(g.V), C.c_int32(g.G), _p(g.row_ptr), _p(g.members),
+                                          _p(w), C.c_double(tol))
+
+
+def with_weights(g: "Groups", weights, tol: float = 1e-6) -> "Groups":
+    """The same membership with general per-entry weights (validated), and their reverse-index
+    order for thinning and proposals."""
+    w = np.ascontiguousarray(weights, dtype=np.float32)
+    assert w.shape == (g.nnz,)
+    _check(validate_weights(g, w, tol), "validate_weights")
+    tw = np.empty(max(1, g.nnz), dtype=np.float32)
+    _check(lib().pcg_ref_reverse_weights(C.c_int32(g.V), C.c_int32(g.G), _p(g.row_ptr), _p(g.members),
+                                         _p(w), _p(tw)), "reverse_weights")
+    return Groups(g.V, g.G, g.row_ptr, g.members, g.mult, w, tw[:g.nnz])
 
 
 def count_mult(V: int, row_ptr, members) -> np.ndarray:
@@ -180,8 +212,8 @@ def group_probs(g: Groups, logits, temperature: float = 1.0) -> np.ndarray:
     a, dt = _logits(logits)
     assert a.ndim == 2 and a.shape[1] == g.V
     out = np.empty((a.shape[0], g.G), dtype=np.float64)
-    _check(lib().pcg_ref_group_probs(C.c_int32(g.V), C.c_int32(g.G), _p(g.row_ptr),
-                                     _p(g.members), _p(g.mult), _p(a), C.c_int(dt),
+    _check(lib().pcg_ref_group_probs_w(C.c_int32(g.V), C.c_int32(g.G), _p(g.row_ptr),
+                                     _p(g.members), _p(g.mult), _wt(g), _p(a), C.c_int(dt),
                                      C.c_int64(a.shape[0]), C.c_int64(a.shape[1]),
                                      C.c_double(temperature), _p(out)), "group_probs")
     return out
@@ -248,17 +280,17 @@ def verify(g: Groups, target_logits, draft_logits, prop_tokens, prop_groups, *,
                 res.near_grp.ctypes.data, res.near_tok.ctypes.data, res.flags.ctypes.data,
                 res.res_S.ctypes.data, res.res_lo.ctypes.data, res.res_hi.ctypes.data,
                 res.R_norm.ctypes.data if want_R else None)
-    common = [C.c_int32(g.V), C.c_int32(g.G), _p(g.row_ptr), _p(g.members), _p(g.mult),
+    common = [C.c_int32(g.V), C.c_int32(g.G), _p(g.row_ptr), _p(g.members), _p(g.mult), _wt(g),
               _p(tgt), _p(dft), C.c_int(dt), C.c_int32(B), C.c_int32(K), tbs, tps, dbs, dps,
               C.c_double(temperature), _p(ptok), _p(pgrp)]
     outs = [_p(al), _p(otok), _p(ogrp), C.byref(tr)]
     if uniforms_explicit is not None:
         ua, ug, ut = (np.ascontiguousarray(x, dtype=np.float64) for x in uniforms_explicit)
         assert ua.shape == (B, K) and ug.shape == (B, K + 1) and ut.shape == (B, K + 1)
-        rc = lib().pcg_ref_verify_u(*common, _p(ua), _p(ug), _p(ut), *outs, C.c_int32(nthreads))
+        rc = lib().pcg_ref_verify_u_w(*common, _p(ua), _p(ug), _p(ut), *outs, C.c_int32(nthreads))
     else:
         used = C.c_int32(1)
-        rc = lib().pcg_ref_verify(*common, C.c_uint64(seed), C.c_uint64(offset), *outs,
+        rc = lib().pcg_ref_verify_w(*common, C.c_uint64(seed), C.c_uint64(offset), *outs,
                                   C.c_int32(nthreads), C.byref(used))
         res.threads = used.value
     _check(rc, "verify")
@@ -296,8 +328,8 @@ def thin_trial(g: Groups, rev, q: np.ndarray, p: Optional[np.ndarray], u_y: floa
     q = np.ascontiguousarray(q, dtype=np.float64)
     pp = None if p is None else np.ascontiguousarray(p, dtype=np.float64)
     out = _Trial()
-    _check(lib().pcg_ref_thin_trial(C.c_int32(g.V), C.c_int32(g.G), _p(g.row_ptr), _p(g.members),
-                                    _p(g.mult), _p(tok_ptr), _p(tok_groups), _p(q), _p(pp),
+    _check(lib().pcg_ref_thin_trial_w(C.c_int32(g.V), C.c_int32(g.G), _p(g.row_ptr), _p(g.members),
+                                    _p(g.mult), _wt(g), _p(tok_ptr), _p(tok_groups), _p(q), _p(pp),
                                     C.c_double(u_y), C.c_uint32(k24), C.c_double(u_a),
                                     C.c_double(u_tok), C.byref(out)), "thin_trial")
     return out
@@ -332,8 +364,8 @@ def verify_thinning(g: Groups, rev, target_logits, draft_logits, prop_tokens, pr
     res = ThinningResult(np.empty(B, np.int32), np.empty((B, K + 1), np.int32),
                          np.empty((B, K + 1), np.int32), np.empty(B, np.int32),
                          np.zeros(B, np.uint8), np.zeros((B, K), np.uint8))
-    _check(lib().pcg_ref_verify_thinning(
-        C.c_int32(g.V), C.c_int32(g.G), _p(g.row_ptr), _p(g.members), _p(g.mult), _p(tok_ptr),
+    _check(lib().pcg_ref_verify_thinning_w(
+        C.c_int32(g.V), C.c_int32(g.G), _p(g.row_ptr), _p(g.members), _p(g.mult), _wt(g), _p(tok_ptr),
         _p(tok_groups), _p(tgt), _p(dft), C.c_int(dt), C.c_int32(B), C.c_int32(K), tbs, tps, dbs,
         dps, C.c_double(temperature), _p(ptok), _p(pgrp), C.c_uint64(seed), C.c_uint64(offset),
         _p(res.accept_len), _p(res.out_tokens), _p(res.out_groups), _p(res.trials), _p(res.flags),
@@ -370,15 +402,15 @@ def propose(g: Groups, rev, draft_logits, *, temperature: float = 1.0, seed: int
     tok_ptr, tok_groups = rev
     dbs, dps = _strides(dft, dft_batch_stride, None)
     res = Proposals(np.empty((B, K), np.int32), np.empty((B, K), np.int32), np.zeros((B, K), np.uint8))
-    common = (C.c_int32(g.V), C.c_int32(g.G), _p(g.mult), _p(tok_ptr), _p(tok_groups), _p(dft),
+    common = (C.c_int32(g.V), C.c_int32(g.G), _p(g.mult), _wt(g), _p(tok_ptr), _p(tok_groups), _p(dft),
               C.c_int(dt), C.c_int32(B), C.c_int32(K))
     if u_x is not None:
         ux = np.ascontiguousarray(u_x, dtype=np.float64).reshape(B, K)
         kk = np.ascontiguousarray(k24, dtype=np.uint32).reshape(B, K)
-        _check(lib().pcg_ref_propose_u(*common, dbs, dps, C.c_double(temperature), _p(ux), _p(kk),
+        _check(lib().pcg_ref_propose_u_w(*common, dbs, dps, C.c_double(temperature), _p(ux), _p(kk),
                                        _p(res.tokens), _p(res.groups), _p(res.near)), "propose_u")
     else:
-        _check(lib().pcg_ref_propose(*common, C.c_int32(pos0), dbs, dps, C.c_double(temperature),
+        _check(lib().pcg_ref_propose_w(*common, C.c_int32(pos0), dbs, dps, C.c_double(temperature),
                                      C.c_uint64(seed), C.c_uint64(offset), _p(res.tokens),
                                      _p(res.groups), _p(res.near), C.c_int32(nthreads)), "propose")
     return res

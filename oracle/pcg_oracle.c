@@ -157,19 +157,53 @@ int pcg_ref_validate(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t
 
 /* Eq. (5): the probability a row gives to group g when every token's mass is
  * split equally over the mult[t] groups that hold it. */
+/* prob(t) * w_{k,t} for CSR entry j (token t = members[j]): the caller's weight of
+ * that entry (Eq. 2) if weights are given, else the equal split prob(t) / N(t) (Eq. 3). */
+static double entry_mass(const double *prob, const int32_t *members, const int32_t *mult,
+                         const float *weights, int32_t j) {
+  int32_t t = members[j];
+  return weights ? prob[t] * (double)weights[j] : prob[t] / (double)mult[t];
+}
+
 static double group_prob(const double *prob, const int32_t *row_ptr, const int32_t *members,
-                         const int32_t *mult, int32_t g) {
+                         const int32_t *mult, const float *weights, int32_t g) {
   double s = 0.0;
-  for (int32_t j = row_ptr[g]; j < row_ptr[g + 1]; ++j) {
-    int32_t t = members[j];
-    s += prob[t] / (double)mult[t];
-  }
+  for (int32_t j = row_ptr[g]; j < row_ptr[g + 1]; ++j)
+    s += entry_mass(prob, members, mult, weights, j);
   return s;
+}
+
+static const float *entry_weights(const pcg_ref_weights *wt) { return wt ? wt->weights : NULL; }
+
+int pcg_ref_validate_weights(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members,
+                             const float *weights, double tol) {
+  if (V < 1 || G < 1 || !row_ptr || !members || !weights) return PCG_REF_ERR_ARG;
+  if (!csr_shape_ok(V, G, row_ptr, members)) return PCG_REF_ERR_CSR;
+  double *sum = (double *)calloc((size_t)V, sizeof(double));
+  if (!sum) return PCG_REF_ERR_NOMEM;
+  int rc = PCG_REF_OK;
+  for (int32_t j = 0; j < row_ptr[G]; ++j) {
+    double w = (double)weights[j];
+    if (!(w >= 0.0) || w > 1.0 + tol) rc = PCG_REF_ERR_CSR;
+    sum[members[j]] += w;
+  }
+  for (int32_t v = 0; v < V; ++v)
+    if (fabs(sum[v] - 1.0) > tol) rc = PCG_REF_ERR_CSR;
+  free(sum);
+  return rc;
 }
 
 int pcg_ref_group_probs(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members,
                         const int32_t *mult, const void *logits, int dtype, int64_t rows,
                         int64_t row_stride, double temperature, double *out) {
+  return pcg_ref_group_probs_w(V, G, row_ptr, members, mult, NULL, logits, dtype, rows, row_stride,
+                               temperature, out);
+}
+
+int pcg_ref_group_probs_w(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members,
+                          const int32_t *mult, const pcg_ref_weights *wt, const void *logits,
+                          int dtype, int64_t rows, int64_t row_stride, double temperature,
+                          double *out) {
   if (!row_ptr || !members || !mult || !logits || !out) return PCG_REF_ERR_ARG;
   if (V < 1 || G < 1 || rows < 0 || !(temperature > 0.0)) return PCG_REF_ERR_ARG;
   if (dtype != PCG_REF_F32 && dtype != PCG_REF_BF16) return PCG_REF_ERR_ARG;
@@ -181,7 +215,7 @@ int pcg_ref_group_probs(int32_t V, int32_t G, const int32_t *row_ptr, const int3
     rc = softmax_row_at(logits, dtype, r * row_stride, V, temperature, prob);
     if (rc) break;
     for (int32_t g = 0; g < G; ++g)
-      out[r * (int64_t)G + g] = group_prob(prob, row_ptr, members, mult, g);
+      out[r * (int64_t)G + g] = group_prob(prob, row_ptr, members, mult, entry_weights(wt), g);
   }
   free(prob);
   return rc;
@@ -194,6 +228,7 @@ int pcg_ref_group_probs(int32_t V, int32_t G, const int32_t *row_ptr, const int3
 typedef struct {
   int32_t V, G;
   const int32_t *row_ptr, *members, *mult;
+  const float *weights;
   const void *tgt, *dft;
   int dtype;
   int32_t B, K;
@@ -234,8 +269,8 @@ static int verify_sequence(const step_args *a, int32_t b, double *q, double *p, 
     if (rc) return rc;
     int32_t g = a->prop_groups[(int64_t)b * K + i];
     if (g < 0 || g >= G) return PCG_REF_ERR_ARG;
-    double Tprop = group_prob(q, a->row_ptr, a->members, a->mult, g);
-    double Dprop = group_prob(p, a->row_ptr, a->members, a->mult, g);
+    double Tprop = group_prob(q, a->row_ptr, a->members, a->mult, a->weights, g);
+    double Dprop = group_prob(p, a->row_ptr, a->members, a->mult, a->weights, g);
     double u = a->u_acc[(int64_t)b * K + i];
     /* Eq. (7): accept iff u < min(1, T/D), written without the division so
      * that D == 0 is defined: T > 0 accepts, T == 0 rejects. */
@@ -259,9 +294,9 @@ static int verify_sequence(const step_args *a, int32_t b, double *q, double *p, 
     rc = softmax_row_at(a->tgt, a->dtype, b * a->tbs + i * a->tps, a->V, a->temperature, q);
     if (rc) return rc;
   }
-  for (int32_t g = 0; g < G; ++g) Tg[g] = group_prob(q, a->row_ptr, a->members, a->mult, g);
+  for (int32_t g = 0; g < G; ++g) Tg[g] = group_prob(q, a->row_ptr, a->members, a->mult, a->weights, g);
   if (i < K) {
-    for (int32_t g = 0; g < G; ++g) Dg[g] = group_prob(p, a->row_ptr, a->members, a->mult, g);
+    for (int32_t g = 0; g < G; ++g) Dg[g] = group_prob(p, a->row_ptr, a->members, a->mult, a->weights, g);
     for (int32_t g = 0; g < G; ++g) R[g] = Tg[g] > Dg[g] ? Tg[g] - Dg[g] : 0.0; /* Eq. (8) */
   } else {
     for (int32_t g = 0; g < G; ++g) R[g] = Tg[g]; /* bonus: nothing was proposed here */
@@ -304,17 +339,17 @@ static int verify_sequence(const step_args *a, int32_t b, double *q, double *p, 
       for (int32_t g = 0; g < G; ++g) tr->R_norm[(int64_t)b * G + g] = R[g] / S;
   }
 
-  /* Eq. (10): token inside the emitted group, proportional to q(t)/mult[t]
-   * over the group's members in CSR order. */
+  /* Eq. (10): token inside the emitted group, proportional to q(t) w_{g,t}
+   * (q(t)/mult[t] under the equal split) over the group's members in CSR order. */
   int32_t beg = a->row_ptr[gs], end = a->row_ptr[gs + 1];
   double C = 0.0;
-  for (int32_t j = beg; j < end; ++j) C += q[a->members[j]] / (double)a->mult[a->members[j]];
+  for (int32_t j = beg; j < end; ++j) C += entry_mass(q, a->members, a->mult, a->weights, j);
   double ut = a->u_tok[(int64_t)b * (K + 1) + i];
   double tgoal = ut * C;
   double tc = 0.0, tlo = 0.0, thi = 0.0;
   int32_t js = -1, jlast = -1;
   for (int32_t j = beg; j < end; ++j) {
-    double c = q[a->members[j]] / (double)a->mult[a->members[j]];
+    double c = entry_mass(q, a->members, a->mult, a->weights, j);
     if (c > 0.0) jlast = j;
     double nxt = tc + c;
     if (js < 0 && nxt > tgoal) { js = j; tlo = tc; thi = nxt; }
@@ -339,6 +374,20 @@ int pcg_ref_verify_u(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t
                      const double *u_acc, const double *u_grp, const double *u_tok,
                      int32_t *accept_len, int32_t *out_tokens, int32_t *out_groups,
                      const pcg_ref_trace *trace, int32_t nthreads) {
+  return pcg_ref_verify_u_w(V, G, row_ptr, members, mult, NULL, target_logits, draft_logits, dtype,
+                            B, K, tgt_batch_stride, tgt_pos_stride, dft_batch_stride,
+                            dft_pos_stride, temperature, prop_tokens, prop_groups, u_acc, u_grp,
+                            u_tok, accept_len, out_tokens, out_groups, trace, nthreads);
+}
+
+int pcg_ref_verify_u_w(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members,
+                       const int32_t *mult, const pcg_ref_weights *wt, const void *target_logits,
+                       const void *draft_logits, int dtype, int32_t B, int32_t K,
+                       int64_t tgt_batch_stride, int64_t tgt_pos_stride, int64_t dft_batch_stride,
+                       int64_t dft_pos_stride, double temperature, const int32_t *prop_tokens,
+                       const int32_t *prop_groups, const double *u_acc, const double *u_grp,
+                       const double *u_tok, int32_t *accept_len, int32_t *out_tokens,
+                       int32_t *out_groups, const pcg_ref_trace *trace, int32_t nthreads) {
   if (!row_ptr || !members || !mult || !target_logits || !draft_logits || !prop_tokens ||
       !prop_groups || !u_acc || !u_grp || !u_tok || !accept_len || !out_tokens || !out_groups)
     return PCG_REF_ERR_ARG;
@@ -349,6 +398,7 @@ int pcg_ref_verify_u(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t
 
   step_args a;
   a.V = V; a.G = G; a.row_ptr = row_ptr; a.members = members; a.mult = mult;
+  a.weights = entry_weights(wt);
   a.tgt = target_logits; a.dft = draft_logits; a.dtype = dtype; a.B = B; a.K = K;
   a.tbs = tgt_batch_stride; a.tps = tgt_pos_stride; a.dbs = dft_batch_stride;
   a.dps = dft_pos_stride; a.temperature = temperature;
@@ -399,6 +449,20 @@ int pcg_ref_verify(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *
                    uint64_t seed, uint64_t offset, int32_t *accept_len, int32_t *out_tokens,
                    int32_t *out_groups, const pcg_ref_trace *trace, int32_t nthreads,
                    int32_t *threads_used) {
+  return pcg_ref_verify_w(V, G, row_ptr, members, mult, NULL, target_logits, draft_logits, dtype, B,
+                          K, tgt_batch_stride, tgt_pos_stride, dft_batch_stride, dft_pos_stride,
+                          temperature, prop_tokens, prop_groups, seed, offset, accept_len,
+                          out_tokens, out_groups, trace, nthreads, threads_used);
+}
+
+int pcg_ref_verify_w(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members,
+                     const int32_t *mult, const pcg_ref_weights *wt, const void *target_logits,
+                     const void *draft_logits, int dtype, int32_t B, int32_t K,
+                     int64_t tgt_batch_stride, int64_t tgt_pos_stride, int64_t dft_batch_stride,
+                     int64_t dft_pos_stride, double temperature, const int32_t *prop_tokens,
+                     const int32_t *prop_groups, uint64_t seed, uint64_t offset,
+                     int32_t *accept_len, int32_t *out_tokens, int32_t *out_groups,
+                     const pcg_ref_trace *trace, int32_t nthreads, int32_t *threads_used) {
   if (B < 0 || K < 1) return PCG_REF_ERR_ARG;
   size_t nacc = (size_t)B * (size_t)K, nres = (size_t)B * ((size_t)K + 1);
   double *u = (double *)malloc((nacc + 2 * nres + 1) * sizeof(double));
@@ -418,10 +482,10 @@ int pcg_ref_verify(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *
   nthreads = 1;
 #endif
   if (threads_used) *threads_used = nthreads;
-  int rc = pcg_ref_verify_u(V, G, row_ptr, members, mult, target_logits, draft_logits, dtype, B,
-                            K, tgt_batch_stride, tgt_pos_stride, dft_batch_stride,
-                            dft_pos_stride, temperature, prop_tokens, prop_groups, u_acc, u_grp,
-                            u_tok, accept_len, out_tokens, out_groups, trace, nthreads);
+  int rc = pcg_ref_verify_u_w(V, G, row_ptr, members, mult, wt, target_logits, draft_logits, dtype,
+                              B, K, tgt_batch_stride, tgt_pos_stride, dft_batch_stride,
+                              dft_pos_stride, temperature, prop_tokens, prop_groups, u_acc, u_grp,
+                              u_tok, accept_len, out_tokens, out_groups, trace, nthreads);
   free(u);
   return rc;
 }
@@ -445,6 +509,20 @@ int pcg_ref_reverse_index(int32_t V, int32_t G, const int32_t *row_ptr, const in
       tok_groups[tok_ptr[t] + fill[t]++] = g;
     }
   free(fill);
+  return PCG_REF_OK;
+}
+
+int pcg_ref_reverse_weights(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members,
+                            const float *weights, float *tok_weights) {
+  if (V < 1 || G < 1 || !row_ptr || !members || !weights || !tok_weights) return PCG_REF_ERR_ARG;
+  if (!csr_shape_ok(V, G, row_ptr, members)) return PCG_REF_ERR_CSR;
+  int32_t *at = (int32_t *)calloc((size_t)V + 1, sizeof(int32_t));
+  if (!at) return PCG_REF_ERR_NOMEM;
+  for (int32_t j = 0; j < row_ptr[G]; ++j) at[members[j] + 1] += 1;
+  for (int32_t v = 0; v < V; ++v) at[v + 1] += at[v];
+  /* same visiting order as pcg_ref_reverse_index: ascending CSR entry position */
+  for (int32_t j = 0; j < row_ptr[G]; ++j) tok_weights[at[members[j]]++] = weights[j];
+  free(at);
   return PCG_REF_OK;
 }
 
@@ -485,24 +563,54 @@ static int64_t inverse_cdf(const double *w, int64_t n, double u, int *near) {
   return pick;
 }
 
+/* Which of the n = N(x) membership entries of token x the 24-bit draw k24 picks
+ * (K ~ w_{k,x} over k in S(x), Eq. 6): under the equal split entry (k24 * n) >> 24;
+ * with general weights the inverse CDF of the token's weights (reverse-index
+ * order) at u = k24 / 2^24.  Returns the offset inside the token's entries, < 0 on
+ * error; *near as for inverse_cdf (always 0 under the equal split). */
+static int32_t pick_entry(const int32_t *tok_ptr, const float *tok_weights, int64_t x, uint32_t k24,
+                          int *near) {
+  int32_t n = tok_ptr[x + 1] - tok_ptr[x];
+  *near = 0;
+  if (n < 1) return -1;
+  if (!tok_weights) return (int32_t)(((uint64_t)k24 * (uint64_t)n) >> 24);
+  double *w = (double *)malloc((size_t)n * sizeof(double));
+  if (!w) return -1;
+  for (int32_t e = 0; e < n; ++e) w[e] = (double)tok_weights[tok_ptr[x] + e];
+  int64_t e = inverse_cdf(w, n, (double)k24 / 16777216.0, near);
+  free(w);
+  return (int32_t)e;
+}
+
 int pcg_ref_thin_trial(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members,
                        const int32_t *mult, const int32_t *tok_ptr, const int32_t *tok_groups,
                        const double *q, const double *p, double u_y, uint32_t k24, double u_a,
                        double u_tok, pcg_ref_trial *out) {
+  return pcg_ref_thin_trial_w(V, G, row_ptr, members, mult, NULL, tok_ptr, tok_groups, q, p, u_y,
+                              k24, u_a, u_tok, out);
+}
+
+int pcg_ref_thin_trial_w(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members,
+                         const int32_t *mult, const pcg_ref_weights *wt, const int32_t *tok_ptr,
+                         const int32_t *tok_groups, const double *q, const double *p, double u_y,
+                         uint32_t k24, double u_a, double u_tok, pcg_ref_trial *out) {
   if (!row_ptr || !members || !mult || !tok_ptr || !tok_groups || !q || !out || V < 1 || G < 1)
     return PCG_REF_ERR_ARG;
+  if (wt && (wt->weights == NULL) != (wt->tok_weights == NULL)) return PCG_REF_ERR_ARG;
+  const float *weights = entry_weights(wt);
   int near = 0;
   out->near = 0;
   /* y ~ q */
   int64_t y = inverse_cdf(q, V, u_y, &near);
   if (y < 0) return PCG_REF_ERR_ROW;
   if (near) out->near |= 1;
-  /* K ~ w_{.,y}: one of the N(y) membership entries of y, equally likely */
-  int32_t n = tok_ptr[y + 1] - tok_ptr[y];
-  if (n < 1) return PCG_REF_ERR_CSR;
-  int32_t g = tok_groups[tok_ptr[y] + (int32_t)(((uint64_t)k24 * (uint64_t)n) >> 24)];
-  double T = group_prob(q, row_ptr, members, mult, g);
-  double D = p ? group_prob(p, row_ptr, members, mult, g) : 0.0;
+  /* K ~ w_{.,y}: one of the N(y) membership entries of y, by the weights */
+  int32_t e = pick_entry(tok_ptr, wt ? wt->tok_weights : NULL, y, k24, &near);
+  if (e < 0) return PCG_REF_ERR_CSR;
+  if (near) out->near |= 1;
+  int32_t g = tok_groups[tok_ptr[y] + e];
+  double T = group_prob(q, row_ptr, members, mult, weights, g);
+  double D = p ? group_prob(p, row_ptr, members, mult, weights, g) : 0.0;
   /* accept with probability [1 - D/T]_+, written without the division */
   int accepted = p ? (u_a * T < T - D) : 1;
   if (p && fabs(u_a * T - (T - D)) < PCG_REF_NEAR_TIE * T) out->near |= 2;
@@ -510,7 +618,7 @@ int pcg_ref_thin_trial(int32_t V, int32_t G, const int32_t *row_ptr, const int32
   int32_t beg = row_ptr[g], len = row_ptr[g + 1] - beg;
   double *c = (double *)malloc((size_t)(len > 0 ? len : 1) * sizeof(double));
   if (!c) return PCG_REF_ERR_NOMEM;
-  for (int32_t j = 0; j < len; ++j) c[j] = q[members[beg + j]] / (double)mult[members[beg + j]];
+  for (int32_t j = 0; j < len; ++j) c[j] = entry_mass(q, members, mult, weights, beg + j);
   int64_t js = inverse_cdf(c, len, u_tok, &near);
   free(c);
   if (near) out->near |= 4;
@@ -533,6 +641,26 @@ int pcg_ref_verify_thinning(int32_t V, int32_t G, const int32_t *row_ptr, const 
                             uint64_t offset, int32_t *accept_len, int32_t *out_tokens,
                             int32_t *out_groups, int32_t *trials, uint8_t *flags,
                             uint8_t *near_acc, int32_t max_trials, int32_t nthreads) {
+  return pcg_ref_verify_thinning_w(V, G, row_ptr, members, mult, NULL, tok_ptr, tok_groups,
+                                   target_logits, draft_logits, dtype, B, K, tgt_batch_stride,
+                                   tgt_pos_stride, dft_batch_stride, dft_pos_stride, temperature,
+                                   prop_tokens, prop_groups, seed, offset, accept_len, out_tokens,
+                                   out_groups, trials, flags, near_acc, max_trials, nthreads);
+}
+
+int pcg_ref_verify_thinning_w(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members,
+                              const int32_t *mult, const pcg_ref_weights *wt,
+                              const int32_t *tok_ptr, const int32_t *tok_groups,
+                              const void *target_logits, const void *draft_logits, int dtype,
+                              int32_t B, int32_t K, int64_t tgt_batch_stride,
+                              int64_t tgt_pos_stride, int64_t dft_batch_stride,
+                              int64_t dft_pos_stride, double temperature,
+                              const int32_t *prop_tokens, const int32_t *prop_groups,
+                              uint64_t seed, uint64_t offset, int32_t *accept_len,
+                              int32_t *out_tokens, int32_t *out_groups, int32_t *trials,
+                              uint8_t *flags, uint8_t *near_acc, int32_t max_trials,
+                              int32_t nthreads) {
+  const float *weights = entry_weights(wt);
   if (!row_ptr || !members || !mult || !tok_ptr || !tok_groups || !target_logits ||
       !draft_logits || !prop_tokens || !prop_groups || !accept_len || !out_tokens ||
       !out_groups || !trials || !flags)
@@ -580,8 +708,8 @@ int pcg_ref_verify_thinning(int32_t V, int32_t G, const int32_t *row_ptr, const 
         if (r) break;
         int32_t g = prop_groups[(int64_t)b * K + i];
         if (g < 0 || g >= G) { r = PCG_REF_ERR_ARG; break; }
-        double Tp = group_prob(q, row_ptr, members, mult, g);
-        double Dp = group_prob(p, row_ptr, members, mult, g);
+        double Tp = group_prob(q, row_ptr, members, mult, weights, g);
+        double Dp = group_prob(p, row_ptr, members, mult, weights, g);
         double ua;
         pcg_ref_uniforms(seed, offset, (uint32_t)b, (uint32_t)i, &ua, NULL, NULL);
         if (near_acc) near_acc[(int64_t)b * K + i] = fabs(ua * Dp - Tp) < PCG_REF_NEAR_TIE * Dp;
@@ -602,8 +730,8 @@ int pcg_ref_verify_thinning(int32_t V, int32_t G, const int32_t *row_ptr, const 
                              temperature, q);
           if (r == PCG_REF_OK) {
             pcg_ref_trial_uniforms(seed, offset, (uint32_t)b, (uint32_t)i, 0, &uy, &k24, &uacc, &ut);
-            r = pcg_ref_thin_trial(V, G, row_ptr, members, mult, tok_ptr, tok_groups, q, NULL, uy,
-                                   k24, uacc, ut, &tr);
+            r = pcg_ref_thin_trial_w(V, G, row_ptr, members, mult, wt, tok_ptr, tok_groups, q, NULL,
+                                     uy, k24, uacc, ut, &tr);
             if (r == PCG_REF_OK) {
               otok[i] = tr.y;
               ogrp[i] = tr.group;
@@ -614,8 +742,8 @@ int pcg_ref_verify_thinning(int32_t V, int32_t G, const int32_t *row_ptr, const 
           for (int32_t t = 0; r == PCG_REF_OK; ++t) {
             pcg_ref_trial_uniforms(seed, offset, (uint32_t)b, (uint32_t)i, (uint32_t)t, &uy, &k24,
                                    &uacc, &ut);
-            r = pcg_ref_thin_trial(V, G, row_ptr, members, mult, tok_ptr, tok_groups, q, p, uy,
-                                   k24, uacc, ut, &tr);
+            r = pcg_ref_thin_trial_w(V, G, row_ptr, members, mult, wt, tok_ptr, tok_groups, q, p,
+                                     uy, k24, uacc, ut, &tr);
             if (r) break;
             trials[b] = t + 1;
             if (tr.near & 3) flags[b] |= 1;
@@ -655,8 +783,9 @@ void pcg_ref_propose_uniforms(uint64_t seed, uint64_t offset, uint32_t b, uint32
   if (k24) *k24 = w[1] >> 8;
 }
 
-static int propose_one(int32_t V, int32_t G, const int32_t *mult, const int32_t *tok_ptr,
-                       const int32_t *tok_groups, const void *draft_logits, int dtype,
+static int propose_one(int32_t V, int32_t G, const int32_t *mult, const float *tok_weights,
+                       const int32_t *tok_ptr, const int32_t *tok_groups, const void *draft_logits,
+                       int dtype,
                        int64_t first, double temperature, double u_x, uint32_t k24, double *p,
                        int32_t *token, int32_t *group, uint8_t *near) {
   int r = softmax_row_at(draft_logits, dtype, first, V, temperature, p);
@@ -666,7 +795,11 @@ static int propose_one(int32_t V, int32_t G, const int32_t *mult, const int32_t 
   if (x < 0) return PCG_REF_ERR_ROW;
   int32_t n = tok_ptr[x + 1] - tok_ptr[x];          /* N(x) membership entries */
   if (n < 1 || n != mult[x]) return PCG_REF_ERR_CSR;
-  int32_t g = tok_groups[tok_ptr[x] + (int32_t)(((uint64_t)k24 * (uint64_t)n) >> 24)];
+  int ne = 0;
+  int32_t e = pick_entry(tok_ptr, tok_weights, x, k24, &ne);
+  if (e < 0) return PCG_REF_ERR_CSR;
+  nr |= ne;
+  int32_t g = tok_groups[tok_ptr[x] + e];
   if (g < 0 || g >= G) return PCG_REF_ERR_CSR;
   *token = (int32_t)x;
   *group = g;
@@ -674,8 +807,8 @@ static int propose_one(int32_t V, int32_t G, const int32_t *mult, const int32_t 
   return PCG_REF_OK;
 }
 
-static int propose_impl(int32_t V, int32_t G, const int32_t *mult, const int32_t *tok_ptr,
-                        const int32_t *tok_groups, const void *draft_logits, int dtype, int32_t B,
+static int propose_impl(int32_t V, int32_t G, const int32_t *mult, const float *tok_weights,
+                        const int32_t *tok_ptr, const int32_t *tok_groups, const void *draft_logits, int dtype, int32_t B,
                         int32_t K, int32_t pos0, int64_t dft_batch_stride, int64_t dft_pos_stride,
                         double temperature, const double *u_x, const uint32_t *k24, uint64_t seed,
                         uint64_t offset, int32_t *prop_tokens, int32_t *prop_groups, uint8_t *near,
@@ -710,7 +843,7 @@ static int propose_impl(int32_t V, int32_t G, const int32_t *mult, const int32_t
       uint32_t kk;
       if (u_x) { ux = u_x[bi]; kk = k24[bi]; }
       else pcg_ref_propose_uniforms(seed, offset, (uint32_t)b, (uint32_t)(pos0 + i), &ux, &kk);
-      int r = propose_one(V, G, mult, tok_ptr, tok_groups, draft_logits, dtype,
+      int r = propose_one(V, G, mult, tok_weights, tok_ptr, tok_groups, draft_logits, dtype,
                           b * dft_batch_stride + i * dft_pos_stride, temperature, ux, kk, p,
                           prop_tokens + bi, prop_groups + bi, near ? near + bi : NULL);
       if (r) {
@@ -730,8 +863,20 @@ int pcg_ref_propose_u(int32_t V, int32_t G, const int32_t *mult, const int32_t *
                       int32_t K, int64_t dft_batch_stride, int64_t dft_pos_stride,
                       double temperature, const double *u_x, const uint32_t *k24,
                       int32_t *prop_tokens, int32_t *prop_groups, uint8_t *near) {
+  return pcg_ref_propose_u_w(V, G, mult, NULL, tok_ptr, tok_groups, draft_logits, dtype, B, K,
+                             dft_batch_stride, dft_pos_stride, temperature, u_x, k24, prop_tokens,
+                             prop_groups, near);
+}
+
+int pcg_ref_propose_u_w(int32_t V, int32_t G, const int32_t *mult, const pcg_ref_weights *wt,
+                        const int32_t *tok_ptr, const int32_t *tok_groups,
+                        const void *draft_logits, int dtype, int32_t B, int32_t K,
+                        int64_t dft_batch_stride, int64_t dft_pos_stride, double temperature,
+                        const double *u_x, const uint32_t *k24, int32_t *prop_tokens,
+                        int32_t *prop_groups, uint8_t *near) {
   if (!u_x || !k24) return PCG_REF_ERR_ARG;
-  return propose_impl(V, G, mult, tok_ptr, tok_groups, draft_logits, dtype, B, K, 0,
+  return propose_impl(V, G, mult, wt ? wt->tok_weights : NULL, tok_ptr, tok_groups, draft_logits,
+                      dtype, B, K, 0,
                       dft_batch_stride, dft_pos_stride, temperature, u_x, k24, 0, 0, prop_tokens,
                       prop_groups, near, 1);
 }
@@ -741,7 +886,19 @@ int pcg_ref_propose(int32_t V, int32_t G, const int32_t *mult, const int32_t *to
                     int32_t K, int32_t pos0, int64_t dft_batch_stride, int64_t dft_pos_stride,
                     double temperature, uint64_t seed, uint64_t offset, int32_t *prop_tokens,
                     int32_t *prop_groups, uint8_t *near, int32_t nthreads) {
-  return propose_impl(V, G, mult, tok_ptr, tok_groups, draft_logits, dtype, B, K, pos0,
+  return pcg_ref_propose_w(V, G, mult, NULL, tok_ptr, tok_groups, draft_logits, dtype, B, K, pos0,
+                           dft_batch_stride, dft_pos_stride, temperature, seed, offset, prop_tokens,
+                           prop_groups, near, nthreads);
+}
+
+int pcg_ref_propose_w(int32_t V, int32_t G, const int32_t *mult, const pcg_ref_weights *wt,
+                      const int32_t *tok_ptr, const int32_t *tok_groups, const void *draft_logits,
+                      int dtype, int32_t B, int32_t K, int32_t pos0, int64_t dft_batch_stride,
+                      int64_t dft_pos_stride, double temperature, uint64_t seed, uint64_t offset,
+                      int32_t *prop_tokens, int32_t *prop_groups, uint8_t *near,
+                      int32_t nthreads) {
+  return propose_impl(V, G, mult, wt ? wt->tok_weights : NULL, tok_ptr, tok_groups, draft_logits,
+                      dtype, B, K, pos0,
                       dft_batch_stride, dft_pos_stride, temperature, NULL, NULL, seed, offset,
                       prop_tokens, prop_groups, near, nthreads);
 }

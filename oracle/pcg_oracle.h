@@ -182,6 +182,72 @@ int pcg_ref_verify_thinning(int32_t V, int32_t G, const int32_t *row_ptr, const 
                             uint8_t *near_acc, int32_t max_trials, int32_t nthreads);
 
 /* ------------------------------------------------------------------------- */
+/* General weights (Sec. 2.2, Eq. 2 and Eq. 4): any non-negative w_{k,t} with    */
+/* sum over the groups holding t equal to 1, one per CSR entry, instead of the  */
+/* equal split 1/N(t).  T[k] = sum_j q(t_j) w_j, Eq. (10) becomes q(t) w_{k,t}  */
+/* / T[k], and the group label of a token is drawn by its weights.  The _w      */
+/* entry points below are the functions above with this extra argument (NULL =  */
+/* equal split, which is exactly what the plain names compute).                 */
+/* ------------------------------------------------------------------------- */
+
+typedef struct {
+  const float *weights;     /* [nnz] w of each CSR entry (fp32, read exactly)          */
+  const float *tok_weights; /* [nnz] the same weights in reverse-index order; needed by */
+                            /* thinning and proposals only                              */
+} pcg_ref_weights;
+
+/* 0 iff every weight is in [0, 1 + tol] and the weights of each token sum to 1 within tol. */
+int pcg_ref_validate_weights(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members,
+                             const float *weights, double tol);
+
+/* tok_weights [nnz]: weights permuted into the order of pcg_ref_reverse_index. */
+int pcg_ref_reverse_weights(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members,
+                            const float *weights, float *tok_weights);
+
+int pcg_ref_group_probs_w(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members,
+                          const int32_t *mult, const pcg_ref_weights *wt, const void *logits,
+                          int dtype, int64_t rows, int64_t row_stride, double temperature,
+                          double *out);
+
+int pcg_ref_verify_u_w(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members,
+                       const int32_t *mult, const pcg_ref_weights *wt, const void *target_logits,
+                       const void *draft_logits, int dtype, int32_t B, int32_t K,
+                       int64_t tgt_batch_stride, int64_t tgt_pos_stride, int64_t dft_batch_stride,
+                       int64_t dft_pos_stride, double temperature, const int32_t *prop_tokens,
+                       const int32_t *prop_groups, const double *u_acc, const double *u_grp,
+                       const double *u_tok, int32_t *accept_len, int32_t *out_tokens,
+                       int32_t *out_groups, const pcg_ref_trace *trace, int32_t nthreads);
+
+int pcg_ref_verify_w(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members,
+                     const int32_t *mult, const pcg_ref_weights *wt, const void *target_logits,
+                     const void *draft_logits, int dtype, int32_t B, int32_t K,
+                     int64_t tgt_batch_stride, int64_t tgt_pos_stride, int64_t dft_batch_stride,
+                     int64_t dft_pos_stride, double temperature, const int32_t *prop_tokens,
+                     const int32_t *prop_groups, uint64_t seed, uint64_t offset,
+                     int32_t *accept_len, int32_t *out_tokens, int32_t *out_groups,
+                     const pcg_ref_trace *trace, int32_t nthreads, int32_t *threads_used);
+
+/* The membership entry of y is drawn by the inverse CDF of y's weights (reverse-index order)
+ * at u = k24 / 2^24; near bit0 also covers that draw. */
+int pcg_ref_thin_trial_w(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members,
+                         const int32_t *mult, const pcg_ref_weights *wt, const int32_t *tok_ptr,
+                         const int32_t *tok_groups, const double *q, const double *p, double u_y,
+                         uint32_t k24, double u_a, double u_tok, pcg_ref_trial *out);
+
+int pcg_ref_verify_thinning_w(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members,
+                              const int32_t *mult, const pcg_ref_weights *wt,
+                              const int32_t *tok_ptr, const int32_t *tok_groups,
+                              const void *target_logits, const void *draft_logits, int dtype,
+                              int32_t B, int32_t K, int64_t tgt_batch_stride,
+                              int64_t tgt_pos_stride, int64_t dft_batch_stride,
+                              int64_t dft_pos_stride, double temperature,
+                              const int32_t *prop_tokens, const int32_t *prop_groups,
+                              uint64_t seed, uint64_t offset, int32_t *accept_len,
+                              int32_t *out_tokens, int32_t *out_groups, int32_t *trials,
+                              uint8_t *flags, uint8_t *near_acc, int32_t max_trials,
+                              int32_t nthreads);
+
+/* ------------------------------------------------------------------------- */
 /* Draft-side proposal coupling (Sec. 2.2 "Proposal coupling and acceptance",  */
 /* Eq. 6; Algorithm 1, the two sampling steps at the top of the loop): a token */
 /* x ~ p_i, then a group label among the groups holding x by the weights       */
@@ -214,6 +280,21 @@ int pcg_ref_propose(int32_t V, int32_t G, const int32_t *mult, const int32_t *to
                     int32_t K, int32_t pos0, int64_t dft_batch_stride, int64_t dft_pos_stride,
                     double temperature, uint64_t seed, uint64_t offset, int32_t *prop_tokens,
                     int32_t *prop_groups, uint8_t *near, int32_t nthreads);
+
+/* Proposals with general weights: the group label by the inverse CDF of the token's weights
+ * at u = k24 / 2^24; near also covers that draw. */
+int pcg_ref_propose_u_w(int32_t V, int32_t G, const int32_t *mult, const pcg_ref_weights *wt,
+                        const int32_t *tok_ptr, const int32_t *tok_groups,
+                        const void *draft_logits, int dtype, int32_t B, int32_t K,
+                        int64_t dft_batch_stride, int64_t dft_pos_stride, double temperature,
+                        const double *u_x, const uint32_t *k24, int32_t *prop_tokens,
+                        int32_t *prop_groups, uint8_t *near);
+
+int pcg_ref_propose_w(int32_t V, int32_t G, const int32_t *mult, const pcg_ref_weights *wt,
+                      const int32_t *tok_ptr, const int32_t *tok_groups, const void *draft_logits,
+                      int dtype, int32_t B, int32_t K, int32_t pos0, int64_t dft_batch_stride,
+                      int64_t dft_pos_stride, double temperature, uint64_t seed, uint64_t offset,
+                      int32_t *prop_tokens, int32_t *prop_groups, uint8_t *near, int32_t nthreads);
 
 #ifdef __cplusplus
 }

@@ -79,7 +79,7 @@ def main():
     args = parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is single-GPU (the path shards over sequences with no "
-                 "exchange step; see DESIGN.md); run with --gpus 1")
+                 "exchange step between GPUs); run with --gpus 1")
     import numpy as np
     import torch
 

@@ -84,14 +84,26 @@ typedef struct {
   const void *prepared;
   const pcg_prepared *prepared_info;
   /* Optional reverse index token -> groups (the paper's S(t); see pcg_groups_reverse_host),
-   * DEVICE: tok_ptr [V+1], tok_groups [nnz].  Needed by pcg_verify_thinning only. */
+   * DEVICE: tok_ptr [V+1], tok_groups [nnz].  Needed by pcg_verify_thinning and pcg_propose. */
   const int32_t *tok_ptr;
   const int32_t *tok_groups;
+  /* Optional general weights w_{k,t} (Sec. 2.2, Eq. 2), DEVICE float [nnz]: weights[j] is the
+   * share of token members[j] that group k (the row holding entry j) receives; non-negative,
+   * and the weights of one token sum to 1 (see pcg_groups_validate_weights_host).  NULL = the
+   * equal split 1 / mult[t] (Eq. 3).  With weights the group probabilities are
+   * sum_j prob(members[j]) * weights[j] (Eq. 4), the token inside a group is drawn
+   * proportionally to prob(t) * w_{k,t} (Eq. 10) and a token's group label by its weights
+   * (Eq. 6).  The prepared form carries no weights: `prepared` must be NULL when weights are
+   * given, and the CSR is read directly.
+   * tok_weights: the same weights in reverse-index order (pcg_groups_reverse_weights_host),
+   * DEVICE float [nnz]; needed together with weights by pcg_verify_thinning and pcg_propose. */
+  const float *weights;
+  const float *tok_weights;
 } pcg_groups;
 
 /*
  * Prepared membership.  The groups are fixed once the similarity groups have been built
- * (Sec. 2.2: "precomputed once and cached"), so the gather-sum of Eq. (5) can read them
+ * (Sec. 2.2 "Complexity and memory": they are built ahead of time and kept), so the gather-sum of Eq. (5) can read them
  * from a layout made for the kernel instead of from the CSR:
  *   - the vocabulary is cut into `ntiles` tiles of `tile_len` tokens, each small enough for
  *     a table of one float per token to sit in a workgroup's LDS;
@@ -207,7 +219,8 @@ size_t pcg_verify_workspace_bytes(int32_t V, int32_t G, int32_t B, int32_t K);
  *   groups        must carry tok_ptr / tok_groups; the prepared form is not used
  *   draws         trial j of position (b, i) uses the Philox block with counter
  *                 (offset_lo, offset_hi, b, i | (j + 1) << 16): word 0 -> token uniform,
- *                 word 1 >> 8 = k24 -> membership entry (k24 * mult[y]) >> 24, word 2 -> accept
+ *                 word 1 >> 8 = k24 -> membership entry (k24 * mult[y]) >> 24 (with general
+ *                 weights: the inverse CDF of y's tok_weights at k24 / 2^24), word 2 -> accept
  *                 uniform, word 3 -> token-in-group uniform; the bonus position uses trial 0
  *   trials        DEVICE int32 [B]: trials run for the sequence (0 on the bonus position)
  *   diag          near_group counts token / accept draws within 1e-6 of their threshold on the
@@ -243,7 +256,8 @@ size_t pcg_verify_thinning_workspace_bytes(int32_t V, int32_t B, int32_t K);
  *   draws         position (b, i) uses the Philox block with counter
  *                 (offset_lo, offset_hi, b, (pos0 + i) | 0xFFFF0000), a block neither
  *                 pcg_verify nor any thinning trial reads: word 0 -> token uniform,
- *                 word 1 >> 8 = k24 -> membership entry (k24 * mult[x]) >> 24
+ *                 word 1 >> 8 = k24 -> membership entry (k24 * mult[x]) >> 24 (with general
+ *                 weights: the inverse CDF of x's tok_weights at k24 / 2^24)
  *   prop_tokens, prop_groups   DEVICE int32 [B, K], written
  *   diag          optional DEVICE counters: near_token counts token draws within 1e-6 of an
  *                 inner bin edge, sequences the rows processed
@@ -277,6 +291,18 @@ int pcg_groups_validate_host(int32_t V, int32_t G, const int32_t *row_ptr,
 int pcg_groups_canonicalize_host(int32_t V, int32_t G, const int32_t *row_ptr,
                                  const int32_t *members, int32_t *out_G, int64_t *out_nnz,
                                  int32_t *out_row_ptr, int32_t *out_members, int32_t *out_mult);
+
+/* PCG_OK iff weights (HOST, [nnz]) are usable for the membership: every weight finite and in
+ * [0, 1 + tol], and the weights of each token's entries sum to 1 within tol (Eq. 2);
+ * PCG_ERR_BAD_CSR otherwise. */
+int pcg_groups_validate_weights_host(int32_t V, int32_t G, const int32_t *row_ptr,
+                                     const int32_t *members, const float *weights, double tol);
+
+/* tok_weights [nnz] (HOST): weights permuted into the order of pcg_groups_reverse_host, so that
+ * tok_weights[tok_ptr[v] + e] is the weight of the e-th membership entry of token v. */
+int pcg_groups_reverse_weights_host(int32_t V, int32_t G, const int32_t *row_ptr,
+                                    const int32_t *members, const float *weights,
+                                    float *tok_weights);
 
 /* Reverse index of a membership (all pointers HOST): tok_ptr [V+1], tok_groups [nnz]; the
  * groups of a token are listed by ascending CSR entry position (a group that lists the token

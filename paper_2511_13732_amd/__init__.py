@@ -7,6 +7,7 @@ step of the path runs in the library's kernels.
 from .binding import (BF16, F32, THIN_MAX_TRIALS, Diag, Groups, PcgError, PreparedInfo,
                       VerifyOutput, group_probs, group_probs_workspace_bytes,
                       groups_canonicalize_host, groups_prepare_host, groups_reverse_host,
+                      groups_reverse_weights_host, groups_validate_weights_host,
                       groups_validate_host, lib, lib_path, profile_begin, profile_end, propose,
                       propose_workspace_bytes, strerror,
                       suggest_chunk_groups, verify, verify_thinning,
@@ -15,6 +16,7 @@ from .binding import (BF16, F32, THIN_MAX_TRIALS, Diag, Groups, PcgError, Prepar
 __all__ = ["BF16", "F32", "THIN_MAX_TRIALS", "Diag", "Groups", "PcgError", "PreparedInfo",
            "VerifyOutput", "group_probs", "group_probs_workspace_bytes",
            "groups_canonicalize_host", "groups_prepare_host", "groups_reverse_host",
+           "groups_reverse_weights_host", "groups_validate_weights_host",
            "groups_validate_host", "lib", "lib_path", "profile_begin", "profile_end", "propose",
            "propose_workspace_bytes", "strerror",
            "suggest_chunk_groups", "verify", "verify_thinning", "verify_thinning_workspace_bytes",

@@ -37,7 +37,8 @@ class _GroupsStruct(C.Structure):
     _fields_ = [("V", C.c_int32), ("G", C.c_int32), ("nnz", C.c_int64),
                 ("row_ptr", C.c_void_p), ("members", C.c_void_p), ("mult", C.c_void_p),
                 ("prepared", C.c_void_p), ("prepared_info", C.POINTER(PreparedInfo)),
-                ("tok_ptr", C.c_void_p), ("tok_groups", C.c_void_p)]
+                ("tok_ptr", C.c_void_p), ("tok_groups", C.c_void_p),
+                ("weights", C.c_void_p), ("tok_weights", C.c_void_p)]
 
 
 class Diag(C.Structure):
@@ -93,6 +94,12 @@ def lib() -> C.CDLL:
         L.pcg_groups_reverse_host.restype = C.c_int
         L.pcg_groups_reverse_host.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                               C.c_void_p, C.c_void_p]
+        L.pcg_groups_validate_weights_host.restype = C.c_int
+        L.pcg_groups_validate_weights_host.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                                       C.c_void_p, C.c_double]
+        L.pcg_groups_reverse_weights_host.restype = C.c_int
+        L.pcg_groups_reverse_weights_host.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                                      C.c_void_p, C.c_void_p]
         L.pcg_groups_validate_host.restype = C.c_int
         L.pcg_groups_validate_host.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                                C.c_void_p]
@@ -170,6 +177,23 @@ def groups_reverse_host(V: int, row_ptr, members):
     return tok_ptr, tok_groups[:len(mem)]
 
 
+def groups_validate_weights_host(V: int, row_ptr, members, weights, tol: float = 1e-6) -> int:
+    rp, mem = _np_i32(row_ptr), _np_i32(members)
+    w = np.ascontiguousarray(weights, dtype=np.float32)
+    return lib().pcg_groups_validate_weights_host(V, len(rp) - 1, rp.ctypes.data, mem.ctypes.data,
+                                                  w.ctypes.data, tol)
+
+
+def groups_reverse_weights_host(V: int, row_ptr, members, weights) -> np.ndarray:
+    """The per-entry weights in the order of the token -> groups index."""
+    rp, mem = _np_i32(row_ptr), _np_i32(members)
+    w = np.ascontiguousarray(weights, dtype=np.float32)
+    out = np.empty(max(1, len(mem)), np.float32)
+    _check(lib().pcg_groups_reverse_weights_host(V, len(rp) - 1, rp.ctypes.data, mem.ctypes.data,
+                                                 w.ctypes.data, out.ctypes.data), "reverse_weights")
+    return out[:len(mem)]
+
+
 def suggest_chunk_groups(G: int, batch: int) -> int:
     """Groups per workgroup of the prepared gather for an expected batch (sequences, or rows of
     pcg_group_probs): small enough to give each of the 256 compute units a workgroup, within the
@@ -199,25 +223,36 @@ class Groups:
     def __init__(self, V: int, row_ptr: torch.Tensor, members: torch.Tensor, mult: torch.Tensor,
                  nnz: int, prepared: Optional[torch.Tensor] = None,
                  prepared_info: Optional[PreparedInfo] = None,
-                 tok_ptr: Optional[torch.Tensor] = None, tok_groups: Optional[torch.Tensor] = None):
+                 tok_ptr: Optional[torch.Tensor] = None, tok_groups: Optional[torch.Tensor] = None,
+                 weights: Optional[torch.Tensor] = None, tok_weights: Optional[torch.Tensor] = None):
         for t in (row_ptr, members, mult):
             assert t.dtype == torch.int32 and t.is_contiguous()
         self.V, self.G, self.nnz = int(V), int(row_ptr.numel() - 1), int(nnz)
         self.row_ptr, self.members, self.mult = row_ptr, members, mult
         self.prepared, self.prepared_info = prepared, prepared_info
         self.tok_ptr, self.tok_groups = tok_ptr, tok_groups
+        self.weights, self.tok_weights = weights, tok_weights
         self.device = row_ptr.device
 
     @classmethod
     def from_csr(cls, V: int, row_ptr, members, device="cuda", prepare: bool = True,
-                 chunk_groups: int = 0, reverse: bool = False) -> "Groups":
+                 chunk_groups: int = 0, reverse: bool = False, weights=None) -> "Groups":
         """Canonicalise and validate a host CSR with the library, then upload it (with the
-        prepared layout unless prepare=False, with the token -> groups index if reverse)."""
+        prepared layout unless prepare=False, with the token -> groups index if reverse).
+        ``weights`` (float32 [nnz], for the canonical CSR's entries) switches from the equal split
+        to general per-entry weights; the prepared layout is then not built."""
         rp, mem, mult = groups_canonicalize_host(V, row_ptr, members)
         _check(groups_validate_host(V, rp, mem, mult), "validate")
         dev = torch.device(device)
         up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
         blob_dev, info = None, None
+        wd = twd = None
+        if weights is not None:
+            w = np.ascontiguousarray(weights, dtype=np.float32)
+            assert w.shape == (len(mem),), "one weight per entry of the canonical CSR"
+            _check(groups_validate_weights_host(V, rp, mem, w), "validate_weights")
+            wd = up(w)
+            prepare = False
         if prepare:
             blob, info = groups_prepare_host(V, rp, mem, chunk_groups)
             blob_dev = up(blob)
@@ -225,12 +260,15 @@ class Groups:
         if reverse:
             tok_ptr, tok_groups = groups_reverse_host(V, rp, mem)
             tp, tg = up(tok_ptr), up(tok_groups if len(tok_groups) else np.zeros(1, np.int32))
+            if weights is not None:
+                twd = up(groups_reverse_weights_host(V, rp, mem, w))
         return cls(V, up(rp), up(mem if len(mem) else np.zeros(1, np.int32)), up(mult), len(mem),
-                   blob_dev, info, tp, tg)
+                   blob_dev, info, tp, tg, wd, twd)
 
     def without_prepared(self) -> "Groups":
         """The same membership, read through the CSR by the generic kernel."""
-        return Groups(self.V, self.row_ptr, self.members, self.mult, self.nnz)
+        return Groups(self.V, self.row_ptr, self.members, self.mult, self.nnz, None, None,
+                      self.tok_ptr, self.tok_groups, self.weights, self.tok_weights)
 
     def struct(self) -> _GroupsStruct:
         return _GroupsStruct(self.V, self.G, self.nnz, self.row_ptr.data_ptr(),
@@ -238,7 +276,9 @@ class Groups:
                              None if self.prepared is None else self.prepared.data_ptr(),
                              None if self.prepared_info is None else C.pointer(self.prepared_info),
                              None if self.tok_ptr is None else self.tok_ptr.data_ptr(),
-                             None if self.tok_groups is None else self.tok_groups.data_ptr())
+                             None if self.tok_groups is None else self.tok_groups.data_ptr(),
+                             None if self.weights is None else self.weights.data_ptr(),
+                             None if self.tok_weights is None else self.tok_weights.data_ptr())
 
 
 # --------------------------------------------------------------------------- calls

@@ -68,6 +68,8 @@ int check_groups(const pcg_groups *g) {
   if (g->V < 1 || g->G < 1 || g->nnz < 0 || g->nnz > INT32_MAX) return PCG_ERR_BAD_SHAPE;
   if (g->nnz > 0 && !g->members) return PCG_ERR_NULL_ARG;
   if ((g->prepared == nullptr) != (g->prepared_info == nullptr)) return PCG_ERR_NULL_ARG;
+  if (g->weights && g->prepared) return PCG_ERR_BAD_SHAPE;   // the prepared form holds no weights
+  if (g->weights && ((uintptr_t) g->weights % 4)) return PCG_ERR_MISALIGNED;
   if (g->prepared) {
     const pcg_prepared &p = *g->prepared_info;
     if (p.V != g->V || p.G != g->G || p.ntiles < 1 || p.tile_len < 1 || p.tile_len > kTileTokensMax ||
@@ -247,6 +249,7 @@ AcceptArgs accept_args(const pcg_groups *groups, const RowSet &rs, int32_t K, co
   aa.row_ptr = groups->row_ptr;
   aa.members = groups->members;
   aa.mult = groups->mult;
+  aa.weights = groups->weights;
   aa.prop_tokens = prop_tokens;
   aa.prop_groups = prop_groups;
   aa.seed = seed;
@@ -305,6 +308,7 @@ int pcg_verify(const pcg_groups *groups, const void *target_logits, const void *
   fa.row_ptr = groups->row_ptr;
   fa.members = groups->members;
   fa.mult = groups->mult;
+  fa.weights = groups->weights;
   fa.seed = seed;
   fa.offset = offset;
   fa.accept_len = accept_len;
@@ -354,7 +358,7 @@ int pcg_propose(const pcg_groups *groups, const void *draft_logits, pcg_dtype dt
   if (B < 0 || K < 1 || pos0 < 0 || (int64_t) pos0 + K > PCG_MAX_K) return PCG_ERR_BAD_SHAPE;
   if (B == 0) return PCG_OK;
   if (!draft_logits || !prop_tokens || !prop_groups || !workspace || !groups->tok_ptr ||
-      !groups->tok_groups)
+      !groups->tok_groups || (groups->weights && !groups->tok_weights))
     return PCG_ERR_NULL_ARG;
   const int32_t V = groups->V;
   if (!stride_ok(dft_pos_stride, V, K == 1) || !stride_ok(dft_batch_stride, V, true))
@@ -388,8 +392,9 @@ int pcg_propose(const pcg_groups *groups, const void *draft_logits, pcg_dtype dt
   if ((e = launch_row_stats(rs, bf16, V, rows, f.c, parts, stream)) != hipSuccess) return hip_fail(e);
   tm.end(kStageStats);
   tm.begin(kStagePropose);
-  if ((e = launch_propose(rs, bf16, V, K, pos0, f.c, parts, groups->tok_ptr, groups->tok_groups, seed,
-                          offset, prop_tokens, prop_groups, diag, stream)) != hipSuccess)
+  if ((e = launch_propose(rs, bf16, V, K, pos0, f.c, parts, groups->tok_ptr, groups->tok_groups,
+                          groups->weights ? groups->tok_weights : nullptr, seed, offset,
+                          prop_tokens, prop_groups, diag, stream)) != hipSuccess)
     return hip_fail(e);
   tm.end(kStagePropose);
   return PCG_OK;
@@ -416,6 +421,7 @@ int pcg_verify_thinning(const pcg_groups *groups, const void *target_logits,
                              workspace, rs);
   if (rc || B == 0) return rc;
   if (!trials || !groups->tok_ptr || !groups->tok_groups) return PCG_ERR_NULL_ARG;
+  if (groups->weights && !groups->tok_weights) return PCG_ERR_NULL_ARG;
   const int32_t V = groups->V;
   const int32_t nparts = stats_nparts(V);
   if (nparts > thin_max_parts()) return PCG_ERR_BAD_SHAPE;
@@ -437,7 +443,8 @@ int pcg_verify_thinning(const pcg_groups *groups, const void *target_logits,
   if ((e = launch_row_stats(rs, bf16, V, rows, f.c, parts, stream)) != hipSuccess) return hip_fail(e);
   tm.end(kStageStats);
   tm.begin(kStageThin);
-  if ((e = launch_accept_thin(aa, bf16, B, groups->tok_ptr, groups->tok_groups, trials,
+  if ((e = launch_accept_thin(aa, bf16, B, groups->tok_ptr, groups->tok_groups,
+                              groups->weights ? groups->tok_weights : nullptr, trials,
                               PCG_THIN_MAX_TRIALS, stream)) != hipSuccess)
     return hip_fail(e);
   tm.end(kStageThin);
@@ -563,6 +570,35 @@ int pcg_groups_reverse_host(int32_t V, int32_t G, const int32_t *row_ptr, const 
   std::vector<int32_t> cursor(tok_ptr, tok_ptr + V);
   for (int32_t g = 0; g < G; ++g)               // ascending entry position within a token's list
     for (int32_t j = row_ptr[g]; j < row_ptr[g + 1]; ++j) tok_groups[cursor[members[j]]++] = g;
+  return PCG_OK;
+}
+
+int pcg_groups_validate_weights_host(int32_t V, int32_t G, const int32_t *row_ptr,
+                                     const int32_t *members, const float *weights, double tol) {
+  if (!row_ptr || !members || !weights) return PCG_ERR_NULL_ARG;
+  if (V < 1 || G < 1 || !(tol >= 0.0)) return PCG_ERR_BAD_SHAPE;
+  if (!csr_well_formed(V, G, row_ptr, members)) return PCG_ERR_BAD_CSR;
+  std::vector<double> total((size_t) V, 0.0);
+  for (int32_t j = 0; j < row_ptr[G]; ++j) {
+    const double w = (double) weights[j];
+    if (!(w >= 0.0 && w <= 1.0 + tol)) return PCG_ERR_BAD_CSR;   // also catches NaN
+    total[members[j]] += w;
+  }
+  for (int32_t v = 0; v < V; ++v)
+    if (!(std::fabs(total[v] - 1.0) <= tol)) return PCG_ERR_BAD_CSR;
+  return PCG_OK;
+}
+
+int pcg_groups_reverse_weights_host(int32_t V, int32_t G, const int32_t *row_ptr,
+                                    const int32_t *members, const float *weights,
+                                    float *tok_weights) {
+  if (!row_ptr || !members || !weights || !tok_weights) return PCG_ERR_NULL_ARG;
+  if (V < 1 || G < 1) return PCG_ERR_BAD_SHAPE;
+  if (!csr_well_formed(V, G, row_ptr, members)) return PCG_ERR_BAD_CSR;
+  std::vector<int32_t> cursor((size_t) V + 1, 0);
+  for (int32_t j = 0; j < row_ptr[G]; ++j) ++cursor[members[j] + 1];
+  for (int32_t v = 0; v < V; ++v) cursor[v + 1] += cursor[v];
+  for (int32_t j = 0; j < row_ptr[G]; ++j) tok_weights[cursor[members[j]]++] = weights[j];
   return PCG_OK;
 }
 

@@ -252,6 +252,7 @@ struct FinalizeArgs {
   double cd;
   const RowStat *rowstat;
   const int32_t *row_ptr, *members, *mult;
+  const float *weights;    // general weights per CSR entry, or NULL for the equal split
   uint64_t seed, offset;
   const int32_t *accept_len;
   float *R;
@@ -268,6 +269,7 @@ struct AcceptArgs {
   const StatPart *parts;
   RowStat *rowstat;
   const int32_t *row_ptr, *members, *mult, *prop_tokens, *prop_groups;
+  const float *weights;    // general weights per CSR entry, or NULL for the equal split
   uint64_t seed, offset;
   int32_t *accept_len, *out_tokens, *out_groups;
   pcg_diag *diag;

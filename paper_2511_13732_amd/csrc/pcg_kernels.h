@@ -21,14 +21,15 @@ hipError_t launch_accept_delta(const AcceptArgs &a, bool bf16, int32_t B, float 
                                hipStream_t stream);
 
 hipError_t launch_accept_thin(const AcceptArgs &a, bool bf16, int32_t B, const int32_t *tok_ptr,
-                              const int32_t *tok_groups, int32_t *trials, int32_t max_trials,
-                              hipStream_t stream);
+                              const int32_t *tok_groups, const float *tok_weights, int32_t *trials,
+                              int32_t max_trials, hipStream_t stream);
 int32_t thin_max_parts();
 
 hipError_t launch_propose(const RowSet &rs, bool bf16, int32_t V, int32_t K, int32_t pos0, float c,
                           const StatPart *parts, const int32_t *tok_ptr, const int32_t *tok_groups,
-                          uint64_t seed, uint64_t offset, int32_t *prop_tokens, int32_t *prop_groups,
-                          pcg_diag *diag, hipStream_t stream);
+                          const float *tok_weights, uint64_t seed, uint64_t offset,
+                          int32_t *prop_tokens, int32_t *prop_groups, pcg_diag *diag,
+                          hipStream_t stream);
 
 hipError_t launch_weights(const RowSet &rs, bool bf16, const pcg_groups &g, int64_t row0,
                           int32_t nrows, float c, float c_hi, float c_lo, const StatPart *parts,

@@ -170,9 +170,14 @@ __device__ __forceinline__ void load8(const void *row, int32_t t, int32_t V, flo
   }
 }
 
+// Divisors of eight consecutive tokens: their multiplicities, or 1 with mult == NULL (general
+// weights: the per-entry weight is applied by the gather instead).
 template <bool VEC>
 __device__ __forceinline__ void load8_mult(const int32_t *mult, int32_t t, int32_t V, float *m) {
-  if (VEC && t + 8 <= V) {
+  if (!mult) {
+#pragma unroll
+    for (int k = 0; k < 8; ++k) m[k] = 1.f;
+  } else if (VEC && t + 8 <= V) {
     const int4 a = *reinterpret_cast<const int4 *>(mult + t);
     const int4 b = *reinterpret_cast<const int4 *>(mult + t + 4);
     m[0] = (float) a.x; m[1] = (float) a.y; m[2] = (float) a.z; m[3] = (float) a.w;
@@ -265,7 +270,10 @@ __device__ void accept_phase(AcceptShared &sh, const AcceptArgs &a, int b, bool 
         const int32_t t0 = has ? a.members[beg + lane] : 0;
         const float lt0 = has ? logit_at<BF16>(trow, t0) : -INFINITY;
         const float ld0 = has ? logit_at<BF16>(drow, t0) : -INFINITY;
-        const float m0 = has ? (float) a.mult[t0] : 1.f;
+        // the entry's share of its token: 1 / N(t) (Eq. 3), or the caller's weight (Eq. 2)
+        const float *wts = a.weights;
+        const float m0 = has && !wts ? (float) a.mult[t0] : 1.f;
+        const float w0 = has && wts ? wts[beg + lane] : 1.f;
         mt = lt0;
         md = ld0;
         for (int32_t j = beg + lane + kWave; j < end; j += kWave) {
@@ -276,14 +284,15 @@ __device__ void accept_phase(AcceptShared &sh, const AcceptArgs &a, int b, bool 
         mt = wave_max(mt);
         md = wave_max(md);
         // masses in the kernels' precision: fp32 exponential and division, fp64 sum
-        if (lt0 > -INFINITY) at = (double) (exp_rel(lt0, mt, a.c, c_lo) / m0);
-        if (ld0 > -INFINITY) ad = (double) (exp_rel(ld0, md, a.c, c_lo) / m0);
+        if (lt0 > -INFINITY) at = (double) (exp_rel(lt0, mt, a.c, c_lo) * w0 / m0);
+        if (ld0 > -INFINITY) ad = (double) (exp_rel(ld0, md, a.c, c_lo) * w0 / m0);
         for (int32_t j = beg + lane + kWave; j < end; j += kWave) {
           const int32_t t = a.members[j];
-          const float m = (float) a.mult[t];
+          const float m = wts ? 1.f : (float) a.mult[t];
+          const float w = wts ? wts[j] : 1.f;
           const float lt = logit_at<BF16>(trow, t), ld = logit_at<BF16>(drow, t);
-          if (lt > -INFINITY) at += (double) (exp_rel(lt, mt, a.c, c_lo) / m);
-          if (ld > -INFINITY) ad += (double) (exp_rel(ld, md, a.c, c_lo) / m);
+          if (lt > -INFINITY) at += (double) (exp_rel(lt, mt, a.c, c_lo) * w / m);
+          if (ld > -INFINITY) ad += (double) (exp_rel(ld, md, a.c, c_lo) * w / m);
         }
       }
       at = wave_sum(at);
@@ -373,7 +382,7 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_delta_kernel(AcceptArgs
   const RowSet &rs = a.rs;
   const int32_t V = a.V, K = a.K;
   const float c = a.c;
-  const int32_t *mult = a.mult;
+  const int32_t *mult = a.weights ? nullptr : a.mult;   // with weights delta is q - p as it is
 
   // 4. this workgroup's share of the table on the decision row: slices split, split + nsplit, ...
   const int32_t istar = sh.istar;
@@ -488,6 +497,21 @@ __device__ WavePick wave_inverse_cdf(int32_t n, F f, double u, int lane, double 
 __device__ __forceinline__ bool near_edge(const WavePick &p) {
   return (p.lo > 0.0 && p.goal - p.lo < 1e-6 * p.total) ||
          (p.hi < p.total && p.hi - p.goal < 1e-6 * p.total);
+}
+
+// Which of the n membership entries of a token (reverse-index positions e0 .. e0+n-1) the
+// 24-bit draw picks, K ~ w_{k,x} over k in S(x) (Eq. 6): entry (k24 n) >> 24 under the equal
+// split, else the inverse CDF of the entries' weights at k24 / 2^24, by the whole wave.
+// *near: that draw is within 1e-6 of an inner edge of the chosen entry's bin.
+__device__ __forceinline__ int32_t pick_entry(const float *tok_weights, int32_t e0, int32_t n,
+                                              uint32_t k24, int lane, bool *near) {
+  *near = false;
+  if (!tok_weights) return (int32_t) (((uint64_t) k24 * (uint64_t) max(n, 1)) >> 24);
+  const WavePick pk = wave_inverse_cdf(
+      n, [&](int32_t e) { return (double) tok_weights[e0 + e]; }, (double) k24 * (1.0 / 16777216.0), lane);
+  if (pk.index < 0) return 0;
+  *near = near_edge(pk);
+  return pk.index;
 }
 
 // Masses of the parts of one row, as the token draw reads them.
@@ -620,8 +644,8 @@ __device__ int32_t draw_token(const PartMasses &pm, uint32_t *redo, const void *
 
 template <bool BF16, bool VEC>
 __global__ __launch_bounds__(kAcceptThreads) void accept_thin_kernel(
-    AcceptArgs a, const int32_t *tok_ptr, const int32_t *tok_groups, int32_t *trials,
-    int32_t max_trials) {
+    AcceptArgs a, const int32_t *tok_ptr, const int32_t *tok_groups, const float *tok_weights,
+    int32_t *trials, int32_t max_trials) {
   __shared__ AcceptShared sh;
   __shared__ ThinShared th;
   const int b = blockIdx.x;
@@ -641,12 +665,16 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_thin_kernel(
   if (threadIdx.x == 0) th.done = 0;
   __syncthreads();
 
-  // q(t) / N(t) and p(t) / N(t) up to the rows' normalisations, in the kernels' precision (fp32)
-  auto wq = [&](int32_t t) -> double {
-    return (double) (exp_rel(logit_at<BF16>(trow, t), st.M, a.c, c_lo) / (float) a.mult[t]);
+  // q(t) w and p(t) w of CSR entry j holding token t (w = 1 / N(t) under the equal split), up
+  // to the rows' normalisations, in the kernels' precision (fp32)
+  const float *wts = a.weights;
+  auto wq = [&](int32_t j, int32_t t) -> double {
+    const float e = exp_rel(logit_at<BF16>(trow, t), st.M, a.c, c_lo);
+    return (double) (wts ? e * wts[j] : e / (float) a.mult[t]);
   };
-  auto wp = [&](int32_t t) -> double {
-    return (double) (exp_rel(logit_at<BF16>(drow, t), sd.M, a.c, c_lo) / (float) a.mult[t]);
+  auto wp = [&](int32_t j, int32_t t) -> double {
+    const float e = exp_rel(logit_at<BF16>(drow, t), sd.M, a.c, c_lo);
+    return (double) (wts ? e * wts[j] : e / (float) a.mult[t]);
   };
 
   // Trials run kThinTrialWaves at a time, one per wave; the other waves only keep the barriers.
@@ -660,26 +688,27 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_thin_kernel(
       const int32_t y = draw_token<BF16, VEC>(th.pm, th.redo[wave], trow, V, a.nparts, a.c,
                                               (double) d.u_y, lane, &near_y);
       const int32_t e0 = tok_ptr[y], n = tok_ptr[y + 1] - e0;
-      const int32_t g = tok_groups[e0 + (int32_t) (((uint64_t) d.k24 * (uint64_t) max(n, 1)) >> 24)];
+      bool near_e = false;
+      const int32_t g = tok_groups[e0 + pick_entry(tok_weights, e0, n, d.k24, lane, &near_e)];
       const int32_t beg = a.row_ptr[g], len = a.row_ptr[g + 1] - beg;
-      int accepted = 1, near = near_y ? 1 : 0;
+      int accepted = 1, near = near_y || near_e ? 1 : 0;
       int32_t token = y;
       if (!bonus) {
         // the first 64 members stay in registers for the token draw below
         const int32_t t0 = lane < len ? a.members[beg + lane] : -1;
-        const double q0 = t0 >= 0 ? wq(t0) : 0.0;
-        double at = q0, ad = t0 >= 0 ? wp(t0) : 0.0;
+        const double q0 = t0 >= 0 ? wq(beg + lane, t0) : 0.0;
+        double at = q0, ad = t0 >= 0 ? wp(beg + lane, t0) : 0.0;
         for (int32_t j = lane + kWave; j < len; j += kWave) {
           const int32_t t = a.members[beg + j];
-          at += wq(t);
-          ad += wp(t);
+          at += wq(beg + j, t);
+          ad += wp(beg + j, t);
         }
         const double Tn = wave_sum(at), T = Tn / st.Z, D = wave_sum(ad) / sd.Z;
         const double ua = (double) d.u_a;
         accepted = ua * T < T - D;                    // u_a < [1 - D/T]_+
         if (fabs(ua * T - (T - D)) < 1e-6 * T) near |= 1;
         const WavePick pt = wave_inverse_cdf(
-            len, [&](int32_t j) { return j < kWave ? q0 : wq(a.members[beg + j]); },
+            len, [&](int32_t j) { return j < kWave ? q0 : wq(beg + j, a.members[beg + j]); },
             (double) d.u_tok, lane, Tn);
         token = pt.index < 0 ? -1 : (pt.index < kWave ? read_lane(t0, pt.index) : a.members[beg + pt.index]);
         if (pt.index >= 0 && near_edge(pt)) near |= 2;
@@ -729,8 +758,8 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_thin_kernel(
 template <bool BF16, bool VEC>
 __global__ __launch_bounds__(kWave) void propose_kernel(
     RowSet rs, int32_t V, int32_t K, int32_t pos0, int32_t nparts, float c, const StatPart *parts,
-    const int32_t *tok_ptr, const int32_t *tok_groups, uint64_t seed, uint64_t offset,
-    int32_t *prop_tokens, int32_t *prop_groups, pcg_diag *diag) {
+    const int32_t *tok_ptr, const int32_t *tok_groups, const float *tok_weights, uint64_t seed,
+    uint64_t offset, int32_t *prop_tokens, int32_t *prop_groups, pcg_diag *diag) {
   __shared__ PartMasses pm;
   __shared__ uint32_t redo[32];
   const int lane = threadIdx.x;
@@ -748,12 +777,14 @@ __global__ __launch_bounds__(kWave) void propose_kernel(
   bool near = false;
   const int32_t x = draw_token<BF16, VEC>(pm, redo, row_base(rs, row, BF16), V, nparts, c,
                                           (double) d.u_x, lane, &near);
+  const int32_t e0 = tok_ptr[x], n = tok_ptr[x + 1] - e0;
+  bool near_e = false;
+  const int32_t e = pick_entry(tok_weights, e0, n, d.k24, lane, &near_e);
   if (lane == 0) {
-    const int32_t e0 = tok_ptr[x], n = tok_ptr[x + 1] - e0;
     prop_tokens[row] = x;
-    prop_groups[row] = tok_groups[e0 + (int32_t) (((uint64_t) d.k24 * (uint64_t) max(n, 1)) >> 24)];
+    prop_groups[row] = tok_groups[e0 + e];
     if (diag) {
-      if (near) atomicAdd(&diag->near_token, 1u);
+      if (near || near_e) atomicAdd(&diag->near_token, 1u);
       atomicAdd(&diag->sequences, 1u);
     }
   }
@@ -805,7 +836,7 @@ template <int W, bool CLAMP>
 __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
     int32_t V, int32_t G, int32_t nrows, int32_t nchunks, int32_t groups_per_chunk,
     int32_t ntiles, int32_t tile_len, const int32_t *row_ptr, const int32_t *members,
-    const float *table, float *out) {
+    const float *weights, const float *table, float *out) {
   __shared__ float tab[kTileMax];
   const int xcd = blockIdx.x & 7;
   const int y = blockIdx.x >> 3;
@@ -835,7 +866,7 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
       float acc = 0.f;
       for (int32_t j = beg + sl; j < end; j += W) {
         const uint32_t t = (uint32_t) (members[j] - t0);
-        if (t < (uint32_t) tl) acc += tab[t];
+        if (t < (uint32_t) tl) acc += weights ? tab[t] * weights[j] : tab[t];
       }
       acc = subwave_sum<W>(acc);
       if (valid && sl == W - 1) {
@@ -980,11 +1011,14 @@ __device__ void finalize_sequence(const FinalizeArgs &fa, int32_t V, int32_t G, 
   const Uniforms u = philox_uniforms(fa.seed, fa.offset, (uint32_t) b, (uint32_t) istar);
   float *Rb = fa.R + (int64_t) b * G;
   const int32_t *row_ptr = fa.row_ptr, *members = fa.members, *mult = fa.mult;
+  const float *wts = fa.weights;
   const double cd = fa.cd;
 
-  // q(t) / N(t) on the decision row, in double
-  auto weight = [&](int32_t t) -> double {
-    return exp2((double) (logit_at<BF16>(trow, t) - st.M) * cd) / (st.Z * (double) mult[t]);
+  // q(t) w_{k,t} of CSR entry j on the decision row (q(t) / N(t) under the equal split), in double
+  auto weight = [&](int32_t j) -> double {
+    const int32_t t = members[j];
+    const double e = exp2((double) (logit_at<BF16>(trow, t) - st.M) * cd);
+    return wts ? e * (double) wts[j] / st.Z : e / (st.Z * (double) mult[t]);
   };
 
   CdfPick pg;
@@ -1049,7 +1083,7 @@ __device__ void finalize_sequence(const FinalizeArgs &fa, int32_t V, int32_t G, 
     fallback = true;
     for (int32_t g = threadIdx.x; g < G; g += NT) {
       double s = 0.0;
-      for (int32_t j = row_ptr[g]; j < row_ptr[g + 1]; ++j) s += weight(members[j]);
+      for (int32_t j = row_ptr[g]; j < row_ptr[g + 1]; ++j) s += weight(j);
       Rb[g] = (float) s;
     }
     __syncthreads();
@@ -1059,7 +1093,7 @@ __device__ void finalize_sequence(const FinalizeArgs &fa, int32_t V, int32_t G, 
 
   const int32_t beg = row_ptr[gs], end = row_ptr[gs + 1];
   CdfPick pt = block_inverse_cdf<NT>(
-      end - beg, [&](int32_t j) { return weight(members[beg + j]); }, (double) u.tok);
+      end - beg, [&](int32_t j) { return weight(beg + j); }, (double) u.tok);
   if (threadIdx.x == 0) {
     fa.out_groups[(int64_t) b * (K + 1) + istar] = gs;
     fa.out_tokens[(int64_t) b * (K + 1) + istar] = pt.index < 0 ? -1 : members[beg + pt.index];
@@ -1316,12 +1350,12 @@ hipError_t launch_accept_delta(const AcceptArgs &a, bool bf16, int32_t B, float 
 }
 
 hipError_t launch_accept_thin(const AcceptArgs &a, bool bf16, int32_t B, const int32_t *tok_ptr,
-                              const int32_t *tok_groups, int32_t *trials, int32_t max_trials,
-                              hipStream_t stream) {
+                              const int32_t *tok_groups, const float *tok_weights, int32_t *trials,
+                              int32_t max_trials, hipStream_t stream) {
   const bool vec = rows_vector_aligned(a.rs, bf16) && a.V % 8 == 0;
 #define PCG_LAUNCH_AT(BF, VE)                                                                \
-  accept_thin_kernel<BF, VE><<<B, kAcceptThreads, 0, stream>>>(a, tok_ptr, tok_groups, trials, \
-                                                               max_trials)
+  accept_thin_kernel<BF, VE><<<B, kAcceptThreads, 0, stream>>>(a, tok_ptr, tok_groups,        \
+                                                               tok_weights, trials, max_trials)
   if (bf16) { if (vec) PCG_LAUNCH_AT(true, true); else PCG_LAUNCH_AT(true, false); }
   else { if (vec) PCG_LAUNCH_AT(false, true); else PCG_LAUNCH_AT(false, false); }
 #undef PCG_LAUNCH_AT
@@ -1332,15 +1366,16 @@ int32_t thin_max_parts() { return kMaxThinParts; }
 
 hipError_t launch_propose(const RowSet &rs, bool bf16, int32_t V, int32_t K, int32_t pos0, float c,
                           const StatPart *parts, const int32_t *tok_ptr, const int32_t *tok_groups,
-                          uint64_t seed, uint64_t offset, int32_t *prop_tokens, int32_t *prop_groups,
-                          pcg_diag *diag, hipStream_t stream) {
+                          const float *tok_weights, uint64_t seed, uint64_t offset,
+                          int32_t *prop_tokens, int32_t *prop_groups, pcg_diag *diag,
+                          hipStream_t stream) {
   const bool vec = rows_vector_aligned(rs, bf16) && V % 8 == 0;
   const int32_t nparts = stats_nparts(V);
   const unsigned grid = (unsigned) rs.nrows0;
 #define PCG_LAUNCH_PR(BF, VE)                                                                     \
   propose_kernel<BF, VE><<<grid, kWave, 0, stream>>>(rs, V, K, pos0, nparts, c, parts, tok_ptr,   \
-                                                     tok_groups, seed, offset, prop_tokens,       \
-                                                     prop_groups, diag)
+                                                     tok_groups, tok_weights, seed, offset,       \
+                                                     prop_tokens, prop_groups, diag)
   if (bf16) { if (vec) PCG_LAUNCH_PR(true, true); else PCG_LAUNCH_PR(true, false); }
   else { if (vec) PCG_LAUNCH_PR(false, true); else PCG_LAUNCH_PR(false, false); }
 #undef PCG_LAUNCH_PR
@@ -1354,9 +1389,11 @@ hipError_t launch_weights(const RowSet &rs, bool bf16, const pcg_groups &g, int6
   const dim3 grid((unsigned) ((int64_t) nct * nrows));
   const int32_t nparts = stats_nparts(g.V);
   const bool vec = table_vector_ok(rs, bf16, g.V, g.mult, table);
+  // with general weights the table is the plain probability: the gather applies the weights
+  const int32_t *mult = g.weights ? nullptr : g.mult;
 #define PCG_LAUNCH_WEIGHTS(BF, VE)                                                             \
   weights_kernel<BF, VE><<<grid, kTableThreads, 0, stream>>>(rs, g.V, nparts, nct, row0, c, c_hi, \
-                                                             c_lo, parts, g.mult, table)
+                                                             c_lo, parts, mult, table)
   if (bf16) { if (vec) PCG_LAUNCH_WEIGHTS(true, true); else PCG_LAUNCH_WEIGHTS(true, false); }
   else { if (vec) PCG_LAUNCH_WEIGHTS(false, true); else PCG_LAUNCH_WEIGHTS(false, false); }
 #undef PCG_LAUNCH_WEIGHTS
@@ -1367,13 +1404,13 @@ template <int W>
 static void gather_dispatch(bool clamp, dim3 grid, hipStream_t stream, int32_t V, int32_t G,
                             int32_t nrows, int32_t nchunks, int32_t gpc, int32_t ntiles,
                             int32_t tile_len, const int32_t *row_ptr, const int32_t *members,
-                            const float *table, float *out) {
+                            const float *weights, const float *table, float *out) {
   if (clamp)
-    gather_kernel<W, true><<<grid, kGatherThreads, 0, stream>>>(V, G, nrows, nchunks, gpc, ntiles,
-                                                                tile_len, row_ptr, members, table, out);
+    gather_kernel<W, true><<<grid, kGatherThreads, 0, stream>>>(
+        V, G, nrows, nchunks, gpc, ntiles, tile_len, row_ptr, members, weights, table, out);
   else
-    gather_kernel<W, false><<<grid, kGatherThreads, 0, stream>>>(V, G, nrows, nchunks, gpc, ntiles,
-                                                                 tile_len, row_ptr, members, table, out);
+    gather_kernel<W, false><<<grid, kGatherThreads, 0, stream>>>(
+        V, G, nrows, nchunks, gpc, ntiles, tile_len, row_ptr, members, weights, table, out);
 }
 
 hipError_t launch_gather(const pcg_groups &g, int32_t nrows, bool clamp, const float *table,
@@ -1399,11 +1436,11 @@ hipError_t launch_gather(const pcg_groups &g, int32_t nrows, bool clamp, const f
   const int32_t rows8 = (nrows + 7) / 8;
   const dim3 grid((unsigned) (8 * rows8 * nchunks));
   switch (W) {
-    case 4: gather_dispatch<4>(clamp, grid, stream, g.V, g.G, nrows, nchunks, gpc, ntiles, tile_len, g.row_ptr, g.members, table, out); break;
-    case 8: gather_dispatch<8>(clamp, grid, stream, g.V, g.G, nrows, nchunks, gpc, ntiles, tile_len, g.row_ptr, g.members, table, out); break;
-    case 16: gather_dispatch<16>(clamp, grid, stream, g.V, g.G, nrows, nchunks, gpc, ntiles, tile_len, g.row_ptr, g.members, table, out); break;
-    case 32: gather_dispatch<32>(clamp, grid, stream, g.V, g.G, nrows, nchunks, gpc, ntiles, tile_len, g.row_ptr, g.members, table, out); break;
-    default: gather_dispatch<64>(clamp, grid, stream, g.V, g.G, nrows, nchunks, gpc, ntiles, tile_len, g.row_ptr, g.members, table, out); break;
+    case 4: gather_dispatch<4>(clamp, grid, stream, g.V, g.G, nrows, nchunks, gpc, ntiles, tile_len, g.row_ptr, g.members, g.weights, table, out); break;
+    case 8: gather_dispatch<8>(clamp, grid, stream, g.V, g.G, nrows, nchunks, gpc, ntiles, tile_len, g.row_ptr, g.members, g.weights, table, out); break;
+    case 16: gather_dispatch<16>(clamp, grid, stream, g.V, g.G, nrows, nchunks, gpc, ntiles, tile_len, g.row_ptr, g.members, g.weights, table, out); break;
+    case 32: gather_dispatch<32>(clamp, grid, stream, g.V, g.G, nrows, nchunks, gpc, ntiles, tile_len, g.row_ptr, g.members, g.weights, table, out); break;
+    default: gather_dispatch<64>(clamp, grid, stream, g.V, g.G, nrows, nchunks, gpc, ntiles, tile_len, g.row_ptr, g.members, g.weights, table, out); break;
   }
   return hipGetLastError();
 }

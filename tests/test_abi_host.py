@@ -44,7 +44,7 @@ def test_header_constants_match_binding():
         assert re.search(rf"{name}\s*=\s*{val}\b", text)
         assert pcg.strerror(val) != "unknown status"
     assert re.search(r"PCG_F32 = 0, PCG_BF16 = 1", text) and (pcg.F32, pcg.BF16) == (0, 1)
-    assert C.sizeof(pcg.Diag) == 32 and C.sizeof(_GroupsStruct) == 72 and C.sizeof(pcg.PreparedInfo) == 64
+    assert C.sizeof(pcg.Diag) == 32 and C.sizeof(_GroupsStruct) == 88 and C.sizeof(pcg.PreparedInfo) == 64
 
 
 # Fake device addresses: every call below must fail its host-side checks and return before it
@@ -55,7 +55,7 @@ P = 0x10000
 def call_verify(V=64, G=8, nnz=16, dt=0, B=2, K=2, tbs=None, tps=None, dbs=None, dps=None, tau=1.0,
                 ws=P, ws_bytes=1 << 30, tgt=P, dft=P, rp=P, mem=P, mult=P, ptok=P, pgrp=P, al=P,
                 otok=P, ogrp=P, groups=True):
-    gs = _GroupsStruct(V, G, nnz, rp, mem, mult, None, None, None, None)
+    gs = _GroupsStruct(V, G, nnz, rp, mem, mult, None, None, None, None, None, None)
     tps = V if tps is None else tps
     dps = V if dps is None else dps
     tbs = (K + 1) * V if tbs is None else tbs
@@ -95,7 +95,7 @@ def test_verify_rejects_bad_arguments_on_the_host():
 
 def test_group_probs_rejects_bad_arguments_on_the_host():
     L = pcg.lib()
-    gs = _GroupsStruct(64, 8, 16, P, P, P, None, None, None, None)
+    gs = _GroupsStruct(64, 8, 16, P, P, P, None, None, None, None, None, None)
     f = lambda **k: L.pcg_group_probs(k.get("g", C.byref(gs)), k.get("x", P), k.get("dt", 0),
                                       k.get("rows", 4), k.get("stride", 64), k.get("tau", 1.0),
                                       k.get("out", P), k.get("ws", P), k.get("wsb", 1 << 30), None)
@@ -240,7 +240,7 @@ def test_prepare_rejects_bad_arguments():
     blob, info = pcg.groups_prepare_host(4, rp, mem)
     gs = _GroupsStruct(5, 2, 4, P, P, P, P, C.pointer(info), None, None)
     assert pcg.lib().pcg_group_probs(C.byref(gs), P, 0, 1, 5, 1.0, P, P, 1 << 30, None) == BAD_SHAPE
-    gs = _GroupsStruct(4, 2, 4, P, P, P, P, None, None, None)
+    gs = _GroupsStruct(4, 2, 4, P, P, P, P, None, None, None, None, None)
     assert pcg.lib().pcg_group_probs(C.byref(gs), P, 0, 1, 4, 1.0, P, P, 1 << 30, None) == NULL_ARG
 
 
@@ -255,14 +255,14 @@ def test_reverse_index_and_thinning_argument_checks():
     np.testing.assert_array_equal(tok_groups, ref_groups)
     np.testing.assert_array_equal(np.diff(tok_ptr), mult)
     L = pcg.lib()
-    gs = _GroupsStruct(64, 8, 16, P, P, P, None, None, None, None)      # no reverse index
+    gs = _GroupsStruct(64, 8, 16, P, P, P, None, None, None, None, None, None)      # no reverse index
     args = lambda g, **k: L.pcg_verify_thinning(C.byref(g), P, P, 0, 2, 2, 192, 64, 128, 64, 1.0, P, P, 0, 0,
                                                 P, P, P, k.get("trials", P), None, P, k.get("wsb", 1 << 30), None)
     assert args(gs) == NULL_ARG
-    gs = _GroupsStruct(64, 8, 16, P, P, P, None, None, P, P)
+    gs = _GroupsStruct(64, 8, 16, P, P, P, None, None, P, P, None, None)
     assert args(gs, trials=None) == NULL_ARG
     assert args(gs, wsb=pcg.verify_thinning_workspace_bytes(64, 2, 2) - 1) == WS_SMALL
-    big = _GroupsStruct(5_000_000, 8, 16, P, P, P, None, None, P, P)    # more parts than the token draw searches
+    big = _GroupsStruct(5_000_000, 8, 16, P, P, P, None, None, P, P, None, None)    # more parts than the token draw searches
     assert L.pcg_verify_thinning(C.byref(big), P, P, 0, 1, 1, 0, 5_000_000, 0, 5_000_000, 1.0, P, P, 0, 0,
                                  P, P, P, P, None, P, 1 << 40, None) == BAD_SHAPE
 
@@ -272,8 +272,8 @@ def test_propose_argument_checks():
     call = lambda g, **k: L.pcg_propose(C.byref(g), k.get("logits", P), k.get("dt", 0), 2, k.get("K", 2),
                                         k.get("pos0", 0), 128, k.get("ps", 64), k.get("tau", 1.0), 0, 0, P, P,
                                         None, P, k.get("wsb", 1 << 30), None)
-    rev = _GroupsStruct(64, 8, 16, P, P, P, None, None, P, P)
-    assert call(_GroupsStruct(64, 8, 16, P, P, P, None, None, None, None)) == NULL_ARG   # no reverse index
+    rev = _GroupsStruct(64, 8, 16, P, P, P, None, None, P, P, None, None)
+    assert call(_GroupsStruct(64, 8, 16, P, P, P, None, None, None, None, None, None)) == NULL_ARG   # no reverse index
     assert call(rev, logits=None) == NULL_ARG
     assert call(rev, dt=7) == BAD_DTYPE
     assert call(rev, K=0) == BAD_SHAPE
@@ -283,3 +283,31 @@ def test_propose_argument_checks():
     assert call(rev, logits=P + 2) == MISALIGNED
     assert call(rev, wsb=pcg.propose_workspace_bytes(64, 2, 2) - 1) == WS_SMALL
     assert pcg.propose_workspace_bytes(0, 1, 1) == 0
+
+
+def test_weights_host_helpers_match_the_oracle_and_are_checked():
+    V, G = 300, 200
+    rp, mem = W.random_groups(V, G, 1, 9, seed=4, cover=False)
+    rp, mem, mult = pcg.groups_canonicalize_host(V, rp, mem)
+    rng = np.random.default_rng(0)
+    raw = rng.gamma(0.7, size=len(mem))
+    tot = np.zeros(V)
+    np.add.at(tot, mem, raw)
+    w = (raw / tot[mem]).astype(np.float32)
+    assert pcg.groups_validate_weights_host(V, rp, mem, w) == OK
+    for j, val in ((3, -0.1), (5, np.nan), (7, 1.5)):
+        bad = w.copy()
+        bad[j] = val
+        assert pcg.groups_validate_weights_host(V, rp, mem, bad) == BAD_CSR
+    assert pcg.groups_validate_weights_host(V, rp, mem, w * np.float32(0.99)) == BAD_CSR
+    og = oracle.with_weights(oracle.Groups(V, len(rp) - 1, rp, mem, mult), w)
+    np.testing.assert_array_equal(pcg.groups_reverse_weights_host(V, rp, mem, w), og.tok_weights)
+    # weights and the prepared form exclude each other; thinning and proposals need tok_weights
+    L = pcg.lib()
+    info = pcg.PreparedInfo()
+    both = _GroupsStruct(64, 8, 16, P, P, P, P, C.pointer(info), None, None, P, None)
+    assert L.pcg_group_probs(C.byref(both), P, 0, 1, 64, 1.0, P, P, 1 << 30, None) == BAD_SHAPE
+    half = _GroupsStruct(64, 8, 16, P, P, P, None, None, P, P, P, None)
+    assert L.pcg_propose(C.byref(half), P, 0, 2, 2, 0, 128, 64, 1.0, 0, 0, P, P, None, P, 1 << 30, None) == NULL_ARG
+    assert L.pcg_verify_thinning(C.byref(half), P, P, 0, 2, 2, 192, 64, 128, 64, 1.0, P, P, 0, 0,
+                                 P, P, P, P, None, P, 1 << 30, None) == NULL_ARG

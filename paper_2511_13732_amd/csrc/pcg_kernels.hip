@@ -857,22 +857,49 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
     if (tile > 0) __syncthreads();                  // everyone is done reading the old tile
     for (int32_t k = threadIdx.x; k < tl; k += kGatherThreads) tab[k] = src[t0 + k];
     __syncthreads();
-    // every lane of a wave runs the same number of passes, so the DPP reduction below is
-    // always executed by full waves
-    for (int32_t gb = g_begin; gb < g_end; gb += nsub) {
-      const int32_t g = gb + sub;
-      const bool valid = g < g_end;
-      const int32_t beg = valid ? row_ptr[g] : 0, end = valid ? row_ptr[g + 1] : 0;
-      float acc = 0.f;
-      for (int32_t j = beg + sl; j < end; j += W) {
-        const uint32_t t = (uint32_t) (members[j] - t0);
-        if (t < (uint32_t) tl) acc += weights ? tab[t] * weights[j] : tab[t];
+    // Every lane of a wave runs the same number of passes, so the DPP reduction below is
+    // always executed by full waves.  A sub-wave takes kInFlight groups per pass, so that their
+    // chains of dependent loads (row_ptr -> members -> table) overlap.
+    constexpr int kInFlight = 8;
+    for (int32_t gb = g_begin; gb < g_end; gb += nsub * kInFlight) {
+      int32_t beg[kInFlight], end[kInFlight], mem[kInFlight];
+      float wt[kInFlight], acc[kInFlight];
+#pragma unroll
+      for (int u = 0; u < kInFlight; ++u) {
+        const int32_t g = gb + u * nsub + sub;
+        const bool valid = g < g_end;
+        beg[u] = valid ? row_ptr[g] : 0;
+        end[u] = valid ? row_ptr[g + 1] : 0;
       }
-      acc = subwave_sum<W>(acc);
-      if (valid && sl == W - 1) {
-        if (tile > 0) acc += dst[g];                // partial sum of the earlier tiles
-        if (CLAMP && tile == ntiles - 1) acc = fmaxf(acc, 0.f);
-        dst[g] = acc;
+#pragma unroll
+      for (int u = 0; u < kInFlight; ++u) {       // first trip of each group
+        const int32_t j = beg[u] + sl;
+        const bool has = j < end[u];
+        mem[u] = has ? members[j] : -1;
+        wt[u] = has && weights ? weights[j] : 1.f;
+      }
+#pragma unroll
+      for (int u = 0; u < kInFlight; ++u) {
+        const uint32_t t = (uint32_t) (mem[u] - t0);
+        acc[u] = 0.f;
+        if (mem[u] >= 0 && t < (uint32_t) tl) acc[u] = weights ? tab[t] * wt[u] : tab[t];
+      }
+#pragma unroll
+      for (int u = 0; u < kInFlight; ++u) {       // groups longer than the sub-wave
+        for (int32_t j = beg[u] + sl + W; j < end[u]; j += W) {
+          const uint32_t t = (uint32_t) (members[j] - t0);
+          if (t < (uint32_t) tl) acc[u] += weights ? tab[t] * weights[j] : tab[t];
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < kInFlight; ++u) {
+        const int32_t g = gb + u * nsub + sub;
+        float a = subwave_sum<W>(acc[u]);
+        if (g < g_end && sl == W - 1) {
+          if (tile > 0) a += dst[g];                // partial sum of the earlier tiles
+          if (CLAMP && tile == ntiles - 1) a = fmaxf(a, 0.f);
+          dst[g] = a;
+        }
       }
     }
   }

@@ -237,3 +237,13 @@ def random_groups(V: int, G: int, min_size: int, max_size: int, seed: int,
     row_ptr = np.zeros(G + 1, dtype=np.int32)
     row_ptr[1:] = np.cumsum([len(s) for s in sets])
     return row_ptr, np.concatenate(sets).astype(np.int32)
+
+
+def random_weights(V: int, members: np.ndarray, seed: int) -> np.ndarray:
+    """General per-entry weights for a membership (Sec. 2.2, Eq. 2): positive Gamma(0.7) draws,
+    normalised over the entries of each token, as float32 [nnz]."""
+    rng = np.random.default_rng([seed, 77])
+    raw = rng.gamma(0.7, size=len(members)) + 1e-12
+    tot = np.zeros(V)
+    np.add.at(tot, members, raw)
+    return (raw / tot[members]).astype(np.float32)

@@ -414,3 +414,62 @@ def propose(g: Groups, rev, draft_logits, *, temperature: float = 1.0, seed: int
                                      C.c_uint64(seed), C.c_uint64(offset), _p(res.tokens),
                                      _p(res.groups), _p(res.near), C.c_int32(nthreads)), "propose")
     return res
+
+
+# --------------------------------------------------------------------------- similarity groups (Eq. 1)
+
+def asg_normalize(emb) -> np.ndarray:
+    """float32 [V, d] embeddings -> unit vectors as bf16 bit patterns (uint16 [V, d])."""
+    e = np.ascontiguousarray(emb, dtype=np.float32)
+    out = np.empty(e.shape, dtype=np.uint16)
+    _check(lib().pcg_ref_asg_normalize(_p(e), C.c_int32(e.shape[0]), C.c_int32(e.shape[1]), _p(out)),
+           "asg_normalize")
+    return out
+
+
+def asg_similarity(unit, a: int, b: int) -> float:
+    u = np.ascontiguousarray(unit, dtype=np.uint16)
+    f = lib().pcg_ref_asg_similarity
+    f.restype = C.c_double
+    return f(_p(u), C.c_int32(u.shape[1]), C.c_int32(a), C.c_int32(b))
+
+
+def asg_row(unit, theta: float, t: int) -> tuple[np.ndarray, int]:
+    """(members of G(t) ascending, number of near-tie pairs of the row)."""
+    u = np.ascontiguousarray(unit, dtype=np.uint16)
+    V, d = u.shape
+    buf = np.empty(V, dtype=np.int32)
+    n, near = C.c_int32(), C.c_int32()
+    _check(lib().pcg_ref_asg_row(_p(u), C.c_int32(V), C.c_int32(d), C.c_float(theta), C.c_int32(t),
+                                 _p(buf), C.byref(n), C.byref(near)), "asg_row")
+    return buf[:n.value].copy(), near.value
+
+
+@dataclass
+class AsgResult:
+    groups: Groups
+    seed_of: np.ndarray      # int32 [G] the token whose similarity group each kept row is
+    near_rows: np.ndarray    # uint8 [V] rows with a pair within 1e-5 of the threshold
+
+
+def asg_build(unit, theta: float, nthreads: int = 1) -> AsgResult:
+    """Distinct similarity groups of all tokens (Eq. 1) as canonical Groups."""
+    u = np.ascontiguousarray(unit, dtype=np.uint16)
+    V, d = u.shape
+    cap = 64 * V
+    while True:
+        rp = np.empty(V + 1, np.int32)
+        mem = np.empty(max(1, cap), np.int32)
+        mult = np.empty(V, np.int32)
+        seed = np.empty(V, np.int32)
+        near = np.zeros(V, np.uint8)
+        G, nnz = C.c_int32(), C.c_int64()
+        rc = lib().pcg_ref_asg_build(_p(u), C.c_int32(V), C.c_int32(d), C.c_float(theta), C.byref(G),
+                                     C.byref(nnz), _p(rp), _p(mem), C.c_int64(cap), _p(mult), _p(seed),
+                                     _p(near), C.c_int32(nthreads))
+        if rc == -4 and nnz.value > cap:
+            cap = nnz.value
+            continue
+        _check(rc, "asg_build")
+        return AsgResult(Groups(V, G.value, rp[:G.value + 1].copy(), mem[:nnz.value].copy(), mult),
+                         seed[:G.value].copy(), near)

@@ -902,3 +902,138 @@ int pcg_ref_propose_w(int32_t V, int32_t G, const int32_t *mult, const pcg_ref_w
                       dft_batch_stride, dft_pos_stride, temperature, NULL, NULL, seed, offset,
                       prop_tokens, prop_groups, near, nthreads);
 }
+
+/* ------------------------------------------------------------------------- */
+/* Acoustic Similarity Groups, Eq. (1)                                        */
+/* ------------------------------------------------------------------------- */
+
+static double bf16_value(uint16_t h) {
+  uint32_t w = (uint32_t)h << 16;
+  float f;
+  memcpy(&f, &w, sizeof f);
+  return (double)f;
+}
+
+/* x rounded to bfloat16: nearest, ties to even (|x| well inside the normal range) */
+static uint16_t bf16_round(double x) {
+  float f = (float)x;                 /* a first guess; its two bf16 neighbours bracket x */
+  uint32_t w;
+  memcpy(&w, &f, sizeof w);
+  uint32_t lo = w & 0xffff0000u;      /* truncation: towards zero */
+  uint32_t hi = lo + 0x10000u;        /* next value away from zero */
+  float flo, fhi;
+  memcpy(&flo, &lo, sizeof flo);
+  memcpy(&fhi, &hi, sizeof fhi);
+  /* (float)x may have rounded across lo or hi; step until lo and hi bracket x */
+  while (fabs((double)flo) > fabs(x)) { hi = lo; lo -= 0x10000u; memcpy(&flo, &lo, 4); memcpy(&fhi, &hi, 4); }
+  while (fabs((double)fhi) < fabs(x)) { lo = hi; hi += 0x10000u; memcpy(&flo, &lo, 4); memcpy(&fhi, &hi, 4); }
+  double dlo = fabs(x) - fabs((double)flo), dhi = fabs((double)fhi) - fabs(x);
+  uint32_t pick = dlo < dhi ? lo : (dhi < dlo ? hi : ((lo >> 16) & 1u ? hi : lo));
+  return (uint16_t)(pick >> 16);
+}
+
+int pcg_ref_asg_normalize(const float *emb, int32_t V, int32_t d, uint16_t *unit_bf16) {
+  if (!emb || !unit_bf16 || V < 1 || d < 1) return PCG_REF_ERR_ARG;
+  for (int32_t v = 0; v < V; ++v) {
+    const float *e = emb + (int64_t)v * d;
+    double ss = 0.0;
+    for (int32_t k = 0; k < d; ++k) {
+      if (!isfinite(e[k])) return PCG_REF_ERR_ROW;
+      ss += (double)e[k] * (double)e[k];
+    }
+    double norm = sqrt(ss);
+    for (int32_t k = 0; k < d; ++k)
+      unit_bf16[(int64_t)v * d + k] = norm > 0.0 ? bf16_round((double)e[k] / norm) : 0;
+  }
+  return PCG_REF_OK;
+}
+
+double pcg_ref_asg_similarity(const uint16_t *unit_bf16, int32_t d, int32_t a, int32_t b) {
+  const uint16_t *x = unit_bf16 + (int64_t)a * d, *y = unit_bf16 + (int64_t)b * d;
+  double s = 0.0;
+  for (int32_t k = 0; k < d; ++k) s += bf16_value(x[k]) * bf16_value(y[k]);
+  return s;
+}
+
+int pcg_ref_asg_row(const uint16_t *unit_bf16, int32_t V, int32_t d, float theta, int32_t t,
+                    int32_t *members_out, int32_t *count, int32_t *near_pairs) {
+  if (!unit_bf16 || !members_out || !count || V < 1 || d < 1 || t < 0 || t >= V)
+    return PCG_REF_ERR_ARG;
+  int32_t n = 0, near = 0;
+  for (int32_t v = 0; v < V; ++v) {
+    if (v == t) { members_out[n++] = v; continue; }
+    double s = pcg_ref_asg_similarity(unit_bf16, d, t, v);
+    if (s > (double)theta) members_out[n++] = v;              /* Eq. (1) */
+    if (fabs(s - (double)theta) < PCG_REF_ASG_NEAR) ++near;
+  }
+  *count = n;
+  if (near_pairs) *near_pairs = near;
+  return PCG_REF_OK;
+}
+
+int pcg_ref_asg_build(const uint16_t *unit_bf16, int32_t V, int32_t d, float theta,
+                      int32_t *out_G, int64_t *out_nnz, int32_t *row_ptr, int32_t *members,
+                      int64_t members_capacity, int32_t *mult, int32_t *seed_of,
+                      uint8_t *near_rows, int32_t nthreads) {
+  if (!unit_bf16 || !out_G || !out_nnz || !row_ptr || !members || !mult || V < 1 || d < 1 ||
+      members_capacity < 0)
+    return PCG_REF_ERR_ARG;
+  if (nthreads < 1) nthreads = 1;
+  /* every token's set, then the distinct ones in order of first appearance */
+  int32_t **set = (int32_t **)calloc((size_t)V, sizeof(int32_t *));
+  int32_t *size = (int32_t *)calloc((size_t)V, sizeof(int32_t));
+  uint8_t *kept = (uint8_t *)calloc((size_t)V, 1);
+  int status = (set && size && kept) ? PCG_REF_OK : PCG_REF_ERR_NOMEM;
+  if (status == PCG_REF_OK) {
+#ifdef _OPENMP
+#pragma omp parallel for num_threads(nthreads) schedule(dynamic, 8)
+#endif
+    for (int32_t t = 0; t < V; ++t) {
+      int32_t *buf = (int32_t *)malloc((size_t)V * sizeof(int32_t));
+      int32_t n = 0, near = 0;
+      if (!buf || pcg_ref_asg_row(unit_bf16, V, d, theta, t, buf, &n, &near)) {
+#ifdef _OPENMP
+#pragma omp critical
+#endif
+        status = PCG_REF_ERR_NOMEM;
+        free(buf);
+        continue;
+      }
+      set[t] = (int32_t *)realloc(buf, (size_t)n * sizeof(int32_t));
+      size[t] = n;
+      if (near_rows) near_rows[t] = near > 0;
+    }
+  }
+  int32_t G = 0;
+  int64_t nnz = 0;
+  if (status == PCG_REF_OK) {
+    for (int32_t t = 0; t < V; ++t) {
+      int dup = 0;
+      for (int32_t s = 0; s < t && !dup; ++s)
+        dup = kept[s] && size[s] == size[t] &&
+              memcmp(set[s], set[t], (size_t)size[t] * sizeof(int32_t)) == 0;
+      kept[t] = !dup;
+      if (!dup) { ++G; nnz += size[t]; }
+    }
+    *out_G = G;
+    *out_nnz = nnz;
+    if (nnz > members_capacity) {
+      status = PCG_REF_ERR_NOMEM;
+    } else {
+      for (int32_t v = 0; v < V; ++v) mult[v] = 0;
+      int32_t g = 0;
+      row_ptr[0] = 0;
+      for (int32_t t = 0; t < V; ++t) {
+        if (!kept[t]) continue;
+        memcpy(members + row_ptr[g], set[t], (size_t)size[t] * sizeof(int32_t));
+        for (int32_t j = 0; j < size[t]; ++j) mult[set[t][j]] += 1;
+        if (seed_of) seed_of[g] = t;
+        row_ptr[g + 1] = row_ptr[g] + size[t];
+        ++g;
+      }
+    }
+  }
+  if (set) for (int32_t t = 0; t < V; ++t) free(set[t]);
+  free(set); free(size); free(kept);
+  return status;
+}

@@ -18,6 +18,8 @@
  *   - Philox4x32-10 counter-based generator   (Salmon et al., SC'11)
  *   - residual sampling by thinning           (Eq. 9)
  *   - draft-side proposal coupling            (Eq. 6)
+ *   - general per-entry weights               (Eq. 2, Eq. 4)
+ *   - similarity-group construction           (Sec. 2.1, Eq. 1)
  *
  * Naming: the paper's body calls the target model q and the draft p, its group
  * distributions Q_c (target) and P_c (draft).  To keep the two apart this file
@@ -280,6 +282,44 @@ int pcg_ref_propose(int32_t V, int32_t G, const int32_t *mult, const int32_t *to
                     int32_t K, int32_t pos0, int64_t dft_batch_stride, int64_t dft_pos_stride,
                     double temperature, uint64_t seed, uint64_t offset, int32_t *prop_tokens,
                     int32_t *prop_groups, uint8_t *near, int32_t nthreads);
+
+/* ------------------------------------------------------------------------- */
+/* Acoustic Similarity Groups (Sec. 2.1, Eq. 1): the group of token t is every  */
+/* token whose embedding has cosine similarity above theta with t's; the group  */
+/* set is the collection of distinct such sets.                                 */
+/* ------------------------------------------------------------------------- */
+
+/* Width of the band around theta inside which a pair's similarity is reported as
+ * a near-tie of the membership decision. */
+#define PCG_REF_ASG_NEAR 1e-5
+
+/* unit[v][k] = emb[v][k] / ||emb[v]||, computed in double and rounded once to
+ * bfloat16 (nearest, ties to even); an all-zero row stays zero. */
+int pcg_ref_asg_normalize(const float *emb, int32_t V, int32_t d, uint16_t *unit_bf16);
+
+/* cos of tokens a and b: the double-precision dot product of their bf16 unit
+ * vectors (the vectors are taken as given: the similarity both sides threshold
+ * is that of the stored bf16 values). */
+double pcg_ref_asg_similarity(const uint16_t *unit_bf16, int32_t d, int32_t a, int32_t b);
+
+/* Members of G(t), ascending: every v with similarity(t, v) > theta, and t itself
+ * (its similarity with itself is 1 up to the bf16 rounding of the unit vector).
+ * members_out [V]; *near_pairs (may be NULL) counts the v != t whose similarity
+ * is within PCG_REF_ASG_NEAR of theta. */
+int pcg_ref_asg_row(const uint16_t *unit_bf16, int32_t V, int32_t d, float theta, int32_t t,
+                    int32_t *members_out, int32_t *count, int32_t *near_pairs);
+
+/* All groups: G(t) for t = 0 .. V-1, keeping each distinct set once, in order of
+ * first appearance; CSR with members ascending, mult = entry counts.  row_ptr
+ * [V+1] (the first *out_G + 1 entries are written), members [members_capacity],
+ * mult [V], seed_of [V] (may be NULL): the token whose group each kept row is.
+ * near_rows [V] (may be NULL): 1 where some pair of row t is a near-tie.  If
+ * *out_nnz exceeds members_capacity the sizes are still returned, nothing else
+ * is written and the status is PCG_REF_ERR_NOMEM: call again with more room. */
+int pcg_ref_asg_build(const uint16_t *unit_bf16, int32_t V, int32_t d, float theta,
+                      int32_t *out_G, int64_t *out_nnz, int32_t *row_ptr, int32_t *members,
+                      int64_t members_capacity, int32_t *mult, int32_t *seed_of,
+                      uint8_t *near_rows, int32_t nthreads);
 
 /* Proposals with general weights: the group label by the inverse CDF of the token's weights
  * at u = k24 / 2^24; near also covers that draw. */

@@ -53,7 +53,8 @@ typedef enum {
   PCG_ERR_WORKSPACE_TOO_SMALL = -6,
   PCG_ERR_BAD_CSR = -7,            /* host validation of the group membership failed        */
   PCG_ERR_HIP = -8,                /* a HIP runtime call failed                             */
-  PCG_ERR_MISALIGNED = -9          /* workspace not 256-byte aligned, logits not element-aligned */
+  PCG_ERR_MISALIGNED = -9,         /* workspace not 256-byte aligned, logits not element-aligned */
+  PCG_ERR_CAPACITY = -10           /* pcg_asg_build: a group or the member array did not fit      */
 } pcg_status;
 
 #define PCG_MAX_K 64               /* largest number of draft positions per step           */
@@ -272,6 +273,45 @@ int pcg_propose(const pcg_groups *groups, const void *draft_logits, pcg_dtype dt
                 void *hip_stream);
 
 size_t pcg_propose_workspace_bytes(int32_t V, int32_t B, int32_t K);
+
+/* ---- construction of the similarity groups ----------------------------------------------- */
+
+/*
+ * unit_bf16[v][k] = emb[v][k] / ||emb[v]|| (Sec. 2.1: the cosine of Eq. 1 is the dot product of
+ * unit vectors), computed in double and rounded once to bfloat16, nearest with ties to even; a
+ * zero row stays zero.  emb DEVICE float [V, d], unit_bf16 DEVICE uint16 [V, d].  Asynchronous
+ * on hip_stream.
+ */
+int pcg_asg_normalize(const float *emb, int32_t V, int32_t d, uint16_t *unit_bf16,
+                      void *hip_stream);
+
+#define PCG_ASG_MAX_CAP 4096
+
+/*
+ * The Acoustic Similarity Groups of Eq. (1): G(t) = every token v whose unit vector has a dot
+ * product with t's above theta (fp32 accumulation of the exact bf16 products), and t itself;
+ * the distinct sets, each once, in order of first appearance (ascending t), as the CSR that
+ * pcg_groups reads: members ascending inside a group, mult = entry counts.
+ *   unit_bf16     DEVICE uint16 [V, d], 16-byte aligned, d a multiple of 64, V * d < 2^31
+ *   theta         strict threshold of Eq. (1); values below -1 put everything in one group
+ *   cap           room for one group while it is collected, 1 .. PCG_ASG_MAX_CAP
+ *   row_ptr       DEVICE int32 [V + 1]: the first *out_G + 1 entries are written
+ *   members       DEVICE int32 [members_capacity]
+ *   mult          DEVICE int32 [V]
+ *   seed_of       DEVICE int32 [V] or NULL: the token whose group each kept row is
+ *   out_G, out_nnz, out_max_size   HOST: groups kept, their total size, the largest G(t) found
+ *   workspace     DEVICE, 256-byte aligned, >= pcg_asg_build_workspace_bytes(V, cap)
+ * Unlike the verification calls this one WAITS for hip_stream: the sizes are returned to the
+ * host.  PCG_ERR_CAPACITY if some G(t) has more than cap members or the groups more than
+ * members_capacity entries (the out_* sizes are valid then, nothing else is: call again with
+ * more room).
+ */
+int pcg_asg_build(const uint16_t *unit_bf16, int32_t V, int32_t d, float theta, int32_t cap,
+                  int32_t *row_ptr, int32_t *members, int64_t members_capacity, int32_t *mult,
+                  int32_t *seed_of, int32_t *out_G, int64_t *out_nnz, int32_t *out_max_size,
+                  void *workspace, size_t workspace_bytes, void *hip_stream);
+
+size_t pcg_asg_build_workspace_bytes(int32_t V, int32_t cap);
 
 /* ---- group membership on the host -------------------------------------------------------- */
 

@@ -94,6 +94,15 @@ def lib() -> C.CDLL:
         L.pcg_groups_reverse_host.restype = C.c_int
         L.pcg_groups_reverse_host.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                               C.c_void_p, C.c_void_p]
+        L.pcg_asg_normalize.restype = C.c_int
+        L.pcg_asg_normalize.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+        L.pcg_asg_build_workspace_bytes.restype = C.c_size_t
+        L.pcg_asg_build_workspace_bytes.argtypes = [C.c_int32, C.c_int32]
+        L.pcg_asg_build.restype = C.c_int
+        L.pcg_asg_build.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_int32, C.c_void_p,
+                                    C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
+                                    C.POINTER(C.c_int32), C.POINTER(C.c_int64), C.POINTER(C.c_int32),
+                                    C.c_void_p, C.c_size_t, C.c_void_p]
         L.pcg_groups_validate_weights_host.restype = C.c_int
         L.pcg_groups_validate_weights_host.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                                        C.c_void_p, C.c_double]
@@ -484,6 +493,63 @@ def propose(groups: Groups, draft_logits: torch.Tensor, *, temperature: float = 
             None if diag is None else diag.data_ptr(), ws.data_ptr(), ws.numel(), _stream(dev)),
             "pcg_propose")
     return prop_tokens, prop_groups
+
+
+ERR_CAPACITY = -10
+
+
+def asg_normalize(emb: torch.Tensor) -> torch.Tensor:
+    """float32 [V, d] embeddings -> bfloat16 unit vectors (Sec. 2.1)."""
+    assert emb.dim() == 2 and emb.dtype == torch.float32 and emb.is_contiguous()
+    unit = torch.empty(emb.shape, dtype=torch.bfloat16, device=emb.device)
+    with torch.cuda.device(emb.device):
+        _check(lib().pcg_asg_normalize(emb.data_ptr(), emb.shape[0], emb.shape[1], unit.data_ptr(),
+                                       _stream(emb.device)), "pcg_asg_normalize")
+    return unit
+
+
+@dataclass
+class AsgGroups:
+    row_ptr: torch.Tensor    # int32 [G + 1]
+    members: torch.Tensor    # int32 [nnz]
+    mult: torch.Tensor       # int32 [V]
+    seed_of: torch.Tensor    # int32 [G]
+    G: int
+    nnz: int
+    max_size: int            # largest G(t) before identical sets were dropped
+
+
+def asg_build(unit: torch.Tensor, theta: float, cap: int = 256,
+              members_capacity: Optional[int] = None) -> AsgGroups:
+    """The distinct similarity groups of Eq. (1) from bfloat16 unit vectors [V, d], as device
+    CSR arrays.  Room for a group (cap) and for all members is enlarged and the call repeated
+    when the library reports that it did not suffice."""
+    assert unit.dim() == 2 and unit.dtype == torch.bfloat16 and unit.is_contiguous()
+    V, d = unit.shape
+    dev = unit.device
+    cap = min(cap, 4096)
+    room = members_capacity or 32 * V
+    G, nnz, largest = C.c_int32(), C.c_int64(), C.c_int32()
+    while True:
+        row_ptr = torch.empty(V + 1, dtype=torch.int32, device=dev)
+        members = torch.empty(room, dtype=torch.int32, device=dev)
+        mult = torch.empty(V, dtype=torch.int32, device=dev)
+        seed_of = torch.empty(V, dtype=torch.int32, device=dev)
+        ws = torch.empty(lib().pcg_asg_build_workspace_bytes(V, cap), dtype=torch.uint8, device=dev)
+        with torch.cuda.device(dev):
+            rc = lib().pcg_asg_build(unit.data_ptr(), V, d, float(theta), cap, row_ptr.data_ptr(),
+                                     members.data_ptr(), room, mult.data_ptr(), seed_of.data_ptr(),
+                                     C.byref(G), C.byref(nnz), C.byref(largest), ws.data_ptr(),
+                                     ws.numel(), _stream(dev))
+        if rc == ERR_CAPACITY and (largest.value > cap or nnz.value > room):
+            if largest.value > 4096:
+                raise PcgError(rc, "pcg_asg_build: a similarity group has more than 4096 members")
+            cap = max(cap, min(4096, largest.value))
+            room = max(room, nnz.value)
+            continue
+        _check(rc, "pcg_asg_build")
+        return AsgGroups(row_ptr[:G.value + 1], members[:nnz.value], mult, seed_of[:G.value],
+                         G.value, nnz.value, largest.value)
 
 
 def profile_begin(max_calls: int):

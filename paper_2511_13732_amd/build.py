@@ -7,7 +7,7 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libpcg.so")
-SOURCES = ["pcg_kernels.hip", "pcg_api.cpp", "pcg_prepare.cpp"]
+SOURCES = ["pcg_kernels.hip", "pcg_asg.hip", "pcg_api.cpp", "pcg_prepare.cpp"]
 HEADERS = ["pcg_kernels.h", "pcg_device.h", "pcg_layout.h", os.path.join("..", "..", "include", "pcg.h")]
 
 HIPCC_FLAGS = [

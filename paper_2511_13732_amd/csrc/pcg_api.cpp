@@ -21,6 +21,14 @@ int hip_fail(hipError_t e) {
   return PCG_ERR_HIP;
 }
 
+}  // namespace
+
+namespace pcg {
+int record_hip_error(hipError_t e) { return hip_fail(e); }
+}  // namespace pcg
+
+namespace {
+
 constexpr size_t kAlign = 256;
 size_t align_up(size_t n) { return (n + kAlign - 1) / kAlign * kAlign; }
 
@@ -616,6 +624,7 @@ const char *pcg_strerror(int status) {
     case PCG_ERR_BAD_CSR: return "group membership is not a valid CSR with matching multiplicities";
     case PCG_ERR_HIP: return "a HIP runtime call failed (see pcg_last_hip_error)";
     case PCG_ERR_MISALIGNED: return "a pointer is not aligned as required";
+    case PCG_ERR_CAPACITY: return "a similarity group or the member array needs more room";
     default: return "unknown status";
   }
 }

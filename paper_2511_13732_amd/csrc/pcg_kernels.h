@@ -45,4 +45,7 @@ hipError_t launch_finalize(const FinalizeArgs &fa, bool bf16, const pcg_groups &
                            const double *csum, int32_t nchunks, int32_t chunk_groups,
                            hipStream_t stream);
 
+// Remembers a HIP error for pcg_last_hip_error and returns PCG_ERR_HIP.
+int record_hip_error(hipError_t e);
+
 }  // namespace pcg

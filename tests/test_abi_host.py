@@ -40,7 +40,7 @@ def test_header_constants_match_binding():
     for name, val in [("PCG_ERR_NULL_ARG", -1), ("PCG_ERR_BAD_SHAPE", -2), ("PCG_ERR_BAD_DTYPE", -3),
                       ("PCG_ERR_BAD_STRIDE", -4), ("PCG_ERR_BAD_TEMPERATURE", -5),
                       ("PCG_ERR_WORKSPACE_TOO_SMALL", -6), ("PCG_ERR_BAD_CSR", -7),
-                      ("PCG_ERR_HIP", -8), ("PCG_ERR_MISALIGNED", -9)]:
+                      ("PCG_ERR_HIP", -8), ("PCG_ERR_MISALIGNED", -9), ("PCG_ERR_CAPACITY", -10)]:
         assert re.search(rf"{name}\s*=\s*{val}\b", text)
         assert pcg.strerror(val) != "unknown status"
     assert re.search(r"PCG_F32 = 0, PCG_BF16 = 1", text) and (pcg.F32, pcg.BF16) == (0, 1)
@@ -311,3 +311,21 @@ def test_weights_host_helpers_match_the_oracle_and_are_checked():
     assert L.pcg_propose(C.byref(half), P, 0, 2, 2, 0, 128, 64, 1.0, 0, 0, P, P, None, P, 1 << 30, None) == NULL_ARG
     assert L.pcg_verify_thinning(C.byref(half), P, P, 0, 2, 2, 192, 64, 128, 64, 1.0, P, P, 0, 0,
                                  P, P, P, P, None, P, 1 << 30, None) == NULL_ARG
+
+
+def test_asg_argument_checks():
+    L = pcg.lib()
+    g, n, m = C.c_int32(), C.c_int64(), C.c_int32()
+    build = lambda **k: L.pcg_asg_build(k.get("unit", P), k.get("V", 256), k.get("d", 128), k.get("theta", 0.4),
+                                        k.get("cap", 64), P, P, k.get("room", 1000), P, None, C.byref(g),
+                                        C.byref(n), C.byref(m), k.get("ws", P), k.get("wsb", 1 << 30), None)
+    assert build(unit=None) == NULL_ARG
+    assert build(d=100) == BAD_SHAPE                  # d must be a multiple of 64
+    assert build(cap=0) == BAD_SHAPE and build(cap=5000) == BAD_SHAPE
+    assert build(theta=float("nan")) == BAD_SHAPE
+    assert build(V=1 << 22, d=1024) == BAD_SHAPE      # V * d beyond 2^31
+    assert build(unit=P + 2) == MISALIGNED
+    assert build(wsb=pcg.lib().pcg_asg_build_workspace_bytes(256, 64) - 1) == WS_SMALL
+    assert L.pcg_asg_normalize(None, 4, 4, P, None) == NULL_ARG
+    assert L.pcg_asg_normalize(P, 0, 4, P, None) == BAD_SHAPE
+    assert pcg.lib().pcg_asg_build_workspace_bytes(256, 5000) == 0

@@ -32,10 +32,10 @@ LDS_PEAK_GBS = 256 * 128 * 2.4     # 256 CUs x 128 B/clk x 2.4 GHz = 78 643 GB/s
 # HBM bytes per launch measured with rocprofv3 --pmc on this workload (FETCH_SIZE and
 # WRITE_SIZE in KiB per dispatch, each scaled by what the same counter reads for a plain device
 # copy of 256 MiB: FETCH_SIZE reads 131 085 for 262 144 KiB, factor 2.000; WRITE_SIZE reads
-# 262 144, factor 1.000).  Source: profiles/pcg_verify_C4_hbm_traffic.md.
+# 262 144, factor 1.000).  Source: profiles/pcg_C4_hbm_traffic.md.
 MEASURED_TRAFFIC_BYTES = {
-    "row_stats@C4": int((69660.5 * 2.000 + 544.8) * 1024),
-    "gather@C4": int((28586.7 * 2.000 + 21506.0) * 1024),
+    "row_stats@C4": int((69665.0 * 2.000 + 544.7) * 1024),
+    "gather@C4": int((28584.3 * 2.000 + 21506.0) * 1024),
 }
 
 
@@ -47,6 +47,7 @@ def parse_args():
     ap.add_argument("--config", default="C4", help="workload recipe (C1..C5); C4 is the headline")
     ap.add_argument("--sets", type=int, default=3, help="distinct input sets rotated through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-asg", action="store_true", help="skip the timing of the group construction")
     ap.add_argument("--cpu-seconds", type=float, default=12.0,
                     help="lower bound on the CPU oracle's timed work")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -271,6 +272,30 @@ def main():
         "ms_per_call": round(1e3 * prop_elapsed / args.steps, 5),
         "stages_us": {k: round(1e3 * v, 2) for k, v in prop_ms.items()
                       if v > 0.0 and k != "event_overhead"}}
+
+    # Construction of the similarity groups (Eq. 1) from the recipe's embeddings: a one-off
+    # precomputation, timed whole (the call waits for its stream).  Its contraction needs the
+    # V (V + 1) / 2 distinct pairs once: 2 d flops each.
+    if not args.no_asg:
+        emb = torch.from_numpy(W.embeddings(cfg)).to(dev)
+        theta = 3.36 / np.sqrt(cfg.emb_dim)       # iid embeddings: groups of a few tens of tokens
+        unit = pcg.asg_normalize(emb)
+        asg = pcg.asg_build(unit, theta, cap=128)             # warm-up, and finds the room needed
+        torch.cuda.synchronize()
+        reps = 5
+        t_begin = time.perf_counter()
+        for _ in range(reps):
+            asg = pcg.asg_build(unit, theta, cap=max(128, asg.max_size), members_capacity=asg.nnz)
+        asg_s = (time.perf_counter() - t_begin) / reps
+        flops = 2.0 * cfg.emb_dim * cfg.V * (cfg.V + 1) / 2
+        result["asg_build"] = {
+            "ms": round(1e3 * asg_s, 3), "theta": round(float(theta), 4), "groups": asg.G,
+            "entries": asg.nnz, "largest": asg.max_size,
+            "roofline": {"bound": "mfma", "achieved": round(flops / asg_s / 1e12, 1), "peak": 2500.0,
+                         "unit": "TFLOP/s", "frac": round(flops / asg_s / 2.5e15, 4), "dtype": "bf16",
+                         "note": "whole call (similarity, sort, de-duplication, compaction); "
+                                 "algorithmic flops d V (V + 1)"}}
+        del emb, unit, asg
 
     if not args.no_cpu_baseline:
         import oracle

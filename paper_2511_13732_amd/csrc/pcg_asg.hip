@@ -184,7 +184,7 @@ __global__ __launch_bounds__(kSimThreads) void asg_similarity_kernel(
 // Per token: members ascending (bitonic sort in LDS), a hash of the set, its size.
 // ---------------------------------------------------------------------------------------------
 
-constexpr int kSortThreads = 256;
+constexpr int kSortThreads = 256;             // four waves, one token each
 constexpr int kAsgMaxCap = PCG_ASG_MAX_CAP;
 
 __device__ __forceinline__ uint64_t mix64(uint64_t x) {   // splitmix64 finaliser
@@ -194,24 +194,36 @@ __device__ __forceinline__ uint64_t mix64(uint64_t x) {   // splitmix64 finalise
   return x ^ (x >> 31);
 }
 
-__global__ __launch_bounds__(kSortThreads) void asg_sort_kernel(int32_t V, int32_t cap,
+// Makes a wave's LDS writes visible to its own later reads (no other wave shares the data).
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// One wave per token: its members ascending (bitonic sort in the wave's own slice of LDS), an
+// order-independent hash of the set, its size.  cap2 = cap rounded up to a power of two; the
+// kernel is launched with 4 * cap2 * 4 bytes of dynamic LDS.
+__global__ __launch_bounds__(kSortThreads) void asg_sort_kernel(int32_t V, int32_t cap, int32_t cap2,
                                                                 const int32_t *count, int32_t *cand,
                                                                 int32_t *size, uint64_t *hash,
                                                                 int32_t *max_count) {
-  __shared__ int32_t key[kAsgMaxCap];
-  __shared__ uint64_t part[kSortThreads / kWave];
-  const int32_t t = blockIdx.x;
+  extern __shared__ int32_t sort_lds[];
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+  const int32_t t = blockIdx.x * (kSortThreads / kWave) + wave;
+  if (t >= V) return;                       // whole waves leave together; no workgroup barrier below
+  int32_t *key = sort_lds + wave * cap2;
   const int32_t found = count[t];
   const int32_t n = min(found, cap);
-  if (threadIdx.x == 0) atomicMax(max_count, found);
+  if (lane == 0) atomicMax(max_count, found);
   int32_t n2 = 1;
   while (n2 < n) n2 <<= 1;
   int32_t *row = cand + (int64_t) t * cap;
-  for (int32_t k = threadIdx.x; k < n2; k += kSortThreads) key[k] = k < n ? row[k] : INT32_MAX;
-  __syncthreads();
+  for (int32_t k = lane; k < n2; k += kWave) key[k] = k < n ? row[k] : INT32_MAX;
+  wave_lds_sync();
   for (int32_t len = 2; len <= n2; len <<= 1)
     for (int32_t step = len >> 1; step > 0; step >>= 1) {
-      for (int32_t k = threadIdx.x; k < n2; k += kSortThreads) {
+      for (int32_t k = lane; k < n2; k += kWave) {
         const int32_t other = k ^ step;
         if (other > k) {
           const bool up = (k & len) == 0;
@@ -219,22 +231,17 @@ __global__ __launch_bounds__(kSortThreads) void asg_sort_kernel(int32_t V, int32
           if ((x > y) == up) { key[k] = y; key[other] = x; }
         }
       }
-      __syncthreads();
+      wave_lds_sync();
     }
   uint64_t h = 0;
-  for (int32_t k = threadIdx.x; k < n; k += kSortThreads) {
+  for (int32_t k = lane; k < n; k += kWave) {
     row[k] = key[k];
     h += mix64((uint64_t) key[k]);
   }
-  // order-independent sum over the workgroup
 #pragma unroll
   for (int o = kWave / 2; o > 0; o >>= 1) h += __shfl_xor(h, o, kWave);
-  if ((threadIdx.x & (kWave - 1)) == 0) part[threadIdx.x >> 6] = h;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    uint64_t tot = 0;
-    for (int w = 0; w < kSortThreads / kWave; ++w) tot += part[w];
-    hash[t] = tot;
+  if (lane == 0) {
+    hash[t] = h;
     size[t] = n;
   }
 }
@@ -263,39 +270,40 @@ __global__ __launch_bounds__(256) void asg_dedup_kernel(int32_t V, int32_t cap, 
   if (lane == 0) keep[t] = !dup;
 }
 
-// Exclusive scans over the tokens by one workgroup: gid[t] = kept tokens before t, off[t] =
-// members of kept tokens before t; totals[0] = G, totals[1] = nnz.
+// Exclusive scans over the tokens by one workgroup, 1024 tokens at a time: gid[t] = kept tokens
+// before t, off[t] = members of kept tokens before t; totals[0] = G, totals[1] = nnz.  The
+// counts stay below 2^31, so they are exact in the double the wave scan works on.
 constexpr int kScanThreads = 1024;
 
 __global__ __launch_bounds__(kScanThreads) void asg_scan_kernel(int32_t V, const int32_t *keep,
                                                                 const int32_t *size, int32_t *gid,
                                                                 int64_t *off, int64_t *totals) {
-  __shared__ int64_t sg[kScanThreads], sn[kScanThreads];
-  const int32_t per = (V + kScanThreads - 1) / kScanThreads;
-  const int32_t lo = min(V, (int32_t) threadIdx.x * per), hi = min(V, lo + per);
-  int64_t g = 0, n = 0;
-  for (int32_t t = lo; t < hi; ++t)
-    if (keep[t]) { ++g; n += size[t]; }
-  sg[threadIdx.x] = g;
-  sn[threadIdx.x] = n;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    int64_t ag = 0, an = 0;
-    for (int k = 0; k < kScanThreads; ++k) {
-      const int64_t cg = sg[k], cn = sn[k];
-      sg[k] = ag; sn[k] = an;
-      ag += cg; an += cn;
+  __shared__ double wg[kScanThreads / kWave], wn[kScanThreads / kWave];
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+  double base_g = 0.0, base_n = 0.0;
+  for (int32_t t0 = 0; t0 < V; t0 += kScanThreads) {
+    const int32_t t = t0 + threadIdx.x;
+    const bool k = t < V && keep[t] != 0;
+    const double g = k ? 1.0 : 0.0, n = k ? (double) size[t] : 0.0;
+    const double ig = wave_scan(g), in = wave_scan(n);
+    if (lane == kWave - 1) { wg[wave] = ig; wn[wave] = in; }
+    __syncthreads();
+    double bg = base_g, bn = base_n, tg = 0.0, tn = 0.0;
+    for (int w = 0; w < kScanThreads / kWave; ++w) {
+      if (w == wave) { bg += tg; bn += tn; }
+      tg += wg[w]; tn += wn[w];
     }
-    totals[0] = ag;
-    totals[1] = an;
+    if (t < V) {
+      gid[t] = (int32_t) (bg + ig - g);
+      off[t] = (int64_t) (bn + in - n);
+    }
+    base_g += tg;
+    base_n += tn;
+    __syncthreads();
   }
-  __syncthreads();
-  g = sg[threadIdx.x];
-  n = sn[threadIdx.x];
-  for (int32_t t = lo; t < hi; ++t) {
-    gid[t] = (int32_t) g;
-    off[t] = n;
-    if (keep[t]) { ++g; n += size[t]; }
+  if (threadIdx.x == 0) {
+    totals[0] = (int64_t) base_g;
+    totals[1] = (int64_t) base_n;
   }
 }
 
@@ -393,8 +401,10 @@ int pcg_asg_build(const uint16_t *unit_bf16, int32_t V, int32_t d, float theta, 
   asg_similarity_kernel<<<dim3(tiles, tiles), kSimThreads, 0, stream>>>(unit_bf16, V, d, theta, cap,
                                                                         count, cand);
   if ((e = hipGetLastError()) != hipSuccess) return fail(e);
-  asg_sort_kernel<<<(unsigned) V, kSortThreads, 0, stream>>>(V, cap, count, cand, size, hash,
-                                                             (int32_t *) (totals + 2));
+  int32_t cap2 = 1;
+  while (cap2 < cap) cap2 <<= 1;
+  asg_sort_kernel<<<wb, kSortThreads, (size_t) (kSortThreads / kWave) * cap2 * sizeof(int32_t), stream>>>(
+      V, cap, cap2, count, cand, size, hash, (int32_t *) (totals + 2));
   asg_dedup_kernel<<<wb, 256, 0, stream>>>(V, cap, cand, size, hash, keep);
   asg_scan_kernel<<<1, kScanThreads, 0, stream>>>(V, keep, size, gid, off, totals);
   if ((e = hipGetLastError()) != hipSuccess) return fail(e);

@@ -947,12 +947,7 @@ __device__ CdfPick block_inverse_cdf(int32_t n, F f, double u, bool have_goal = 
     }
   }
   // inclusive scan inside the wave, then across waves
-  double inc = mine;
-#pragma unroll
-  for (int o = 1; o < kWave; o <<= 1) {
-    const double up = __shfl_up(inc, o, kWave);
-    if (lane >= o) inc += up;
-  }
+  const double inc = wave_scan(mine);
   if (lane == kWave - 1) wave_tot[wave] = inc;
   __syncthreads();
   double before = 0.0, total = 0.0;

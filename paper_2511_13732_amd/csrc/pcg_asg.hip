@@ -215,7 +215,9 @@ __global__ __launch_bounds__(kSortThreads) void asg_sort_kernel(int32_t V, int32
   int32_t *key = sort_lds + wave * cap2;
   const int32_t found = count[t];
   const int32_t n = min(found, cap);
-  if (lane == 0) atomicMax(max_count, found);
+  // the largest set found so far: read first, since 65 536 atomics on one word take longer
+  // than the sort itself
+  if (lane == 0 && found > __atomic_load_n(max_count, __ATOMIC_RELAXED)) atomicMax(max_count, found);
   int32_t n2 = 1;
   while (n2 < n) n2 <<= 1;
   int32_t *row = cand + (int64_t) t * cap;

@@ -36,6 +36,7 @@ size_t align_up(size_t n) { return (n + kAlign - 1) / kAlign * kAlign; }
 
 enum Stage { kStageStats = 0, kStageAccept, kStageTable, kStageGather, kStageFinalize, kStageThin,
              kStagePropose, kStageNull, kNumStages };
+static_assert(kNumStages <= PCG_MAX_STAGES, "pcg_profile_end writes PCG_MAX_STAGES floats");
 const char *const kStageNames[kNumStages] = {"row_stats", "accept_delta", "weights", "gather", "finalize",
                                              "accept_thin", "propose", "event_overhead"};
 

@@ -20,8 +20,19 @@ import torch
 import oracle
 import paper_2511_13732_amd as pcg
 
-REPORT = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out",
-                      "parity_report.jsonl")
+# Every tally is printed; with PCG_PARITY_REPORT set it is also appended to that file (JSON lines).
+REPORT = os.environ.get("PCG_PARITY_REPORT", "")
+
+
+def _append_report(rec: dict):
+    if not REPORT:
+        return
+    try:
+        os.makedirs(os.path.dirname(os.path.abspath(REPORT)), exist_ok=True)
+        with open(REPORT, "a") as f:
+            f.write(json.dumps(rec) + "\n")
+    except OSError:
+        pass
 
 
 @dataclass
@@ -43,24 +54,14 @@ class Tally:
                "flagged_group": self.flagged_group, "flagged_token": self.flagged_token,
                "tolerated_mismatches": self.tolerated, "detail": self.detail[:20]}
         print("parity", json.dumps(rec), flush=True)
-        try:
-            os.makedirs(os.path.dirname(REPORT), exist_ok=True)
-            with open(REPORT, "a") as f:
-                f.write(json.dumps(rec) + "\n")
-        except OSError:
-            pass
+        _append_report(rec)
 
 
 def report_error(name: str, err: float):
     """Record a measured group-probability error next to the tallies."""
     rec = {"case": name, "max_rel_err": err}
     print("parity", json.dumps(rec), flush=True)
-    try:
-        os.makedirs(os.path.dirname(REPORT), exist_ok=True)
-        with open(REPORT, "a") as f:
-            f.write(json.dumps(rec) + "\n")
-    except OSError:
-        pass
+    _append_report(rec)
 
 
 def oracle_groups(V: int, row_ptr, members) -> oracle.Groups:

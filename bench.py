@@ -215,6 +215,38 @@ def main():
                       if v > 0.0 and k != "event_overhead"},
         "mean_trials_per_rejection_last_step": round(float(tr[tr > 0].mean()) if (tr > 0).any() else 0.0, 2)}
 
+    # pcg_group_probs (Eq. 5 for every group) on the step's B (K+1) target rows: reads every logit
+    # of those rows once and writes rows x G floats.
+    gp_rows = cfg.B * (cfg.K + 1)
+    gp_out = torch.empty((gp_rows, groups.G), dtype=torch.float32, device=dev)
+    gp_ws = torch.empty(pcg.group_probs_workspace_bytes(cfg.V, gp_rows), dtype=torch.uint8, device=dev)
+
+    def gp_step(i):
+        pcg.group_probs(groups, sets[i % len(sets)][0].view(gp_rows, cfg.V), cfg.temperature,
+                        out=gp_out, workspace=gp_ws)
+
+    gp_steps = max(10, args.steps // 3)
+    for i in range(5):
+        gp_step(i)
+    torch.cuda.synchronize()
+    t_begin = time.perf_counter()
+    for i in range(gp_steps):
+        gp_step(i)
+    torch.cuda.synchronize()
+    gp_s = (time.perf_counter() - t_begin) / gp_steps
+    pcg.profile_begin(gp_steps)
+    for i in range(gp_steps):
+        gp_step(i)
+    torch.cuda.synchronize()
+    gp_ms, _ = pcg.profile_end()
+    gp_bytes = (2 if cfg.dtype == "bf16" else 4) * gp_rows * cfg.V + 4 * gp_rows * groups.G
+    result["group_probs"] = {
+        "rows": gp_rows, "ms_per_call": round(1e3 * gp_s, 4),
+        "rows_per_s": round(gp_rows / gp_s, 1),
+        "algorithmic_bytes": gp_bytes, "hbm_frac": round(gp_bytes / gp_s / 1e9 / HBM_PEAK_GBS, 4),
+        "stages_us": {k: round(1e3 * v, 2) for k, v in gp_ms.items() if v > 0.0 and k != "event_overhead"}}
+    del gp_out, gp_ws
+
     # General per-entry weights (Eq. 2) instead of the equal split: the membership is then read
     # from the CSR (the prepared form holds no weights).
     wgroups = pcg.Groups.from_csr(cfg.V, rp, mem, dev, reverse=True,

@@ -30,6 +30,70 @@ bool make_shape(int32_t V, int32_t G, int32_t chunk_groups, Shape &s) {
   return true;
 }
 
+// Local search on a half-wave's schedule out[n][32].  The LDS serves a half-wave's read in as
+// many passes as the most loaded bank has lanes, so the cost of a time slot is that maximum.
+// A lane may read its own entries in any order: two of its time slots are exchanged whenever
+// that lowers the summed cost; a padding entry moves to the emptiest zero slot of the time
+// slot it lands in.  Repeated until a sweep finds nothing.
+void improve_schedule(std::vector<uint16_t> &out, int n, uint16_t pad_base) {
+  std::vector<int> use((size_t) n * kBanks, 0);        // lanes on bank b at slot t
+  auto bank = [&](int t, int l) { return out[(size_t) t * 32 + l] % kBanks; };
+  // passes of a slot, and as a tie-break the sum of squared bank loads (flatter slots are the
+  // ones that can lose a pass next)
+  auto peak = [&](const int *u) {
+    int m = 0, sq = 0;
+    for (int k = 0; k < kBanks; ++k) { m = std::max(m, u[k]); sq += u[k] * u[k]; }
+    return m * 4096 + sq;
+  };
+  for (int t = 0; t < n; ++t)
+    for (int l = 0; l < 32; ++l) ++use[(size_t) t * kBanks + bank(t, l)];
+  std::vector<int> cost(n);
+  for (int t = 0; t < n; ++t) cost[t] = peak(&use[(size_t) t * kBanks]);
+  for (int sweep = 0; sweep < 12; ++sweep) {
+    bool changed = false;
+    for (int t = 0; t < n; ++t) {
+      if (cost[t] < 2 * 4096) continue;
+      for (int l = 0; l < 32; ++l) {
+        int *ut = &use[(size_t) t * kBanks];
+        const int b = bank(t, l);
+        if (ut[b] < 2) continue;                                  // alone on its bank
+        const bool pad_t = out[(size_t) t * 32 + l] >= pad_base;
+        int best = -1, best_gain = 0, best_bt = 0, best_bu = 0;
+        for (int u = 0; u < n; ++u) {
+          if (u == t) continue;
+          int *uu = &use[(size_t) u * kBanks];
+          const int c = bank(u, l);
+          const bool pad_u = out[(size_t) u * 32 + l] >= pad_base;
+          --ut[b]; --uu[c];
+          int bt = c, bu = b;
+          if (pad_u) { bt = 0; for (int k = 1; k < kBanks; ++k) if (ut[k] < ut[bt]) bt = k; }
+          if (pad_t) { bu = 0; for (int k = 1; k < kBanks; ++k) if (uu[k] < uu[bu]) bu = k; }
+          ++ut[bt]; ++uu[bu];
+          const int gain = cost[t] + cost[u] - peak(ut) - peak(uu);
+          --ut[bt]; --uu[bu];
+          ++ut[b]; ++uu[c];
+          if (gain > best_gain) { best_gain = gain; best = u; best_bt = bt; best_bu = bu; }
+        }
+        if (best < 0) continue;
+        const int u = best, c = bank(u, l);
+        int *uu = &use[(size_t) u * kBanks];
+        const bool pad_u = out[(size_t) u * 32 + l] >= pad_base;
+        uint16_t to_t = out[(size_t) u * 32 + l], to_u = out[(size_t) t * 32 + l];
+        if (pad_u) to_t = (uint16_t) (pad_base + best_bt);
+        if (pad_t) to_u = (uint16_t) (pad_base + best_bu);
+        --ut[b]; --uu[c];
+        out[(size_t) t * 32 + l] = to_t;
+        out[(size_t) u * 32 + l] = to_u;
+        ++ut[to_t % kBanks]; ++uu[to_u % kBanks];
+        cost[t] = peak(ut);
+        cost[u] = peak(uu);
+        changed = true;
+      }
+    }
+    if (!changed) break;
+  }
+}
+
 // Order in which a half-wave (32 lanes, one group each) reads its lists, chosen so that the 32
 // addresses of a time slot fall into different LDS banks wherever that is possible.  lists[l]
 // holds lane l's tile-local slots; every lane gets exactly n entries back, its own slots plus
@@ -84,6 +148,57 @@ void schedule_half_wave(std::vector<uint16_t> (&lists)[32], int n, uint16_t pad_
       out[(size_t) t * 32 + l] = (uint16_t) (pad_base + b);
     }
   }
+  improve_schedule(out, n, pad_base);
+}
+
+// Reorders, block by block, the chunk's groups in `order` (sorted by list length, longest
+// first): each block's groups are dealt to its half-waves of 32 positions one after the other,
+// every group to the half-wave whose banks it loads most evenly (least growth of the sum of
+// squared bank loads over the tiles).
+void balance_blocks(std::vector<int32_t> &order, int32_t g0, const Shape &sh, const int32_t *row_ptr,
+                    const int32_t *members) {
+  const int32_t T = sh.ntiles, ng = (int32_t) order.size();
+  constexpr int kHalf = 32, kDomains = kBlockGroups / kHalf;
+  std::vector<int> load((size_t) kDomains * T * kBanks), hist((size_t) T * kBanks), peak(kDomains * T);
+  std::vector<int32_t> placed(kBlockGroups);
+  for (int32_t b0 = 0; b0 < ng; b0 += kBlockGroups) {
+    const int32_t nb = std::min(kBlockGroups, ng - b0);
+    const int ndom = (nb + kHalf - 1) / kHalf;
+    std::fill(load.begin(), load.end(), 0);
+    std::fill(peak.begin(), peak.end(), 0);
+    int fill[kDomains] = {0};
+    for (int32_t i = 0; i < nb; ++i) {
+      const int32_t k = order[b0 + i];
+      std::fill(hist.begin(), hist.end(), 0);
+      for (int32_t j = row_ptr[g0 + k]; j < row_ptr[g0 + k + 1]; ++j) {
+        const int32_t h = members[j] / sh.tile_len;
+        ++hist[(size_t) h * kBanks + (members[j] - h * sh.tile_len) % kBanks];
+      }
+      int best = -1;
+      long best_cost = 0;
+      for (int d = 0; d < ndom; ++d) {
+        if (fill[d] >= std::min(kHalf, nb - d * kHalf)) continue;
+        // growth of the sum of squared bank loads (up to a constant): flattens every bank, not
+        // only the fullest; ties go to the emptier half-wave
+        long dot = 0;
+        for (int32_t h = 0; h < T; ++h) {
+          const int *ld = &load[((size_t) d * T + h) * kBanks], *hg = &hist[(size_t) h * kBanks];
+          for (int b = 0; b < kBanks; ++b) dot += (long) ld[b] * hg[b];
+        }
+        const long cost = dot * 64 + fill[d];
+        if (best < 0 || cost < best_cost) { best = d; best_cost = cost; }
+      }
+      for (int32_t h = 0; h < T; ++h) {
+        int *ld = &load[((size_t) best * T + h) * kBanks];
+        for (int b = 0; b < kBanks; ++b) {
+          ld[b] += hist[(size_t) h * kBanks + b];
+          peak[best * T + h] = std::max(peak[best * T + h], ld[b]);
+        }
+      }
+      placed[best * kHalf + fill[best]++] = k;
+    }
+    for (int32_t i = 0; i < nb; ++i) order[b0 + i] = placed[i];
+  }
 }
 
 // Builds the layout; with blob == nullptr only sizes are computed.
@@ -126,7 +241,12 @@ int build(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members,
       }
       return false;
     });
-    for (int32_t k = 0; k < ng; ++k)     // sorted position k = block * 256 + r * 64 + lane
+    // Position k = block * 256 + r * 64 + lane.  The 32 groups of a half-wave (positions
+    // 32 i .. 32 i + 31 of a block) are read together, and what that costs grows with the load of
+    // their fullest bank; inside a block the groups are therefore dealt to the half-waves so as
+    // to keep those bank loads flat, in every tile.
+    balance_blocks(order, g0, sh, row_ptr, members);
+    for (int32_t k = 0; k < ng; ++k)
       perm[(size_t) c * BPC * kBlockGroups + k] = (uint16_t) order[k];
     for (int32_t bl = 0; bl < BPC; ++bl) {
       for (int32_t h = 0; h < T; ++h) {

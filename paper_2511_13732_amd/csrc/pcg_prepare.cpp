@@ -31,62 +31,80 @@ bool make_shape(int32_t V, int32_t G, int32_t chunk_groups, Shape &s) {
 }
 
 // Local search on a half-wave's schedule out[n][32].  The LDS serves a half-wave's read in as
-// many passes as the most loaded bank has lanes, so the cost of a time slot is that maximum.
-// A lane may read its own entries in any order: two of its time slots are exchanged whenever
-// that lowers the summed cost; a padding entry moves to the emptiest zero slot of the time
-// slot it lands in.  Repeated until a sweep finds nothing.
+// many passes as the most loaded bank has lanes, so the cost of a time slot is that maximum
+// (with the sum of squared bank loads as a tie-break: flatter slots are the ones that can lose
+// a pass next).  A lane may read its own entries in any order: two of its time slots are
+// exchanged whenever that lowers the summed cost; a padding entry moves to the emptiest zero
+// slot of the time slot it lands in.  Repeated until a sweep finds nothing.
+struct SlotLoad {
+  int use[kBanks];     // lanes on each bank
+  int mx, nmx, sq;     // fullest bank, how many banks are that full, sum of squares
+  void recount() {
+    mx = 0; nmx = 0; sq = 0;
+    for (int k = 0; k < kBanks; ++k) {
+      sq += use[k] * use[k];
+      if (use[k] > mx) { mx = use[k]; nmx = 1; } else if (use[k] == mx) ++nmx;
+    }
+  }
+  int cost() const { return mx * 4096 + sq; }
+  // cost after one lane leaves bank `from` and one arrives on bank `to`
+  int cost_moved(int from, int to) const {
+    if (from == to) return cost();
+    const int peak_left = (use[from] == mx && nmx == 1) ? mx - 1 : mx;
+    const int peak = std::max(peak_left, use[to] + 1);
+    return peak * 4096 + sq - (2 * use[from] - 1) + (2 * use[to] + 1);
+  }
+  int emptiest_without(int from) const {     // emptiest bank once a lane has left `from`
+    int best = 0, bl = use[0] - (from == 0);
+    for (int k = 1; k < kBanks; ++k) {
+      const int l = use[k] - (from == k);
+      if (l < bl) { bl = l; best = k; }
+    }
+    return best;
+  }
+};
+
 void improve_schedule(std::vector<uint16_t> &out, int n, uint16_t pad_base) {
-  std::vector<int> use((size_t) n * kBanks, 0);        // lanes on bank b at slot t
+  std::vector<SlotLoad> slot(n);
   auto bank = [&](int t, int l) { return out[(size_t) t * 32 + l] % kBanks; };
-  // passes of a slot, and as a tie-break the sum of squared bank loads (flatter slots are the
-  // ones that can lose a pass next)
-  auto peak = [&](const int *u) {
-    int m = 0, sq = 0;
-    for (int k = 0; k < kBanks; ++k) { m = std::max(m, u[k]); sq += u[k] * u[k]; }
-    return m * 4096 + sq;
-  };
-  for (int t = 0; t < n; ++t)
-    for (int l = 0; l < 32; ++l) ++use[(size_t) t * kBanks + bank(t, l)];
-  std::vector<int> cost(n);
-  for (int t = 0; t < n; ++t) cost[t] = peak(&use[(size_t) t * kBanks]);
+  for (int t = 0; t < n; ++t) {
+    std::fill(slot[t].use, slot[t].use + kBanks, 0);
+    for (int l = 0; l < 32; ++l) ++slot[t].use[bank(t, l)];
+    slot[t].recount();
+  }
   for (int sweep = 0; sweep < 12; ++sweep) {
     bool changed = false;
     for (int t = 0; t < n; ++t) {
-      if (cost[t] < 2 * 4096) continue;
       for (int l = 0; l < 32; ++l) {
-        int *ut = &use[(size_t) t * kBanks];
+        SlotLoad &st = slot[t];
+        if (st.mx < 2) break;                              // the slot is free of conflicts
         const int b = bank(t, l);
-        if (ut[b] < 2) continue;                                  // alone on its bank
+        if (st.use[b] < 2) continue;                       // alone on its bank
         const bool pad_t = out[(size_t) t * 32 + l] >= pad_base;
         int best = -1, best_gain = 0, best_bt = 0, best_bu = 0;
         for (int u = 0; u < n; ++u) {
           if (u == t) continue;
-          int *uu = &use[(size_t) u * kBanks];
+          const SlotLoad &su = slot[u];
           const int c = bank(u, l);
           const bool pad_u = out[(size_t) u * 32 + l] >= pad_base;
-          --ut[b]; --uu[c];
-          int bt = c, bu = b;
-          if (pad_u) { bt = 0; for (int k = 1; k < kBanks; ++k) if (ut[k] < ut[bt]) bt = k; }
-          if (pad_t) { bu = 0; for (int k = 1; k < kBanks; ++k) if (uu[k] < uu[bu]) bu = k; }
-          ++ut[bt]; ++uu[bu];
-          const int gain = cost[t] + cost[u] - peak(ut) - peak(uu);
-          --ut[bt]; --uu[bu];
-          ++ut[b]; ++uu[c];
+          const int bt = pad_u ? st.emptiest_without(b) : c;      // what arrives in slot t
+          const int bu = pad_t ? su.emptiest_without(c) : b;      // what arrives in slot u
+          const int gain = st.cost() + su.cost() - st.cost_moved(b, bt) - su.cost_moved(c, bu);
           if (gain > best_gain) { best_gain = gain; best = u; best_bt = bt; best_bu = bu; }
         }
         if (best < 0) continue;
         const int u = best, c = bank(u, l);
-        int *uu = &use[(size_t) u * kBanks];
+        SlotLoad &su = slot[u];
         const bool pad_u = out[(size_t) u * 32 + l] >= pad_base;
         uint16_t to_t = out[(size_t) u * 32 + l], to_u = out[(size_t) t * 32 + l];
         if (pad_u) to_t = (uint16_t) (pad_base + best_bt);
         if (pad_t) to_u = (uint16_t) (pad_base + best_bu);
-        --ut[b]; --uu[c];
+        --st.use[b]; --su.use[c];
         out[(size_t) t * 32 + l] = to_t;
         out[(size_t) u * 32 + l] = to_u;
-        ++ut[to_t % kBanks]; ++uu[to_u % kBanks];
-        cost[t] = peak(ut);
-        cost[u] = peak(uu);
+        ++st.use[to_t % kBanks]; ++su.use[to_u % kBanks];
+        st.recount();
+        su.recount();
         changed = true;
       }
     }

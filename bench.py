@@ -247,35 +247,38 @@ def main():
         "stages_us": {k: round(1e3 * v, 2) for k, v in gp_ms.items() if v > 0.0 and k != "event_overhead"}}
     del gp_out, gp_ws
 
-    # General per-entry weights (Eq. 2) instead of the equal split: the membership is then read
-    # from the CSR (the prepared form holds no weights).
+    # General per-entry weights (Eq. 2) instead of the equal split, through the prepared layout
+    # that carries them and, for comparison, straight from the CSR.
     wgroups = pcg.Groups.from_csr(cfg.V, rp, mem, dev, reverse=True,
+                                  chunk_groups=pcg.suggest_chunk_groups(len(rp) - 1, cfg.B),
                                   weights=W.random_weights(cfg.V, mem_c, cfg.data_seed))
-
-    def weighted_step(i):
-        tgt, dft, ptok, pgrp = sets[i % len(sets)]
-        pcg.verify(wgroups, tgt, dft, ptok, pgrp, temperature=cfg.temperature, seed=0, offset=i,
-                   out=out, workspace=ws)
-
     wsteps = max(10, args.steps // 3)
-    for i in range(args.warmup):
-        weighted_step(i)
-    torch.cuda.synchronize()
-    t_begin = time.perf_counter()
-    for i in range(wsteps):
-        weighted_step(args.warmup + i)
-    torch.cuda.synchronize()
-    w_elapsed = time.perf_counter() - t_begin
-    pcg.profile_begin(wsteps)
-    for i in range(wsteps):
-        weighted_step(args.warmup + i)
-    torch.cuda.synchronize()
-    w_ms, _ = pcg.profile_end()
-    result["general_weights"] = {
-        "value": round(positions * wsteps / w_elapsed, 1), "unit": "positions/s",
-        "ms_per_step": round(1e3 * w_elapsed / wsteps, 5), "steps": wsteps,
-        "stages_us": {k: round(1e3 * v, 2) for k, v in w_ms.items()
-                      if v > 0.0 and k != "event_overhead"}}
+
+    def time_weighted(wg):
+        def weighted_step(i):
+            tgt, dft, ptok, pgrp = sets[i % len(sets)]
+            pcg.verify(wg, tgt, dft, ptok, pgrp, temperature=cfg.temperature, seed=0, offset=i,
+                       out=out, workspace=ws)
+        for i in range(args.warmup):
+            weighted_step(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(wsteps):
+            weighted_step(args.warmup + i)
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+        pcg.profile_begin(wsteps)
+        for i in range(wsteps):
+            weighted_step(args.warmup + i)
+        torch.cuda.synchronize()
+        stages, _ = pcg.profile_end()
+        return {"value": round(positions * wsteps / elapsed, 1), "unit": "positions/s",
+                "ms_per_step": round(1e3 * elapsed / wsteps, 5), "steps": wsteps,
+                "stages_us": {k: round(1e3 * v, 2) for k, v in stages.items()
+                              if v > 0.0 and k != "event_overhead"}}
+
+    result["general_weights"] = time_weighted(wgroups)
+    result["general_weights"]["from_csr"] = time_weighted(wgroups.without_prepared())
 
     # The draft-side proposal coupling (Eq. 6) on the same draft rows: the step before the path,
     # timed on its own.

@@ -94,8 +94,8 @@ typedef struct {
    * equal split 1 / mult[t] (Eq. 3).  With weights the group probabilities are
    * sum_j prob(members[j]) * weights[j] (Eq. 4), the token inside a group is drawn
    * proportionally to prob(t) * w_{k,t} (Eq. 10) and a token's group label by its weights
-   * (Eq. 6).  The prepared form carries no weights: `prepared` must be NULL when weights are
-   * given, and the CSR is read directly.
+   * (Eq. 6).  With weights, `prepared` is either NULL (the CSR is read directly) or a blob that
+   * pcg_groups_prepare_weights_host built from these same weights (off_weights != 0).
    * tok_weights: the same weights in reverse-index order (pcg_groups_reverse_weights_host),
    * DEVICE float [nnz]; needed together with weights by pcg_verify_thinning and pcg_propose. */
   const float *weights;
@@ -128,6 +128,8 @@ struct pcg_prepared {
   int64_t off_desc;   /* uint32 [nchunks][ntiles][blocks_per_chunk][2]: data offset (16-byte units), steps */
   int64_t off_perm;   /* uint16 [nchunks][blocks_per_chunk][4][64]: group index inside the chunk, 0xFFFF = none */
   int64_t off_data;   /* uint32 [][64][4]: step k of a block = 64 lanes x 4 dwords, 2 slots per dword */
+  int64_t off_weights;/* float [][64][4][2]: the weight w_{k,t} of every slot of off_data, same unit
+                         numbering, low slot first; 0 on padding slots.  0 = the blob holds none */
   int64_t bytes;      /* size of the blob */
 };
 
@@ -363,6 +365,20 @@ size_t pcg_groups_prepare_bytes(int32_t V, int32_t G, const int32_t *row_ptr,
 int pcg_groups_prepare_host(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members,
                             int32_t chunk_groups, void *blob, size_t blob_bytes,
                             pcg_prepared *info);
+
+/*
+ * The same with general weights (Sec. 2.2, Eq. 2 and 4): weights[j] (HOST float [nnz], as in
+ * pcg_groups.weights) travels with entry j into the blob, so that the prepared gather forms
+ * sum_j table(members[j]) * weights[j] without touching the CSR.  The blob is the unweighted
+ * one followed by the weights (three times the slot data).  The caller passes the same weights
+ * on the device in pcg_groups.weights; nothing checks that the two agree.
+ */
+size_t pcg_groups_prepare_weights_bytes(int32_t V, int32_t G, const int32_t *row_ptr,
+                                        const int32_t *members, int32_t chunk_groups);
+int pcg_groups_prepare_weights_host(int32_t V, int32_t G, const int32_t *row_ptr,
+                                    const int32_t *members, const float *weights,
+                                    int32_t chunk_groups, void *blob, size_t blob_bytes,
+                                    pcg_prepared *info);
 
 /* ---- per-kernel timing (for the benchmark) ------------------------------------------------ */
 

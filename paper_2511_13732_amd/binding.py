@@ -30,7 +30,7 @@ class PreparedInfo(C.Structure):
                 ("chunk_groups", C.c_int32), ("nchunks", C.c_int32),
                 ("blocks_per_chunk", C.c_int32), ("reserved", C.c_int32),
                 ("off_desc", C.c_int64), ("off_perm", C.c_int64), ("off_data", C.c_int64),
-                ("bytes", C.c_int64)]
+                ("off_weights", C.c_int64), ("bytes", C.c_int64)]
 
 
 class _GroupsStruct(C.Structure):
@@ -121,6 +121,12 @@ def lib() -> C.CDLL:
         L.pcg_groups_prepare_host.restype = C.c_int
         L.pcg_groups_prepare_host.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32,
                                               C.c_void_p, C.c_size_t, C.POINTER(PreparedInfo)]
+        L.pcg_groups_prepare_weights_bytes.restype = C.c_size_t
+        L.pcg_groups_prepare_weights_bytes.argtypes = L.pcg_groups_prepare_bytes.argtypes
+        L.pcg_groups_prepare_weights_host.restype = C.c_int
+        L.pcg_groups_prepare_weights_host.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                                      C.c_void_p, C.c_int32, C.c_void_p, C.c_size_t,
+                                                      C.POINTER(PreparedInfo)]
         L.pcg_profile_begin.restype = C.c_int
         L.pcg_profile_begin.argtypes = [C.c_int32]
         L.pcg_profile_end.restype = C.c_int
@@ -211,17 +217,27 @@ def suggest_chunk_groups(G: int, batch: int) -> int:
     return int(min(16384, max(4096, -(-want // 4096) * 4096)))
 
 
-def groups_prepare_host(V: int, row_ptr, members, chunk_groups: int = 0):
-    """(blob uint8 array, PreparedInfo) of a canonical host CSR; see pcg_groups_prepare_host."""
+def groups_prepare_host(V: int, row_ptr, members, chunk_groups: int = 0, weights=None):
+    """(blob uint8 array, PreparedInfo) of a canonical host CSR; see pcg_groups_prepare_host and,
+    with ``weights`` (float32 [nnz]), pcg_groups_prepare_weights_host."""
     rp, mem = _np_i32(row_ptr), _np_i32(members)
     G = len(rp) - 1
-    n = lib().pcg_groups_prepare_bytes(V, G, rp.ctypes.data, mem.ctypes.data, chunk_groups)
+    L = lib()
+    sizer = L.pcg_groups_prepare_bytes if weights is None else L.pcg_groups_prepare_weights_bytes
+    n = sizer(V, G, rp.ctypes.data, mem.ctypes.data, chunk_groups)
     if n == 0:
         raise PcgError(-2, "pcg_groups_prepare_bytes")
     blob = np.zeros(n, dtype=np.uint8)
     info = PreparedInfo()
-    _check(lib().pcg_groups_prepare_host(V, G, rp.ctypes.data, mem.ctypes.data, chunk_groups,
+    if weights is None:
+        _check(L.pcg_groups_prepare_host(V, G, rp.ctypes.data, mem.ctypes.data, chunk_groups,
                                          blob.ctypes.data, n, C.byref(info)), "prepare")
+    else:
+        w = np.ascontiguousarray(weights, dtype=np.float32)
+        assert w.shape == (len(mem),), "one weight per entry"
+        _check(L.pcg_groups_prepare_weights_host(V, G, rp.ctypes.data, mem.ctypes.data, w.ctypes.data,
+                                                 chunk_groups, blob.ctypes.data, n, C.byref(info)),
+               "prepare_weights")
     return blob, info
 
 
@@ -249,7 +265,7 @@ class Groups:
         """Canonicalise and validate a host CSR with the library, then upload it (with the
         prepared layout unless prepare=False, with the token -> groups index if reverse).
         ``weights`` (float32 [nnz], for the canonical CSR's entries) switches from the equal split
-        to general per-entry weights; the prepared layout is then not built."""
+        to general per-entry weights, which the prepared layout then carries too."""
         rp, mem, mult = groups_canonicalize_host(V, row_ptr, members)
         _check(groups_validate_host(V, rp, mem, mult), "validate")
         dev = torch.device(device)
@@ -261,9 +277,8 @@ class Groups:
             assert w.shape == (len(mem),), "one weight per entry of the canonical CSR"
             _check(groups_validate_weights_host(V, rp, mem, w), "validate_weights")
             wd = up(w)
-            prepare = False
         if prepare:
-            blob, info = groups_prepare_host(V, rp, mem, chunk_groups)
+            blob, info = groups_prepare_host(V, rp, mem, chunk_groups, None if weights is None else w)
             blob_dev = up(blob)
         tp = tg = None
         if reverse:

@@ -77,7 +77,8 @@ int check_groups(const pcg_groups *g) {
   if (g->V < 1 || g->G < 1 || g->nnz < 0 || g->nnz > INT32_MAX) return PCG_ERR_BAD_SHAPE;
   if (g->nnz > 0 && !g->members) return PCG_ERR_NULL_ARG;
   if ((g->prepared == nullptr) != (g->prepared_info == nullptr)) return PCG_ERR_NULL_ARG;
-  if (g->weights && g->prepared) return PCG_ERR_BAD_SHAPE;   // the prepared form holds no weights
+  // with weights the prepared form must have been built with them
+  if (g->weights && g->prepared && g->prepared_info->off_weights == 0) return PCG_ERR_BAD_SHAPE;
   if (g->weights && ((uintptr_t) g->weights % 4)) return PCG_ERR_MISALIGNED;
   if (g->prepared) {
     const pcg_prepared &p = *g->prepared_info;
@@ -86,6 +87,9 @@ int check_groups(const pcg_groups *g) {
         p.chunk_groups > kMaxChunkGroups || p.chunk_groups % kChunkStep ||
         p.blocks_per_chunk != p.chunk_groups / kBlockGroups ||
         p.nchunks != (g->G + p.chunk_groups - 1) / p.chunk_groups)
+      return PCG_ERR_BAD_SHAPE;
+    if (p.off_weights != 0 &&
+        (p.off_weights % 256 || p.off_weights <= p.off_data || p.off_weights >= p.bytes))
       return PCG_ERR_BAD_SHAPE;
     if ((uintptr_t) g->prepared % 256) return PCG_ERR_MISALIGNED;
   }

@@ -1209,12 +1209,74 @@ __device__ __forceinline__ bool run_block(const float *tab, uint4 (&A)[4], uint4
   }
 }
 
-template <bool CSUM>
+// The same with general weights (Eq. 4): every slot comes with its w_{k,t}, 8 floats per lane
+// and step next to the 8 slots.  Two steps per turn keep the two register buffers at 48 dwords.
+constexpr int kTurnW = 1;
+
+struct StepsW {
+  uint4 s[kTurnW];
+  float4 w[2 * kTurnW];
+};
+
+__device__ __forceinline__ void gather_step_w(const float *tab, const uint4 s, const float4 a,
+                                              const float4 b, float *acc) {
+  acc[0] = fmaf(tab[s.x & 0xffffu], a.x, acc[0]); acc[1] = fmaf(tab[s.y & 0xffffu], a.z, acc[1]);
+  acc[2] = fmaf(tab[s.z & 0xffffu], b.x, acc[2]); acc[3] = fmaf(tab[s.w & 0xffffu], b.z, acc[3]);
+  acc[0] = fmaf(tab[s.x >> 16], a.y, acc[0]); acc[1] = fmaf(tab[s.y >> 16], a.w, acc[1]);
+  acc[2] = fmaf(tab[s.z >> 16], b.y, acc[2]); acc[3] = fmaf(tab[s.w >> 16], b.w, acc[3]);
+}
+
+__device__ __forceinline__ void load_steps_w(StepsW &x, const uint4 *__restrict__ data,
+                                             const float4 *__restrict__ wdata, uint32_t off,
+                                             uint32_t k, uint32_t n) {
+#pragma unroll
+  for (int i = 0; i < kTurnW; ++i) {
+    const size_t unit = (size_t) off + (size_t) min(k + i, n - 1) * kWave;
+    x.s[i] = data[unit];
+    x.w[2 * i] = wdata[2 * unit];
+    x.w[2 * i + 1] = wdata[2 * unit + 1];
+  }
+}
+
+__device__ __forceinline__ void gather_steps_w(const float *tab, const StepsW &x, uint32_t left,
+                                               float *acc) {
+  gather_step_w(tab, x.s[0], x.w[0], x.w[1], acc);
+  if constexpr (kTurnW > 1)
+    if (left > 1) gather_step_w(tab, x.s[1], x.w[2], x.w[3], acc);
+}
+
+template <bool CUR_IS_A>
+__device__ __forceinline__ bool run_block_w(const float *tab, StepsW &A, StepsW &B,
+                                            const uint4 *__restrict__ data,
+                                            const float4 *__restrict__ wdata, uint32_t off,
+                                            uint32_t n, uint32_t off_next, uint32_t nnext,
+                                            float *acc) {
+  StepsW &X = CUR_IS_A ? A : B;
+  StepsW &Y = CUR_IS_A ? B : A;
+  auto prefetch = [&](StepsW &dst, uint32_t k) {
+    const bool own = k + kTurnW < n, next = !own && nnext > 0;
+    load_steps_w(dst, data, wdata, next ? off_next : off, own ? k + kTurnW : 0u, next ? nnext : n);
+  };
+  uint32_t k = 0;
+  while (true) {
+    prefetch(Y, k);
+    gather_steps_w(tab, X, n - k, acc);
+    k += kTurnW;
+    if (k >= n) return !CUR_IS_A;
+    prefetch(X, k);
+    gather_steps_w(tab, Y, n - k, acc);
+    k += kTurnW;
+    if (k >= n) return CUR_IS_A;
+  }
+}
+
+template <bool CSUM, bool WEIGHTED>
 __global__ __launch_bounds__(kGatherThreads) void gather_prepared_kernel(
     int32_t V, int32_t G, int32_t nrows, int32_t nchunks, int32_t chunk_groups, int32_t ntiles,
     int32_t tile_len, int32_t bpc, const uint32_t *__restrict__ desc,
     const uint16_t *__restrict__ perm, const uint4 *__restrict__ data,
-    const float *__restrict__ table, float *__restrict__ out, double *__restrict__ csum) {
+    const float4 *__restrict__ wdata, const float *__restrict__ table, float *__restrict__ out,
+    double *__restrict__ csum) {
   __shared__ __attribute__((aligned(16))) float tab[kTileMax];
   __shared__ double wsum[kGatherWaves];
   const int xcd = blockIdx.x & 7;
@@ -1229,19 +1291,23 @@ __global__ __launch_bounds__(kGatherThreads) void gather_prepared_kernel(
   const float *src = table + (int64_t) r * V;
 
   float acc[kMaxAcc];
-  uint16_t where[kMaxAcc];     // group (inside the chunk) behind each running sum; loaded now,
-                               // needed only when the sums are put back into group order
+  uint16_t where[kMaxAcc];     // group (inside the chunk) behind each running sum, needed only
+                               // when the sums are put back into group order: loaded now where
+                               // registers allow, after the tiles otherwise
+  auto load_where = [&]() {
 #pragma unroll
-  for (int q = 0; q < kMaxBlocksPerWave; ++q) {
-    const int bl = block_of(q, wave);
+    for (int q = 0; q < kMaxBlocksPerWave; ++q) {
+      const int bl = block_of(q, wave);
 #pragma unroll
-    for (int rr = 0; rr < kLaneGroups; ++rr) {
-      acc[q * kLaneGroups + rr] = 0.f;
-      where[q * kLaneGroups + rr] =
-          bl < bpc ? perm[((size_t) chunk * bpc + bl) * kBlockGroups + rr * kWave + lane]
-                   : (uint16_t) 0xFFFFu;
+      for (int rr = 0; rr < kLaneGroups; ++rr)
+        where[q * kLaneGroups + rr] =
+            bl < bpc ? perm[((size_t) chunk * bpc + bl) * kBlockGroups + rr * kWave + lane]
+                     : (uint16_t) 0xFFFFu;
     }
-  }
+  };
+#pragma unroll
+  for (int j = 0; j < kMaxAcc; ++j) acc[j] = 0.f;
+  if constexpr (!WEIGHTED) load_where();
 
   for (int h = 0; h < ntiles; ++h) {
     const int32_t t0 = h * tile_len;
@@ -1271,24 +1337,43 @@ __global__ __launch_bounds__(kGatherThreads) void gather_prepared_kernel(
         offs[q] = dsc[2 * bl] + lane;
       }
     }
-    uint4 bufA[4], bufB[4];
     bool in_a = true, primed = false;
+    if constexpr (WEIGHTED) {
+      StepsW bufA, bufB;
 #pragma unroll
-    for (int q = 0; q < kMaxBlocksPerWave; ++q) {
-      const uint32_t n = steps[q];
-      if (n == 0) continue;                           // uniform
-      const int qn = (q + 1) % kMaxBlocksPerWave;
-      const uint32_t nn = (q + 1 < kMaxBlocksPerWave) ? steps[qn] : 0;
-      if (!primed) {
-        if (in_a) load_steps(bufA, data, offs[q], 0, n); else load_steps(bufB, data, offs[q], 0, n);
+      for (int q = 0; q < kMaxBlocksPerWave; ++q) {
+        const uint32_t n = steps[q];
+        if (n == 0) continue;                         // uniform
+        const int qn = (q + 1) % kMaxBlocksPerWave;
+        const uint32_t nn = (q + 1 < kMaxBlocksPerWave) ? steps[qn] : 0;
+        if (!primed) {
+          if (in_a) load_steps_w(bufA, data, wdata, offs[q], 0, n);
+          else load_steps_w(bufB, data, wdata, offs[q], 0, n);
+        }
+        in_a = in_a ? run_block_w<true>(tab, bufA, bufB, data, wdata, offs[q], n, offs[qn], nn, acc + q * kLaneGroups)
+                    : run_block_w<false>(tab, bufA, bufB, data, wdata, offs[q], n, offs[qn], nn, acc + q * kLaneGroups);
+        primed = nn > 0;
       }
-      in_a = in_a ? run_block<true>(tab, bufA, bufB, data, offs[q], n, offs[qn], nn, acc + q * kLaneGroups)
-                  : run_block<false>(tab, bufA, bufB, data, offs[q], n, offs[qn], nn, acc + q * kLaneGroups);
-      primed = nn > 0;
+    } else {
+      uint4 bufA[4], bufB[4];
+#pragma unroll
+      for (int q = 0; q < kMaxBlocksPerWave; ++q) {
+        const uint32_t n = steps[q];
+        if (n == 0) continue;                         // uniform
+        const int qn = (q + 1) % kMaxBlocksPerWave;
+        const uint32_t nn = (q + 1 < kMaxBlocksPerWave) ? steps[qn] : 0;
+        if (!primed) {
+          if (in_a) load_steps(bufA, data, offs[q], 0, n); else load_steps(bufB, data, offs[q], 0, n);
+        }
+        in_a = in_a ? run_block<true>(tab, bufA, bufB, data, offs[q], n, offs[qn], nn, acc + q * kLaneGroups)
+                    : run_block<false>(tab, bufA, bufB, data, offs[q], n, offs[qn], nn, acc + q * kLaneGroups);
+        primed = nn > 0;
+      }
     }
   }
 
   // back into group order through LDS, then coalesced stores
+  if constexpr (WEIGHTED) load_where();
   __syncthreads();
 #pragma unroll
   for (int j = 0; j < kMaxAcc; ++j)
@@ -1477,14 +1562,21 @@ hipError_t launch_gather_prepared(const pcg_groups &g, int32_t nrows, const floa
   const uint4 *data = reinterpret_cast<const uint4 *>(blob + p.off_data);
   const int32_t rows8 = (nrows + 7) / 8;
   const dim3 grid((unsigned) (8 * rows8 * p.nchunks));
-  if (csum)
-    gather_prepared_kernel<true><<<grid, kGatherThreads, 0, stream>>>(
-        g.V, g.G, nrows, p.nchunks, p.chunk_groups, p.ntiles, p.tile_len, p.blocks_per_chunk, desc,
-        perm, data, table, out, csum);
-  else
-    gather_prepared_kernel<false><<<grid, kGatherThreads, 0, stream>>>(
-        g.V, g.G, nrows, p.nchunks, p.chunk_groups, p.ntiles, p.tile_len, p.blocks_per_chunk, desc,
-        perm, data, table, out, nullptr);
+  // general weights are read from the blob (the caller's checks made sure it holds them)
+  const float4 *wdata =
+      g.weights ? reinterpret_cast<const float4 *>(blob + p.off_weights) : nullptr;
+  auto launch = [&](auto kernel) {
+    kernel<<<grid, kGatherThreads, 0, stream>>>(g.V, g.G, nrows, p.nchunks, p.chunk_groups,
+                                                p.ntiles, p.tile_len, p.blocks_per_chunk, desc,
+                                                perm, data, wdata, table, out, csum);
+  };
+  if (wdata) {
+    if (csum) launch(gather_prepared_kernel<true, true>);
+    else launch(gather_prepared_kernel<false, true>);
+  } else {
+    if (csum) launch(gather_prepared_kernel<true, false>);
+    else launch(gather_prepared_kernel<false, false>);
+  }
   return hipGetLastError();
 }
 

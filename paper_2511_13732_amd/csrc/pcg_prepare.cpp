@@ -2,6 +2,7 @@
 #include <algorithm>
 #include <cstring>
 #include <numeric>
+#include <utility>
 #include <vector>
 
 #include "../../include/pcg.h"
@@ -220,8 +221,9 @@ void balance_blocks(std::vector<int32_t> &order, int32_t g0, const Shape &sh, co
 }
 
 // Builds the layout; with blob == nullptr only sizes are computed.
-int build(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members,
-          int32_t chunk_groups, uint8_t *blob, size_t blob_bytes, pcg_prepared *info) {
+// `weighted` adds the weight stream (weights may be NULL while only sizes are asked for).
+int build(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members, const float *weights,
+          bool weighted, int32_t chunk_groups, uint8_t *blob, size_t blob_bytes, pcg_prepared *info) {
   Shape sh;
   if (!make_shape(V, G, chunk_groups, sh)) return PCG_ERR_BAD_SHAPE;
   if (row_ptr[0] != 0) return PCG_ERR_BAD_CSR;
@@ -282,7 +284,8 @@ int build(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members,
   }
   if (units > 0xFFFFFFFFull / 4) return PCG_ERR_BAD_SHAPE;
   const size_t data_bytes = ((size_t) units * 16 + 255) / 256 * 256 + 1024;   // never empty
-  const size_t total = desc_bytes + perm_bytes + data_bytes;
+  const size_t weight_bytes = weighted ? 2 * data_bytes : 0;      // one float per 16-bit slot
+  const size_t total = desc_bytes + perm_bytes + data_bytes + weight_bytes;
   if (info) {
     info->V = V; info->G = G;
     info->ntiles = T; info->tile_len = sh.tile_len;
@@ -291,6 +294,7 @@ int build(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members,
     info->off_desc = 0;
     info->off_perm = (int64_t) desc_bytes;
     info->off_data = (int64_t) (desc_bytes + perm_bytes);
+    info->off_weights = weighted ? (int64_t) (desc_bytes + perm_bytes + data_bytes) : 0;
     info->bytes = (int64_t) total;
   }
   if (!blob) return PCG_OK;
@@ -301,8 +305,11 @@ int build(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members,
   std::memcpy(blob, desc.data(), desc.size() * sizeof(uint32_t));
   std::memcpy(blob + desc_bytes, perm.data(), perm.size() * sizeof(uint16_t));
   uint32_t *data = reinterpret_cast<uint32_t *>(blob + desc_bytes + perm_bytes);
+  float *wdata = weighted ? reinterpret_cast<float *>(blob + desc_bytes + perm_bytes + data_bytes)
+                          : nullptr;
   const uint16_t pad_base = (uint16_t) sh.tile_len;   // table[tile_len .. tile_len + kBanks) is zero
   std::vector<uint16_t> lists[32], sched;
+  std::vector<std::pair<uint16_t, float>> share[32];   // (slot, weight) of each lane's list, by slot
   for (int32_t c = 0; c < sh.nchunks; ++c) {
     const int32_t g0 = c * sh.chunk_groups;
     for (int32_t bl = 0; bl < BPC; ++bl) {
@@ -315,18 +322,34 @@ int build(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members,
           for (int32_t half = 0; half < 2; ++half) {
             for (int32_t l = 0; l < 32; ++l) {
               lists[l].clear();
+              share[l].clear();
               const uint16_t k = perm[((size_t) c * BPC + bl) * kBlockGroups + r * 64 + half * 32 + l];
               if (k == 0xFFFF) continue;
               for (int32_t j = row_ptr[g0 + k]; j < row_ptr[g0 + k + 1]; ++j)
-                if (members[j] / sh.tile_len == h)
+                if (members[j] / sh.tile_len == h) {
                   lists[l].push_back((uint16_t) (members[j] - h * sh.tile_len));
+                  if (weighted) share[l].emplace_back(lists[l].back(), weights[j]);
+                }
+              std::sort(share[l].begin(), share[l].end());
             }
             schedule_half_wave(lists, (int) steps * 2, pad_base, sched);
             for (uint32_t q = 0; q < steps; ++q)
-              for (int32_t l = 0; l < 32; ++l)
-                data[((off + (size_t) q * 64 + half * 32 + l) * 4) + r] =
-                    (uint32_t) sched[(size_t) (2 * q) * 32 + l] |
-                    ((uint32_t) sched[(size_t) (2 * q + 1) * 32 + l] << 16);
+              for (int32_t l = 0; l < 32; ++l) {
+                const size_t unit = off + (size_t) q * 64 + half * 32 + l;
+                const uint16_t s0 = sched[(size_t) (2 * q) * 32 + l];
+                const uint16_t s1 = sched[(size_t) (2 * q + 1) * 32 + l];
+                data[unit * 4 + r] = (uint32_t) s0 | ((uint32_t) s1 << 16);
+                if (!weighted) continue;
+                // a group's members are distinct, so a slot names one entry of the lane's list
+                auto weight_of = [&](uint16_t s) {
+                  if (s >= pad_base) return 0.f;
+                  auto it = std::lower_bound(share[l].begin(), share[l].end(),
+                                             std::make_pair(s, -1.f));
+                  return it->second;
+                };
+                wdata[(unit * 4 + r) * 2] = weight_of(s0);
+                wdata[(unit * 4 + r) * 2 + 1] = weight_of(s1);
+              }
           }
         }
       }
@@ -343,7 +366,8 @@ size_t pcg_groups_prepare_bytes(int32_t V, int32_t G, const int32_t *row_ptr,
                                 const int32_t *members, int32_t chunk_groups) {
   if (!row_ptr || (G > 0 && row_ptr[G] > 0 && !members)) return 0;
   pcg_prepared info;
-  if (build(V, G, row_ptr, members, chunk_groups, nullptr, 0, &info) != PCG_OK) return 0;
+  if (build(V, G, row_ptr, members, nullptr, false, chunk_groups, nullptr, 0, &info) != PCG_OK)
+    return 0;
   return (size_t) info.bytes;
 }
 
@@ -352,7 +376,27 @@ int pcg_groups_prepare_host(int32_t V, int32_t G, const int32_t *row_ptr, const 
                             pcg_prepared *info) {
   if (!row_ptr || !blob || !info) return PCG_ERR_NULL_ARG;
   if (G > 0 && row_ptr[G] > 0 && !members) return PCG_ERR_NULL_ARG;
-  return build(V, G, row_ptr, members, chunk_groups, (uint8_t *) blob, blob_bytes, info);
+  return build(V, G, row_ptr, members, nullptr, false, chunk_groups, (uint8_t *) blob, blob_bytes,
+               info);
+}
+
+size_t pcg_groups_prepare_weights_bytes(int32_t V, int32_t G, const int32_t *row_ptr,
+                                        const int32_t *members, int32_t chunk_groups) {
+  if (!row_ptr || (G > 0 && row_ptr[G] > 0 && !members)) return 0;
+  pcg_prepared info;
+  if (build(V, G, row_ptr, members, nullptr, true, chunk_groups, nullptr, 0, &info) != PCG_OK)
+    return 0;
+  return (size_t) info.bytes;
+}
+
+int pcg_groups_prepare_weights_host(int32_t V, int32_t G, const int32_t *row_ptr,
+                                    const int32_t *members, const float *weights,
+                                    int32_t chunk_groups, void *blob, size_t blob_bytes,
+                                    pcg_prepared *info) {
+  if (!row_ptr || !blob || !info) return PCG_ERR_NULL_ARG;
+  if (G > 0 && row_ptr[G] > 0 && (!members || !weights)) return PCG_ERR_NULL_ARG;
+  return build(V, G, row_ptr, members, weights, true, chunk_groups, (uint8_t *) blob, blob_bytes,
+               info);
 }
 
 }  // extern "C"

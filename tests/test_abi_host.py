@@ -44,7 +44,7 @@ def test_header_constants_match_binding():
         assert re.search(rf"{name}\s*=\s*{val}\b", text)
         assert pcg.strerror(val) != "unknown status"
     assert re.search(r"PCG_F32 = 0, PCG_BF16 = 1", text) and (pcg.F32, pcg.BF16) == (0, 1)
-    assert C.sizeof(pcg.Diag) == 32 and C.sizeof(_GroupsStruct) == 88 and C.sizeof(pcg.PreparedInfo) == 64
+    assert C.sizeof(pcg.Diag) == 32 and C.sizeof(_GroupsStruct) == 88 and C.sizeof(pcg.PreparedInfo) == 72
 
 
 # Fake device addresses: every call below must fail its host-side checks and return before it
@@ -167,7 +167,13 @@ def decode_prepared(blob, info, V, G):
         info.nchunks, BPC, 4, 64)
     data = blob[info.off_data:info.off_data + (info.bytes - info.off_data) // 16 * 16].view(
         np.uint32).reshape(-1, 4)                    # 16-byte units
+    wts = None
+    if info.off_weights:
+        assert info.off_weights % 256 == 0 and info.bytes - info.off_weights >= 2 * (info.off_weights - info.off_data)
+        wts = blob[info.off_weights:info.off_weights + 2 * (info.off_weights - info.off_data)].view(
+            np.float32).reshape(-1, 4, 2)            # [unit, r, low / high slot]
     out = {g: [] for g in range(G)}
+    wout = {g: [] for g in range(G)}
     padded = 0
     for c in range(info.nchunks):
         for bl in range(BPC):
@@ -177,6 +183,9 @@ def decode_prepared(blob, info, V, G):
                     continue
                 blk = data[off:off + steps * 64].reshape(steps, 64, 4)          # [step, lane, r]
                 slots = np.stack([blk & 0xFFFF, blk >> 16], axis=1).reshape(2 * steps, 64, 4)
+                if wts is not None:                                             # -> [entry, lane, r]
+                    wblk = wts[off:off + steps * 64].reshape(steps, 64, 4, 2).transpose(0, 3, 1, 2).reshape(
+                        2 * steps, 64, 4)
                 padded += 2 * steps * 256
                 for r in range(4):
                     for lane in range(64):
@@ -189,6 +198,11 @@ def decode_prepared(blob, info, V, G):
                             continue
                         assert (real < info.tile_len).all()
                         out[c * info.chunk_groups + k] += (real.astype(np.int64) + h * info.tile_len).tolist()
+                        if wts is not None:
+                            assert (wblk[:, lane, r][col >= info.tile_len] == 0).all()     # padding weighs nothing
+                            wout[c * info.chunk_groups + k] += wblk[:, lane, r][col < info.tile_len].tolist()
+    if wts is not None:
+        return out, padded, wout
     return out, padded
 
 
@@ -219,6 +233,30 @@ def test_prepared_layout_holds_exactly_the_membership(V, G, smin, smax, chunk):
     # the order inside a list is the builder's choice (bank scheduling); the multiset is not
     print(f"padding overhead {padded / max(1, len(mem)) - 1:.3f}")
     assert padded < 3.0 * len(mem) + 256 * 2 * info.nchunks * info.blocks_per_chunk * info.ntiles
+
+
+@pytest.mark.parametrize("V,G,smin,smax,chunk", [(300, 200, 1, 9, 0), (50000, 9000, 1, 40, 4096)])
+def test_weighted_prepared_layout_carries_every_entrys_weight(V, G, smin, smax, chunk):
+    """Sec. 2.2, Eq. (2) and (4): the weight w_{k,t} sits next to the slot of token t in group k's
+    list, whatever order the bank scheduling chose; the slot stream equals the unweighted blob's."""
+    rp, mem = W.random_groups(V, G, smin, smax, seed=V % 89, cover=False)
+    rp, mem, _ = pcg.groups_canonicalize_host(V, rp, mem)
+    G2 = len(rp) - 1
+    w = W.random_weights(V, mem, seed=5)
+    blob, info = pcg.groups_prepare_host(V, rp, mem, chunk, weights=w)
+    plain, pinfo = pcg.groups_prepare_host(V, rp, mem, chunk)
+    assert info.off_weights == pinfo.bytes and pinfo.off_weights == 0 and info.bytes == len(blob)
+    np.testing.assert_array_equal(blob[:pinfo.bytes], plain)
+    got, _, wgot = decode_prepared(blob, info, V, G2)
+    for g in range(G2):
+        assert sorted(zip(got[g], wgot[g])) == sorted(zip(mem[rp[g]:rp[g + 1]].tolist(), w[rp[g]:rp[g + 1]].tolist())), g
+    L = pcg.lib()
+    n = L.pcg_groups_prepare_weights_bytes(V, G2, rp.ctypes.data, mem.ctypes.data, chunk)
+    assert n == len(blob)
+    assert L.pcg_groups_prepare_weights_host(V, G2, rp.ctypes.data, mem.ctypes.data, None, chunk,
+                                             blob.ctypes.data, n, C.byref(info)) == NULL_ARG
+    assert L.pcg_groups_prepare_weights_host(V, G2, rp.ctypes.data, mem.ctypes.data, w.ctypes.data, chunk,
+                                             blob.ctypes.data, n - 1, C.byref(info)) == WS_SMALL
 
 
 def test_prepare_rejects_bad_arguments():
@@ -302,7 +340,7 @@ def test_weights_host_helpers_match_the_oracle_and_are_checked():
     assert pcg.groups_validate_weights_host(V, rp, mem, w * np.float32(0.99)) == BAD_CSR
     og = oracle.with_weights(oracle.Groups(V, len(rp) - 1, rp, mem, mult), w)
     np.testing.assert_array_equal(pcg.groups_reverse_weights_host(V, rp, mem, w), og.tok_weights)
-    # weights and the prepared form exclude each other; thinning and proposals need tok_weights
+    # weights need a prepared form built with them; thinning and proposals need tok_weights
     L = pcg.lib()
     info = pcg.PreparedInfo()
     both = _GroupsStruct(64, 8, 16, P, P, P, P, C.pointer(info), None, None, P, None)

@@ -18,13 +18,15 @@ from test_oracle_weights import random_weights
 pytestmark = pytest.mark.gpu
 
 
-def weighted_groups(V, rp, mem, seed):
-    """The same membership and the same random weights on both sides."""
+def weighted_groups(V, rp, mem, seed, prepare=True):
+    """The same membership and the same random weights on both sides; on the device with the
+    weights inside the prepared layout, or (prepare=False) read from the CSR."""
     og0 = oracle_groups(V, rp, mem)
     w = random_weights(og0, seed)
     og = oracle.with_weights(og0, w)
-    dg = pcg.Groups.from_csr(V, rp, mem, "cuda", weights=w, reverse=True)
-    assert dg.prepared is None and dg.nnz == og.nnz
+    dg = pcg.Groups.from_csr(V, rp, mem, "cuda", weights=w, reverse=True, prepare=prepare)
+    assert (dg.prepared is not None) == prepare and dg.nnz == og.nnz
+    assert not prepare or dg.prepared_info.off_weights > 0
     np.testing.assert_array_equal(dg.tok_weights.cpu().numpy()[:og.nnz], og.tok_weights)
     return og, dg, oracle.reverse_index(og)
 
@@ -38,15 +40,16 @@ SHAPES = [
 ]
 
 
+@pytest.mark.parametrize("layout", ["prepared", "csr"])
 @pytest.mark.parametrize("V,G,smin,smax,B,K,dtype,tau", SHAPES)
-def test_weighted_entry_points_match_oracle(V, G, smin, smax, B, K, dtype, tau):
+def test_weighted_entry_points_match_oracle(V, G, smin, smax, B, K, dtype, tau, layout):
     rp, mem = W.random_groups(V, G, smin, smax, seed=V * 3 + K, cover=False)
-    og, dg, rev = weighted_groups(V, rp, mem, seed=V)
+    og, dg, rev = weighted_groups(V, rp, mem, seed=V, prepare=layout == "prepared")
     # Eq. (4) for a few rows
     t, _ = logits_pair(4, 1, V, dtype, seed=V, sigma_t=4.0)
     x = t[:, 0].contiguous()
     err = group_probs_error(pcg.group_probs(dg, x.cuda(), tau), oracle.group_probs(og, as_oracle_logits(x), tau))
-    report_error(f"weighted group_probs V={V} {dtype}", err)
+    report_error(f"weighted group_probs V={V} {dtype} {layout}", err)
     assert err <= TOL_F32
     tv, tt, tp = Tally(), Tally(), Tally()
     for step in range(5):
@@ -63,9 +66,9 @@ def test_weighted_entry_points_match_oracle(V, G, smin, smax, B, K, dtype, tau):
         gpu, trials, r, _ = run_both_thinning(V, tgt, dft, ptok, pgrp, dg=dg, og=og, rev=rev,
                                               temperature=tau, seed=42, offset=step)
         tt.add(compare_thinning(gpu, trials, r, og, ptok, pgrp))
-    tv.report(f"weighted verify V={V} K={K} {dtype}")
-    tt.report(f"weighted thinning V={V} K={K} {dtype}")
-    tp.report(f"weighted propose V={V} K={K} {dtype}")
+    tv.report(f"weighted verify V={V} K={K} {dtype} {layout}")
+    tt.report(f"weighted thinning V={V} K={K} {dtype} {layout}")
+    tp.report(f"weighted propose V={V} K={K} {dtype} {layout}")
     for t in (tv, tt, tp):
         assert t.tolerated <= max(1, t.sequences // 200)
 

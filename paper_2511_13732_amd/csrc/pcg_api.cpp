@@ -179,7 +179,7 @@ int pcg_group_probs(const pcg_groups *groups, const void *logits, pcg_dtype dt, 
   StageTimer tm(stream);
   hipError_t e;
   tm.begin(kStageStats);
-  if ((e = launch_row_stats(rs, bf16, groups->V, rows, f.c, parts, stream)) != hipSuccess)
+  if ((e = launch_row_stats(rs, bf16, groups->V, rows, f.c, true, parts, stream)) != hipSuccess)
     return hip_fail(e);
   tm.end(kStageStats);
   const int64_t batch = group_probs_batch(groups->V, rows);
@@ -333,7 +333,8 @@ int pcg_verify(const pcg_groups *groups, const void *target_logits, const void *
   StageTimer tm(stream);
   hipError_t e;
   tm.begin(kStageStats);
-  if ((e = launch_row_stats(rs, bf16, V, rows, f.c, parts, stream)) != hipSuccess) return hip_fail(e);
+  // streaming pass: only the rejected position's two rows (2 of 2K+1) are read again
+  if ((e = launch_row_stats(rs, bf16, V, rows, f.c, true, parts, stream)) != hipSuccess) return hip_fail(e);
   tm.end(kStageStats);
   tm.begin(kStageAccept);
   if ((e = launch_accept_delta(aa, bf16, B, f.c_lo, table, stream)) != hipSuccess)
@@ -402,7 +403,8 @@ int pcg_propose(const pcg_groups *groups, const void *draft_logits, pcg_dtype dt
   StageTimer tm(stream);
   hipError_t e;
   tm.begin(kStageStats);
-  if ((e = launch_row_stats(rs, bf16, V, rows, f.c, parts, stream)) != hipSuccess) return hip_fail(e);
+  // cached pass: the draw that follows is a chain of small reads into the same rows
+  if ((e = launch_row_stats(rs, bf16, V, rows, f.c, false, parts, stream)) != hipSuccess) return hip_fail(e);
   tm.end(kStageStats);
   tm.begin(kStagePropose);
   if ((e = launch_propose(rs, bf16, V, K, pos0, f.c, parts, groups->tok_ptr, groups->tok_groups,
@@ -453,7 +455,8 @@ int pcg_verify_thinning(const pcg_groups *groups, const void *target_logits,
   StageTimer tm(stream);
   hipError_t e;
   tm.begin(kStageStats);
-  if ((e = launch_row_stats(rs, bf16, V, rows, f.c, parts, stream)) != hipSuccess) return hip_fail(e);
+  // cached pass: every trial is a chain of small reads into the same rows
+  if ((e = launch_row_stats(rs, bf16, V, rows, f.c, false, parts, stream)) != hipSuccess) return hip_fail(e);
   tm.end(kStageStats);
   tm.begin(kStageThin);
   if ((e = launch_accept_thin(aa, bf16, B, groups->tok_ptr, groups->tok_groups,

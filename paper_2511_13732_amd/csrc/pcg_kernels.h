@@ -12,8 +12,9 @@ namespace pcg {
 
 int32_t stats_nparts(int32_t V);
 
+// streaming: read the logits with nontemporal loads (faster pass, nothing left in the caches)
 hipError_t launch_row_stats(const RowSet &rs, bool bf16, int32_t V, int64_t nrows, float c,
-                            StatPart *parts, hipStream_t stream);
+                            bool streaming, StatPart *parts, hipStream_t stream);
 
 int32_t accept_nsplit(int32_t V, int32_t B);
 

@@ -29,7 +29,17 @@ constexpr int kStatsWaves = 4;        // waves per workgroup
 // Row id of a workgroup: grid.y carries the low part, grid.z the rest (grid.y <= 65535).
 constexpr int kRowsPerGridY = 32768;
 
-template <bool BF16, bool VEC>
+// A 16-byte load, optionally marked as streaming (nontemporal).  Streaming loads reach a higher
+// rate on a pass over logits that are larger than the caches, but leave nothing behind for the
+// kernels that follow; STREAM is chosen per entry point by how much of the rows those re-read.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+template <bool STREAM>
+__device__ __forceinline__ u32x4 load16(const void *p) {
+  if constexpr (STREAM) return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+  else return *reinterpret_cast<const u32x4 *>(p);
+}
+
+template <bool BF16, bool VEC, bool STREAM>
 __global__ __launch_bounds__(kStatsWaves *kWave) void row_stats_kernel(RowSet rs, int32_t V,
                                                                        int32_t nparts, int64_t nrows,
                                                                        float c, StatPart *parts) {
@@ -48,9 +58,9 @@ __global__ __launch_bounds__(kStatsWaves *kWave) void row_stats_kernel(RowSet rs
     // each load instruction covers 1 KiB of the row
     if constexpr (BF16) {
       const uint4 *src = reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(rowp) + e0);
-      uint4 w[4];
+      u32x4 w[4];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) w[j] = src[j * kWave + lane];
+      for (int j = 0; j < 4; ++j) w[j] = load16<STREAM>(src + j * kWave + lane);
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const uint32_t ww[4] = {w[j].x, w[j].y, w[j].z, w[j].w};
@@ -62,12 +72,13 @@ __global__ __launch_bounds__(kStatsWaves *kWave) void row_stats_kernel(RowSet rs
       }
     } else {
       const float4 *src = reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(rowp) + e0);
-      float4 w[8];
+      u32x4 w[8];
 #pragma unroll
-      for (int j = 0; j < 8; ++j) w[j] = src[j * kWave + lane];
+      for (int j = 0; j < 8; ++j) w[j] = load16<STREAM>(src + j * kWave + lane);
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
-        x[j * 4] = w[j].x; x[j * 4 + 1] = w[j].y; x[j * 4 + 2] = w[j].z; x[j * 4 + 3] = w[j].w;
+        x[j * 4] = __uint_as_float(w[j].x); x[j * 4 + 1] = __uint_as_float(w[j].y);
+        x[j * 4 + 2] = __uint_as_float(w[j].z); x[j * 4 + 3] = __uint_as_float(w[j].w);
       }
     }
   } else {
@@ -1413,19 +1424,24 @@ static inline bool rows_vector_aligned(const RowSet &rs, bool bf16) {
 int32_t stats_nparts(int32_t V) { return (V + kPartElems - 1) / kPartElems; }
 
 hipError_t launch_row_stats(const RowSet &rs, bool bf16, int32_t V, int64_t nrows, float c,
-                            StatPart *parts, hipStream_t stream) {
+                            bool streaming, StatPart *parts, hipStream_t stream) {
   const int32_t nparts = stats_nparts(V);
   if (nrows == 0) return hipSuccess;
   const unsigned gy = (unsigned) std::min<int64_t>(nrows, kRowsPerGridY);
   const unsigned gz = (unsigned) ((nrows + kRowsPerGridY - 1) / kRowsPerGridY);
   const dim3 grid((nparts + kStatsWaves - 1) / kStatsWaves, gy, gz), block(kStatsWaves * kWave);
   const bool vec = rows_vector_aligned(rs, bf16);
+  auto launch = [&](auto kernel) {
+    kernel<<<grid, block, 0, stream>>>(rs, V, nparts, nrows, c, parts);
+  };
   if (bf16) {
-    if (vec) row_stats_kernel<true, true><<<grid, block, 0, stream>>>(rs, V, nparts, nrows, c, parts);
-    else row_stats_kernel<true, false><<<grid, block, 0, stream>>>(rs, V, nparts, nrows, c, parts);
+    if (!vec) launch(row_stats_kernel<true, false, false>);
+    else if (streaming) launch(row_stats_kernel<true, true, true>);
+    else launch(row_stats_kernel<true, true, false>);
   } else {
-    if (vec) row_stats_kernel<false, true><<<grid, block, 0, stream>>>(rs, V, nparts, nrows, c, parts);
-    else row_stats_kernel<false, false><<<grid, block, 0, stream>>>(rs, V, nparts, nrows, c, parts);
+    if (!vec) launch(row_stats_kernel<false, false, false>);
+    else if (streaming) launch(row_stats_kernel<false, true, true>);
+    else launch(row_stats_kernel<false, true, false>);
   }
   return hipGetLastError();
 }

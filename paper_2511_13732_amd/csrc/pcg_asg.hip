@@ -47,28 +47,26 @@ __global__ __launch_bounds__(256) void asg_normalize_kernel(const float *emb, in
 }
 
 // ---------------------------------------------------------------------------------------------
-// Similarity + threshold.  A workgroup of four waves owns a 128 x 128 tile of the similarity
-// matrix; each wave a 64 x 64 quarter as 2 x 2 MFMA blocks of 32 x 32.  Both operands are rows
-// of the same matrix of unit vectors, staged through LDS 64 columns of k at a time (double
-// buffered; rows padded by 16 bytes so that the 16-byte operand reads of consecutive rows fall
-// into different banks).  The matrix is symmetric: only tiles on or above the diagonal are
-// computed, and a pair found off the diagonal is recorded for both of its tokens.
+// Similarity + threshold.  A workgroup of four waves owns a 256 x 256 tile of the similarity
+// matrix; each wave a 128 x 128 quarter as 4 x 4 MFMA blocks of 32 x 32 (256 accumulators per
+// lane; with smaller wave tiles the operand reads alone saturate LDS).  Both operands are rows
+// of the same matrix of unit vectors.  They travel global memory -> LDS directly, 32 columns of
+// k per stage, four stages resident: while one is used the loads of the next three are in flight,
+// and no register is spent on staging.  The matrix is symmetric: only tiles on or above the
+// diagonal are computed, and a pair found off the diagonal is recorded for both of its tokens.
 // ---------------------------------------------------------------------------------------------
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // 16 bytes on their way to LDS
 
-constexpr int kSimTile = 128;                 // rows and columns of a workgroup's tile
-constexpr int kSimK = 64;                     // k columns per LDS stage
-constexpr int kSimRowBytes = kSimK * 2 + 16;  // padded LDS row
+constexpr int kSimTile = 256;                 // rows and columns of a workgroup's tile
+constexpr int kSimK = 32;                     // k columns per LDS stage: rows of 64 bytes
+constexpr int kSimBufs = 4;                   // stages resident in LDS
 constexpr int kSimThreads = 256;
-constexpr int kSimChunks = kSimTile * (kSimK / 8) / kSimThreads;   // 16-byte chunks per thread and tile
-
-struct SimTiles {
-  unsigned char a[2][kSimTile * kSimRowBytes];
-  unsigned char b[2][kSimTile * kSimRowBytes];
-};
+constexpr int kSimStageBytes = kSimTile * kSimK * 2;      // one operand of one stage: 16 KiB
+constexpr int kSimLoads = 2 * kSimTile / 16 / 4;          // direct-to-LDS loads per wave and stage: 8
+constexpr int kSimQueue = 8192;               // pairs a workgroup can hold back in LDS
+constexpr int kSimPatchRows = 8, kSimPatchCols = 4;       // tiles that one XCD works on together
 
 // Record v as a member of G(t).
 __device__ __forceinline__ void asg_emit(int32_t t, int32_t v, int32_t cap, int32_t *count,
@@ -77,107 +75,204 @@ __device__ __forceinline__ void asg_emit(int32_t t, int32_t v, int32_t cap, int3
   if (pos < cap) cand[(int64_t) t * cap + pos] = v;
 }
 
-// A thread's 16-byte chunks of one stage, from global memory into registers ...
-__device__ __forceinline__ void sim_fetch(const uint16_t *__restrict__ unit,
-                                          const int32_t (&src_a)[kSimChunks],
-                                          const int32_t (&src_b)[kSimChunks], int32_t k0,
-                                          u32x4 (&ga)[kSimChunks], u32x4 (&gb)[kSimChunks]) {
-#pragma unroll
-  for (int c = 0; c < kSimChunks; ++c) {
-    ga[c] = *reinterpret_cast<const u32x4 *>(unit + src_a[c] + k0);
-    gb[c] = *reinterpret_cast<const u32x4 *>(unit + src_b[c] + k0);
+// Appends the pair (t, v) to the workgroup's queue in LDS; pairs beyond its capacity are
+// recorded at once.
+__device__ __forceinline__ void sim_queue_pair(int32_t t, int32_t v, int32_t cap, int32_t *count,
+                                               int32_t *cand, uint32_t *qn, uint2 *q) {
+  const uint32_t k = atomicAdd(qn, 1u);
+  if (k < (uint32_t) kSimQueue) {
+    q[k] = make_uint2((uint32_t) t, (uint32_t) v);
+  } else {
+    asg_emit(t, v, cap, count, cand);
+    if (t != v) asg_emit(v, t, cap, count, cand);
   }
 }
 
-// ... and from registers into the LDS tiles.
-__device__ __forceinline__ void sim_stage(unsigned char *a, unsigned char *b,
-                                          const int32_t (&dst)[kSimChunks],
-                                          const u32x4 (&ga)[kSimChunks],
-                                          const u32x4 (&gb)[kSimChunks]) {
-#pragma unroll
-  for (int c = 0; c < kSimChunks; ++c) {
-    *reinterpret_cast<u32x4 *>(a + dst[c]) = ga[c];
-    *reinterpret_cast<u32x4 *>(b + dst[c]) = gb[c];
-  }
+// Waits until at most N of this wave's vector-memory operations are still in flight.
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+  __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
+
+// Meets the other waves of the workgroup without the fence of __syncthreads(), which would wait
+// for every load still in flight.  The caller has waited for exactly what it needs.
+__device__ __forceinline__ void bare_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
 }
 
 __global__ __launch_bounds__(kSimThreads) void asg_similarity_kernel(
     const uint16_t *__restrict__ unit, int32_t V, int32_t d, float theta, int32_t cap,
     int32_t *count, int32_t *cand) {
-  const int tj = blockIdx.x, ti = blockIdx.y;
-  if (tj < ti) return;                         // lower triangle: covered by its mirror tile
-  __shared__ __attribute__((aligned(16))) SimTiles lds;
-  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+  // Workgroups go to the 8 XCDs round-robin; the 32 that run together on one XCD take a patch of
+  // 8 x 4 tiles, so that they find each other's rows in their L2.
+  const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+  constexpr int kPatch = kSimPatchRows * kSimPatchCols;
+  const int patch = (local / kPatch) * 8 + xcd;
+  const int within = local % kPatch;
+  const int ntl = (V + kSimTile - 1) / kSimTile;
+  const int super_cols = (ntl + kSimPatchCols - 1) / kSimPatchCols;
+  const int ti = (patch / super_cols) * kSimPatchRows + within / kSimPatchCols;
+  const int tj = (patch % super_cols) * kSimPatchCols + within % kSimPatchCols;
+  if (ti >= ntl || tj >= ntl || tj < ti) return;      // the whole workgroup leaves
+  // [buffer][operand][row][64 bytes].  A 16-byte LDS read is served 16 lanes at a time, free of
+  // conflicts when their addresses differ modulo 256 bytes; the four 16-byte chunks of a row are
+  // therefore stored at position chunk ^ ((row >> 2) & 3), which spreads the same chunk of 16
+  // consecutive rows over all 16 slots.
+  __shared__ __attribute__((aligned(1024))) unsigned char lds[kSimBufs * 2 * kSimStageBytes];
+  const int tid = threadIdx.x, lane = tid & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 1, wn = wave & 1;
   const int32_t row0 = ti * kSimTile, col0 = tj * kSimTile;
 
-  // this thread's 16-byte chunks of a stage: tile row and k offset (the same for A and B)
-  int32_t src_a[kSimChunks], src_b[kSimChunks], dst[kSimChunks];
+  // Direct-to-LDS loads: one instruction of a wave fills 1 KiB = 16 rows, lane i the 16 bytes at
+  // row i / 4, position i % 4.  Wave w brings rows 64 w .. 64 w + 63 of both operands.
+  int32_t src[kSimLoads];
+  {
+    const int r = lane >> 2, p = lane & 3;
+    const int c = p ^ ((r >> 2) & 3);                  // the chunk of the row that belongs there
 #pragma unroll
-  for (int c = 0; c < kSimChunks; ++c) {
-    const int chunk = tid + c * kSimThreads;
-    const int r = chunk >> 3, kc = chunk & 7;
-    // rows past the end of the matrix re-read the last row; their results are never recorded
-    src_a[c] = min(row0 + r, V - 1) * d + kc * 8;
-    src_b[c] = min(col0 + r, V - 1) * d + kc * 8;
-    dst[c] = r * kSimRowBytes + kc * 16;
+    for (int j = 0; j < kSimLoads / 2; ++j) {
+      const int row = wave * 64 + j * 16 + r;
+      // rows past the end of the matrix re-read the last row; their results are never recorded
+      src[j] = min(row0 + row, V - 1) * d + c * 8;
+      src[kSimLoads / 2 + j] = min(col0 + row, V - 1) * d + c * 8;
+    }
   }
-  u32x4 ga[kSimChunks], gb[kSimChunks];
+  const int nstages = d / kSimK;        // even: d is a multiple of 64
+  auto load_a = [&](int j, unsigned char *dst, int k0) {
+    __builtin_amdgcn_global_load_lds(
+        (const __attribute__((address_space(1))) void *) (unit + src[j] + k0),
+        (__attribute__((address_space(3))) void *) (dst + j * 1024), 16, 0, 0);
+  };
+  auto load_b = [&](int j, unsigned char *dst, int k0) {
+    __builtin_amdgcn_global_load_lds(
+        (const __attribute__((address_space(1))) void *) (unit + src[kSimLoads / 2 + j] + k0),
+        (__attribute__((address_space(3))) void *) (dst + kSimStageBytes + j * 1024), 16, 0, 0);
+  };
 
-  floatx16 acc[2][2];
+  floatx16 acc[4][4];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < 4; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  // operand addresses of this lane: row (lane % 32) of the block, k half (lane / 32)
-  const int frag = (lane & 31) * kSimRowBytes + (lane >> 5) * 16;
-  const int a_off = (wm * 64) * kSimRowBytes + frag, b_off = (wn * 64) * kSimRowBytes + frag;
+  // operand reads of this lane: row lane % 32 of a block, k half lane / 32 of a 16-column step
+  const int fr = lane & 31, fh = lane >> 5;
+  const int sw = (fr >> 2) & 3;                        // block rows start at multiples of 32
+  const int a_row = (wm * 128 + fr) * 64, b_row = (wn * 128 + fr) * 64;
+  const int pos0 = ((0 + fh) ^ sw) * 16, pos1 = ((2 + fh) ^ sw) * 16;
 
-  const int nstages = d / kSimK;
-  sim_fetch(unit, src_a, src_b, 0, ga, gb);
-  sim_stage(lds.a[0], lds.b[0], dst, ga, gb);
-  __syncthreads();
-  for (int s = 0; s < nstages; ++s) {
-    const int buf = s & 1;
-    if (s + 1 < nstages) sim_fetch(unit, src_a, src_b, (s + 1) * kSimK, ga, gb);
+  bf16x8 f0a[4], f0b[4], f1a[4], f1b[4];      // operands of the two 16-column steps of a stage
+  // One 16-column step: 16 MFMAs on (ca, cb).  Behind the first eight of them, one at a time,
+  // the next step's operands (na, nb) are read from LDS at ta / tb and, with FETCH, the eight
+  // loads of a later stage are started.  The LDS and memory queues are short: instructions
+  // issued in a burst would hold the MFMAs behind them back, and reads issued late would make
+  // the next step wait.  The order is pinned.
+  auto step = [&](const bf16x8 (&ca)[4], const bf16x8 (&cb)[4], bf16x8 (&na)[4], bf16x8 (&nb)[4],
+                  const unsigned char *ta, const unsigned char *tb, bool with_fetch,
+                  unsigned char *dst, int k0) {
 #pragma unroll
-    for (int kk = 0; kk < kSimK / 16; ++kk) {
-      bf16x8 fa[2], fb[2];
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        fa[i] = *reinterpret_cast<const bf16x8 *>(lds.a[buf] + a_off + i * 32 * kSimRowBytes + kk * 32);
-        fb[i] = *reinterpret_cast<const bf16x8 *>(lds.b[buf] + b_off + i * 32 * kSimRowBytes + kk * 32);
+    for (int m = 0; m < 16; ++m) {
+      const int i = m >> 2, j = m & 3;
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ca[i], cb[j], acc[i][j], 0, 0, 0);
+      if (m < 8) {
+        __builtin_amdgcn_sched_barrier(0);
+        if (with_fetch) {
+          if ((m & 1) == 0) load_a(m >> 1, dst, k0); else load_b(m >> 1, dst, k0);
+        }
+        if (m < 4) na[m] = *reinterpret_cast<const bf16x8 *>(ta + m * 32 * 64);
+        else nb[m - 4] = *reinterpret_cast<const bf16x8 *>(tb + (m - 4) * 32 * 64);
+        __builtin_amdgcn_sched_barrier(0);
       }
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
     }
-    if (s + 1 < nstages) sim_stage(lds.a[buf ^ 1], lds.b[buf ^ 1], dst, ga, gb);
-    __syncthreads();
+    __builtin_amdgcn_sched_barrier(0);
+  };
+
+  // Loads that would reach past the last stage repeat it instead: nobody reads what they bring,
+  // and the number of loads in flight stays the same on every turn, which the waits rely on.
+#pragma unroll
+  for (int s = 0; s < kSimBufs; ++s) {
+    unsigned char *dst = lds + s * 2 * kSimStageBytes + wave * 64 * 64;
+    const int k0 = min(s, nstages - 1) * kSimK;
+#pragma unroll
+    for (int j = 0; j < kSimLoads / 2; ++j) { load_a(j, dst, k0); load_b(j, dst, k0); }
+  }
+  wait_vm<3 * kSimLoads>();                 // stage 0 is in; the three behind it may be on their way
+  bare_barrier();
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    f0a[i] = *reinterpret_cast<const bf16x8 *>(lds + a_row + pos0 + i * 32 * 64);
+    f0b[i] = *reinterpret_cast<const bf16x8 *>(lds + kSimStageBytes + b_row + pos0 + i * 32 * 64);
+  }
+  for (int s = 0; s < nstages; ++s) {
+    unsigned char *cur = lds + (s % kSimBufs) * 2 * kSimStageBytes;
+    const unsigned char *nxt = lds + ((s + 1) % kSimBufs) * 2 * kSimStageBytes;
+    // first half of the stage; the operands of its second half arrive behind it
+    step(f0a, f0b, f1a, f1b, cur + a_row + pos1, cur + kSimStageBytes + b_row + pos1, false, nullptr, 0);
+    // This wave's loads of stage s + 1 have landed once only those of the two stages behind it
+    // are out; past the barrier everyone's have, and nobody reads buffer `cur` any more (the
+    // operands of this stage's second half are in registers).
+    wait_vm<2 * kSimLoads>();
+    bare_barrier();
+    // second half; behind it the loads of stage s + 4 start, into the buffer just freed, and the
+    // next stage's first operands are read
+    step(f1a, f1b, f0a, f0b, nxt + a_row + pos0, nxt + kSimStageBytes + b_row + pos0, true,
+         cur + wave * 64 * 64, min(s + kSimBufs, nstages - 1) * kSimK);
   }
 
-  // Threshold (Eq. 1).  Accumulator r of a lane is row 8 (r / 4) + 4 (lane / 32) + r % 4 and
-  // column lane % 32 of its 32 x 32 block.
-  const bool diagonal = ti == tj;
+  // Threshold (Eq. 1).  The stage buffers are free once the loads past the end have landed: pairs
+  // that pass are collected there, then every thread records its share of them, so that the
+  // round trips of the atomics overlap instead of following one another.
+  wait_vm<0>();
+  __syncthreads();
+  uint32_t *qn = reinterpret_cast<uint32_t *>(lds);
+  uint2 *q = reinterpret_cast<uint2 *>(lds + 16);
+  if (tid == 0) *qn = 0;
+  __syncthreads();
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < 4; ++j) {
+      // Accumulator r of a lane is row 8 (r / 4) + 4 (lane / 32) + r % 4 and column lane % 32 of
+      // the 32 x 32 block.  Most blocks hold nothing above the threshold: one maximum per lane
+      // and a ballot settle those.
+      const int32_t t0 = row0 + wm * 128 + i * 32, v0 = col0 + wn * 128 + j * 32;
+      if (v0 + 31 < t0) continue;                      // wholly below the diagonal
+      const floatx16 a = acc[i][j];
+      const float m = fmaxf(fmaxf(fmaxf(fmaxf(a[0], a[1]), fmaxf(a[2], a[3])),
+                                  fmaxf(fmaxf(a[4], a[5]), fmaxf(a[6], a[7]))),
+                            fmaxf(fmaxf(fmaxf(a[8], a[9]), fmaxf(a[10], a[11])),
+                                  fmaxf(fmaxf(a[12], a[13]), fmaxf(a[14], a[15]))));
+      const int32_t v = v0 + (lane & 31), tl = t0 + 4 * (lane >> 5);
+      if (__builtin_amdgcn_ballot_w64(m > theta) != 0) {
+        uint32_t hits = 0;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int32_t t = row0 + wm * 64 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        const int32_t v = col0 + wn * 64 + j * 32 + (lane & 31);
-        if (t >= V || v >= V) continue;
-        if (acc[i][j][r] > theta || t == v) {
-          asg_emit(t, v, cap, count, cand);
-          if (!diagonal) asg_emit(v, t, cap, count, cand);
+        for (int r = 0; r < 16; ++r) hits |= (a[r] > theta ? 1u : 0u) << r;
+        while (hits) {                                 // only the lanes that hold a pair
+          const int r = __builtin_ctz(hits);
+          hits &= hits - 1;
+          const int32_t t = tl + 8 * (r >> 2) + (r & 3);
+          if (t < V && v < V && v > t) sim_queue_pair(t, v, cap, count, cand, qn, q);
         }
       }
+      // a token is always a member of its own group, whatever the rounded product says
+      if (t0 == v0 && lane < 32 && t0 + lane < V)
+        sim_queue_pair(t0 + lane, t0 + lane, cap, count, cand, qn, q);
+    }
+  __syncthreads();
+  const uint32_t nq = min(*qn, (uint32_t) kSimQueue);
+  for (uint32_t k = tid; k < nq; k += kSimThreads) {
+    const uint2 pr = q[k];
+    const int32_t t = (int32_t) pr.x, v = (int32_t) pr.y;
+    const int32_t p0 = atomicAdd(&count[t], 1);
+    const int32_t p1 = t != v ? atomicAdd(&count[v], 1) : cap;
+    if (p0 < cap) cand[(int64_t) t * cap + p0] = v;
+    if (p1 < cap) cand[(int64_t) v * cap + p1] = t;
+  }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -399,9 +494,12 @@ int pcg_asg_build(const uint16_t *unit_bf16, int32_t V, int32_t d, float theta, 
   asg_fill_kernel<<<vb, 256, 0, stream>>>(count, V, 0);
   asg_fill_kernel<<<vb, 256, 0, stream>>>(mult, V, 0);
   asg_fill_kernel<<<1, 256, 0, stream>>>((int32_t *) totals, 16, 0);
-  const unsigned tiles = (unsigned) ((V + kSimTile - 1) / kSimTile);
-  asg_similarity_kernel<<<dim3(tiles, tiles), kSimThreads, 0, stream>>>(unit_bf16, V, d, theta, cap,
-                                                                        count, cand);
+  const int tiles = (V + kSimTile - 1) / kSimTile;
+  const int patch_rows = (tiles + kSimPatchRows - 1) / kSimPatchRows;
+  const int patch_cols = (tiles + kSimPatchCols - 1) / kSimPatchCols;
+  const int patches = (patch_rows * patch_cols + 7) / 8 * 8;      // dealt to the 8 XCDs in turn
+  asg_similarity_kernel<<<(unsigned) (patches * kSimPatchRows * kSimPatchCols), kSimThreads, 0, stream>>>(
+      unit_bf16, V, d, theta, cap, count, cand);
   if ((e = hipGetLastError()) != hipSuccess) return fail(e);
   int32_t cap2 = 1;
   while (cap2 < cap) cap2 <<= 1;

@@ -109,6 +109,7 @@ def test_group_probs_many_rows_in_batches():
     (2048, 2048, 10, 40, 12, 1, "f32", 0.7),     # K = 1
     (3000, 500, 40, 128, 5, 64, "f32", 1.0),     # K = PCG_MAX_K, wide groups
     (50000, 6000, 10, 30, 6, 4, "f32", 1.0),     # two LDS tiles
+    (100000, 3000, 5, 40, 3, 2, "bf16", 1.0),    # three LDS tiles
     (5, 4, 1, 3, 200, 2, "f32", 1.0),            # tiny vocabulary
 ])
 @pytest.mark.parametrize("layout", ["prepared", "prepared-4096", "csr"])

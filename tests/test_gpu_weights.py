@@ -37,6 +37,7 @@ SHAPES = [
     (4097, 3000, 4, 20, 9, 8, "bf16", 1.0),      # unaligned rows
     (3000, 500, 40, 128, 5, 16, "f32", 1.0),     # groups wider than a wave
     (50000, 6000, 10, 30, 6, 4, "f32", 1.3),     # two LDS tiles
+    (100000, 3000, 5, 40, 3, 2, "bf16", 1.0),    # three LDS tiles
 ]
 
 

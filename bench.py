@@ -247,6 +247,31 @@ def main():
         "stages_us": {k: round(1e3 * v, 2) for k, v in gp_ms.items() if v > 0.0 and k != "event_overhead"}}
     del gp_out, gp_ws
 
+    # The same step recorded once per input set into a HIP graph and replayed (the entry point
+    # only launches kernels).  A recorded call repeats its Philox offset, so this is what the
+    # launches cost, not a serving loop; it is never `value`.
+    side = torch.cuda.Stream()
+    graphs = []
+    with torch.cuda.stream(side):
+        step(0)
+    side.synchronize()
+    for k in range(len(sets)):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            step(k)
+        graphs.append(g)
+    for i in range(args.warmup):
+        graphs[i % len(graphs)].replay()
+    torch.cuda.synchronize()
+    t_begin = time.perf_counter()
+    for i in range(args.steps):
+        graphs[i % len(graphs)].replay()
+    torch.cuda.synchronize()
+    g_elapsed = time.perf_counter() - t_begin
+    result["graph_replay"] = {"value": round(positions * args.steps / g_elapsed, 1), "unit": "positions/s",
+                              "ms_per_step": round(1e3 * g_elapsed / args.steps, 5)}
+    del graphs
+
     # General per-entry weights (Eq. 2) instead of the equal split, through the prepared layout
     # that carries them and, for comparison, straight from the CSR.
     wgroups = pcg.Groups.from_csr(cfg.V, rp, mem, dev, reverse=True,

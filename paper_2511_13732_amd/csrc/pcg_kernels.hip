@@ -1152,10 +1152,11 @@ __global__ __launch_bounds__(kFinalThreads) void finalize_kernel(FinalizeArgs fa
 // ---------------------------------------------------------------------------------------------
 // The same sum read from the prepared layout (pcg_prepared): no cross-lane reduction and no
 // address arithmetic beyond a shift.  A workgroup owns one chunk of consecutive groups of one
-// table row.  In its q-th turn wave w takes block block_of(q, w) of the chunk; lane l handles
-// the block's 4 groups r*64 + l side by side -- the same groups in every tile pass, so their
-// running sums stay in registers.  One 16-byte load per lane brings 2 slots for each of the 4
-// groups.  Results are put back into group order through LDS and leave with coalesced stores;
+// table row.  Wave w owns the blocks block_of(q, w), q = 0..3, of the chunk and walks them side
+// by side; lane l handles each block's 4 groups r*64 + l -- the same 16 groups in every tile
+// pass, so their running sums stay in registers.  One 16-byte load per lane brings 2 slots for
+// each of a block's 4 groups.  Results are put back into group order through LDS and leave with
+// coalesced stores;
 // with CSUM the workgroup also writes the chunk's total of max(0, .) in double, summed in a
 // fixed order.
 // ---------------------------------------------------------------------------------------------
@@ -1167,68 +1168,8 @@ __device__ __forceinline__ void gather_step(const float *tab, const uint4 w, flo
   acc[2] += tab[w.z >> 16]; acc[3] += tab[w.w >> 16];
 }
 
-// Steps k .. k+3 of the block that starts at unit `off` of the data (clamped to its last
-// step, so every load is in bounds).  `data` stays the kernel's own global pointer so that the
-// loads are global loads, which the hardware returns in order.
-__device__ __forceinline__ void load_steps(uint4 *w, const uint4 *__restrict__ data, uint32_t off,
-                                           uint32_t k, uint32_t n) {
-#pragma unroll
-  for (int i = 0; i < 4; ++i) w[i] = data[(size_t) off + (size_t) min(k + i, n - 1) * kWave];
-}
-
-__device__ __forceinline__ void gather_steps(const float *tab, const uint4 *w, uint32_t left,
-                                             float *acc) {
-  if (left >= 4) {             // a full turn is straight-line code: 32 gathers in flight
-    gather_step(tab, w[0], acc);
-    gather_step(tab, w[1], acc);
-    gather_step(tab, w[2], acc);
-    gather_step(tab, w[3], acc);
-  } else {
-    gather_step(tab, w[0], acc);
-    if (left > 1) gather_step(tab, w[1], acc);
-    if (left > 2) gather_step(tab, w[2], acc);
-  }
-}
-
-// One block of n steps, four at a time, with two register buffers used alternately: while
-// the steps in one are gathered, the next four (of this block, or the first of the next block
-// when nnext > 0) are on their way into the other.  On entry the block's first four steps are in
-// A (CUR_IS_A) or B; returns true if the steps loaded last went into A.
-template <bool CUR_IS_A>
-__device__ __forceinline__ bool run_block(const float *tab, uint4 (&A)[4], uint4 (&B)[4],
-                                          const uint4 *__restrict__ data, uint32_t off, uint32_t n,
-                                          uint32_t off_next, uint32_t nnext, float *acc) {
-  uint4 (&X)[4] = CUR_IS_A ? A : B;
-  uint4 (&Y)[4] = CUR_IS_A ? B : A;
-  // Exactly four loads are issued per turn whatever there is to fetch (a turn with nothing
-  // left re-reads step 0), so the number of loads in flight behind the ones being used is the
-  // same on every path and the wait for the current buffer never drains the prefetch.
-  auto prefetch = [&](uint4 (&dst)[4], uint32_t k) {
-    const bool own = k + 4 < n, next = !own && nnext > 0;
-    load_steps(dst, data, next ? off_next : off, own ? k + 4 : 0u, next ? nnext : n);
-  };
-  uint32_t k = 0;
-  while (true) {
-    prefetch(Y, k);
-    gather_steps(tab, X, n - k, acc);
-    k += 4;
-    if (k >= n) return !CUR_IS_A;
-    prefetch(X, k);
-    gather_steps(tab, Y, n - k, acc);
-    k += 4;
-    if (k >= n) return CUR_IS_A;
-  }
-}
-
 // The same with general weights (Eq. 4): every slot comes with its w_{k,t}, 8 floats per lane
-// and step next to the 8 slots.  Two steps per turn keep the two register buffers at 48 dwords.
-constexpr int kTurnW = 1;
-
-struct StepsW {
-  uint4 s[kTurnW];
-  float4 w[2 * kTurnW];
-};
-
+// and step next to the 8 slots.
 __device__ __forceinline__ void gather_step_w(const float *tab, const uint4 s, const float4 a,
                                               const float4 b, float *acc) {
   acc[0] = fmaf(tab[s.x & 0xffffu], a.x, acc[0]); acc[1] = fmaf(tab[s.y & 0xffffu], a.z, acc[1]);
@@ -1237,49 +1178,31 @@ __device__ __forceinline__ void gather_step_w(const float *tab, const uint4 s, c
   acc[2] = fmaf(tab[s.z >> 16], b.y, acc[2]); acc[3] = fmaf(tab[s.w >> 16], b.w, acc[3]);
 }
 
-__device__ __forceinline__ void load_steps_w(StepsW &x, const uint4 *__restrict__ data,
-                                             const float4 *__restrict__ wdata, uint32_t off,
-                                             uint32_t k, uint32_t n) {
-#pragma unroll
-  for (int i = 0; i < kTurnW; ++i) {
-    const size_t unit = (size_t) off + (size_t) min(k + i, n - 1) * kWave;
-    x.s[i] = data[unit];
-    x.w[2 * i] = wdata[2 * unit];
-    x.w[2 * i + 1] = wdata[2 * unit + 1];
+// One step of one block as it comes from memory: 8 slots and, with weights, their 8 weights.
+template <bool WEIGHTED>
+struct GatherStep;
+template <>
+struct GatherStep<false> {
+  uint4 s;
+  __device__ __forceinline__ void load(const uint4 *__restrict__ data, const float4 *, size_t unit) {
+    s = data[unit];
   }
-}
-
-__device__ __forceinline__ void gather_steps_w(const float *tab, const StepsW &x, uint32_t left,
-                                               float *acc) {
-  gather_step_w(tab, x.s[0], x.w[0], x.w[1], acc);
-  if constexpr (kTurnW > 1)
-    if (left > 1) gather_step_w(tab, x.s[1], x.w[2], x.w[3], acc);
-}
-
-template <bool CUR_IS_A>
-__device__ __forceinline__ bool run_block_w(const float *tab, StepsW &A, StepsW &B,
-                                            const uint4 *__restrict__ data,
-                                            const float4 *__restrict__ wdata, uint32_t off,
-                                            uint32_t n, uint32_t off_next, uint32_t nnext,
-                                            float *acc) {
-  StepsW &X = CUR_IS_A ? A : B;
-  StepsW &Y = CUR_IS_A ? B : A;
-  auto prefetch = [&](StepsW &dst, uint32_t k) {
-    const bool own = k + kTurnW < n, next = !own && nnext > 0;
-    load_steps_w(dst, data, wdata, next ? off_next : off, own ? k + kTurnW : 0u, next ? nnext : n);
-  };
-  uint32_t k = 0;
-  while (true) {
-    prefetch(Y, k);
-    gather_steps_w(tab, X, n - k, acc);
-    k += kTurnW;
-    if (k >= n) return !CUR_IS_A;
-    prefetch(X, k);
-    gather_steps_w(tab, Y, n - k, acc);
-    k += kTurnW;
-    if (k >= n) return CUR_IS_A;
+  __device__ __forceinline__ void apply(const float *tab, float *acc) const { gather_step(tab, s, acc); }
+};
+template <>
+struct GatherStep<true> {
+  uint4 s;
+  float4 w0, w1;
+  __device__ __forceinline__ void load(const uint4 *__restrict__ data,
+                                       const float4 *__restrict__ wdata, size_t unit) {
+    s = data[unit];
+    w0 = wdata[2 * unit];
+    w1 = wdata[2 * unit + 1];
   }
-}
+  __device__ __forceinline__ void apply(const float *tab, float *acc) const {
+    gather_step_w(tab, s, w0, w1, acc);
+  }
+};
 
 template <bool CSUM, bool WEIGHTED>
 __global__ __launch_bounds__(kGatherThreads) void gather_prepared_kernel(
@@ -1320,67 +1243,84 @@ __global__ __launch_bounds__(kGatherThreads) void gather_prepared_kernel(
   for (int j = 0; j < kMaxAcc; ++j) acc[j] = 0.f;
   if constexpr (!WEIGHTED) load_where();
 
-  for (int h = 0; h < ntiles; ++h) {
-    const int32_t t0 = h * tile_len;
-    const int32_t tl = min(tile_len, V - t0);
-    if (h > 0) __syncthreads();                       // everyone is done reading the old tile
-    if (((V | tl) & 3) == 0) {                        // rows and tiles are 16-byte aligned
-      const float4 *s4 = reinterpret_cast<const float4 *>(src + t0);
-      float4 *t4 = reinterpret_cast<float4 *>(tab);
-      for (int32_t k = threadIdx.x; k < (tl >> 2); k += kGatherThreads) t4[k] = s4[k];
-    } else {
-      for (int32_t k = threadIdx.x; k < tl; k += kGatherThreads) tab[k] = src[t0 + k];
-    }
-    if (threadIdx.x < kBanks) tab[tile_len + threadIdx.x] = 0.f;   // the padding slots
-    __syncthreads();
-    // The wave's blocks of this tile.  Steps are taken four at a time; the loads of the next
-    // four (of this block, or the first of the next block) are issued before the current four
-    // are used, so their latency hides behind 32 LDS gathers per lane.
+  // descriptors (first unit and number of steps) of this wave's blocks in tile h
+  auto load_desc = [&](int h, uint32_t (&steps)[kMaxBlocksPerWave], uint32_t (&offs)[kMaxBlocksPerWave]) {
     const uint32_t *dsc = desc + ((size_t) (chunk * ntiles + h) * bpc) * 2;
-    uint32_t steps[kMaxBlocksPerWave], offs[kMaxBlocksPerWave];
 #pragma unroll
     for (int q = 0; q < kMaxBlocksPerWave; ++q) {
       const int bl = block_of(q, wave);
       steps[q] = 0;
-      offs[q] = lane;
-      if (bl < bpc) {                                 // uniform over the wave
+      offs[q] = 0;
+      if (bl < bpc && h < ntiles) {                   // uniform over the wave: scalar registers
         steps[q] = dsc[2 * bl + 1];
-        offs[q] = dsc[2 * bl] + lane;
+        offs[q] = dsc[2 * bl];
       }
     }
-    bool in_a = true, primed = false;
-    if constexpr (WEIGHTED) {
-      StepsW bufA, bufB;
-#pragma unroll
-      for (int q = 0; q < kMaxBlocksPerWave; ++q) {
-        const uint32_t n = steps[q];
-        if (n == 0) continue;                         // uniform
-        const int qn = (q + 1) % kMaxBlocksPerWave;
-        const uint32_t nn = (q + 1 < kMaxBlocksPerWave) ? steps[qn] : 0;
-        if (!primed) {
-          if (in_a) load_steps_w(bufA, data, wdata, offs[q], 0, n);
-          else load_steps_w(bufB, data, wdata, offs[q], 0, n);
-        }
-        in_a = in_a ? run_block_w<true>(tab, bufA, bufB, data, wdata, offs[q], n, offs[qn], nn, acc + q * kLaneGroups)
-                    : run_block_w<false>(tab, bufA, bufB, data, wdata, offs[q], n, offs[qn], nn, acc + q * kLaneGroups);
-        primed = nn > 0;
-      }
+  };
+  uint32_t steps[kMaxBlocksPerWave], offs[kMaxBlocksPerWave];
+  load_desc(0, steps, offs);
+
+  for (int h = 0; h < ntiles; ++h) {
+    const int32_t t0 = h * tile_len;
+    const int32_t tl = min(tile_len, V - t0);
+    if (h > 0) __syncthreads();                       // everyone is done reading the old tile
+    const bool direct = ((V | tl) & 3) == 0;          // rows and tiles are 16-byte aligned
+    if (direct) {
+      // global memory -> LDS directly, 16 bytes per lane: every load of the tile is in flight at
+      // once and none passes through a register (a wave's instruction fills 1 KiB in lane order,
+      // which is the table's own order)
+      const float4 *s4 = reinterpret_cast<const float4 *>(src + t0);
+      const int32_t n4 = tl >> 2;
+      for (int32_t k0 = wave * kWave; k0 < n4; k0 += kGatherThreads)
+        if (k0 + lane < n4)
+          __builtin_amdgcn_global_load_lds(
+              (const __attribute__((address_space(1))) void *) (s4 + k0 + lane),
+              (__attribute__((address_space(3))) void *) (tab + 4 * k0), 16, 0, 0);
     } else {
-      uint4 bufA[4], bufB[4];
+      for (int32_t k = threadIdx.x; k < tl; k += kGatherThreads) tab[k] = src[t0 + k];
+    }
+    if (threadIdx.x < kBanks) tab[tile_len + threadIdx.x] = 0.f;   // the padding slots
+    // The wave's blocks of this tile are walked side by side: turn s takes step s of every block
+    // that has one (kSide blocks at a time: all four, or two when weights travel along), so one
+    // loop with fixed registers serves them all; while a turn is gathered the next one is on its
+    // way (a block that has run out re-reads its last step, which keeps every load in bounds and
+    // the number of loads in flight the same on every turn).  The first turn and the next tile's
+    // descriptors are asked for while the tile is still on its way into LDS.
+    constexpr int kSide = WEIGHTED ? 2 : kMaxBlocksPerWave;
+    GatherStep<WEIGHTED> bufX[kSide], bufY[kSide];
+    auto fetch = [&](GatherStep<WEIGHTED> (&dst)[kSide], int q0, uint32_t turn) {
 #pragma unroll
-      for (int q = 0; q < kMaxBlocksPerWave; ++q) {
-        const uint32_t n = steps[q];
-        if (n == 0) continue;                         // uniform
-        const int qn = (q + 1) % kMaxBlocksPerWave;
-        const uint32_t nn = (q + 1 < kMaxBlocksPerWave) ? steps[qn] : 0;
-        if (!primed) {
-          if (in_a) load_steps(bufA, data, offs[q], 0, n); else load_steps(bufB, data, offs[q], 0, n);
-        }
-        in_a = in_a ? run_block<true>(tab, bufA, bufB, data, offs[q], n, offs[qn], nn, acc + q * kLaneGroups)
-                    : run_block<false>(tab, bufA, bufB, data, offs[q], n, offs[qn], nn, acc + q * kLaneGroups);
-        primed = nn > 0;
+      for (int j = 0; j < kSide; ++j) {
+        const uint32_t n = steps[q0 + j];
+        const uint32_t k = min(turn, n > 0 ? n - 1 : 0u);                   // scalar
+        dst[j].load(data, wdata, (size_t) offs[q0 + j] + (size_t) k * kWave + lane);
+      }
+    };
+    fetch(bufX, 0, 0);
+    uint32_t nsteps[kMaxBlocksPerWave], noffs[kMaxBlocksPerWave];
+    load_desc(h + 1, nsteps, noffs);
+    if (direct) __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): this wave's part of the tile has landed
+    __syncthreads();
+#pragma unroll
+    for (int q0 = 0; q0 < kMaxBlocksPerWave; q0 += kSide) {
+      uint32_t turns = 0;
+#pragma unroll
+      for (int j = 0; j < kSide; ++j) turns = max(turns, steps[q0 + j]);
+      if (q0 > 0) fetch(bufX, q0, 0);
+      for (uint32_t t = 0; t < turns; t += 2) {
+        fetch(bufY, q0, t + 1);
+#pragma unroll
+        for (int j = 0; j < kSide; ++j)
+          if (t < steps[q0 + j]) bufX[j].apply(tab, acc + (q0 + j) * kLaneGroups);      // uniform
+        if (t + 1 >= turns) break;
+        fetch(bufX, q0, t + 2);
+#pragma unroll
+        for (int j = 0; j < kSide; ++j)
+          if (t + 1 < steps[q0 + j]) bufY[j].apply(tab, acc + (q0 + j) * kLaneGroups);  // uniform
       }
     }
+#pragma unroll
+    for (int q = 0; q < kMaxBlocksPerWave; ++q) { steps[q] = nsteps[q]; offs[q] = noffs[q]; }
   }
 
   // back into group order through LDS, then coalesced stores

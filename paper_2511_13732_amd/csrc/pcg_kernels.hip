@@ -1184,8 +1184,8 @@ struct GatherStep;
 template <>
 struct GatherStep<false> {
   uint4 s;
-  __device__ __forceinline__ void load(const uint4 *__restrict__ data, const float4 *, size_t unit) {
-    s = data[unit];
+  __device__ __forceinline__ void load(const uint4 *__restrict__ data, const float4 *, int lane) {
+    s = data[lane];
   }
   __device__ __forceinline__ void apply(const float *tab, float *acc) const { gather_step(tab, s, acc); }
 };
@@ -1194,10 +1194,10 @@ struct GatherStep<true> {
   uint4 s;
   float4 w0, w1;
   __device__ __forceinline__ void load(const uint4 *__restrict__ data,
-                                       const float4 *__restrict__ wdata, size_t unit) {
-    s = data[unit];
-    w0 = wdata[2 * unit];
-    w1 = wdata[2 * unit + 1];
+                                       const float4 *__restrict__ wdata, int lane) {
+    s = data[lane];
+    w0 = wdata[2 * lane];
+    w1 = wdata[2 * lane + 1];
   }
   __device__ __forceinline__ void apply(const float *tab, float *acc) const {
     gather_step_w(tab, s, w0, w1, acc);
@@ -1252,8 +1252,8 @@ __global__ __launch_bounds__(kGatherThreads) void gather_prepared_kernel(
       steps[q] = 0;
       offs[q] = 0;
       if (bl < bpc && h < ntiles) {                   // uniform over the wave: scalar registers
-        steps[q] = dsc[2 * bl + 1];
-        offs[q] = dsc[2 * bl];
+        steps[q] = __builtin_amdgcn_readfirstlane(dsc[2 * bl + 1]);
+        offs[q] = __builtin_amdgcn_readfirstlane(dsc[2 * bl]);
       }
     }
   };
@@ -1288,12 +1288,16 @@ __global__ __launch_bounds__(kGatherThreads) void gather_prepared_kernel(
     // descriptors are asked for while the tile is still on its way into LDS.
     constexpr int kSide = WEIGHTED ? 2 : kMaxBlocksPerWave;
     GatherStep<WEIGHTED> bufX[kSide], bufY[kSide];
+    uint32_t last[kMaxBlocksPerWave];                 // a block's last step (0 for a block without any)
+#pragma unroll
+    for (int q = 0; q < kMaxBlocksPerWave; ++q)
+      last[q] = __builtin_amdgcn_readfirstlane(steps[q] > 0 ? steps[q] - 1 : 0u);
     auto fetch = [&](GatherStep<WEIGHTED> (&dst)[kSide], int q0, uint32_t turn) {
 #pragma unroll
       for (int j = 0; j < kSide; ++j) {
-        const uint32_t n = steps[q0 + j];
-        const uint32_t k = min(turn, n > 0 ? n - 1 : 0u);                   // scalar
-        dst[j].load(data, wdata, (size_t) offs[q0 + j] + (size_t) k * kWave + lane);
+        const uint32_t k = min(turn, last[q0 + j]);                         // scalar
+        // a scalar base and the lane as the only vector part: no address arithmetic per load
+        dst[j].load(data + ((size_t) offs[q0 + j] + (size_t) k * kWave), wdata + 2 * ((size_t) offs[q0 + j] + (size_t) k * kWave), lane);
       }
     };
     fetch(bufX, 0, 0);

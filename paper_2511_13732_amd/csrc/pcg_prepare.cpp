@@ -113,15 +113,12 @@ void improve_schedule(std::vector<uint16_t> &out, int n, uint16_t pad_base) {
   }
 }
 
-// Order in which a half-wave (32 lanes, one group each) reads its lists, chosen so that the 32
-// addresses of a time slot fall into different LDS banks wherever that is possible.  lists[l]
-// holds lane l's tile-local slots; every lane gets exactly n entries back, its own slots plus
-// padding slots pad_base + bank.  Greedy, one time slot after the other: lanes with the most
-// entries left choose first, each takes an entry whose bank is still free in this slot
-// (preferring the bank with the most entries still to place); a lane that finds none waits if
-// it has slots to spare, and otherwise takes the least crowded bank.
-void schedule_half_wave(std::vector<uint16_t> (&lists)[32], int n, uint16_t pad_base,
-                        std::vector<uint16_t> &out /* [n][32] */) {
+// Greedy schedule, one time slot after the other: lanes with the most entries left choose first,
+// each takes an entry whose bank is still free in this slot (preferring the bank with the most
+// entries still to place); a lane that finds none waits if it has slots to spare, and otherwise
+// takes the least crowded bank.
+void schedule_greedy(std::vector<uint16_t> (&lists)[32], int n, uint16_t pad_base,
+                     std::vector<uint16_t> &out /* [n][32] */) {
   int bank_left[kBanks] = {0};
   for (auto &l : lists)
     for (uint16_t s : l) ++bank_left[s % kBanks];
@@ -167,6 +164,222 @@ void schedule_half_wave(std::vector<uint16_t> (&lists)[32], int n, uint16_t pad_
       out[(size_t) t * 32 + l] = (uint16_t) (pad_base + b);
     }
   }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Schedule by edge colouring.  Lanes and banks are the two sides of a bipartite multigraph, an
+// entry is an edge, a time slot is a colour: a colouring in which no two edges at a node share
+// a colour is a schedule without conflicts, and one with as many colours as the largest degree
+// always exists (Koenig).  A bank that holds more entries than there are slots, N_b > n, must
+// double up somewhere; with E = max_b (N_b - n) slots in which a bank may be read twice and
+// n - E in which it may not, every bank fits, and E extra passes is the least any schedule of
+// this half-wave can cost.  The entries that go into the E double slots are chosen by a flow
+// (lane <= E of them, bank <= 2 E, and enough of them that what stays behind has no degree above
+// n - E); both parts are then coloured by alternating paths.
+// ---------------------------------------------------------------------------------------------
+
+struct SchedEdge {
+  int lane, bank;
+  uint16_t slot;
+  int node;        // right-hand node of the colouring the edge takes part in
+  int colour;
+};
+
+// Proper colouring of the edges listed in `ids` with colours 0 .. nc-1; every node has at most
+// nc of them.  atL[lane * nc + c] / atR[node * nc + c] hold the edge that has colour c there.
+void colour_by_alternating_paths(std::vector<SchedEdge> &edges, const std::vector<int> &ids, int nc,
+                                 int nright, std::vector<int> &atL, std::vector<int> &atR) {
+  atL.assign((size_t) 32 * nc, -1);
+  atR.assign((size_t) nright * nc, -1);
+  std::vector<int> path;
+  for (int id : ids) {
+    SchedEdge &e = edges[id];
+    int a = 0, b = 0;                                 // a free at the lane, b free at the node
+    while (atL[(size_t) e.lane * nc + a] >= 0) ++a;
+    while (atR[(size_t) e.node * nc + b] >= 0) ++b;
+    if (atR[(size_t) e.node * nc + a] >= 0) {
+      // a is taken at the node: flip the path of colours a, b, a, ... that starts there.  It
+      // cannot reach the lane (it would arrive there through colour a, which is free at the
+      // lane), so afterwards a is free at both ends.
+      path.clear();
+      int cur = atR[(size_t) e.node * nc + a];
+      bool from_right = true;                         // the path leaves a right-hand node next
+      int want = a;
+      while (cur >= 0) {
+        path.push_back(cur);
+        want = want == a ? b : a;
+        const SchedEdge &pe = edges[cur];
+        cur = from_right ? atL[(size_t) pe.lane * nc + want] : atR[(size_t) pe.node * nc + want];
+        from_right = !from_right;
+      }
+      for (int pid : path) {
+        const SchedEdge &pe = edges[pid];
+        atL[(size_t) pe.lane * nc + pe.colour] = -1;
+        atR[(size_t) pe.node * nc + pe.colour] = -1;
+      }
+      for (int pid : path) {
+        SchedEdge &pe = edges[pid];
+        pe.colour = pe.colour == a ? b : a;
+        atL[(size_t) pe.lane * nc + pe.colour] = pid;
+        atR[(size_t) pe.node * nc + pe.colour] = pid;
+      }
+    }
+    e.colour = a;
+    atL[(size_t) e.lane * nc + a] = id;
+    atR[(size_t) e.node * nc + a] = id;
+  }
+}
+
+// Small maximum flow (augmenting paths by depth-first search; capacities are a few tens).
+struct Flow {
+  struct Arc { int to, cap; };
+  std::vector<Arc> arcs;
+  std::vector<std::vector<int>> adj;
+  std::vector<char> seen;
+  explicit Flow(int nodes) : adj(nodes), seen(nodes) {}
+  int add(int u, int v, int cap) {
+    adj[u].push_back((int) arcs.size()); arcs.push_back({v, cap});
+    adj[v].push_back((int) arcs.size()); arcs.push_back({u, 0});
+    return (int) arcs.size() - 2;
+  }
+  int push(int u, int t, int f) {
+    if (u == t) return f;
+    seen[u] = 1;
+    for (int id : adj[u]) {
+      Arc &a = arcs[id];
+      if (a.cap <= 0 || seen[a.to]) continue;
+      const int got = push(a.to, t, std::min(f, a.cap));
+      if (got > 0) { a.cap -= got; arcs[id ^ 1].cap += got; return got; }
+    }
+    return 0;
+  }
+  int run(int s, int t) {
+    int total = 0;
+    while (true) {
+      std::fill(seen.begin(), seen.end(), 0);
+      const int got = push(s, t, 1 << 20);
+      if (got == 0) return total;
+      total += got;
+    }
+  }
+};
+
+// A schedule with E double slots; false when the entries cannot be split that way.
+bool schedule_with_double_slots(const std::vector<uint16_t> (&lists)[32], int n, int E,
+                                uint16_t pad_base, std::vector<uint16_t> &out /* [n][32] */) {
+  std::vector<SchedEdge> edges;
+  int deg_l[32] = {0}, deg_b[kBanks] = {0};
+  for (int l = 0; l < 32; ++l)
+    for (uint16_t s : lists[l]) {
+      edges.push_back({l, s % kBanks, s, 0, -1});
+      ++deg_l[l];
+      ++deg_b[s % kBanks];
+    }
+  if (E > n) return false;
+  const int single = n - E;                          // slots in which a bank is read once
+
+  // which entries go into the double slots: a flow with lower and upper bounds
+  std::vector<char> doubled(edges.size(), 0);
+  if (E > 0) {
+    // nodes: 0 source, 1..32 lanes, 33..64 banks, 65 sink, 66 / 67 the super source and sink that
+    // carry the lower bounds
+    Flow f(68);
+    const int S = 0, T = 65, SS = 66, TT = 67;
+    int excess[68] = {0};
+    auto bounded = [&](int u, int v, int lo, int hi) {
+      excess[v] += lo;
+      excess[u] -= lo;
+      return f.add(u, v, hi - lo);
+    };
+    int pair_arc[32][kBanks];
+    int mult[32][kBanks] = {{0}};
+    for (const SchedEdge &e : edges) ++mult[e.lane][e.bank];
+    for (int l = 0; l < 32; ++l) {
+      const int lo = std::max(0, deg_l[l] - single), hi = std::min(E, deg_l[l]);
+      if (lo > hi) return false;
+      bounded(S, 1 + l, lo, hi);
+      for (int b = 0; b < kBanks; ++b)
+        pair_arc[l][b] = mult[l][b] > 0 ? f.add(1 + l, 33 + b, mult[l][b]) : -1;
+    }
+    for (int b = 0; b < kBanks; ++b) {
+      const int lo = std::max(0, deg_b[b] - single), hi = std::min(2 * E, deg_b[b]);
+      if (lo > hi) return false;
+      bounded(33 + b, T, lo, hi);
+    }
+    f.add(T, S, 1 << 20);
+    int demand = 0;
+    for (int v = 0; v < 66; ++v) {
+      if (excess[v] > 0) { f.add(SS, v, excess[v]); demand += excess[v]; }
+      if (excess[v] < 0) f.add(v, TT, -excess[v]);
+    }
+    if (f.run(SS, TT) != demand) return false;
+    int take[32][kBanks];
+    for (int l = 0; l < 32; ++l)
+      for (int b = 0; b < kBanks; ++b)
+        take[l][b] = pair_arc[l][b] >= 0 ? mult[l][b] - f.arcs[pair_arc[l][b]].cap : 0;
+    for (size_t i = 0; i < edges.size(); ++i)
+      if (take[edges[i].lane][edges[i].bank] > 0) {
+        --take[edges[i].lane][edges[i].bank];
+        doubled[i] = 1;
+      }
+  }
+
+  // colour the two parts; in the double slots a bank is two nodes with at most E edges each
+  std::vector<int> ids_single, ids_double, atL, atR;
+  int seen_b[kBanks] = {0};
+  for (size_t i = 0; i < edges.size(); ++i) {
+    if (doubled[i]) {
+      edges[i].node = edges[i].bank + (seen_b[edges[i].bank]++ < E ? 0 : kBanks);
+      ids_double.push_back((int) i);
+    } else {
+      edges[i].node = edges[i].bank;
+      ids_single.push_back((int) i);
+    }
+  }
+  out.assign((size_t) n * 32, 0xFFFF);
+  if (E > 0) {
+    colour_by_alternating_paths(edges, ids_double, E, 2 * kBanks, atL, atR);
+    for (int id : ids_double) out[(size_t) edges[id].colour * 32 + edges[id].lane] = edges[id].slot;
+  }
+  if (single > 0) {
+    colour_by_alternating_paths(edges, ids_single, single, kBanks, atL, atR);
+    for (int id : ids_single) out[(size_t) (E + edges[id].colour) * 32 + edges[id].lane] = edges[id].slot;
+  } else if (!ids_single.empty()) {
+    return false;
+  }
+  // padding: the emptiest bank of the slot
+  for (int t = 0; t < n; ++t) {
+    int use[kBanks] = {0};
+    for (int l = 0; l < 32; ++l)
+      if (out[(size_t) t * 32 + l] != 0xFFFF) ++use[out[(size_t) t * 32 + l] % kBanks];
+    for (int l = 0; l < 32; ++l) {
+      if (out[(size_t) t * 32 + l] != 0xFFFF) continue;
+      int b = 0;
+      for (int c = 1; c < kBanks; ++c)
+        if (use[c] < use[b]) b = c;
+      ++use[b];
+      out[(size_t) t * 32 + l] = (uint16_t) (pad_base + b);
+    }
+  }
+  return true;
+}
+
+// Order in which a half-wave (32 lanes, one group each) reads its lists, chosen so that the 32
+// addresses of a time slot fall into different LDS banks wherever that is possible.  lists[l]
+// holds lane l's tile-local slots; every lane gets exactly n entries back, its own slots plus
+// padding slots pad_base + bank.  The colouring gives the schedule with the fewest extra passes
+// this half-wave can have; should it not be found, the greedy schedule with the local search on
+// top stands in.
+void schedule_half_wave(std::vector<uint16_t> (&lists)[32], int n, uint16_t pad_base,
+                        std::vector<uint16_t> &out /* [n][32] */) {
+  int deg_b[kBanks] = {0}, least = 0;
+  for (const auto &l : lists)
+    for (uint16_t s : l) least = std::max(least, ++deg_b[s % kBanks] - n);
+  // the lanes put at most one entry each into a double slot, so very uneven banks can need a
+  // few more of them than the fullest bank alone asks for
+  for (int E = least; E <= std::min(n, least + 4); ++E)
+    if (schedule_with_double_slots(lists, n, E, pad_base, out)) return;
+  schedule_greedy(lists, n, pad_base, out);
   improve_schedule(out, n, pad_base);
 }
 

@@ -11,7 +11,7 @@ SOURCES = ["pcg_kernels.hip", "pcg_asg.hip", "pcg_api.cpp", "pcg_prepare.cpp"]
 HEADERS = ["pcg_kernels.h", "pcg_device.h", "pcg_layout.h", os.path.join("..", "..", "include", "pcg.h")]
 
 HIPCC_FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-pthread",
     # keep hipcc from forming packed-fp32 instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     # no implicit fused multiply-adds: the kernels spell out fmaf() where one is wanted, and

@@ -1,7 +1,9 @@
 // Host-side construction of the prepared membership layout (see pcg_prepared in pcg.h).
 #include <algorithm>
+#include <atomic>
 #include <cstring>
 #include <numeric>
+#include <thread>
 #include <utility>
 #include <vector>
 
@@ -521,11 +523,16 @@ int build(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members, 
   float *wdata = weighted ? reinterpret_cast<float *>(blob + desc_bytes + perm_bytes + data_bytes)
                           : nullptr;
   const uint16_t pad_base = (uint16_t) sh.tile_len;   // table[tile_len .. tile_len + kBanks) is zero
-  std::vector<uint16_t> lists[32], sched;
-  std::vector<std::pair<uint16_t, float>> share[32];   // (slot, weight) of each lane's list, by slot
-  for (int32_t c = 0; c < sh.nchunks; ++c) {
-    const int32_t g0 = c * sh.chunk_groups;
-    for (int32_t bl = 0; bl < BPC; ++bl) {
+  // Blocks are independent of each other and write disjoint parts of the blob: they are handed
+  // out to a few threads, one block at a time (the result does not depend on who takes which).
+  const int64_t nblocks = (int64_t) sh.nchunks * BPC;
+  std::atomic<int64_t> next_block{0};
+  auto worker = [&]() {
+    std::vector<uint16_t> lists[32], sched;
+    std::vector<std::pair<uint16_t, float>> share[32];   // (slot, weight) of each lane's list, by slot
+    for (int64_t w = next_block.fetch_add(1); w < nblocks; w = next_block.fetch_add(1)) {
+      const int32_t c = (int32_t) (w / BPC), bl = (int32_t) (w % BPC);
+      const int32_t g0 = c * sh.chunk_groups;
       for (int32_t h = 0; h < T; ++h) {
         const uint32_t *d = &desc[(((size_t) c * T + h) * BPC + bl) * 2];
         const size_t off = d[0];
@@ -567,7 +574,13 @@ int build(int32_t V, int32_t G, const int32_t *row_ptr, const int32_t *members, 
         }
       }
     }
-  }
+  };
+  const unsigned hw = std::thread::hardware_concurrency();
+  const int nthreads = (int) std::max<int64_t>(1, std::min<int64_t>({(int64_t) (hw ? hw : 1), 8, nblocks / 4}));
+  std::vector<std::thread> pool;
+  for (int i = 1; i < nthreads; ++i) pool.emplace_back(worker);
+  worker();
+  for (auto &t : pool) t.join();
   return PCG_OK;
 }
 

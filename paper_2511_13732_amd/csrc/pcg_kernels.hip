@@ -414,7 +414,7 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_delta_kernel(AcceptArgs
         const float ed = exp_rel(xd[k], sd.M, c, c_lo);
         diff = __dsub_rn(diff, __dmul_rn((double) ed, izd));
       }
-      v[k] = (float) diff / m[k];
+      v[k] = (float) diff * __builtin_amdgcn_rcpf(m[k]);   // N(t) is a small integer: 1 ulp, a tenth of a division's cost
     }
   };
   const int32_t stride = nsplit * kAcceptTokens;
@@ -831,7 +831,7 @@ __global__ __launch_bounds__(kTableThreads) void weights_kernel(
   load8_mult<VEC>(mult, t, V, m);
 #pragma unroll
   for (int k = 0; k < 8; ++k)
-    v[k] = (float) ((double) exp_rel(x[k], s.M, c_hi, c_lo) * iz) / m[k];
+    v[k] = (float) ((double) exp_rel(x[k], s.M, c_hi, c_lo) * iz) * __builtin_amdgcn_rcpf(m[k]);
   store8<VEC>(table + (int64_t) local * V, t, V, v);
 }
 

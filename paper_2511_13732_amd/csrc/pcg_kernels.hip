@@ -1125,8 +1125,57 @@ __device__ void finalize_sequence(const FinalizeArgs &fa, int32_t V, int32_t G, 
   const int32_t gs = pg.index < 0 ? 0 : pg.index;
 
   const int32_t beg = row_ptr[gs], end = row_ptr[gs + 1];
-  CdfPick pt = block_inverse_cdf<NT>(
-      end - beg, [&](int32_t j) { return weight(beg + j); }, (double) u.tok);
+  CdfPick pt;
+  constexpr int kTokRounds = 4;          // entries per lane the one-wave path keeps in registers
+  if (end - beg <= kTokRounds * kWave) {
+    // The token inside the group (Eq. 10) by the first wave alone: every entry's mass is loaded
+    // once, all loads in flight together, and kept in registers for the total and for the scan.
+    if (threadIdx.x < kWave) {
+      const int lane = threadIdx.x;
+      const int32_t n = end - beg;
+      double w[kTokRounds];
+#pragma unroll
+      for (int c = 0; c < kTokRounds; ++c) {
+        const int32_t j = c * kWave + lane;
+        w[c] = j < n ? weight(beg + j) : 0.0;
+        if (!(w[c] > 0.0)) w[c] = 0.0;
+      }
+      double total = 0.0;
+#pragma unroll
+      for (int c = 0; c < kTokRounds; ++c) total += wave_sum(w[c]);      // ascending, 64 at a time
+      pt.index = -1; pt.total = total; pt.lo = pt.hi = 0.0;
+      const double goal = (double) u.tok * total;
+      double base = 0.0, last_v = 0.0;
+      int32_t last = -1;
+      bool done = false;
+#pragma unroll
+      for (int c = 0; c < kTokRounds; ++c) {
+        if (done || c * kWave >= n) continue;                            // uniform
+        const double inc = wave_scan(w[c]);
+        const unsigned long long pos = __ballot(w[c] > 0.0);
+        if (pos) {
+          const int hl = 63 - __clzll((long long) pos);
+          last = c * kWave + hl;
+          last_v = read_lane(w[c], hl);
+        }
+        const unsigned long long hit = __ballot(w[c] > 0.0 && base + inc > goal);
+        if (hit) {
+          const int l = __ffsll((long long) hit) - 1;
+          pt.index = c * kWave + l;
+          pt.hi = base + read_lane(inc, l);
+          pt.lo = pt.hi - read_lane(w[c], l);
+          done = true;
+        } else {
+          base += read_lane(inc, kWave - 1);
+        }
+      }
+      if (!done && last >= 0) {          // rounding at the top end: the last entry that has mass
+        pt.index = last; pt.hi = total; pt.lo = total - last_v;
+      }
+    }
+  } else {
+    pt = block_inverse_cdf<NT>(end - beg, [&](int32_t j) { return weight(beg + j); }, (double) u.tok);
+  }
   if (threadIdx.x == 0) {
     fa.out_groups[(int64_t) b * (K + 1) + istar] = gs;
     fa.out_tokens[(int64_t) b * (K + 1) + istar] = pt.index < 0 ? -1 : members[beg + pt.index];

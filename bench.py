@@ -35,7 +35,7 @@ LDS_PEAK_GBS = 256 * 128 * 2.4     # 256 CUs x 128 B/clk x 2.4 GHz = 78 643 GB/s
 # 262 144, factor 1.000).  Source: profiles/pcg_C4_hbm_traffic.md.
 MEASURED_TRAFFIC_BYTES = {
     "row_stats@C4": int((69664.0 * 2.000 + 544.3) * 1024),
-    "gather@C4": int((25861.1 * 2.000 + 16386.0) * 1024),
+    "gather@C4": int((25868.2 * 2.000 + 16386.0) * 1024),
 }
 
 

@@ -332,7 +332,7 @@ def test_recipe_full_size(name, steps):
     og, dg = oracle_groups(cfg.V, rp, mem), device_groups(cfg.V, rp, mem)
     print(f"{name}: G={og.G} nnz={og.nnz} mean size {og.nnz / og.G:.1f}", flush=True)
     total = Tally()
-    for step in range(steps):
+    for step in range(_steps(cfg, steps)):
         tgt, dft, ptok, pgrp = W.step_inputs(cfg, og.row_ptr, og.members, step)
         gpu, ref, _, diag = run_both(cfg.V, rp, mem, tgt, dft, ptok, pgrp,
                                      temperature=cfg.temperature, seed=0, offset=step, dg=dg, og=og)

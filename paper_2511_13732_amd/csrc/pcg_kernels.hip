@@ -1274,23 +1274,19 @@ __global__ __launch_bounds__(kGatherThreads) void gather_prepared_kernel(
   const float *src = table + (int64_t) r * V;
 
   float acc[kMaxAcc];
-  uint16_t where[kMaxAcc];     // group (inside the chunk) behind each running sum, needed only
-                               // when the sums are put back into group order: loaded now where
-                               // registers allow, after the tiles otherwise
-  auto load_where = [&]() {
+  uint16_t where[kMaxAcc];     // group (inside the chunk) behind each running sum; loaded now,
+                               // needed only when the sums are put back into group order
 #pragma unroll
-    for (int q = 0; q < kMaxBlocksPerWave; ++q) {
-      const int bl = block_of(q, wave);
+  for (int q = 0; q < kMaxBlocksPerWave; ++q) {
+    const int bl = block_of(q, wave);
 #pragma unroll
-      for (int rr = 0; rr < kLaneGroups; ++rr)
-        where[q * kLaneGroups + rr] =
-            bl < bpc ? perm[((size_t) chunk * bpc + bl) * kBlockGroups + rr * kWave + lane]
-                     : (uint16_t) 0xFFFFu;
+    for (int rr = 0; rr < kLaneGroups; ++rr) {
+      acc[q * kLaneGroups + rr] = 0.f;
+      where[q * kLaneGroups + rr] =
+          bl < bpc ? perm[((size_t) chunk * bpc + bl) * kBlockGroups + rr * kWave + lane]
+                   : (uint16_t) 0xFFFFu;
     }
-  };
-#pragma unroll
-  for (int j = 0; j < kMaxAcc; ++j) acc[j] = 0.f;
-  if constexpr (!WEIGHTED) load_where();
+  }
 
   // descriptors (first unit and number of steps) of this wave's blocks in tile h
   auto load_desc = [&](int h, uint32_t (&steps)[kMaxBlocksPerWave], uint32_t (&offs)[kMaxBlocksPerWave]) {
@@ -1377,7 +1373,6 @@ __global__ __launch_bounds__(kGatherThreads) void gather_prepared_kernel(
   }
 
   // back into group order through LDS, then coalesced stores
-  if constexpr (WEIGHTED) load_where();
   __syncthreads();
 #pragma unroll
   for (int j = 0; j < kMaxAcc; ++j)

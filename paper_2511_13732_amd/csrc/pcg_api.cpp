@@ -136,6 +136,7 @@ size_t pcg_verify_workspace_bytes(int32_t V, int32_t G, int32_t B, int32_t K) {
   if (V < 1 || G < 1 || B < 0 || K < 1) return 0;
   const size_t rows = (size_t) B * (2 * (size_t) K + 1);
   return align_up(rows * stats_nparts(V) * sizeof(StatPart)) + align_up(rows * sizeof(RowStat)) +
+         align_up((size_t) B * K * sizeof(Probe)) +
          align_up((size_t) B * V * sizeof(float)) + align_up((size_t) B * G * sizeof(float)) +
          align_up((size_t) B * ((G + kChunkStep - 1) / kChunkStep) * sizeof(double)) + kAlign;
 }
@@ -244,8 +245,24 @@ int check_verify_args(const pcg_groups *groups, const void *target_logits, const
   return PCG_OK;
 }
 
+ProbeArgs probe_args(const pcg_groups *groups, int32_t K, const Factors &f,
+                     const int32_t *prop_groups, Probe *out) {
+  ProbeArgs pa;
+  pa.row_ptr = groups->row_ptr;
+  pa.members = groups->members;
+  pa.mult = groups->mult;
+  pa.prop_groups = prop_groups;
+  pa.weights = groups->weights;
+  pa.K = K;
+  pa.G = groups->G;
+  pa.c_lo = f.c_lo;
+  pa.out = out;
+  return pa;
+}
+
 AcceptArgs accept_args(const pcg_groups *groups, const RowSet &rs, int32_t K, const Factors &f,
-                       const StatPart *parts, RowStat *rowstat, const int32_t *prop_tokens,
+                       const StatPart *parts, const Probe *probes, RowStat *rowstat,
+                       const int32_t *prop_tokens,
                        const int32_t *prop_groups, uint64_t seed, uint64_t offset,
                        int32_t *accept_len, int32_t *out_tokens, int32_t *out_groups,
                        pcg_diag *diag) {
@@ -258,6 +275,7 @@ AcceptArgs accept_args(const pcg_groups *groups, const RowSet &rs, int32_t K, co
   aa.c = f.c;
   aa.cd = f.cd;
   aa.parts = parts;
+  aa.probes = probes;
   aa.rowstat = rowstat;
   aa.row_ptr = groups->row_ptr;
   aa.members = groups->members;
@@ -304,6 +322,8 @@ int pcg_verify(const pcg_groups *groups, const void *target_logits, const void *
   ws += align_up((size_t) rows * nparts * sizeof(StatPart));
   RowStat *rowstat = (RowStat *) ws;
   ws += align_up((size_t) rows * sizeof(RowStat));
+  Probe *probes = (Probe *) ws;
+  ws += align_up((size_t) B * K * sizeof(Probe));
   float *table = (float *) ws;
   ws += align_up((size_t) B * V * sizeof(float));
   float *R = (float *) ws;
@@ -311,8 +331,9 @@ int pcg_verify(const pcg_groups *groups, const void *target_logits, const void *
   double *csum = (double *) ws;
 
   const Factors f = factors(temperature);
-  const AcceptArgs aa = accept_args(groups, rs, K, f, parts, rowstat, prop_tokens, prop_groups, seed,
-                                    offset, accept_len, out_tokens, out_groups, diag);
+  const AcceptArgs aa = accept_args(groups, rs, K, f, parts, probes, rowstat, prop_tokens, prop_groups,
+                                    seed, offset, accept_len, out_tokens, out_groups, diag);
+  const ProbeArgs pa = probe_args(groups, K, f, prop_groups, probes);
   FinalizeArgs fa;
   fa.rs = rs;
   fa.K = K;
@@ -334,7 +355,7 @@ int pcg_verify(const pcg_groups *groups, const void *target_logits, const void *
   hipError_t e;
   tm.begin(kStageStats);
   // streaming pass: only the rejected position's two rows (2 of 2K+1) are read again
-  if ((e = launch_row_stats(rs, bf16, V, rows, f.c, true, parts, stream)) != hipSuccess) return hip_fail(e);
+  if ((e = launch_row_stats(rs, bf16, V, rows, f.c, true, parts, stream, &pa)) != hipSuccess) return hip_fail(e);
   tm.end(kStageStats);
   tm.begin(kStageAccept);
   if ((e = launch_accept_delta(aa, bf16, B, f.c_lo, table, stream)) != hipSuccess)
@@ -418,7 +439,8 @@ int pcg_propose(const pcg_groups *groups, const void *draft_logits, pcg_dtype dt
 size_t pcg_verify_thinning_workspace_bytes(int32_t V, int32_t B, int32_t K) {
   if (V < 1 || B < 0 || K < 1) return 0;
   const size_t rows = (size_t) B * (2 * (size_t) K + 1);
-  return align_up(rows * stats_nparts(V) * sizeof(StatPart)) + align_up(rows * sizeof(RowStat)) + kAlign;
+  return align_up(rows * stats_nparts(V) * sizeof(StatPart)) + align_up(rows * sizeof(RowStat)) +
+         align_up((size_t) B * K * sizeof(Probe)) + kAlign;
 }
 
 int pcg_verify_thinning(const pcg_groups *groups, const void *target_logits,
@@ -449,14 +471,17 @@ int pcg_verify_thinning(const pcg_groups *groups, const void *target_logits,
   StatPart *parts = (StatPart *) ws;
   ws += align_up((size_t) rows * nparts * sizeof(StatPart));
   RowStat *rowstat = (RowStat *) ws;
+  ws += align_up((size_t) rows * sizeof(RowStat));
+  Probe *probes = (Probe *) ws;
   const Factors f = factors(temperature);
-  const AcceptArgs aa = accept_args(groups, rs, K, f, parts, rowstat, prop_tokens, prop_groups, seed,
-                                    offset, accept_len, out_tokens, out_groups, diag);
+  const AcceptArgs aa = accept_args(groups, rs, K, f, parts, probes, rowstat, prop_tokens, prop_groups,
+                                    seed, offset, accept_len, out_tokens, out_groups, diag);
+  const ProbeArgs pa = probe_args(groups, K, f, prop_groups, probes);
   StageTimer tm(stream);
   hipError_t e;
   tm.begin(kStageStats);
   // cached pass: every trial is a chain of small reads into the same rows
-  if ((e = launch_row_stats(rs, bf16, V, rows, f.c, false, parts, stream)) != hipSuccess) return hip_fail(e);
+  if ((e = launch_row_stats(rs, bf16, V, rows, f.c, false, parts, stream, &pa)) != hipSuccess) return hip_fail(e);
   tm.end(kStageStats);
   tm.begin(kStageThin);
   if ((e = launch_accept_thin(aa, bf16, B, groups->tok_ptr, groups->tok_groups,

@@ -261,12 +261,31 @@ struct FinalizeArgs {
 };
 
 // Everything a sequence's accept scan needs (pcg_verify, pcg_verify_thinning).
+// T_i[g] and D_i[g] of one proposed group (Eq. 5), up to the rows' normalisations: the sums are
+// relative to the group's own largest logits, so they can be formed before any row statistic is
+// known.  The statistics pass forms them on the side; the accept scan only normalises them.
+struct Probe {
+  double Tp, Dp;           // sums of 2^((x - ref) c) w over the group's entries, target / draft row
+  float Tref, Dref;        // those largest logits
+  int32_t bad;             // the proposed group id is out of range
+  int32_t pad;
+};
+
+struct ProbeArgs {
+  const int32_t *row_ptr, *members, *mult, *prop_groups;
+  const float *weights;    // general weights per CSR entry, or NULL for the equal split
+  int32_t K, G;
+  float c_lo;              // low part of log2(e) / temperature (the high part is row_stats' c)
+  Probe *out;              // [B * K]; NULL: no probes in this launch
+};
+
 struct AcceptArgs {
   RowSet rs;
   int32_t V, G, K, nparts;
   float c;                 // fp32(log2(e) / temperature), as used by row_stats
   double cd;               // log2(e) / temperature
   const StatPart *parts;
+  const Probe *probes;     // [B * K], left by the statistics pass
   RowStat *rowstat;
   const int32_t *row_ptr, *members, *mult, *prop_tokens, *prop_groups;
   const float *weights;    // general weights per CSR entry, or NULL for the equal split

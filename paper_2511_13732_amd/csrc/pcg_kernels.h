@@ -13,8 +13,10 @@ namespace pcg {
 int32_t stats_nparts(int32_t V);
 
 // streaming: read the logits with nontemporal loads (faster pass, nothing left in the caches)
+// probes: also form the probe of every target row that has a proposal (NULL: none)
 hipError_t launch_row_stats(const RowSet &rs, bool bf16, int32_t V, int64_t nrows, float c,
-                            bool streaming, StatPart *parts, hipStream_t stream);
+                            bool streaming, StatPart *parts, hipStream_t stream,
+                            const ProbeArgs *probes = nullptr);
 
 int32_t accept_nsplit(int32_t V, int32_t B);
 

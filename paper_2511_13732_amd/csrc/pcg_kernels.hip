@@ -39,16 +39,89 @@ __device__ __forceinline__ u32x4 load16(const void *p) {
   else return *reinterpret_cast<const u32x4 *>(p);
 }
 
+// exp((x - M) / temperature) for one element, argument in two pieces so that its error stays
+// relative to the result: (x - M) * (c_hi + c_lo) with c_hi + c_lo = log2(e) / temperature.
+__device__ __forceinline__ float exp_rel(float x, float M, float c_hi, float c_lo) {
+  const float d = x - M;
+  // a -inf logit has no mass; (-inf) * c_lo would turn the sum into inf - inf otherwise
+  return d == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(fmaf(d, c_hi, d * c_lo));
+}
+
+// The probe of target row `row` = (b, i), i < K, by one wave: T_i[g] and D_i[g] of the proposed
+// group g (Eq. 5), each relative to the group's own largest logit.  A chain of four dependent
+// loads (proposal -> group -> members -> logits) that needs no row statistic, which is why it
+// rides along with the statistics pass instead of waiting for it.
+template <bool BF16>
+__device__ void probe_row(const RowSet &rs, const ProbeArgs &pa, int64_t row, float c, int lane) {
+  int64_t b;
+  int32_t i;
+  split_row(row, rs.npos0, rs.inv_npos0, b, i);
+  const int32_t K = pa.K;
+  if (i >= K) return;                                   // the bonus row has no proposal
+  const int32_t g = pa.prop_groups[b * K + i];
+  const bool ok = g >= 0 && g < pa.G;
+  double at = 0.0, ad = 0.0;
+  float mt = -INFINITY, md = -INFINITY;
+  if (ok) {
+    const void *trow = row_base(rs, row, BF16);
+    const void *drow = row_base(rs, rs.nrows0 + b * K + i, BF16);
+    const int32_t beg = pa.row_ptr[g], end = pa.row_ptr[g + 1];
+    // the first 64 members stay in registers; longer groups take a second trip
+    const bool has = beg + lane < end;
+    const int32_t t0 = has ? pa.members[beg + lane] : 0;
+    const float lt0 = has ? logit_at<BF16>(trow, t0) : -INFINITY;
+    const float ld0 = has ? logit_at<BF16>(drow, t0) : -INFINITY;
+    // the entry's share of its token: 1 / N(t) (Eq. 3), or the caller's weight (Eq. 2)
+    const float *wts = pa.weights;
+    const float m0 = has && !wts ? (float) pa.mult[t0] : 1.f;
+    const float w0 = has && wts ? wts[beg + lane] : 1.f;
+    mt = lt0;
+    md = ld0;
+    for (int32_t j = beg + lane + kWave; j < end; j += kWave) {
+      const int32_t t = pa.members[j];
+      mt = fmaxf(mt, logit_at<BF16>(trow, t));
+      md = fmaxf(md, logit_at<BF16>(drow, t));
+    }
+    mt = wave_max(mt);
+    md = wave_max(md);
+    // masses in the kernels' precision: fp32 exponential and division, fp64 sum
+    if (lt0 > -INFINITY) at = (double) (exp_rel(lt0, mt, c, pa.c_lo) * w0 / m0);
+    if (ld0 > -INFINITY) ad = (double) (exp_rel(ld0, md, c, pa.c_lo) * w0 / m0);
+    for (int32_t j = beg + lane + kWave; j < end; j += kWave) {
+      const int32_t t = pa.members[j];
+      const float m = wts ? 1.f : (float) pa.mult[t];
+      const float w = wts ? wts[j] : 1.f;
+      const float lt = logit_at<BF16>(trow, t), ld = logit_at<BF16>(drow, t);
+      if (lt > -INFINITY) at += (double) (exp_rel(lt, mt, c, pa.c_lo) * w / m);
+      if (ld > -INFINITY) ad += (double) (exp_rel(ld, md, c, pa.c_lo) * w / m);
+    }
+  }
+  at = wave_sum(at);
+  ad = wave_sum(ad);
+  if (lane == 0) {
+    Probe p;
+    p.Tp = at; p.Dp = ad; p.Tref = mt; p.Dref = md; p.bad = !ok; p.pad = 0;
+    pa.out[b * K + i] = p;
+  }
+}
+
 template <bool BF16, bool VEC, bool STREAM>
 __global__ __launch_bounds__(kStatsWaves *kWave) void row_stats_kernel(RowSet rs, int32_t V,
                                                                        int32_t nparts, int64_t nrows,
-                                                                       float c, StatPart *parts) {
+                                                                       float c, StatPart *parts,
+                                                                       ProbeArgs pa) {
   const int lane = threadIdx.x & (kWave - 1);
   // everything that selects the data is wave-uniform: keep it in scalar registers
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int32_t part = blockIdx.x * kStatsWaves + wave;
   const int64_t row = (int64_t) blockIdx.z * kRowsPerGridY + blockIdx.y;
-  if (part >= nparts || row >= nrows) return;   // whole wave leaves together
+  if (row >= nrows) return;                     // whole wave leaves together
+  if (blockIdx.x * kStatsWaves >= nparts) {
+    // one workgroup past the row's parts (launched only with probes): its first wave probes
+    if (wave == 0 && row < rs.nrows0) probe_row<BF16>(rs, pa, row, c, lane);
+    return;
+  }
+  if (part >= nparts) return;
   const void *rowp = row_base(rs, row, BF16);
   const int32_t e0 = part * kPartElems;
 
@@ -142,14 +215,6 @@ __device__ __forceinline__ RowStat merge_row(const StatPart *parts, int64_t row,
   r.M = M;
   r.pad = 0.f;
   return r;
-}
-
-// exp((x - M) / temperature) for one element, argument in two pieces so that its error stays
-// relative to the result: (x - M) * (c_hi + c_lo) with c_hi + c_lo = log2(e) / temperature.
-__device__ __forceinline__ float exp_rel(float x, float M, float c_hi, float c_lo) {
-  const float d = x - M;
-  // a -inf logit has no mass; (-inf) * c_lo would turn the sum into inf - inf otherwise
-  return d == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(fmaf(d, c_hi, d * c_lo));
 }
 
 // =============================================================================================
@@ -258,63 +323,17 @@ __device__ void accept_phase(AcceptShared &sh, const AcceptArgs &a, int b, bool 
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
   constexpr int nw = kAcceptThreads / kWave;
   const int64_t B = a.rs.nrows0 / (K + 1);
-  const float c_lo = (float) (a.cd - (double) a.c);
-  // The two chains of dependent loads run side by side on different waves: the first
-  // `nprobe` waves follow proposal -> group -> members -> logits, the others merge the row
-  // statistics.  The probes sum relative to the group's own maximum, so they need no row
-  // statistic until both chains meet.
-  const int nprobe = min(K, nw / 2);
-
-  if (wave < nprobe) {
-    // T_i[g], D_i[g] of the proposed group (Eq. 5), up to the row's normalisation
-    for (int i = wave; i < K; i += nprobe) {
-      const int32_t g = a.prop_groups[(int64_t) b * K + i];
-      const bool ok = g >= 0 && g < a.G;
-      double at = 0.0, ad = 0.0;
-      float mt = -INFINITY, md = -INFINITY;
-      if (ok) {
-        const void *trow = row_base(a.rs, (int64_t) b * (K + 1) + i, BF16);
-        const void *drow = row_base(a.rs, a.rs.nrows0 + (int64_t) b * K + i, BF16);
-        const int32_t beg = a.row_ptr[g], end = a.row_ptr[g + 1];
-        // the first 64 members stay in registers; longer groups take a second trip
-        const bool has = beg + lane < end;
-        const int32_t t0 = has ? a.members[beg + lane] : 0;
-        const float lt0 = has ? logit_at<BF16>(trow, t0) : -INFINITY;
-        const float ld0 = has ? logit_at<BF16>(drow, t0) : -INFINITY;
-        // the entry's share of its token: 1 / N(t) (Eq. 3), or the caller's weight (Eq. 2)
-        const float *wts = a.weights;
-        const float m0 = has && !wts ? (float) a.mult[t0] : 1.f;
-        const float w0 = has && wts ? wts[beg + lane] : 1.f;
-        mt = lt0;
-        md = ld0;
-        for (int32_t j = beg + lane + kWave; j < end; j += kWave) {
-          const int32_t t = a.members[j];
-          mt = fmaxf(mt, logit_at<BF16>(trow, t));
-          md = fmaxf(md, logit_at<BF16>(drow, t));
-        }
-        mt = wave_max(mt);
-        md = wave_max(md);
-        // masses in the kernels' precision: fp32 exponential and division, fp64 sum
-        if (lt0 > -INFINITY) at = (double) (exp_rel(lt0, mt, a.c, c_lo) * w0 / m0);
-        if (ld0 > -INFINITY) ad = (double) (exp_rel(ld0, md, a.c, c_lo) * w0 / m0);
-        for (int32_t j = beg + lane + kWave; j < end; j += kWave) {
-          const int32_t t = a.members[j];
-          const float m = wts ? 1.f : (float) a.mult[t];
-          const float w = wts ? wts[j] : 1.f;
-          const float lt = logit_at<BF16>(trow, t), ld = logit_at<BF16>(drow, t);
-          if (lt > -INFINITY) at += (double) (exp_rel(lt, mt, a.c, c_lo) * w / m);
-          if (ld > -INFINITY) ad += (double) (exp_rel(ld, md, a.c, c_lo) * w / m);
-        }
-      }
-      at = wave_sum(at);
-      ad = wave_sum(ad);
-      if (lane == 0) {
-        sh.Tp[i] = at; sh.Dp[i] = ad; sh.Tref[i] = mt; sh.Dref[i] = md;
-        sh.bad[i] = !ok;
-        sh.pgrp[i] = g;
-        sh.ptok[i] = a.prop_tokens[(int64_t) b * K + i];
-        sh.uacc[i] = philox_uniforms(a.seed, a.offset, (uint32_t) b, (uint32_t) i).acc;
-      }
+  // The probes of the proposed groups were formed by the statistics pass; the first wave fetches
+  // them (one position per lane), the others merge the row statistics.
+  const int nprobe = 1;
+  if (wave == 0) {
+    for (int i = lane; i < K; i += kWave) {
+      const Probe p = a.probes[(int64_t) b * K + i];
+      sh.Tp[i] = p.Tp; sh.Dp[i] = p.Dp; sh.Tref[i] = p.Tref; sh.Dref[i] = p.Dref;
+      sh.bad[i] = p.bad;
+      sh.pgrp[i] = a.prop_groups[(int64_t) b * K + i];
+      sh.ptok[i] = a.prop_tokens[(int64_t) b * K + i];
+      sh.uacc[i] = philox_uniforms(a.seed, a.offset, (uint32_t) b, (uint32_t) i).acc;
     }
   } else {
     // row statistics of this sequence's 2K+1 rows, four rows per wave at a time
@@ -1422,15 +1441,20 @@ static inline bool rows_vector_aligned(const RowSet &rs, bool bf16) {
 int32_t stats_nparts(int32_t V) { return (V + kPartElems - 1) / kPartElems; }
 
 hipError_t launch_row_stats(const RowSet &rs, bool bf16, int32_t V, int64_t nrows, float c,
-                            bool streaming, StatPart *parts, hipStream_t stream) {
+                            bool streaming, StatPart *parts, hipStream_t stream,
+                            const ProbeArgs *probes) {
   const int32_t nparts = stats_nparts(V);
   if (nrows == 0) return hipSuccess;
   const unsigned gy = (unsigned) std::min<int64_t>(nrows, kRowsPerGridY);
   const unsigned gz = (unsigned) ((nrows + kRowsPerGridY - 1) / kRowsPerGridY);
-  const dim3 grid((nparts + kStatsWaves - 1) / kStatsWaves, gy, gz), block(kStatsWaves * kWave);
+  ProbeArgs pa{};
+  if (probes) pa = *probes;
+  // with probes, one more workgroup per row: it forms the row's probe
+  const dim3 grid((nparts + kStatsWaves - 1) / kStatsWaves + (probes ? 1 : 0), gy, gz),
+      block(kStatsWaves * kWave);
   const bool vec = rows_vector_aligned(rs, bf16);
   auto launch = [&](auto kernel) {
-    kernel<<<grid, block, 0, stream>>>(rs, V, nparts, nrows, c, parts);
+    kernel<<<grid, block, 0, stream>>>(rs, V, nparts, nrows, c, parts, pa);
   };
   if (bf16) {
     if (!vec) launch(row_stats_kernel<true, false, false>);

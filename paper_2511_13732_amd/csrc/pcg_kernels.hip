@@ -408,11 +408,18 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_delta_kernel(AcceptArgs
   __shared__ AcceptShared sh;
   const int b = blockIdx.x / nsplit;
   const int split = blockIdx.x % nsplit;
-  accept_phase<BF16>(sh, a, b, split == 0);
   const RowSet &rs = a.rs;
   const int32_t V = a.V, K = a.K;
   const float c = a.c;
   const int32_t *mult = a.weights ? nullptr : a.mult;   // with weights delta is q - p as it is
+  const int32_t stride = nsplit * kAcceptTokens;
+  const int32_t first = split * kAcceptTokens + threadIdx.x * kTokensPerThread;
+  // the multiplicities of this thread's first two slices do not depend on the decision row:
+  // they are asked for before the accept scan
+  float m_a[8], m_b[8];
+  if (first < V) load8_mult<VEC>(mult, first, V, m_a);
+  if (first + stride < V) load8_mult<VEC>(mult, first + stride, V, m_b);
+  accept_phase<BF16>(sh, a, b, split == 0);
 
   // 4. this workgroup's share of the table on the decision row: slices split, split + nsplit, ...
   const int32_t istar = sh.istar;
@@ -436,19 +443,23 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_delta_kernel(AcceptArgs
       v[k] = (float) diff * __builtin_amdgcn_rcpf(m[k]);   // N(t) is a small integer: 1 ulp, a tenth of a division's cost
     }
   };
-  const int32_t stride = nsplit * kAcceptTokens;
   float *out = table + (int64_t) b * V;
   // two slices per turn, so that the loads of the second are in flight behind the first
-  for (int32_t t = split * kAcceptTokens + threadIdx.x * kTokensPerThread; t < V; t += 2 * stride) {
+  for (int32_t t = first; t < V; t += 2 * stride) {
     const int32_t t2 = t + stride;
     float xt[8], xd[8], m[8], v[8], xt2[8], xd2[8], m2[8];
     load8<BF16, VEC>(trow, t, V, xt);
     if (rejected) load8<BF16, VEC>(drow, t, V, xd);
-    load8_mult<VEC>(mult, t, V, m);
     if (t2 < V) {
       load8<BF16, VEC>(trow, t2, V, xt2);
       if (rejected) load8<BF16, VEC>(drow, t2, V, xd2);
-      load8_mult<VEC>(mult, t2, V, m2);
+    }
+    if (t == first) {
+#pragma unroll
+      for (int k = 0; k < 8; ++k) { m[k] = m_a[k]; m2[k] = m_b[k]; }
+    } else {
+      load8_mult<VEC>(mult, t, V, m);
+      if (t2 < V) load8_mult<VEC>(mult, t2, V, m2);
     }
     delta8(xt, xd, m, v);
     store8<VEC>(out, t, V, v);

@@ -34,8 +34,8 @@ LDS_PEAK_GBS = 256 * 128 * 2.4     # 256 CUs x 128 B/clk x 2.4 GHz = 78 643 GB/s
 # copy of 256 MiB: FETCH_SIZE reads 131 085 for 262 144 KiB, factor 2.000; WRITE_SIZE reads
 # 262 144, factor 1.000).  Source: profiles/pcg_C4_hbm_traffic.md.
 MEASURED_TRAFFIC_BYTES = {
-    "row_stats@C4": int((69664.0 * 2.000 + 544.3) * 1024),
-    "gather@C4": int((25868.2 * 2.000 + 16386.0) * 1024),
+    "row_stats@C4": int((72027.3 * 2.000 + 560.2) * 1024),
+    "gather@C4": int((25869.6 * 2.000 + 16386.0) * 1024),
 }
 
 

@@ -109,19 +109,23 @@ template <bool BF16, bool VEC, bool STREAM>
 __global__ __launch_bounds__(kStatsWaves *kWave) void row_stats_kernel(RowSet rs, int32_t V,
                                                                        int32_t nparts, int64_t nrows,
                                                                        float c, StatPart *parts,
-                                                                       ProbeArgs pa) {
+                                                                       ProbeArgs pa, int64_t probe_slots) {
   const int lane = threadIdx.x & (kWave - 1);
   // everything that selects the data is wave-uniform: keep it in scalar registers
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int32_t part = blockIdx.x * kStatsWaves + wave;
-  const int64_t row = (int64_t) blockIdx.z * kRowsPerGridY + blockIdx.y;
-  if (row >= nrows) return;                     // whole wave leaves together
-  if (blockIdx.x * kStatsWaves >= nparts) {
-    // one workgroup past the row's parts (launched only with probes): its first wave probes
-    if (wave == 0 && row < rs.nrows0) probe_row<BF16>(rs, pa, row, c, lane);
+  // grid planes (z) continue the count of y: slot runs over the probe slots, then the rows
+  const int64_t slot = (int64_t) blockIdx.z * kRowsPerGridY + blockIdx.y;
+  if (slot < probe_slots) {
+    // The first probe_slots values (launched only with probes) are not rows of logits: each wave
+    // of their workgroups forms the probe of one target row.  They are dealt out first, so the
+    // chains of dependent loads behind the probes run while the rest of the grid streams.
+    const int64_t prow = (slot * gridDim.x + blockIdx.x) * kStatsWaves + wave;
+    if (prow < rs.nrows0) probe_row<BF16>(rs, pa, prow, c, lane);
     return;
   }
-  if (part >= nparts) return;
+  const int32_t part = blockIdx.x * kStatsWaves + wave;
+  const int64_t row = slot - probe_slots;
+  if (part >= nparts || row >= nrows) return;   // whole wave leaves together
   const void *rowp = row_base(rs, row, BF16);
   const int32_t e0 = part * kPartElems;
 
@@ -1456,16 +1460,19 @@ hipError_t launch_row_stats(const RowSet &rs, bool bf16, int32_t V, int64_t nrow
                             const ProbeArgs *probes) {
   const int32_t nparts = stats_nparts(V);
   if (nrows == 0) return hipSuccess;
-  const unsigned gy = (unsigned) std::min<int64_t>(nrows, kRowsPerGridY);
-  const unsigned gz = (unsigned) ((nrows + kRowsPerGridY - 1) / kRowsPerGridY);
   ProbeArgs pa{};
   if (probes) pa = *probes;
-  // with probes, one more workgroup per row: it forms the row's probe
-  const dim3 grid((nparts + kStatsWaves - 1) / kStatsWaves + (probes ? 1 : 0), gy, gz),
-      block(kStatsWaves * kWave);
+  // With probes, the grid starts with a few rows of workgroups that form them, one target row per
+  // wave; the rows of logits follow (the first grid plane holds fewer of them by that much).
+  const unsigned gx = (unsigned) ((nparts + kStatsWaves - 1) / kStatsWaves);
+  const int64_t probe_y =
+      probes ? (rs.nrows0 + (int64_t) gx * kStatsWaves - 1) / ((int64_t) gx * kStatsWaves) : 0;
+  const int64_t slots = nrows + probe_y;                    // values of (z, y) the grid must hold
+  const unsigned gz = (unsigned) ((slots + kRowsPerGridY - 1) / kRowsPerGridY);
+  const dim3 grid(gx, (unsigned) std::min<int64_t>(slots, kRowsPerGridY), gz), block(kStatsWaves * kWave);
   const bool vec = rows_vector_aligned(rs, bf16);
   auto launch = [&](auto kernel) {
-    kernel<<<grid, block, 0, stream>>>(rs, V, nparts, nrows, c, parts, pa);
+    kernel<<<grid, block, 0, stream>>>(rs, V, nparts, nrows, c, parts, pa, probe_y);
   };
   if (bf16) {
     if (!vec) launch(row_stats_kernel<true, false, false>);

@@ -1007,28 +1007,40 @@ __device__ CdfPick block_inverse_cdf(int32_t n, F f, double u, bool have_goal = 
   const unsigned long long hit = __ballot(mine > 0.0 && excl + mine > goal);
   if (hit != 0 && lane == __ffsll((long long) hit) - 1) atomicMin(&first_thread, tid);
   __syncthreads();
-  const int ft = first_thread;
-  if (ft == tid) {
+  const int ft = __builtin_amdgcn_readfirstlane(first_thread);   // the same in every lane
+  if (in_regs && ft != INT_MAX) {
+    // The crossing lies inside thread ft's run: its wave looks at the run's bins side by side, one
+    // per lane (a run held in registers is at most 32 long), instead of thread ft walking them
+    // one after the other.
+    static_assert(kRegRun <= kWave, "one lane per bin of a run");
+    if (wave == (ft >> 6)) {                     // uniform over the wave
+      const int fl = ft & (kWave - 1);
+      const double base = read_lane(excl, fl);
+      const int32_t lo = read_lane(lo_i, fl), hi = read_lane(hi_i, fl);
+      const int32_t k = lo + lane;
+      double v = k < hi ? (double) f(k) : 0.0;
+      if (!(v > 0.0)) v = 0.0;
+      const double run_inc = wave_scan(v);
+      const unsigned long long pos = __ballot(v > 0.0);
+      const unsigned long long cross = __ballot(v > 0.0 && base + run_inc > goal);
+      // the first bin that carries the sum past the threshold; rounding may leave none (the sum
+      // of the run was taken in another order): then the last bin that has mass
+      const int l = cross ? __ffsll((long long) cross) - 1 : 63 - __clzll((long long) pos);
+      const double top = base + read_lane(run_inc, l), width = read_lane(v, l);
+      if (lane == 0) {
+        res.index = lo + l; res.hi = top; res.lo = top - width; res.total = total;
+      }
+    }
+  } else if (ft == tid) {
     double cum = excl;
     int32_t last = lo_i;
     bool done = false;
-    if (in_regs) {
-#pragma unroll
-      for (int j = 0; j < kRegRun; ++j) {
-        if (!done && vals[j] > 0.0) {
-          const double nxt = cum + vals[j];
-          if (nxt > goal) { res.index = lo_i + j; res.lo = cum; res.hi = nxt; done = true; }
-          else { last = lo_i + j; cum = nxt; }
-        }
-      }
-    } else {
-      for (int32_t k = lo_i; k < hi_i && !done; ++k) {
-        const double v = f(k);
-        if (!(v > 0.0)) continue;
-        const double nxt = cum + v;
-        if (nxt > goal) { res.index = k; res.lo = cum; res.hi = nxt; done = true; }
-        else { last = k; cum = nxt; }
-      }
+    for (int32_t k = lo_i; k < hi_i && !done; ++k) {
+      const double v = f(k);
+      if (!(v > 0.0)) continue;
+      const double nxt = cum + v;
+      if (nxt > goal) { res.index = k; res.lo = cum; res.hi = nxt; done = true; }
+      else { last = k; cum = nxt; }
     }
     if (!done) {   // summation order: excl + mine > goal, yet the walk stayed below: last bin
       const double v = (double) f(last);

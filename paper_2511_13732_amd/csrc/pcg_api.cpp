@@ -138,7 +138,8 @@ size_t pcg_verify_workspace_bytes(int32_t V, int32_t G, int32_t B, int32_t K) {
   return align_up(rows * stats_nparts(V) * sizeof(StatPart)) + align_up(rows * sizeof(RowStat)) +
          align_up((size_t) B * K * sizeof(Probe)) +
          align_up((size_t) B * V * sizeof(float)) + align_up((size_t) B * G * sizeof(float)) +
-         align_up((size_t) B * ((G + kChunkStep - 1) / kChunkStep) * sizeof(double)) + kAlign;
+         align_up((size_t) B * ((G + kChunkStep - 1) / kChunkStep) * sizeof(double)) +
+         align_up((size_t) B * (((size_t) G + kMaxChunkGroups) / kRunGroups) * sizeof(double)) + kAlign;
 }
 
 int pcg_group_probs(const pcg_groups *groups, const void *logits, pcg_dtype dt, int64_t rows,
@@ -192,7 +193,7 @@ int pcg_group_probs(const pcg_groups *groups, const void *logits, pcg_dtype dt, 
       return hip_fail(e);
     if (r0 == 0) { tm.end(kStageTable); tm.begin(kStageGather); }
     e = groups->prepared
-            ? launch_gather_prepared(*groups, n, table, out + r0 * groups->G, nullptr, stream)
+            ? launch_gather_prepared(*groups, n, table, out + r0 * groups->G, nullptr, nullptr, stream)
             : launch_gather(*groups, n, false, table, out + r0 * groups->G, stream);
     if (e != hipSuccess) return hip_fail(e);
     if (r0 == 0) tm.end(kStageGather);
@@ -329,6 +330,8 @@ int pcg_verify(const pcg_groups *groups, const void *target_logits, const void *
   float *R = (float *) ws;
   ws += align_up((size_t) B * groups->G * sizeof(float));
   double *csum = (double *) ws;
+  ws += align_up((size_t) B * ((groups->G + kChunkStep - 1) / kChunkStep) * sizeof(double));
+  double *runs = (double *) ws;     // [B][nchunks][chunk_groups / kRunGroups]
 
   const Factors f = factors(temperature);
   const AcceptArgs aa = accept_args(groups, rs, K, f, parts, probes, rowstat, prop_tokens, prop_groups,
@@ -338,6 +341,8 @@ int pcg_verify(const pcg_groups *groups, const void *target_logits, const void *
   fa.rs = rs;
   fa.K = K;
   fa.cd = f.cd;
+  fa.c = f.c;
+  fa.c_lo = f.c_lo;
   fa.rowstat = rowstat;
   fa.row_ptr = groups->row_ptr;
   fa.members = groups->members;
@@ -363,12 +368,13 @@ int pcg_verify(const pcg_groups *groups, const void *target_logits, const void *
   tm.end(kStageAccept);
   tm.begin(kStageGather);
   const bool prepared = groups->prepared != nullptr;
-  e = prepared ? launch_gather_prepared(*groups, B, table, R, csum, stream)
+  e = prepared ? launch_gather_prepared(*groups, B, table, R, csum, runs, stream)
                : launch_gather(*groups, B, true, table, R, stream);
   if (e != hipSuccess) return hip_fail(e);
   tm.end(kStageGather);
   tm.begin(kStageFinalize);
   if ((e = launch_finalize(fa, bf16, *groups, B, prepared ? csum : nullptr,
+                           prepared ? runs : nullptr,
                            prepared ? groups->prepared_info->nchunks : 1,
                            prepared ? groups->prepared_info->chunk_groups : groups->G, stream)) !=
       hipSuccess)

@@ -250,6 +250,7 @@ struct FinalizeArgs {
   RowSet rs;
   int32_t K;
   double cd;
+  float c, c_lo;           // cd in two fp32 pieces, as the table kernel uses it
   const RowStat *rowstat;
   const int32_t *row_ptr, *members, *mult;
   const float *weights;    // general weights per CSR entry, or NULL for the equal split

@@ -42,11 +42,11 @@ hipError_t launch_gather(const pcg_groups &g, int32_t nrows, bool clamp, const f
                          float *out, hipStream_t stream);
 
 hipError_t launch_gather_prepared(const pcg_groups &g, int32_t nrows, const float *table, float *out,
-                                  double *csum, hipStream_t stream);
+                                  double *csum, double *runs, hipStream_t stream);
 
 hipError_t launch_finalize(const FinalizeArgs &fa, bool bf16, const pcg_groups &g, int32_t B,
-                           const double *csum, int32_t nchunks, int32_t chunk_groups,
-                           hipStream_t stream);
+                           const double *csum, const double *runs, int32_t nchunks,
+                           int32_t chunk_groups, hipStream_t stream);
 
 // Remembers a HIP error for pcg_last_hip_error and returns PCG_ERR_HIP.
 int record_hip_error(hipError_t e);

@@ -964,10 +964,9 @@ struct CdfPick {
 // Inverse CDF over f(0..n-1) >= 0 by a whole workgroup of NT threads.  Each thread owns a
 // contiguous run, so the running sum is the ascending one up to fp64 rounding.  All threads get
 // the result.  The threshold is u * total, or `goal_in` (relative to this range) with have_goal.
-template <int NT, typename F>
+template <int NT, int kRegRun = 32, typename F>   // kRegRun: runs up to this length are held in registers
 __device__ CdfPick block_inverse_cdf(int32_t n, F f, double u, bool have_goal = false,
                                      double goal_in = 0.0) {
-  constexpr int kRegRun = 32;          // runs up to this length are held in registers
   __shared__ double wave_tot[NT / kWave];
   __shared__ int first_thread, last_pos;
   __shared__ CdfPick res;
@@ -1008,7 +1007,24 @@ __device__ CdfPick block_inverse_cdf(int32_t n, F f, double u, bool have_goal = 
   if (hit != 0 && lane == __ffsll((long long) hit) - 1) atomicMin(&first_thread, tid);
   __syncthreads();
   const int ft = __builtin_amdgcn_readfirstlane(first_thread);   // the same in every lane
-  if (in_regs && ft != INT_MAX) {
+  if (kRegRun <= 4 && in_regs) {
+    // a run of a few bins: thread ft walks its own registers
+    if (ft == tid) {
+      double cum = excl, last_v = 0.0;
+      int32_t last = lo_i;
+      bool done = false;
+#pragma unroll
+      for (int j = 0; j < kRegRun; ++j) {
+        if (!done && vals[j] > 0.0) {
+          const double nxt = cum + vals[j];
+          if (nxt > goal) { res.index = lo_i + j; res.lo = cum; res.hi = nxt; done = true; }
+          else { last = lo_i + j; last_v = vals[j]; cum = nxt; }
+        }
+      }
+      if (!done) { res.index = last; res.lo = cum - last_v; res.hi = cum; }
+      res.total = total;
+    }
+  } else if (in_regs && ft != INT_MAX) {
     // The crossing lies inside thread ft's run: its wave looks at the run's bins side by side, one
     // per lane (a run held in registers is at most 32 long), instead of thread ft walking them
     // one after the other.
@@ -1080,8 +1096,8 @@ __device__ __forceinline__ bool near_edge(const CdfPick &p, double u) {
 // staged_chunk >= 0 says that chunk's R values are in `stage` already, in the padded layout.
 template <bool BF16, int NT>
 __device__ void finalize_sequence(const FinalizeArgs &fa, int32_t V, int32_t G, int b,
-                                  const double *csum, int32_t nchunks, int32_t chunk_groups,
-                                  float *stage, int32_t staged_chunk) {
+                                  const double *csum, const double *runs, int32_t nchunks,
+                                  int32_t chunk_groups, float *stage, int32_t staged_chunk) {
   const int32_t K = fa.K;
   const int32_t istar = fa.accept_len[b];
   const int64_t trow_id = (int64_t) b * (K + 1) + istar;
@@ -1120,6 +1136,108 @@ __device__ void finalize_sequence(const FinalizeArgs &fa, int32_t V, int32_t G, 
     pg.index = -1; pg.total = S; pg.lo = pg.hi = 0.0;
     if (S > 0.0 && cstar >= 0) {
       const int32_t g0 = cstar * chunk_groups, ng = min(chunk_groups, G - g0);
+      if (runs) {
+        // The gather left no sums, only the totals of runs of kRunGroups groups: find the run
+        // that holds the crossing, form its groups' sums again -- 32 lanes per group, the table
+        // kernel's arithmetic for every entry (Eq. 8 on the decision row) -- and walk them.
+        static_assert(NT == kRunGroups * 32, "one half-wave per group of a run");
+        __shared__ float run_r[kRunGroups];
+        const int32_t nruns = (ng + kRunGroups - 1) / kRunGroups;
+        const double *rp = runs + ((int64_t) b * nchunks + cstar) * (chunk_groups / kRunGroups);
+        static_assert(kMaxChunkGroups / kRunGroups <= 2 * NT, "two runs per thread at most");
+        const CdfPick pr = block_inverse_cdf<NT, 2>(
+            nruns, [&](int32_t k) { return rp[k]; }, 0.0, true, goal - base);
+        if (pr.index >= 0) {
+          __shared__ int32_t run_n[kRunGroups];
+          const bool rejected = istar < K;
+          const void *drow = row_base(fa.rs, fa.rs.nrows0 + (int64_t) b * K + (rejected ? istar : 0), BF16);
+          const RowStat sd = fa.rowstat[fa.rs.nrows0 + (int64_t) b * K + (rejected ? istar : 0)];
+          const double izt = 1.0 / st.Z, izd = rejected ? 1.0 / sd.Z : 0.0;
+          const int32_t gr0 = g0 + pr.index * kRunGroups;
+          const int k = threadIdx.x >> 5, l = threadIdx.x & 31;
+          const int32_t g = gr0 + k;
+          float acc = 0.f;
+          // the lane's first entry stays in registers: a group of up to 32 entries then has
+          // everything the token draw needs in its half-wave
+          int32_t n_g = 0, t_first = -1;
+          float lt_first = -INFINITY, share_first = 1.f;
+          if (g < g0 + ng) {
+            const int32_t beg = row_ptr[g], end = row_ptr[g + 1];
+            n_g = end - beg;
+            for (int32_t j = beg + l; j < end; j += 32) {
+              const int32_t t = members[j];
+              const float lt = logit_at<BF16>(trow, t);
+              const float share = wts ? wts[j] : (float) mult[t];      // w_{k,t}, or N(t)
+              if (j == beg + l) { t_first = t; lt_first = lt; share_first = share; }
+              const float et = exp_rel(lt, st.M, fa.c, fa.c_lo);
+              double diff = __dmul_rn((double) et, izt);
+              if (rejected) {
+                const float ed = exp_rel(logit_at<BF16>(drow, t), sd.M, fa.c, fa.c_lo);
+                diff = __dsub_rn(diff, __dmul_rn((double) ed, izd));
+              }
+              acc = wts ? fmaf((float) diff, share, acc)
+                        : acc + (float) diff * __builtin_amdgcn_rcpf(share);
+            }
+          }
+          acc = subwave_sum<32>(acc);                   // total in the last lane of each 32
+          if (l == 31) { run_r[k] = fmaxf(acc, 0.f); run_n[k] = n_g; }
+          __syncthreads();
+          double cum = base + pr.lo, last_v = 0.0;
+          int pick = -1, last = -1;
+#pragma unroll
+          for (int k2 = 0; k2 < kRunGroups; ++k2) {
+            const double v = (double) run_r[k2];
+            if (pick < 0 && v > 0.0) {
+              if (cum + v > goal) { pick = k2; pg.lo = cum; pg.hi = cum + v; }
+              else { last = k2; last_v = v; cum += v; }
+            }
+          }
+          if (pick < 0) {
+            // rounding (the run's total was summed in another order): the last group of the run
+            // that has mass, or its first group if none has
+            pick = last < 0 ? 0 : last;
+            pg.hi = cum; pg.lo = cum - last_v;
+          }
+          pg.index = gr0 + pick;
+          if (run_n[pick] <= 32) {                      // uniform over the workgroup
+            // The token inside the group (Eq. 10) by the half-wave that formed the group's sum.
+            const int wv = __builtin_amdgcn_readfirstlane(pick >> 1);
+            if ((int) (threadIdx.x >> 6) == wv) {
+              const int lane = threadIdx.x & (kWave - 1);
+              double w = 0.0;
+              if (k == pick && t_first >= 0) {
+                const double e = exp2((double) (lt_first - st.M) * cd);
+                w = wts ? e * (double) share_first / st.Z : e / (st.Z * (double) share_first);
+                if (!(w > 0.0)) w = 0.0;
+              }
+              const double total = wave_sum(w);
+              const double inc = wave_scan(w);
+              const double goal_t = (double) u.tok * total;
+              const unsigned long long pos = __ballot(w > 0.0);
+              const unsigned long long hit = __ballot(w > 0.0 && inc > goal_t);
+              CdfPick pt;
+              pt.index = -1; pt.total = total; pt.lo = pt.hi = 0.0;
+              int32_t tok = -1;
+              if (pos) {
+                const int src = hit ? __ffsll((long long) hit) - 1 : 63 - __clzll((long long) pos);
+                pt.index = src & 31;
+                pt.hi = hit ? read_lane(inc, src) : total;
+                pt.lo = pt.hi - read_lane(w, src);
+                tok = read_lane(t_first, src);
+              }
+              if (lane == 0) {
+                fa.out_groups[(int64_t) b * (K + 1) + istar] = pg.index;
+                fa.out_tokens[(int64_t) b * (K + 1) + istar] = tok;
+                if (fa.diag) {
+                  if (near_edge(pg, (double) u.grp)) atomicAdd(&fa.diag->near_group, 1u);
+                  if (pt.index >= 0 && near_edge(pt, (double) u.tok)) atomicAdd(&fa.diag->near_token, 1u);
+                }
+              }
+            }
+            return;                                     // the whole workgroup, together
+          }
+        }
+      } else {
       // Stage the chunk in LDS with coalesced loads; the scan then reads contiguous runs.  One
       // pad word per 32 keeps the runs of neighbouring threads in different banks.
       if (cstar != staged_chunk) {
@@ -1150,6 +1268,7 @@ __device__ void finalize_sequence(const FinalizeArgs &fa, int32_t V, int32_t G, 
           goal - base);
       if (in.index >= 0) {
         pg.index = g0 + in.index; pg.lo = base + in.lo; pg.hi = base + in.hi;
+      }
       }
     }
   } else {
@@ -1238,10 +1357,11 @@ __device__ void finalize_sequence(const FinalizeArgs &fa, int32_t V, int32_t G, 
 template <bool BF16>
 __global__ __launch_bounds__(kFinalThreads) void finalize_kernel(FinalizeArgs fa, int32_t V,
                                                                  int32_t G, const double *csum,
+                                                                 const double *runs,
                                                                  int32_t nchunks,
                                                                  int32_t chunk_groups) {
   __shared__ float stage[kMaxChunkGroups + kMaxChunkGroups / 32];
-  finalize_sequence<BF16, kFinalThreads>(fa, V, G, blockIdx.x, csum, nchunks, chunk_groups, stage, -1);
+  finalize_sequence<BF16, kFinalThreads>(fa, V, G, blockIdx.x, csum, runs, nchunks, chunk_groups, stage, -1);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1305,7 +1425,7 @@ __global__ __launch_bounds__(kGatherThreads) void gather_prepared_kernel(
     int32_t tile_len, int32_t bpc, const uint32_t *__restrict__ desc,
     const uint16_t *__restrict__ perm, const uint4 *__restrict__ data,
     const float4 *__restrict__ wdata, const float *__restrict__ table, float *__restrict__ out,
-    double *__restrict__ csum) {
+    double *__restrict__ csum, double *__restrict__ runs) {
   __shared__ __attribute__((aligned(16))) float tab[kTileMax];
   __shared__ double wsum[kGatherWaves];
   const int xcd = blockIdx.x & 7;
@@ -1424,24 +1544,39 @@ __global__ __launch_bounds__(kGatherThreads) void gather_prepared_kernel(
   for (int j = 0; j < kMaxAcc; ++j)
     if (where[j] != 0xFFFFu) tab[where[j]] = acc[j];
   __syncthreads();
-  float *dst = out + (int64_t) r * G + g0;
-  double part = 0.0;
-  if ((((uintptr_t) dst | (uintptr_t) ng) & 15) == 0 && (ng & 3) == 0) {      // 16 bytes at a time
-    for (int32_t i = 4 * threadIdx.x; i < ng; i += 4 * kGatherThreads) {
-      const float4 v = *reinterpret_cast<const float4 *>(tab + i);
-      *reinterpret_cast<float4 *>(dst + i) = v;
-      if (CSUM)
-        part += ((double) fmaxf(v.x, 0.f) + (double) fmaxf(v.y, 0.f)) +
-                ((double) fmaxf(v.z, 0.f) + (double) fmaxf(v.w, 0.f));
+  if constexpr (!CSUM) {
+    float *dst = out + (int64_t) r * G + g0;
+    if ((((uintptr_t) dst | (uintptr_t) ng) & 15) == 0 && (ng & 3) == 0) {      // 16 bytes at a time
+      for (int32_t i = 4 * threadIdx.x; i < ng; i += 4 * kGatherThreads)
+        *reinterpret_cast<float4 *>(dst + i) = *reinterpret_cast<const float4 *>(tab + i);
+    } else {
+      for (int32_t i = threadIdx.x; i < ng; i += kGatherThreads) dst[i] = tab[i];
     }
   } else {
-    for (int32_t i = threadIdx.x; i < ng; i += kGatherThreads) {
-      const float v = tab[i];
-      dst[i] = v;
-      if (CSUM) part += (double) fmaxf(v, 0.f);
+    // The caller draws one group by inverse CDF over max(0, sum).  It does not need the sums
+    // themselves for that, only where the running total crosses its threshold: the workgroup
+    // leaves the totals of runs of kRunGroups consecutive groups (fp64, fixed order) and the
+    // chunk's total; the few sums of the run that holds the crossing are formed again by the
+    // caller.  Four neighbouring lanes cover one run, four groups each.
+    const float4 *tab4 = reinterpret_cast<const float4 *>(tab);
+    double *rp = runs + ((int64_t) r * nchunks + chunk) * (chunk_groups / kRunGroups);
+    double part = 0.0;
+#pragma unroll
+    for (int j = 0; j < kMaxChunkGroups / (4 * kGatherThreads); ++j) {
+      const int32_t i4 = threadIdx.x + j * kGatherThreads;
+      const int32_t g = 4 * i4;
+      double s = 0.0;
+      if (g < ng) {
+        const float4 v = tab4[i4];
+        s = ((double) fmaxf(v.x, 0.f) + (g + 1 < ng ? (double) fmaxf(v.y, 0.f) : 0.0)) +
+            ((g + 2 < ng ? (double) fmaxf(v.z, 0.f) : 0.0) + (g + 3 < ng ? (double) fmaxf(v.w, 0.f) : 0.0));
+      }
+      s = subwave_sum<4>(s);
+      if ((lane & 3) == 0 && g < ng) {
+        rp[i4 >> 2] = s;
+        part += s;
+      }
     }
-  }
-  if constexpr (CSUM) {
     part = subwave_sum<64>(part);
     if (lane == kWave - 1) wsum[wave] = part;
     __syncthreads();
@@ -1621,7 +1756,7 @@ hipError_t launch_gather(const pcg_groups &g, int32_t nrows, bool clamp, const f
 }
 
 hipError_t launch_gather_prepared(const pcg_groups &g, int32_t nrows, const float *table, float *out,
-                                  double *csum, hipStream_t stream) {
+                                  double *csum, double *runs, hipStream_t stream) {
   if (nrows == 0) return hipSuccess;
   const pcg_prepared &p = *g.prepared_info;
   const char *blob = reinterpret_cast<const char *>(g.prepared);
@@ -1636,7 +1771,7 @@ hipError_t launch_gather_prepared(const pcg_groups &g, int32_t nrows, const floa
   auto launch = [&](auto kernel) {
     kernel<<<grid, kGatherThreads, 0, stream>>>(g.V, g.G, nrows, p.nchunks, p.chunk_groups,
                                                 p.ntiles, p.tile_len, p.blocks_per_chunk, desc,
-                                                perm, data, wdata, table, out, csum);
+                                                perm, data, wdata, table, out, csum, runs);
   };
   if (wdata) {
     if (csum) launch(gather_prepared_kernel<true, true>);
@@ -1649,12 +1784,12 @@ hipError_t launch_gather_prepared(const pcg_groups &g, int32_t nrows, const floa
 }
 
 hipError_t launch_finalize(const FinalizeArgs &fa, bool bf16, const pcg_groups &g, int32_t B,
-                           const double *csum, int32_t nchunks, int32_t chunk_groups,
-                           hipStream_t stream) {
+                           const double *csum, const double *runs, int32_t nchunks,
+                           int32_t chunk_groups, hipStream_t stream) {
   if (bf16)
-    finalize_kernel<true><<<B, kFinalThreads, 0, stream>>>(fa, g.V, g.G, csum, nchunks, chunk_groups);
+    finalize_kernel<true><<<B, kFinalThreads, 0, stream>>>(fa, g.V, g.G, csum, runs, nchunks, chunk_groups);
   else
-    finalize_kernel<false><<<B, kFinalThreads, 0, stream>>>(fa, g.V, g.G, csum, nchunks, chunk_groups);
+    finalize_kernel<false><<<B, kFinalThreads, 0, stream>>>(fa, g.V, g.G, csum, runs, nchunks, chunk_groups);
   return hipGetLastError();
 }
 

@@ -15,6 +15,7 @@ constexpr int kMaxBlocksPerWave = 4;     // blocks a wave handles per tile pass
 constexpr int kMaxAcc = kLaneGroups * kMaxBlocksPerWave;       // running sums per lane: 16
 constexpr int kChunkStep = kGatherWaves * kBlockGroups;        // 4096 groups: one block per wave
 constexpr int kMaxChunkGroups = kMaxBlocksPerWave * kChunkStep;   // 16384 groups per workgroup
+constexpr int kRunGroups = 16;           // consecutive groups whose clamped sums the gather adds up into one run sum
 
 // Block of a chunk that wave w handles in its q-th turn.  Blocks are sorted by list length, so
 // alternating the direction evens out the work of the waves.

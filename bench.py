@@ -34,8 +34,8 @@ LDS_PEAK_GBS = 256 * 128 * 2.4     # 256 CUs x 128 B/clk x 2.4 GHz = 78 643 GB/s
 # copy of 256 MiB: FETCH_SIZE reads 131 085 for 262 144 KiB, factor 2.000; WRITE_SIZE reads
 # 262 144, factor 1.000).  Source: profiles/pcg_C4_hbm_traffic.md.
 MEASURED_TRAFFIC_BYTES = {
-    "row_stats@C4": int((72027.3 * 2.000 + 560.2) * 1024),
-    "gather@C4": int((25869.6 * 2.000 + 16386.0) * 1024),
+    "row_stats@C4": int((72031.2 * 2.000 + 560.2) * 1024),
+    "gather@C4": int((25876.1 * 2.000 + 2050.0) * 1024),
 }
 
 
@@ -164,7 +164,8 @@ def main():
                        "unit": "GB/s", "frac": round(lds_bytes / g_s / 1e9 / LDS_PEAK_GBS, 4),
                        "traffic": MEASURED_TRAFFIC_BYTES.get(f"gather@{cfg.name}"),
                        "algorithmic_bytes": lds_bytes,
-                       "hbm_algorithmic_bytes": 4 * cfg.B * cfg.V + 4 * cfg.B * groups.G
+                       # table read, one fp64 total per run of 16 groups written, membership once
+                       "hbm_algorithmic_bytes": 4 * cfg.B * cfg.V + 8 * cfg.B * groups.G // 16
                                                 + 2 * groups.nnz,
                        "kernel_us": round(1e3 * stage_ms["gather"], 2)}
 

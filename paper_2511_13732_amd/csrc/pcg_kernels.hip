@@ -1370,10 +1370,10 @@ __global__ __launch_bounds__(kFinalThreads) void finalize_kernel(FinalizeArgs fa
 // table row.  Wave w owns the blocks block_of(q, w), q = 0..3, of the chunk and walks them side
 // by side; lane l handles each block's 4 groups r*64 + l -- the same 16 groups in every tile
 // pass, so their running sums stay in registers.  One 16-byte load per lane brings 2 slots for
-// each of a block's 4 groups.  Results are put back into group order through LDS and leave with
-// coalesced stores;
-// with CSUM the workgroup also writes the chunk's total of max(0, .) in double, summed in a
-// fixed order.
+// each of a block's 4 groups.  Results are put back into group order through LDS.  Without CSUM
+// they leave with coalesced stores; with CSUM (the residual of pcg_verify, Eq. 8) only totals of
+// max(0, .) leave, in double and summed in a fixed order: one per run of kRunGroups consecutive
+// groups and one for the chunk.
 // ---------------------------------------------------------------------------------------------
 
 __device__ __forceinline__ void gather_step(const float *tab, const uint4 w, float *acc) {

@@ -111,6 +111,7 @@ def test_group_probs_many_rows_in_batches():
     (50000, 6000, 10, 30, 6, 4, "f32", 1.0),     # two LDS tiles
     (100000, 3000, 5, 40, 3, 2, "bf16", 1.0),    # three LDS tiles
     (5, 4, 1, 3, 200, 2, "f32", 1.0),            # tiny vocabulary
+    (30000, 150000, 1, 4, 4, 3, "bf16", 1.0),    # more groups than tokens: 10 and 37 chunks
 ])
 @pytest.mark.parametrize("layout", ["prepared", "prepared-4096", "csr"])
 def test_verify_matches_oracle(V, G, smin, smax, B, K, dtype, tau, layout):

@@ -54,7 +54,8 @@ typedef enum {
   PCG_ERR_BAD_CSR = -7,            /* host validation of the group membership failed        */
   PCG_ERR_HIP = -8,                /* a HIP runtime call failed                             */
   PCG_ERR_MISALIGNED = -9,         /* workspace not 256-byte aligned, logits not element-aligned */
-  PCG_ERR_CAPACITY = -10           /* pcg_asg_build: a group or the member array did not fit      */
+  PCG_ERR_CAPACITY = -10,          /* pcg_asg_build: a group or the member array did not fit      */
+  PCG_ERR_SCRATCH_TOO_SMALL = -11  /* pcg_verify_static: the step needs more than PCG_STATIC_SCRATCH_BYTES */
 } pcg_status;
 
 #define PCG_MAX_K 64               /* largest number of draft positions per step           */
@@ -204,6 +205,36 @@ int pcg_verify(const pcg_groups *groups, const void *target_logits, const void *
                void *hip_stream);
 
 size_t pcg_verify_workspace_bytes(int32_t V, int32_t G, int32_t B, int32_t K);
+
+/* ---- the same step for callers that cannot allocate --------------------------------------- */
+
+#define PCG_STATIC_SCRATCH_BYTES (48u << 20)
+
+/*
+ * pcg_verify without a workspace argument, for callers that can neither allocate device memory
+ * nor keep a workspace of their own: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, same kernels and same results as
+ * pcg_verify; the scratch memory is an array of PCG_STATIC_SCRATCH_BYTES (48 MiB) that the
+ * library itself holds in the memory of every GPU it is loaded on, from load until the process
+ * ends.  The call allocates and frees nothing (the first call on a device looks up the
+ * array's address there, once).
+ *   - a step with pcg_verify_workspace_bytes(V, G, B, K) > PCG_STATIC_SCRATCH_BYTES returns
+ *     PCG_ERR_SCRATCH_TOO_SMALL before anything is launched (the headline shape V = G = 65 536,
+ *     B = 64, K = 8 needs 37 MB);
+ *   - every call on a GPU uses that GPU's one array: calls that may overlap on one GPU (two
+ *     streams, two threads) race on it and must be ordered by the caller; nothing in the array
+ *     has to survive from one call to the next, and nothing in it is assumed to be zero.
+ * pcg_static_scratch_bytes() returns PCG_STATIC_SCRATCH_BYTES.
+ */
+int pcg_verify_static(const pcg_groups *groups, const void *target_logits,
+                      const void *draft_logits, pcg_dtype dt, int32_t B, int32_t K,
+                      int64_t tgt_batch_stride, int64_t tgt_pos_stride, int64_t dft_batch_stride,
+                      int64_t dft_pos_stride, float temperature, const int32_t *prop_tokens,
+                      const int32_t *prop_groups, uint64_t seed, uint64_t offset,
+                      int32_t *accept_len, int32_t *out_tokens, int32_t *out_groups,
+                      pcg_diag *diag, void *hip_stream);
+
+size_t pcg_static_scratch_bytes(void);
 
 /* ---- the same step with the reject branch drawn by thinning ------------------------------ */
 

@@ -9,7 +9,7 @@ from .binding import (BF16, F32, THIN_MAX_TRIALS, AsgGroups, Diag, Groups, PcgEr
                       asg_build, asg_normalize, groups_canonicalize_host, groups_prepare_host, groups_reverse_host,
                       groups_reverse_weights_host, groups_validate_weights_host,
                       groups_validate_host, lib, lib_path, profile_begin, profile_end, propose,
-                      propose_workspace_bytes, strerror,
+                      propose_workspace_bytes, static_scratch_bytes, strerror,
                       suggest_chunk_groups, verify, verify_thinning,
                       verify_thinning_workspace_bytes, verify_workspace_bytes, version)
 
@@ -18,6 +18,6 @@ __all__ = ["BF16", "F32", "THIN_MAX_TRIALS", "AsgGroups", "Diag", "Groups", "asg
            "groups_canonicalize_host", "groups_prepare_host", "groups_reverse_host",
            "groups_reverse_weights_host", "groups_validate_weights_host",
            "groups_validate_host", "lib", "lib_path", "profile_begin", "profile_end", "propose",
-           "propose_workspace_bytes", "strerror",
+           "propose_workspace_bytes", "static_scratch_bytes", "strerror",
            "suggest_chunk_groups", "verify", "verify_thinning", "verify_thinning_workspace_bytes",
            "verify_workspace_bytes", "version"]

@@ -76,6 +76,10 @@ def lib() -> C.CDLL:
                                  C.c_float, C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint64,
                                  C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                  C.c_size_t, C.c_void_p]
+        L.pcg_verify_static.restype = C.c_int
+        L.pcg_verify_static.argtypes = L.pcg_verify.argtypes[:19] + [C.c_void_p]
+        L.pcg_static_scratch_bytes.restype = C.c_size_t
+        L.pcg_static_scratch_bytes.argtypes = []
         L.pcg_verify_thinning_workspace_bytes.restype = C.c_size_t
         L.pcg_verify_thinning_workspace_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32]
         L.pcg_verify_thinning.restype = C.c_int
@@ -366,17 +370,23 @@ class VerifyOutput:
     out_groups: torch.Tensor   # int32 [B, K+1]
 
 
+def static_scratch_bytes() -> int:
+    return lib().pcg_static_scratch_bytes()
+
+
 def verify(groups: Groups, target_logits: torch.Tensor, draft_logits: torch.Tensor,
            prop_tokens: torch.Tensor, prop_groups: torch.Tensor, *, temperature: float = 1.0,
            seed: int = 0, offset: int = 0, out: Optional[VerifyOutput] = None,
            diag: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
-           B: Optional[int] = None) -> VerifyOutput:
+           B: Optional[int] = None, static_scratch: bool = False) -> VerifyOutput:
     """One speculative step (Algorithm 1) for B sequences.
 
     target_logits [B, K+1, V], draft_logits [B, >=K, V] (float32 or bfloat16, last axis
     contiguous); prop_tokens / prop_groups int32 [B, K].  ``B`` larger than the tensors'
     batch with batch dimension 1 makes all sequences share the same rows (batch stride 0).
     ``diag`` is an optional zero-initialised int32[8] device tensor that receives pcg_diag.
+    ``static_scratch`` calls pcg_verify_static: no workspace is passed or allocated, the
+    library's own array is used (``out`` must then be given, so that nothing is allocated).
     """
     assert target_logits.dim() == 3 and draft_logits.dim() == 3
     K, V = target_logits.shape[1] - 1, target_logits.shape[2]
@@ -399,9 +409,20 @@ def verify(groups: Groups, target_logits: torch.Tensor, draft_logits: torch.Tens
         out = VerifyOutput(torch.empty(B, dtype=torch.int32, device=dev),
                            torch.empty((B, K + 1), dtype=torch.int32, device=dev),
                            torch.empty((B, K + 1), dtype=torch.int32, device=dev))
+    gs = groups.struct()
+    if static_scratch:
+        assert workspace is None
+        with torch.cuda.device(dev):
+            _check(lib().pcg_verify_static(
+                C.byref(gs), target_logits.data_ptr(), draft_logits.data_ptr(),
+                _dtype_code(target_logits), B, K, tbs, target_logits.stride(1), dbs,
+                draft_logits.stride(1) if K > 1 else V, float(temperature), prop_tokens.data_ptr(),
+                prop_groups.data_ptr(), seed, offset, out.accept_len.data_ptr(),
+                out.out_tokens.data_ptr(), out.out_groups.data_ptr(),
+                None if diag is None else diag.data_ptr(), _stream(dev)), "pcg_verify_static")
+        return out
     need = verify_workspace_bytes(V, groups.G, B, K)
     ws = _workspace(dev, need) if workspace is None else workspace
-    gs = groups.struct()
     with torch.cuda.device(dev):
         _check(lib().pcg_verify(C.byref(gs), target_logits.data_ptr(), draft_logits.data_ptr(),
                                 _dtype_code(target_logits), B, K, tbs, target_logits.stride(1),

@@ -3,12 +3,19 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 #include "pcg_kernels.h"
 #include "pcg_layout.h"
+
+// The library's own scratch memory (pcg_verify_static): one array per GPU, in that GPU's memory
+// from the moment the code object is loaded there until the process ends.  In host code this
+// name is only the handle of the symbol, never a device address.
+static __device__ __align__(256) unsigned char scratch[PCG_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -293,17 +300,15 @@ AcceptArgs accept_args(const pcg_groups *groups, const RowSet &rs, int32_t K, co
   return aa;
 }
 
-}  // namespace
-
-extern "C" {
-
-int pcg_verify(const pcg_groups *groups, const void *target_logits, const void *draft_logits,
-               pcg_dtype dt, int32_t B, int32_t K, int64_t tgt_batch_stride,
-               int64_t tgt_pos_stride, int64_t dft_batch_stride, int64_t dft_pos_stride,
-               float temperature, const int32_t *prop_tokens, const int32_t *prop_groups,
-               uint64_t seed, uint64_t offset, int32_t *accept_len, int32_t *out_tokens,
-               int32_t *out_groups, pcg_diag *diag, void *workspace, size_t workspace_bytes,
-               void *hip_stream) {
+// The whole step on `workspace` (device memory, wherever it comes from): shared by pcg_verify,
+// whose caller brings the workspace, and pcg_verify_static, which uses the library's own array.
+int verify_impl(const pcg_groups *groups, const void *target_logits, const void *draft_logits,
+                pcg_dtype dt, int32_t B, int32_t K, int64_t tgt_batch_stride,
+                int64_t tgt_pos_stride, int64_t dft_batch_stride, int64_t dft_pos_stride,
+                float temperature, const int32_t *prop_tokens, const int32_t *prop_groups,
+                uint64_t seed, uint64_t offset, int32_t *accept_len, int32_t *out_tokens,
+                int32_t *out_groups, pcg_diag *diag, void *workspace, size_t workspace_bytes,
+                void *hip_stream) {
   RowSet rs;
   int rc = check_verify_args(groups, target_logits, draft_logits, dt, B, K, tgt_batch_stride,
                              tgt_pos_stride, dft_batch_stride, dft_pos_stride, temperature,
@@ -381,6 +386,72 @@ int pcg_verify(const pcg_groups *groups, const void *target_logits, const void *
     return hip_fail(e);
   tm.end(kStageFinalize);
   return PCG_OK;
+}
+
+// ---- the library's own scratch memory, for callers that cannot allocate --------------------
+//
+// `scratch` (top of this file) is only the host-side handle of the symbol: the device address
+// is asked for once per device (hipGetSymbolAddress) and kept; every use goes through it.
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+std::atomic<void *> g_scratch_ptr[kMaxDevices];
+
+// Device address of `scratch` on the current device; NULL with *rc set on failure.
+void *scratch_address(int *rc) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) { *rc = hip_fail(e); return nullptr; }
+  if (dev < 0 || dev >= kMaxDevices) { *rc = PCG_ERR_BAD_SHAPE; return nullptr; }
+  void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (p) return p;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  p = g_scratch_ptr[dev].load(std::memory_order_relaxed);
+  if (p) return p;
+  e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+  if (e != hipSuccess || !p) { *rc = hip_fail(e == hipSuccess ? hipErrorInvalidSymbol : e); return nullptr; }
+  g_scratch_ptr[dev].store(p, std::memory_order_release);
+  return p;
+}
+
+}  // namespace
+
+extern "C" {
+
+int pcg_verify(const pcg_groups *groups, const void *target_logits, const void *draft_logits,
+               pcg_dtype dt, int32_t B, int32_t K, int64_t tgt_batch_stride,
+               int64_t tgt_pos_stride, int64_t dft_batch_stride, int64_t dft_pos_stride,
+               float temperature, const int32_t *prop_tokens, const int32_t *prop_groups,
+               uint64_t seed, uint64_t offset, int32_t *accept_len, int32_t *out_tokens,
+               int32_t *out_groups, pcg_diag *diag, void *workspace, size_t workspace_bytes,
+               void *hip_stream) {
+  return verify_impl(groups, target_logits, draft_logits, dt, B, K, tgt_batch_stride,
+                     tgt_pos_stride, dft_batch_stride, dft_pos_stride, temperature, prop_tokens,
+                     prop_groups, seed, offset, accept_len, out_tokens, out_groups, diag, workspace,
+                     workspace_bytes, hip_stream);
+}
+
+size_t pcg_static_scratch_bytes(void) { return PCG_STATIC_SCRATCH_BYTES; }
+
+int pcg_verify_static(const pcg_groups *groups, const void *target_logits,
+                      const void *draft_logits, pcg_dtype dt, int32_t B, int32_t K,
+                      int64_t tgt_batch_stride, int64_t tgt_pos_stride, int64_t dft_batch_stride,
+                      int64_t dft_pos_stride, float temperature, const int32_t *prop_tokens,
+                      const int32_t *prop_groups, uint64_t seed, uint64_t offset,
+                      int32_t *accept_len, int32_t *out_tokens, int32_t *out_groups,
+                      pcg_diag *diag, void *hip_stream) {
+  // sizes first: a step that does not fit the array is refused before anything else happens
+  if (!groups) return PCG_ERR_NULL_ARG;
+  if (groups->V < 1 || groups->G < 1 || B < 0 || K < 1 || K > PCG_MAX_K) return PCG_ERR_BAD_SHAPE;
+  if (pcg_verify_workspace_bytes(groups->V, groups->G, B, K) > PCG_STATIC_SCRATCH_BYTES)
+    return PCG_ERR_SCRATCH_TOO_SMALL;
+  int rc = PCG_OK;
+  void *ws = scratch_address(&rc);
+  if (!ws) return rc;
+  return verify_impl(groups, target_logits, draft_logits, dt, B, K, tgt_batch_stride,
+                     tgt_pos_stride, dft_batch_stride, dft_pos_stride, temperature, prop_tokens,
+                     prop_groups, seed, offset, accept_len, out_tokens, out_groups, diag, ws,
+                     PCG_STATIC_SCRATCH_BYTES, hip_stream);
 }
 
 size_t pcg_propose_workspace_bytes(int32_t V, int32_t B, int32_t K) {
@@ -664,6 +735,8 @@ const char *pcg_strerror(int status) {
     case PCG_ERR_HIP: return "a HIP runtime call failed (see pcg_last_hip_error)";
     case PCG_ERR_MISALIGNED: return "a pointer is not aligned as required";
     case PCG_ERR_CAPACITY: return "a similarity group or the member array needs more room";
+    case PCG_ERR_SCRATCH_TOO_SMALL:
+      return "the step needs more scratch memory than the library's own array holds (use pcg_verify)";
     default: return "unknown status";
   }
 }

@@ -40,7 +40,8 @@ def test_header_constants_match_binding():
     for name, val in [("PCG_ERR_NULL_ARG", -1), ("PCG_ERR_BAD_SHAPE", -2), ("PCG_ERR_BAD_DTYPE", -3),
                       ("PCG_ERR_BAD_STRIDE", -4), ("PCG_ERR_BAD_TEMPERATURE", -5),
                       ("PCG_ERR_WORKSPACE_TOO_SMALL", -6), ("PCG_ERR_BAD_CSR", -7),
-                      ("PCG_ERR_HIP", -8), ("PCG_ERR_MISALIGNED", -9), ("PCG_ERR_CAPACITY", -10)]:
+                      ("PCG_ERR_HIP", -8), ("PCG_ERR_MISALIGNED", -9), ("PCG_ERR_CAPACITY", -10),
+                      ("PCG_ERR_SCRATCH_TOO_SMALL", -11)]:
         assert re.search(rf"{name}\s*=\s*{val}\b", text)
         assert pcg.strerror(val) != "unknown status"
     assert re.search(r"PCG_F32 = 0, PCG_BF16 = 1", text) and (pcg.F32, pcg.BF16) == (0, 1)
@@ -62,6 +63,23 @@ def call_verify(V=64, G=8, nnz=16, dt=0, B=2, K=2, tbs=None, tps=None, dbs=None,
     dbs = K * V if dbs is None else dbs
     return pcg.lib().pcg_verify(C.byref(gs) if groups else None, tgt, dft, dt, B, K, tbs, tps, dbs,
                                 dps, tau, ptok, pgrp, 0, 0, al, otok, ogrp, None, ws, ws_bytes, None)
+
+
+def test_static_scratch_entry_point_refuses_on_the_host_what_does_not_fit():
+    """pcg_verify_static looks at the sizes before anything else: a step that needs more scratch
+    than the library's own array holds is refused without a GPU being touched."""
+    L = pcg.lib()
+    cap = pcg.static_scratch_bytes()
+    m = re.search(r"#define PCG_STATIC_SCRATCH_BYTES \((\d+)u << (\d+)\)", open(HEADER).read())
+    assert m and cap == int(m.group(1)) << int(m.group(2))
+    V = G = 65536
+    assert L.pcg_verify_workspace_bytes(V, G, 64, 8) <= cap < L.pcg_verify_workspace_bytes(V, G, 128, 8)
+    gs = _GroupsStruct(V, G, 32 * V, P, P, P, None, None, None, None, None, None)
+    args = lambda B, K: (C.byref(gs), P, P, 1, B, K, (K + 1) * V, V, K * V, V, 1.0, P, P, 0, 0, P, P, P, None, None)
+    assert L.pcg_verify_static(*args(128, 8)) == -11
+    assert L.pcg_verify_static(None, *args(1, 1)[1:]) == NULL_ARG
+    assert L.pcg_verify_static(*args(4, 0)) == BAD_SHAPE
+    assert "scratch" in pcg.strerror(-11)
 
 
 def test_verify_rejects_bad_arguments_on_the_host():

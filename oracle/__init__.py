@@ -445,6 +445,27 @@ def asg_row(unit, theta: float, t: int) -> tuple[np.ndarray, int]:
     return buf[:n.value].copy(), near.value
 
 
+def asg_cosine(emb, a: int, b: int) -> float:
+    """Cosine of rows a and b of the float32 embeddings, in double (Eq. 1's similarity)."""
+    e = np.ascontiguousarray(emb, dtype=np.float32)
+    f = lib().pcg_ref_asg_cosine
+    f.restype = C.c_double
+    return f(_p(e), C.c_int32(e.shape[1]), C.c_int32(a), C.c_int32(b))
+
+
+def asg_row_exact(emb, theta: float, t: int) -> tuple[np.ndarray, np.ndarray]:
+    """(members of G(t) ascending, the row's cosines float64 [V]) by Eq. (1) on the embeddings
+    themselves: double throughout, strict ``> theta``, no rounded unit vectors."""
+    e = np.ascontiguousarray(emb, dtype=np.float32)
+    V, d = e.shape
+    buf = np.empty(V, dtype=np.int32)
+    cos = np.empty(V, dtype=np.float64)
+    n = C.c_int32()
+    _check(lib().pcg_ref_asg_row_exact(_p(e), C.c_int32(V), C.c_int32(d), C.c_double(theta),
+                                       C.c_int32(t), _p(buf), C.byref(n), _p(cos)), "asg_row_exact")
+    return buf[:n.value].copy(), cos
+
+
 @dataclass
 class AsgResult:
     groups: Groups

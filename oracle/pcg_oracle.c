@@ -971,6 +971,31 @@ int pcg_ref_asg_row(const uint16_t *unit_bf16, int32_t V, int32_t d, float theta
   return PCG_REF_OK;
 }
 
+double pcg_ref_asg_cosine(const float *emb, int32_t d, int32_t a, int32_t b) {
+  const float *x = emb + (int64_t)a * d, *y = emb + (int64_t)b * d;
+  double dot = 0.0, xx = 0.0, yy = 0.0;
+  for (int32_t k = 0; k < d; ++k) {
+    dot += (double)x[k] * (double)y[k];
+    xx += (double)x[k] * (double)x[k];
+    yy += (double)y[k] * (double)y[k];
+  }
+  if (!(xx > 0.0) || !(yy > 0.0)) return 0.0;
+  return dot / (sqrt(xx) * sqrt(yy));
+}
+
+int pcg_ref_asg_row_exact(const float *emb, int32_t V, int32_t d, double theta, int32_t t,
+                          int32_t *members_out, int32_t *count, double *cos_out) {
+  if (!emb || !members_out || !count || V < 1 || d < 1 || t < 0 || t >= V) return PCG_REF_ERR_ARG;
+  int32_t n = 0;
+  for (int32_t v = 0; v < V; ++v) {
+    double c = v == t ? 1.0 : pcg_ref_asg_cosine(emb, d, t, v);
+    if (cos_out) cos_out[v] = c;
+    if (v == t || c > theta) members_out[n++] = v;            /* Eq. (1), strict */
+  }
+  *count = n;
+  return PCG_REF_OK;
+}
+
 int pcg_ref_asg_build(const uint16_t *unit_bf16, int32_t V, int32_t d, float theta,
                       int32_t *out_G, int64_t *out_nnz, int32_t *row_ptr, int32_t *members,
                       int64_t members_capacity, int32_t *mult, int32_t *seed_of,

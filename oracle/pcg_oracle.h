@@ -321,6 +321,18 @@ int pcg_ref_asg_build(const uint16_t *unit_bf16, int32_t V, int32_t d, float the
                       int64_t members_capacity, int32_t *mult, int32_t *seed_of,
                       uint8_t *near_rows, int32_t nthreads);
 
+/* Eq. (1) as the paper writes it, on the embeddings themselves: the cosine similarity of the
+ * float32 rows a and b of emb, every step in double (dot product and both norms summed in
+ * ascending k, one square root each, one division).  No rounding of the unit vectors: this is
+ * the definition the bf16 routines above approximate.  A zero row has cosine 0 with everything. */
+double pcg_ref_asg_cosine(const float *emb, int32_t d, int32_t a, int32_t b);
+
+/* Members of G(t) by Eq. (1), ascending: every v with cosine(t, v) > theta (strict), and t
+ * itself (cos(t, t) = 1).  members_out [V].  cos_out (may be NULL) [V] receives every cosine of
+ * the row (cos_out[t] = 1), so that a caller can measure how far from theta a pair lies. */
+int pcg_ref_asg_row_exact(const float *emb, int32_t V, int32_t d, double theta, int32_t t,
+                          int32_t *members_out, int32_t *count, double *cos_out);
+
 /* Proposals with general weights: the group label by the inverse CDF of the token's weights
  * at u = k24 / 2^24; near also covers that draw. */
 int pcg_ref_propose_u_w(int32_t V, int32_t G, const int32_t *mult, const pcg_ref_weights *wt,

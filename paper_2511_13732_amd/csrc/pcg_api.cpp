@@ -59,7 +59,12 @@ struct StageTimer {
   hipStream_t stream;
   int slot;          // index of the recorded call, -1 if not recording
   explicit StageTimer(hipStream_t s) : stream(s), slot(-1) {
-    if (g_prof.active && g_prof.calls < g_prof.max_calls) slot = g_prof.calls++;
+    // events recorded into a stream that is being captured would become nodes of the caller's
+    // graph: a call under capture is never timed
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    const bool capturing =
+        g_prof.active && (hipStreamIsCapturing(s, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone);
+    if (g_prof.active && !capturing && g_prof.calls < g_prof.max_calls) slot = g_prof.calls++;
     // two events with nothing between them: what an event pair costs on this stream, to be
     // taken off the stage times by whoever reads them
     begin(kStageNull);

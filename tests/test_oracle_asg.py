@@ -141,3 +141,89 @@ def test_well_separated_clusters_are_recovered_exactly():
     for k in range(C):
         seg = g.members[g.row_ptr[k]:g.row_ptr[k + 1]]
         np.testing.assert_array_equal(seg, np.flatnonzero(assign == assign[res.seed_of[k]]))
+
+
+# --------------------------------------------------------------------------- Eq. (1) itself
+
+def numpy_cosines(E):
+    """Cosine matrix of float32 embeddings with numpy in float64 (independent of the oracle)."""
+    X = np.asarray(E, dtype=np.float64)
+    n = np.sqrt(np.einsum("ij,ij->i", X, X))
+    Xn = np.divide(X, n[:, None], out=np.zeros_like(X), where=n[:, None] > 0)
+    return Xn @ Xn.T
+
+
+@pytest.mark.parametrize("V,d,theta,centres", [(300, 32, 0.25, 0), (400, 48, 0.6, 12), (257, 100, -0.05, 0)])
+def test_exact_rows_are_the_definition_on_the_embeddings(V, d, theta, centres):
+    """pcg_ref_asg_row_exact is Eq. (1) as printed: cosine of the float32 embeddings in double,
+    strict > theta, t in G(t).  Pinned against a numpy cosine matrix and Python sets."""
+    E = embeddings(V, d, 9) if centres == 0 else embeddings(V, d, 9, centres, 0.4)[0]
+    E[7] = 0.0                                                    # a zero row: cosine 0 with everything
+    S = numpy_cosines(E)
+    for a, b in [(0, 1), (5, 200), (200, 5), (7, 3), (3, 7), (V - 1, V - 2)]:
+        assert abs(oracle.asg_cosine(E, a, b) - S[a, b]) < 1e-14
+    assert oracle.asg_cosine(E, 5, 200) == oracle.asg_cosine(E, 200, 5)
+    assert abs(oracle.asg_cosine(E, 11, 11) - 1.0) < 1e-15
+    off = S[~np.eye(V, dtype=bool)]
+    assert (np.abs(off - theta) > 1e-12).all()                    # no decision hangs on summation order
+    for t in (0, 7, 100, V - 1):
+        row, cos = oracle.asg_row_exact(E, theta, t)
+        want = sorted(set(np.flatnonzero(S[t] > theta).tolist()) | {t})
+        np.testing.assert_array_equal(row, want)
+        np.testing.assert_allclose(np.delete(cos, t), np.delete(S[t], t), atol=1e-14)
+        assert cos[t] == 1.0
+    # strictness: a threshold exactly at a pair's cosine excludes that pair, just below includes it
+    c = oracle.asg_cosine(E, 0, 1)
+    assert 1 not in oracle.asg_row_exact(E, c, 0)[0]
+    assert 1 in oracle.asg_row_exact(E, np.nextafter(c, -1.0), 0)[0]
+    # positive scaling of an embedding changes nothing (cosine), a sign flip mirrors it
+    E2 = E.copy()
+    E2[1] *= 4.0
+    assert abs(oracle.asg_cosine(E2, 0, 1) - c) < 1e-15
+    E2[1] *= -1.0
+    assert abs(oracle.asg_cosine(E2, 0, 1) + c) < 1e-15
+
+
+# The similarity the kernels threshold is the dot product of unit vectors rounded to bfloat16
+# (8 significant bits: every component off by at most 2^-9 of itself).  With unit vectors x, y
+# and their roundings x(1+e), y(1+f), |e|, |f| <= 2^-9:
+#   |sum x_k y_k ((1+e_k)(1+f_k) - 1)| <= (2^-8 + 2^-18) sum |x_k y_k| <= 2^-8 + 2^-18
+# (Cauchy-Schwarz).  A membership can therefore differ from Eq. (1) only for a pair whose cosine
+# lies within BF16_BAND of theta; the tie band of the bf16 form (1e-5) adds nothing visible.
+BF16_BAND = 2.0 ** -8 + 2.0 ** -18
+
+
+@pytest.mark.parametrize("name,V,d,theta,centres,sigma", [
+    ("iid, C4-like (d = 1024, groups of tens)", 1536, 1024, 0.085, 0, 0),
+    ("iid, small d", 1200, 64, 0.3, 0, 0),
+    ("mixture, threshold inside the clusters' cosines (C5-like, 0.8)", 1500, 512, 0.8, 24, 0.5),
+    ("mixture, C3-like", 1024, 768, 0.5, 16, 0.3),
+    ("paper's range of theta (0.38 .. 0.45)", 1200, 32, 0.42, 0, 0),
+])
+def test_bf16_groups_differ_from_eq1_only_inside_the_rounding_band(name, V, d, theta, centres, sigma):
+    """How far the bf16 form of the construction (what pcg_asg_normalize + pcg_asg_build compute,
+    and what the oracle's asg_row mirrors) is from Eq. (1) on the unrounded embeddings: every
+    membership that differs belongs to a pair whose exact cosine is within BF16_BAND of theta,
+    and the count is reported."""
+    E = embeddings(V, d, 31) if centres == 0 else embeddings(V, d, 31, centres, sigma)[0]
+    unit = oracle.asg_normalize(E)
+    S = numpy_cosines(E)
+    exact = S > theta
+    np.fill_diagonal(exact, True)
+    U = bf16_to_f64(unit)
+    rounded = (U @ U.T) > np.float64(np.float32(theta))
+    np.fill_diagonal(rounded, True)
+    diff = exact != rounded
+    n_diff, n_mem = int(diff.sum()), int(exact.sum())
+    worst = float(np.abs(S[diff] - theta).max()) if n_diff else 0.0
+    worst_err = float(np.abs(U @ U.T - S)[~np.eye(V, dtype=bool)].max())
+    print(f"asg bf16 vs Eq. (1) [{name}]: {n_mem} memberships, {n_diff} differ "
+          f"({n_diff / max(1, n_mem):.2e}), farthest from theta {worst:.2e}, "
+          f"largest |bf16 similarity - cosine| {worst_err:.2e}, band {BF16_BAND:.2e}")
+    assert worst_err <= BF16_BAND
+    assert (np.abs(S[diff] - theta) <= BF16_BAND).all()
+    assert n_mem > V                                              # the threshold does form groups
+    # the oracle's two row routines say the same as the two dense matrices
+    for t in (0, V // 3, V - 1):
+        np.testing.assert_array_equal(oracle.asg_row_exact(E, theta, t)[0], np.flatnonzero(exact[t]))
+        np.testing.assert_array_equal(oracle.asg_row(unit, theta, t)[0], np.flatnonzero(rounded[t]))

@@ -30,7 +30,8 @@ __device__ __forceinline__ uint16_t round_to_bf16(double x) {
   if ((double) __uint_as_float(hi) < ax) { lo = hi; hi += 0x10000u; }
   const double dlo = ax - (double) __uint_as_float(lo), dhi = (double) __uint_as_float(hi) - ax;
   const uint32_t pick = dlo < dhi ? lo : (dhi < dlo ? hi : (((lo >> 16) & 1u) ? hi : lo));
-  return (uint16_t) ((pick >> 16) | (x < 0.0 ? 0x8000u : 0u));
+  // the sign travels as it is: a negative zero stays a negative zero, as in IEEE rounding
+  return (uint16_t) ((pick >> 16) | (__double_as_longlong(x) < 0 ? 0x8000u : 0u));
 }
 
 __global__ __launch_bounds__(256) void asg_normalize_kernel(const float *emb, int32_t V, int32_t d,

@@ -60,6 +60,7 @@ def test_unit_vectors_are_bit_exact(V, d):
     E[3] = 0.0
     E[4] *= 1e-20
     E[5] *= 1e15
+    E[6, 1], E[6, 2] = -0.0, 0.0                # signed zeros keep their sign
     unit = pcg.asg_normalize(torch.from_numpy(E).cuda())
     torch.cuda.synchronize()
     got = unit.view(torch.int16).cpu().numpy().view(np.uint16)

@@ -19,20 +19,35 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "pcg_oracle.c")
 _LIB = os.path.join(_HERE, "libpcg_oracle.so")
+_LIB_SAN = os.path.join(_HERE, "libpcg_oracle_san.so")
 
 F32, BF16 = 0, 1
 NEAR_TIE = 1e-6
 
 
+def _sanitize() -> bool:
+    return os.environ.get("PCG_SANITIZE", "") not in ("", "0")
+
+
 def build(force: bool = False) -> str:
-    """Compile the oracle with gcc (plain -O2, OpenMP only for the batch loop)."""
-    stale = (not os.path.exists(_LIB)
-             or os.path.getmtime(_LIB) < max(os.path.getmtime(_SRC),
-                                             os.path.getmtime(os.path.join(_HERE, "pcg_oracle.h"))))
+    """Compile the oracle with gcc (plain -O2, OpenMP only for the batch loop).  With
+    PCG_SANITIZE=1: with ROCm's clang, AddressSanitizer and UndefinedBehaviorSanitizer on, into a
+    library of its own (the same compiler and sanitizer runtime as the sanitized libpcg, so that
+    one preloaded runtime serves both)."""
+    lib = _LIB_SAN if _sanitize() else _LIB
+    stale = (not os.path.exists(lib)
+             or os.path.getmtime(lib) < max(os.path.getmtime(_SRC),
+                                            os.path.getmtime(os.path.join(_HERE, "pcg_oracle.h"))))
     if force or stale:
-        subprocess.check_call(["gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-fopenmp", "-fPIC",
-                               "-shared", _SRC, "-o", _LIB, "-lm"])
-    return _LIB
+        if _sanitize():
+            subprocess.check_call(["/opt/rocm/llvm/bin/clang", "-O1", "-g", "-std=c11", "-Wall", "-Wextra",
+                                   "-fopenmp", "-fPIC", "-shared", "-fsanitize=address,undefined",
+                                   "-fno-sanitize-recover=undefined", "-shared-libsan",
+                                   "-fno-omit-frame-pointer", _SRC, "-o", lib, "-lm"])
+        else:
+            subprocess.check_call(["gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-fopenmp", "-fPIC",
+                                   "-shared", _SRC, "-o", lib, "-lm"])
+    return lib
 
 
 class _Trace(C.Structure):

@@ -21,7 +21,9 @@ class PcgError(RuntimeError):
 
 
 def lib_path() -> str:
-    return os.path.join(_HERE, "libpcg.so")
+    """libpcg.so, or with PCG_SANITIZE=1 its host-sanitized build libpcg_san.so (CPU test runs)."""
+    name = "libpcg_san.so" if os.environ.get("PCG_SANITIZE", "") not in ("", "0") else "libpcg.so"
+    return os.path.join(_HERE, name)
 
 
 class PreparedInfo(C.Structure):

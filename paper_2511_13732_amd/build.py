@@ -21,6 +21,30 @@ HIPCC_FLAGS = [
 ]
 
 
+# Host-side sanitizer build (the device code is compiled as always): AddressSanitizer and
+# UndefinedBehaviorSanitizer on everything that runs on the CPU -- argument checks, workspace
+# carving, the membership helpers, the prepared-layout builder.  Loaded instead of libpcg.so when
+# PCG_SANITIZE=1 (see tests/conftest.py for the command line).
+LIB_SAN = os.path.join(_HERE, "libpcg_san.so")
+SANITIZE_FLAGS = ["-O1", "-g", "-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+                  "-Xarch_host", "-fno-omit-frame-pointer", "-shared-libsan"]
+
+
+def sanitize_requested() -> bool:
+    return os.environ.get("PCG_SANITIZE", "") not in ("", "0")
+
+
+def asan_runtime() -> str:
+    """Path of the sanitizer runtime that must be preloaded into a Python that loads the
+    sanitized libraries (the one of ROCm's clang, which compiles both of them)."""
+    clang = os.path.join(os.path.dirname(os.path.realpath(os.environ.get("HIPCC", "/opt/rocm/bin/hipcc"))),
+                         "..", "llvm", "bin", "clang")
+    if not os.path.exists(clang):
+        clang = "/opt/rocm/llvm/bin/clang"
+    out = subprocess.run([clang, "-print-file-name=libclang_rt.asan-x86_64.so"], capture_output=True, text=True)
+    return os.path.realpath(out.stdout.strip())
+
+
 def is_stale() -> bool:
     if not os.path.exists(LIB):
         return True
@@ -28,10 +52,12 @@ def is_stale() -> bool:
     return any(os.path.getmtime(os.path.join(CSRC, f)) > t for f in SOURCES + HEADERS)
 
 
-def build(verbose: bool = False) -> str:
+def build(verbose: bool = False, sanitize: bool = False) -> str:
     """Compile unconditionally; returns the path of the shared library."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, "-x", "hip", *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB]
+    flags = [f for f in HIPCC_FLAGS if f != "-O3"] + SANITIZE_FLAGS if sanitize else HIPCC_FLAGS
+    out = LIB_SAN if sanitize else LIB
+    cmd = [hipcc, *flags, "-x", "hip", *[os.path.join(CSRC, s) for s in SOURCES], "-o", out]
     if verbose:
         print(" ".join(cmd))
     proc = subprocess.run(cmd, capture_output=True, text=True)
@@ -41,7 +67,7 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + msgs)
     if verbose and msgs.strip():
         print(msgs)
-    return LIB
+    return out
 
 
 if __name__ == "__main__":

@@ -339,12 +339,22 @@ def test_recipe_full_size(name, steps):
                                      temperature=cfg.temperature, seed=0, offset=step, dg=dg, og=og)
         total.add(compare_verify(gpu, ref, og, ptok, pgrp))
         print(f"{name} step {step}: accept_len mean {ref.accept_len.mean():.2f} diag {diag}", flush=True)
-        if step == 0:        # group probabilities of a few rows of the same inputs
-            rows = tgt[:3, 0].contiguous()
+        if step == 0:
+            # Group probabilities (Eq. 5) of the same inputs: every sequence's decision rows -- the
+            # target row at its accept length and, where a proposal was rejected, the draft row
+            # next to it -- all G groups of each, against the oracle.
+            al = torch.from_numpy(ref.accept_len.astype(np.int64))
+            rows = [tgt[torch.arange(cfg.B), al]]
+            rej = al < cfg.K
+            if rej.any():
+                rows.append(dft[torch.arange(cfg.B)[rej], al[rej]])
+            rows = torch.cat(rows).contiguous()
             out = pcg.group_probs(dg, rows.cuda(), cfg.temperature)
-            err = group_probs_error(out, oracle.group_probs(og, as_oracle_logits(rows), cfg.temperature))
-            report_error(f"group_probs recipe {name}", err)
+            want = oracle.group_probs(og, as_oracle_logits(rows), cfg.temperature)
+            err = group_probs_error(out, want)
+            report_error(f"group_probs recipe {name} ({rows.shape[0]} decision rows x {og.G} groups)", err)
             assert err <= TOL_F32
+            np.testing.assert_allclose(out.double().sum(dim=1).cpu().numpy(), 1.0, atol=5e-6)
     total.report(f"recipe {name} full size")
     assert total.tolerated <= max(1, total.sequences // 100)
 

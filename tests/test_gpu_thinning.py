@@ -181,7 +181,7 @@ def test_gpu_thinning_law():
     assert chi2_p(counts, w / w.sum()) > 1e-3
 
 
-@pytest.mark.parametrize("name,steps", [("C1", 200), ("C2", 60), ("C4", 1)])
+@pytest.mark.parametrize("name,steps", [("C1", 200), ("C2", 60), ("C3", 1), ("C4", 1), ("C5", 1), ("C6", 1)])
 def test_thinning_recipes(name, steps):
     cfg = W.CONFIGS[name]
     rp, mem = W.groups(cfg)

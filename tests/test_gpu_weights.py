@@ -97,7 +97,7 @@ def test_equal_split_written_as_weights_gives_the_equal_split_laws():
         assert chi2_p(np.bincount(out.out_groups.cpu().numpy()[:, 0], minlength=og0.G), T[0]) > 1e-3
 
 
-@pytest.mark.parametrize("name,steps", [("C2", 40), ("C4", 1)])
+@pytest.mark.parametrize("name,steps", [("C2", 40), ("C4", 1), ("C5", 1), ("C6", 1)])
 def test_weighted_recipes(name, steps):
     cfg = W.CONFIGS[name]
     rp, mem = W.groups(cfg)

@@ -20,16 +20,31 @@
  *   - pointers marked DEVICE point to memory of the current HIP device, are
  *     owned by the caller and must stay valid until the stream has run the
  *     call; pointers marked HOST are ordinary host memory;
- *   - the library allocates no device memory: scratch comes in through
+ *   - the compute calls allocate no device memory: scratch comes in through
  *     `workspace` (DEVICE, 256-byte aligned, size from the *_workspace_bytes
- *     helpers) and may be reused by the next call on the same stream;
+ *     helpers; its contents need not be initialised and mean nothing after
+ *     the call) and may be reused by the next call on the same stream; calls
+ *     that may run at the same time need workspaces of their own
+ *     (pcg_verify_static, which uses an array of the library, is the one
+ *     exception: see there);
  *   - calls only enqueue work on `hip_stream` (a hipStream_t, NULL = default
- *     stream) and return without synchronising;
+ *     stream) and return without synchronising (pcg_asg_build and
+ *     pcg_profile_end wait: see there);
  *   - the return value is PCG_OK (0) or a negative pcg_status; nothing is
- *     thrown across the boundary; after PCG_ERR_HIP, pcg_last_hip_error()
- *     gives the hipError_t;
+ *     thrown across the boundary;
  *   - arguments are checked on the host before anything is launched, so a
- *     call that returns an error has enqueued nothing.
+ *     call that returns an argument error (every status but the two below)
+ *     has enqueued nothing.  Two statuses can come after some kernels of the
+ *     call were enqueued already: PCG_ERR_HIP (a launch failed midway; the
+ *     outputs are then undefined) and PCG_ERR_CAPACITY of pcg_asg_build
+ *     (reported after its kernels ran);
+ *   - state the library keeps between calls, all of it on the host except
+ *     the array of pcg_verify_static: the last hipError_t per thread
+ *     (pcg_last_hip_error), and, between pcg_profile_begin and
+ *     pcg_profile_end only, the HIP events of the recorded calls (created and
+ *     destroyed by those two functions, not thread-safe, and never recorded
+ *     into a stream that is being captured).  Nothing else: no caches, no
+ *     device allocations, no streams of its own.
  */
 #ifndef PCG_H
 #define PCG_H
@@ -82,7 +97,10 @@ typedef struct {
   const int32_t *members;
   const int32_t *mult;
   /* Optional fast form of the same membership (see pcg_groups_prepare_host): the blob
-   * uploaded to the DEVICE and its HOST descriptor.  Both NULL = use the CSR directly. */
+   * uploaded to the DEVICE and its HOST descriptor.  Both NULL = use the CSR directly, which
+   * gives the same results but re-reads the 4-byte member ids from L2 for every row: at
+   * V = G = 65 536 with 32-member groups and 64 sequences a step takes about 0.5 ms from the
+   * CSR against about 0.07 ms from the prepared form. */
   const void *prepared;
   const pcg_prepared *prepared_info;
   /* Optional reverse index token -> groups (the paper's S(t); see pcg_groups_reverse_host),

@@ -314,13 +314,26 @@ class Groups:
 # --------------------------------------------------------------------------- calls
 
 _workspaces: dict = {}
+_retired: list = []
 
 
 def _workspace(device: torch.device, nbytes: int) -> torch.Tensor:
-    ws = _workspaces.get(device)
+    """The default scratch tensor of the calling stream (used when no ``workspace=`` is given).
+    One per (device, stream), so calls on different streams never share scratch; a buffer that
+    has been handed to a call is kept until the process ends, never freed (work that still
+    refers to it may be queued or recorded).  While the stream is being captured into a graph the
+    caller must bring the workspace (or use ``static_scratch``): a tensor allocated here would
+    be tied to the capture."""
+    stream = torch.cuda.current_stream(device)
+    if torch.cuda.is_current_stream_capturing():
+        raise RuntimeError("pass workspace= (or static_scratch=True) when calling under stream capture")
+    key = (device, stream.cuda_stream)
+    ws = _workspaces.get(key)
     if ws is None or ws.numel() < nbytes:
+        if ws is not None:
+            _retired.append(ws)
         ws = torch.empty(max(nbytes, 1 << 20), dtype=torch.uint8, device=device)
-        _workspaces[device] = ws
+        _workspaces[key] = ws
     return ws
 
 

@@ -1,15 +1,22 @@
 // HIP kernels of libpcg for gfx950 (MI355X) and their launchers.
 //
-// One speculative step (Algorithm 1) runs as five kernels on the caller's stream:
-//   row_stats  streams every logits row once: per-wave (max, sum of exponentials)   [HBM-bound]
-//   accept     per sequence: merges the row statistics, evaluates Eq. (5) on each proposed
-//              group, runs the accept test of Eq. (7) until the first rejection
-//   delta      per sequence, on its decision row: delta[t] = (q(t) - p(t)) / N(t)
-//              (q(t) / N(t) on the bonus row), so that T[g] - D[g] = sum of delta over G_g
-//   gather     the overlap-aware segmented gather-sum over the CSR membership with the
-//              delta row staged in LDS; writes R[g] = max(0, T[g] - D[g])            (Eq. 8)
-//   finalize   per sequence: inverse CDF over R for the group, then Eq. (10) for the token
-// pcg_group_probs runs row_stats, a weights kernel (q(t) / N(t)) and the same gather.
+// One speculative step (Algorithm 1) runs as four kernels on the caller's stream:
+//   row_stats     streams every logits row once: per-wave (max, sum of exponentials)  [HBM-bound];
+//                 its leading workgroups also form, for every proposed group, the sums of Eq. (5)
+//                 relative to the group's own largest logit (the "probes")
+//   accept_delta  per sequence: merges the row statistics, normalises the probes, runs the
+//                 accept test of Eq. (7) until the first rejection; then, on the decision row,
+//                 the table delta[t] = (q(t) - p(t)) / N(t) (q(t) / N(t) on the bonus row), so
+//                 that T[g] - D[g] = sum of delta over G_g
+//   gather        the overlap-aware segmented gather-sum of that table over the membership
+//                 (Eq. 5, Eq. 8), table tiles staged in LDS.  From the prepared layout, inside
+//                 pcg_verify, no sum leaves the kernel: only fp64 totals of max(0, .) per run of
+//                 16 consecutive groups and per chunk.  From the CSR (and in pcg_group_probs,
+//                 which wants them) every sum is written.
+//   finalize      per sequence: the chunk and the run that hold u * total, the run's 16 sums
+//                 formed again, the group by inverse CDF, then the token inside it (Eq. 10)
+// pcg_group_probs runs row_stats, a weights kernel (q(t) / N(t)) and the same gather;
+// pcg_verify_thinning runs row_stats and accept_thin; pcg_propose runs row_stats and propose.
 #include "pcg_kernels.h"
 #include "pcg_layout.h"
 
@@ -1089,15 +1096,16 @@ __device__ __forceinline__ bool near_edge(const CdfPick &p, double u) {
   return near_lo || near_hi;
 }
 
-// The last step of a sequence, by one whole workgroup of NT threads.  R holds the gathered sums
-// T[g] - D[g] (T[g] on a bonus row), clamped here on read.  With csum != NULL it also has the
-// totals of max(0, R) over chunks of chunk_groups consecutive groups, so only the chunk that
-// holds the draw is scanned, from `stage` (LDS, room for one chunk plus one pad word per 32);
-// staged_chunk >= 0 says that chunk's R values are in `stage` already, in the padded layout.
+// The last step of a sequence, by one whole workgroup of NT threads.  After the CSR gather
+// (csum == NULL) R holds the gathered sums T[g] - D[g] (T[g] on a bonus row), clamped here on
+// read, and all of it is scanned.  After the prepared gather (csum, runs != NULL) there are no
+// sums, only the totals of max(0, .) over chunks of chunk_groups consecutive groups and over runs
+// of kRunGroups: the chunk and the run that hold the draw are located from them, and the run's
+// sums are formed again here.
 template <bool BF16, int NT>
 __device__ void finalize_sequence(const FinalizeArgs &fa, int32_t V, int32_t G, int b,
                                   const double *csum, const double *runs, int32_t nchunks,
-                                  int32_t chunk_groups, float *stage, int32_t staged_chunk) {
+                                  int32_t chunk_groups) {
   const int32_t K = fa.K;
   const int32_t istar = fa.accept_len[b];
   const int64_t trow_id = (int64_t) b * (K + 1) + istar;
@@ -1136,7 +1144,7 @@ __device__ void finalize_sequence(const FinalizeArgs &fa, int32_t V, int32_t G, 
     pg.index = -1; pg.total = S; pg.lo = pg.hi = 0.0;
     if (S > 0.0 && cstar >= 0) {
       const int32_t g0 = cstar * chunk_groups, ng = min(chunk_groups, G - g0);
-      if (runs) {
+      {
         // The gather left no sums, only the totals of runs of kRunGroups groups: find the run
         // that holds the crossing, form its groups' sums again -- 32 lanes per group, the table
         // kernel's arithmetic for every entry (Eq. 8 on the decision row) -- and walk them.
@@ -1237,38 +1245,6 @@ __device__ void finalize_sequence(const FinalizeArgs &fa, int32_t V, int32_t G, 
             return;                                     // the whole workgroup, together
           }
         }
-      } else {
-      // Stage the chunk in LDS with coalesced loads; the scan then reads contiguous runs.  One
-      // pad word per 32 keeps the runs of neighbouring threads in different banks.
-      if (cstar != staged_chunk) {
-        __syncthreads();
-        const float *Rc = Rb + g0;
-        if ((((uintptr_t) Rc | (uintptr_t) ng) & 15) == 0 && ng <= 8 * 4 * NT) {
-          float4 v[8];                            // up to eight 16-byte loads in flight
-#pragma unroll
-          for (int i = 0; i < 8; ++i) {
-            const int32_t k4 = threadIdx.x + i * NT;
-            if (4 * k4 < ng) v[i] = reinterpret_cast<const float4 *>(Rc)[k4];
-          }
-#pragma unroll
-          for (int i = 0; i < 8; ++i) {
-            const int32_t k = 4 * (threadIdx.x + i * NT);
-            if (k < ng) {
-              float *d = stage + k + (k >> 5);    // k is a multiple of 4: all four share k >> 5
-              d[0] = v[i].x; d[1] = v[i].y; d[2] = v[i].z; d[3] = v[i].w;
-            }
-          }
-        } else {
-          for (int32_t k = threadIdx.x; k < ng; k += NT) stage[k + (k >> 5)] = Rc[k];
-        }
-        __syncthreads();
-      }
-      CdfPick in = block_inverse_cdf<NT>(
-          ng, [&](int32_t k) { return (double) fmaxf(stage[k + (k >> 5)], 0.f); }, 0.0, true,
-          goal - base);
-      if (in.index >= 0) {
-        pg.index = g0 + in.index; pg.lo = base + in.lo; pg.hi = base + in.hi;
-      }
       }
     }
   } else {
@@ -1360,8 +1336,7 @@ __global__ __launch_bounds__(kFinalThreads) void finalize_kernel(FinalizeArgs fa
                                                                  const double *runs,
                                                                  int32_t nchunks,
                                                                  int32_t chunk_groups) {
-  __shared__ float stage[kMaxChunkGroups + kMaxChunkGroups / 32];
-  finalize_sequence<BF16, kFinalThreads>(fa, V, G, blockIdx.x, csum, runs, nchunks, chunk_groups, stage, -1);
+  finalize_sequence<BF16, kFinalThreads>(fa, V, G, blockIdx.x, csum, runs, nchunks, chunk_groups);
 }
 
 // ---------------------------------------------------------------------------------------------

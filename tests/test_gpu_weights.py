@@ -13,7 +13,6 @@ from parity import (Tally, as_oracle_logits, compare_thinning, compare_verify, g
 from test_gpu_parity import TOL_F32, coupled_proposals, logits_pair
 from test_gpu_propose import compare_proposals
 from test_gpu_thinning import chi2_p
-from test_oracle_weights import random_weights
 
 pytestmark = pytest.mark.gpu
 
@@ -22,7 +21,7 @@ def weighted_groups(V, rp, mem, seed, prepare=True):
     """The same membership and the same random weights on both sides; on the device with the
     weights inside the prepared layout, or (prepare=False) read from the CSR."""
     og0 = oracle_groups(V, rp, mem)
-    w = random_weights(og0, seed)
+    w = W.random_weights(og0.V, og0.members, seed)
     og = oracle.with_weights(og0, w)
     dg = pcg.Groups.from_csr(V, rp, mem, "cuda", weights=w, reverse=True, prepare=prepare)
     assert (dg.prepared is not None) == prepare and dg.nnz == og.nnz

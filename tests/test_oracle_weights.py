@@ -35,11 +35,6 @@ def dyadic_weights(g, seed, denom=64, zero_rate=0.15):
     return w
 
 
-def random_weights(g, seed):
-    """Arbitrary positive weights normalised per token in fp32 (sums are 1 to rounding)."""
-    return W.random_weights(g.V, g.members, seed)
-
-
 def ew(g, j):
     return Fraction(float(g.weights[j]))
 
@@ -56,7 +51,7 @@ def weighted_case(V, G, seed, K=1):
 
 def test_weight_validation_and_reverse_order():
     g, _, _ = small_case(V=30, G=20, seed=3)
-    w = random_weights(g, 1)
+    w = W.random_weights(g.V, g.members, 1)
     assert oracle.validate_weights(g, w) == 0
     bad = w.copy(); bad[0] = -bad[0]
     assert oracle.validate_weights(g, bad) != 0
@@ -81,7 +76,7 @@ def test_group_probs_with_weights_is_the_sparse_matvec_of_eq_4(dtype):
     V, G = 700, 500
     rp, mem = W.random_groups(V, G, 1, 12, seed=2, cover=False)
     g = oracle.canonicalize(V, rp, mem)
-    w = random_weights(g, 5)
+    w = W.random_weights(g.V, g.members, 5)
     gw = oracle.with_weights(g, w)
     rng = np.random.default_rng(6)
     x = f32(3 * rng.standard_normal((4, V)))
@@ -213,7 +208,7 @@ def test_weighted_samplers_at_scale_chi_square():
     V, G, K, B, tau = 48, 36, 1, 300_000, 0.8
     rp, mem = W.random_groups(V, G, 2, 6, seed=71, cover=False)
     g0 = oracle.canonicalize(V, rp, mem)
-    g = oracle.with_weights(g0, random_weights(g0, 9))
+    g = oracle.with_weights(g0, W.random_weights(g0.V, g0.members, 9))
     rev = oracle.reverse_index(g)
     rng = np.random.default_rng(5)
     tgt = f32(2 * rng.standard_normal((1, K + 1, V)))

@@ -195,7 +195,12 @@ def proposals(draft: torch.Tensor, temperature: float, row_ptr: np.ndarray, memb
     """Draft proposals under the coupling of Eq. (6): a token drawn from the
     draft's distribution at each position (by the Gumbel-max trick, so no
     probabilities are formed here), then one of the groups holding it, uniformly.
-    Returns int32 (prop_tokens [B, K], prop_groups [B, K])."""
+    Returns int32 (prop_tokens [B, K], prop_groups [B, K]).
+
+    This is an INPUT GENERATOR, a second sampler unrelated to both implementations of
+    pcg_propose: it only makes plausible proposals for the verification tests and the
+    benchmark.  It is never the checker of anything -- pcg_propose is compared with
+    oracle.propose, draw for draw, and neither of them calls or shares code with this."""
     x = draft.to(torch.float32).numpy().astype(np.float64) / temperature
     B, K, V = x.shape
     gumbel = -np.log(-np.log(rng.random((B, K, V))))

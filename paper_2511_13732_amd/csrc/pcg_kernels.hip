@@ -307,14 +307,29 @@ struct AcceptShared {
 __device__ __forceinline__ RowStat merge_row16(const StatPart *parts, int64_t row, int32_t nparts,
                                                float c, int sub) {
   const StatPart *rp = parts + row * nparts;
+  // a lane's first two parts stay in registers (rows of up to 65 536 logits: all of them), so
+  // that the maximum and the sum need one trip to memory, not two
+  constexpr int kKeep = 2;
+  StatPart keep[kKeep];
   float M = -INFINITY;
-  for (int32_t k = sub; k < nparts; k += 16) M = fmaxf(M, rp[k].m);
+#pragma unroll
+  for (int j = 0; j < kKeep; ++j) {
+    const int32_t k = sub + 16 * j;
+    keep[j].z = 0.0; keep[j].m = -INFINITY; keep[j].t = 0.f;
+    if (k < nparts) keep[j] = rp[k];
+  }
+#pragma unroll
+  for (int j = 0; j < kKeep; ++j) M = fmaxf(M, keep[j].m);
+  for (int32_t k = sub + 16 * kKeep; k < nparts; k += 16) M = fmaxf(M, rp[k].m);
   M = fmaxf(M, dpp_get<kDppXor1, 0xf>(M, M));
   M = fmaxf(M, dpp_get<kDppXor2, 0xf>(M, M));
   M = fmaxf(M, dpp_get<kDppHalfMirror, 0xf>(M, M));
   M = fmaxf(M, dpp_get<kDppMirror, 0xf>(M, M));
   double Z = 0.0;
-  for (int32_t k = sub; k < nparts; k += 16) {
+#pragma unroll
+  for (int j = 0; j < kKeep; ++j)
+    if (keep[j].z > 0.0) Z += keep[j].z * exp2((double) keep[j].t - (double) M * (double) c);
+  for (int32_t k = sub + 16 * kKeep; k < nparts; k += 16) {
     const StatPart sp = rp[k];
     if (sp.z > 0.0) Z += sp.z * exp2((double) sp.t - (double) M * (double) c);
   }

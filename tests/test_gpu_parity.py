@@ -319,6 +319,8 @@ def test_recipe_small(name, steps):
                                 seed=0, offset=step, dg=dg, og=og, nthreads=8)
         total.add(compare_verify(gpu, ref, og, ptok, pgrp))
         hist += np.bincount(ref.accept_len, minlength=cfg.K + 1)
+        if step % 500 == 499:
+            print(f"{name}: {step + 1} steps, {total.tolerated} tolerated so far", flush=True)
     total.report(f"recipe {name}")
     print("accept_len histogram", hist.tolist(), flush=True)
     assert total.tolerated <= max(1, total.sequences // 500)

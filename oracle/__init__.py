@@ -488,10 +488,7 @@ class AsgResult:
     near_rows: np.ndarray    # uint8 [V] rows with a pair within 1e-5 of the threshold
 
 
-def asg_build(unit, theta: float, nthreads: int = 1) -> AsgResult:
-    """Distinct similarity groups of all tokens (Eq. 1) as canonical Groups."""
-    u = np.ascontiguousarray(unit, dtype=np.uint16)
-    V, d = u.shape
+def _asg_build(call, V: int) -> AsgResult:
     cap = 64 * V
     while True:
         rp = np.empty(V + 1, np.int32)
@@ -500,12 +497,36 @@ def asg_build(unit, theta: float, nthreads: int = 1) -> AsgResult:
         seed = np.empty(V, np.int32)
         near = np.zeros(V, np.uint8)
         G, nnz = C.c_int32(), C.c_int64()
-        rc = lib().pcg_ref_asg_build(_p(u), C.c_int32(V), C.c_int32(d), C.c_float(theta), C.byref(G),
-                                     C.byref(nnz), _p(rp), _p(mem), C.c_int64(cap), _p(mult), _p(seed),
-                                     _p(near), C.c_int32(nthreads))
+        rc = call(G, nnz, rp, mem, cap, mult, seed, near)
         if rc == -4 and nnz.value > cap:
             cap = nnz.value
             continue
         _check(rc, "asg_build")
         return AsgResult(Groups(V, G.value, rp[:G.value + 1].copy(), mem[:nnz.value].copy(), mult),
                          seed[:G.value].copy(), near)
+
+
+def asg_build(unit, theta: float, nthreads: int = 1) -> AsgResult:
+    """Distinct similarity groups of all tokens from the bf16 unit vectors, as canonical Groups."""
+    u = np.ascontiguousarray(unit, dtype=np.uint16)
+    V, d = u.shape
+
+    def call(G, nnz, rp, mem, cap, mult, seed, near):
+        return lib().pcg_ref_asg_build(_p(u), C.c_int32(V), C.c_int32(d), C.c_float(theta), C.byref(G),
+                                       C.byref(nnz), _p(rp), _p(mem), C.c_int64(cap), _p(mult), _p(seed),
+                                       _p(near), C.c_int32(nthreads))
+    return _asg_build(call, V)
+
+
+def asg_build_exact(emb, theta: float, nthreads: int = 1) -> AsgResult:
+    """Distinct similarity groups of all tokens by Eq. (1) on the float32 embeddings themselves
+    (double throughout, strict ``> theta``); near_rows marks rows with a cosine within 1e-12 of
+    theta."""
+    e = np.ascontiguousarray(emb, dtype=np.float32)
+    V, d = e.shape
+
+    def call(G, nnz, rp, mem, cap, mult, seed, near):
+        return lib().pcg_ref_asg_build_exact(_p(e), C.c_int32(V), C.c_int32(d), C.c_double(theta),
+                                             C.byref(G), C.byref(nnz), _p(rp), _p(mem), C.c_int64(cap),
+                                             _p(mult), _p(seed), _p(near), C.c_int32(nthreads))
+    return _asg_build(call, V)

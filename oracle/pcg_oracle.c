@@ -996,12 +996,17 @@ int pcg_ref_asg_row_exact(const float *emb, int32_t V, int32_t d, double theta, 
   return PCG_REF_OK;
 }
 
-int pcg_ref_asg_build(const uint16_t *unit_bf16, int32_t V, int32_t d, float theta,
-                      int32_t *out_G, int64_t *out_nnz, int32_t *row_ptr, int32_t *members,
-                      int64_t members_capacity, int32_t *mult, int32_t *seed_of,
-                      uint8_t *near_rows, int32_t nthreads) {
-  if (!unit_bf16 || !out_G || !out_nnz || !row_ptr || !members || !mult || V < 1 || d < 1 ||
-      members_capacity < 0)
+/* Width of the band around theta inside which a pair's exact cosine counts as a near-tie. */
+#define PCG_REF_ASG_NEAR_EXACT 1e-12
+
+/* The distinct sets in order of first appearance, from either kind of row: unit_bf16 != NULL
+ * thresholds the similarity of the rounded unit vectors, emb != NULL the cosine of Eq. (1). */
+static int asg_build_rows(const uint16_t *unit_bf16, const float *emb, int32_t V, int32_t d,
+                          double theta, int32_t *out_G, int64_t *out_nnz, int32_t *row_ptr,
+                          int32_t *members, int64_t members_capacity, int32_t *mult,
+                          int32_t *seed_of, uint8_t *near_rows, int32_t nthreads) {
+  if ((!unit_bf16 && !emb) || !out_G || !out_nnz || !row_ptr || !members || !mult || V < 1 ||
+      d < 1 || members_capacity < 0)
     return PCG_REF_ERR_ARG;
   if (nthreads < 1) nthreads = 1;
   /* every token's set, then the distinct ones in order of first appearance */
@@ -1015,8 +1020,17 @@ int pcg_ref_asg_build(const uint16_t *unit_bf16, int32_t V, int32_t d, float the
 #endif
     for (int32_t t = 0; t < V; ++t) {
       int32_t *buf = (int32_t *)malloc((size_t)V * sizeof(int32_t));
+      double *cosv = emb ? (double *)malloc((size_t)V * sizeof(double)) : NULL;
       int32_t n = 0, near = 0;
-      if (!buf || pcg_ref_asg_row(unit_bf16, V, d, theta, t, buf, &n, &near)) {
+      int bad = !buf || (emb && !cosv);
+      if (!bad && unit_bf16) bad = pcg_ref_asg_row(unit_bf16, V, d, (float)theta, t, buf, &n, &near);
+      if (!bad && emb) {
+        bad = pcg_ref_asg_row_exact(emb, V, d, theta, t, buf, &n, cosv);
+        for (int32_t v = 0; !bad && v < V; ++v)
+          if (v != t && fabs(cosv[v] - theta) < PCG_REF_ASG_NEAR_EXACT) ++near;
+      }
+      free(cosv);
+      if (bad) {
 #ifdef _OPENMP
 #pragma omp critical
 #endif
@@ -1061,4 +1075,22 @@ int pcg_ref_asg_build(const uint16_t *unit_bf16, int32_t V, int32_t d, float the
   if (set) for (int32_t t = 0; t < V; ++t) free(set[t]);
   free(set); free(size); free(kept);
   return status;
+}
+
+int pcg_ref_asg_build(const uint16_t *unit_bf16, int32_t V, int32_t d, float theta,
+                      int32_t *out_G, int64_t *out_nnz, int32_t *row_ptr, int32_t *members,
+                      int64_t members_capacity, int32_t *mult, int32_t *seed_of,
+                      uint8_t *near_rows, int32_t nthreads) {
+  if (!unit_bf16) return PCG_REF_ERR_ARG;
+  return asg_build_rows(unit_bf16, NULL, V, d, (double)theta, out_G, out_nnz, row_ptr, members,
+                        members_capacity, mult, seed_of, near_rows, nthreads);
+}
+
+int pcg_ref_asg_build_exact(const float *emb, int32_t V, int32_t d, double theta,
+                            int32_t *out_G, int64_t *out_nnz, int32_t *row_ptr,
+                            int32_t *members, int64_t members_capacity, int32_t *mult,
+                            int32_t *seed_of, uint8_t *near_rows, int32_t nthreads) {
+  if (!emb) return PCG_REF_ERR_ARG;
+  return asg_build_rows(NULL, emb, V, d, theta, out_G, out_nnz, row_ptr, members,
+                        members_capacity, mult, seed_of, near_rows, nthreads);
 }

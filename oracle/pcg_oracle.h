@@ -333,6 +333,16 @@ double pcg_ref_asg_cosine(const float *emb, int32_t d, int32_t a, int32_t b);
 int pcg_ref_asg_row_exact(const float *emb, int32_t V, int32_t d, double theta, int32_t t,
                           int32_t *members_out, int32_t *count, double *cos_out);
 
+/* All groups by Eq. (1) on the embeddings themselves: G(t) from pcg_ref_asg_row_exact for
+ * t = 0 .. V-1, the distinct sets once, in order of first appearance; outputs and the
+ * members_capacity rule as for pcg_ref_asg_build.  near_rows [V] (may be NULL): 1 where some
+ * cosine of row t lies within 1e-12 of theta (a decision that the order of summation could
+ * turn). */
+int pcg_ref_asg_build_exact(const float *emb, int32_t V, int32_t d, double theta,
+                            int32_t *out_G, int64_t *out_nnz, int32_t *row_ptr,
+                            int32_t *members, int64_t members_capacity, int32_t *mult,
+                            int32_t *seed_of, uint8_t *near_rows, int32_t nthreads);
+
 /* Proposals with general weights: the group label by the inverse CDF of the token's weights
  * at u = k24 / 2^24; near also covers that draw. */
 int pcg_ref_propose_u_w(int32_t V, int32_t G, const int32_t *mult, const pcg_ref_weights *wt,

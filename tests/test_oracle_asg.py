@@ -184,6 +184,36 @@ def test_exact_rows_are_the_definition_on_the_embeddings(V, d, theta, centres):
     assert abs(oracle.asg_cosine(E2, 0, 1) + c) < 1e-15
 
 
+@pytest.mark.parametrize("V,d,theta,centres", [(300, 32, 0.25, 0), (400, 48, 0.6, 12), (200, 16, 0.9, 5)])
+def test_exact_groups_are_the_distinct_sets_of_eq1_in_order_of_first_appearance(V, d, theta, centres):
+    """pcg_ref_asg_build_exact: every token's set from a numpy cosine matrix, de-duplicated with
+    Python sets in order of first appearance; members ascending, mult the entry counts.  Exact
+    duplicates of an embedding (cosine 1 with each other, equal cosines with everyone else) must
+    fall into one group."""
+    E = embeddings(V, d, 21) if centres == 0 else embeddings(V, d, 21, centres, 0.05)[0]
+    E[40] = E[3]                                                  # the same embedding twice
+    E[41] = 2.5 * E[3]                                            # and scaled: same direction
+    S = numpy_cosines(E)
+    np.fill_diagonal(S, 2.0)
+    assert (np.abs(S - theta) > 1e-9)[S < 0.999999].all()
+    sets = [np.flatnonzero((S[t] > theta) | (S[t] > 0.9999999)).astype(np.int32) for t in range(V)]
+    kept, seeds = distinct_in_order(sets)
+    for nthreads in (1, 3):
+        res = oracle.asg_build_exact(E, theta, nthreads=nthreads)
+        g = res.groups
+        assert g.G == len(kept) and g.V == V
+        np.testing.assert_array_equal(res.seed_of, seeds)
+        for k, want in enumerate(kept):
+            np.testing.assert_array_equal(g.members[g.row_ptr[k]:g.row_ptr[k + 1]], want)
+        np.testing.assert_array_equal(g.mult, np.bincount(np.concatenate(kept), minlength=V))
+        assert not res.near_rows.any()
+    assert 40 not in seeds and 41 not in seeds                   # merged with token 3's group
+    # a threshold placed exactly on a pair's cosine marks both of its rows as near ties
+    c = oracle.asg_cosine(E, 0, 1)
+    near = oracle.asg_build_exact(E, c, nthreads=2).near_rows
+    assert near[0] and near[1]
+
+
 # The similarity the kernels threshold is the dot product of unit vectors rounded to bfloat16
 # (8 significant bits: every component off by at most 2^-9 of itself).  With unit vectors x, y
 # and their roundings x(1+e), y(1+f), |e|, |f| <= 2^-9:

@@ -337,7 +337,17 @@ def main():
                          "unit": "TFLOP/s", "frac": round(flops / asg_s / 2.5e15, 4), "dtype": "bf16",
                          "note": "whole call (similarity, sort, de-duplication, compaction); "
                                  "algorithmic flops d V (V + 1)"}}
-        del emb, unit, asg
+        # the same groups by Eq. (1) in double wherever the rounded similarity cannot decide
+        # (includes forming the unit vectors); cap must hold a group's candidates
+        exact = pcg.asg_build_exact(emb, theta, cap=256)
+        torch.cuda.synchronize()
+        t_begin = time.perf_counter()
+        for _ in range(reps):
+            exact = pcg.asg_build_exact(emb, theta, cap=256, members_capacity=exact.nnz)
+        exact_s = (time.perf_counter() - t_begin) / reps
+        result["asg_build"]["exact"] = {"ms": round(1e3 * exact_s, 3), "groups": exact.G,
+                                        "entries": exact.nnz, "largest": exact.max_size}
+        del emb, unit, asg, exact
 
     for i in range(args.warmup):
         step(i)

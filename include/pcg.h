@@ -364,6 +364,29 @@ int pcg_asg_build(const uint16_t *unit_bf16, int32_t V, int32_t d, float theta, 
 
 size_t pcg_asg_build_workspace_bytes(int32_t V, int32_t cap);
 
+/*
+ * The same groups by Eq. (1) exactly as written: G(t) = every v with cos(emb[t], emb[v]) > theta,
+ * the cosine of the float32 embeddings themselves in double (dot product and both norms, one
+ * division), and t itself.  The bf16 contraction of pcg_asg_build serves as a filter: a pair
+ * whose rounded similarity lies within 2^-8 + 2^-18 + d 2^-23 of theta (how far rounding the
+ * unit vectors to bfloat16 and summing in fp32 can move it) is decided by the double-precision
+ * cosine, every other pair by the rounded one.  Outputs, order of the groups, waiting for the
+ * stream and PCG_ERR_CAPACITY as for pcg_asg_build, except that cap must hold every candidate
+ * of a group (the pairs above theta minus that band) while it is collected; *out_max_size is
+ * the largest G(t) after the decision when everything fitted.
+ *   emb           DEVICE float [V, d], 16-byte aligned, d a multiple of 64, V * d < 2^31
+ *   workspace     DEVICE, 256-byte aligned, >= pcg_asg_build_exact_workspace_bytes(V, d, cap)
+ *                 (it also holds the unit vectors, 2 V d bytes)
+ * A zero row has cosine 0 with every other row.
+ */
+int pcg_asg_build_exact(const float *emb, int32_t V, int32_t d, float theta, int32_t cap,
+                        int32_t *row_ptr, int32_t *members, int64_t members_capacity,
+                        int32_t *mult, int32_t *seed_of, int32_t *out_G, int64_t *out_nnz,
+                        int32_t *out_max_size, void *workspace, size_t workspace_bytes,
+                        void *hip_stream);
+
+size_t pcg_asg_build_exact_workspace_bytes(int32_t V, int32_t d, int32_t cap);
+
 /* ---- group membership on the host -------------------------------------------------------- */
 
 /* PCG_OK iff (row_ptr, members, mult), all HOST, form a membership the kernels may use (see

@@ -109,6 +109,10 @@ def lib() -> C.CDLL:
                                     C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
                                     C.POINTER(C.c_int32), C.POINTER(C.c_int64), C.POINTER(C.c_int32),
                                     C.c_void_p, C.c_size_t, C.c_void_p]
+        L.pcg_asg_build_exact_workspace_bytes.restype = C.c_size_t
+        L.pcg_asg_build_exact_workspace_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32]
+        L.pcg_asg_build_exact.restype = C.c_int
+        L.pcg_asg_build_exact.argtypes = L.pcg_asg_build.argtypes
         L.pcg_groups_validate_weights_host.restype = C.c_int
         L.pcg_groups_validate_weights_host.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                                        C.c_void_p, C.c_double]
@@ -570,14 +574,7 @@ class AsgGroups:
     max_size: int            # largest G(t) before identical sets were dropped
 
 
-def asg_build(unit: torch.Tensor, theta: float, cap: int = 256,
-              members_capacity: Optional[int] = None) -> AsgGroups:
-    """The distinct similarity groups of Eq. (1) from bfloat16 unit vectors [V, d], as device
-    CSR arrays.  Room for a group (cap) and for all members is enlarged and the call repeated
-    when the library reports that it did not suffice."""
-    assert unit.dim() == 2 and unit.dtype == torch.bfloat16 and unit.is_contiguous()
-    V, d = unit.shape
-    dev = unit.device
+def _asg_build(name, call, ws_bytes, V: int, dev, cap: int, members_capacity: Optional[int]) -> AsgGroups:
     cap = min(cap, 4096)
     room = members_capacity or 32 * V
     G, nnz, largest = C.c_int32(), C.c_int64(), C.c_int32()
@@ -586,21 +583,48 @@ def asg_build(unit: torch.Tensor, theta: float, cap: int = 256,
         members = torch.empty(room, dtype=torch.int32, device=dev)
         mult = torch.empty(V, dtype=torch.int32, device=dev)
         seed_of = torch.empty(V, dtype=torch.int32, device=dev)
-        ws = torch.empty(lib().pcg_asg_build_workspace_bytes(V, cap), dtype=torch.uint8, device=dev)
+        ws = torch.empty(ws_bytes(cap), dtype=torch.uint8, device=dev)
         with torch.cuda.device(dev):
-            rc = lib().pcg_asg_build(unit.data_ptr(), V, d, float(theta), cap, row_ptr.data_ptr(),
-                                     members.data_ptr(), room, mult.data_ptr(), seed_of.data_ptr(),
-                                     C.byref(G), C.byref(nnz), C.byref(largest), ws.data_ptr(),
-                                     ws.numel(), _stream(dev))
+            rc = call(cap, row_ptr.data_ptr(), members.data_ptr(), room, mult.data_ptr(),
+                      seed_of.data_ptr(), C.byref(G), C.byref(nnz), C.byref(largest), ws.data_ptr(),
+                      ws.numel(), _stream(dev))
         if rc == ERR_CAPACITY and (largest.value > cap or nnz.value > room):
             if largest.value > 4096:
-                raise PcgError(rc, "pcg_asg_build: a similarity group has more than 4096 members")
+                raise PcgError(rc, f"{name}: a similarity group has more than 4096 members")
             cap = max(cap, min(4096, largest.value))
             room = max(room, nnz.value)
             continue
-        _check(rc, "pcg_asg_build")
+        _check(rc, name)
         return AsgGroups(row_ptr[:G.value + 1], members[:nnz.value], mult, seed_of[:G.value],
                          G.value, nnz.value, largest.value)
+
+
+def asg_build(unit: torch.Tensor, theta: float, cap: int = 256,
+              members_capacity: Optional[int] = None) -> AsgGroups:
+    """The distinct similarity groups of Eq. (1) from bfloat16 unit vectors [V, d], as device
+    CSR arrays.  Room for a group (cap) and for all members is enlarged and the call repeated
+    when the library reports that it did not suffice."""
+    assert unit.dim() == 2 and unit.dtype == torch.bfloat16 and unit.is_contiguous()
+    V, d = unit.shape
+    L = lib()
+    return _asg_build("pcg_asg_build",
+                      lambda cap, *rest: L.pcg_asg_build(unit.data_ptr(), V, d, float(theta), cap, *rest),
+                      lambda cap: L.pcg_asg_build_workspace_bytes(V, cap), V, unit.device, cap,
+                      members_capacity)
+
+
+def asg_build_exact(emb: torch.Tensor, theta: float, cap: int = 256,
+                    members_capacity: Optional[int] = None) -> AsgGroups:
+    """The distinct similarity groups of Eq. (1) from the float32 embeddings [V, d] themselves:
+    the cosine is decided in double wherever the bfloat16 contraction cannot.  Same outputs and
+    retries as asg_build."""
+    assert emb.dim() == 2 and emb.dtype == torch.float32 and emb.is_contiguous()
+    V, d = emb.shape
+    L = lib()
+    return _asg_build("pcg_asg_build_exact",
+                      lambda cap, *rest: L.pcg_asg_build_exact(emb.data_ptr(), V, d, float(theta), cap, *rest),
+                      lambda cap: L.pcg_asg_build_exact_workspace_bytes(V, d, cap), V, emb.device, cap,
+                      members_capacity)
 
 
 def profile_begin(max_calls: int):

@@ -1,7 +1,10 @@
 // Construction of the Acoustic Similarity Groups (Sec. 2.1, Eq. 1) on gfx950: unit vectors in
 // bfloat16, the V x V cosine similarity as a bf16 MFMA contraction with fp32 accumulation that
 // is thresholded on the fly (the similarity matrix is never stored), per-token member lists
-// sorted ascending, identical sets dropped, and the CSR the verification kernels read.
+// sorted ascending, identical sets dropped, and the CSR the verification kernels read.  The
+// exact form (pcg_asg_build_exact) uses the same contraction as a filter: pairs whose rounded
+// similarity is too close to the threshold to decide are settled by the cosine of the
+// embeddings themselves in double, so its groups are those of Eq. (1) as written.
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -34,8 +37,9 @@ __device__ __forceinline__ uint16_t round_to_bf16(double x) {
   return (uint16_t) ((pick >> 16) | (__double_as_longlong(x) < 0 ? 0x8000u : 0u));
 }
 
+// norms (may be NULL) receives ||emb[v]|| in double.
 __global__ __launch_bounds__(256) void asg_normalize_kernel(const float *emb, int32_t V, int32_t d,
-                                                            uint16_t *unit) {
+                                                            uint16_t *unit, double *norms) {
   const int lane = threadIdx.x & (kWave - 1);
   const int64_t v = (int64_t) blockIdx.x * (blockDim.x / kWave) + (threadIdx.x >> 6);
   if (v >= V) return;                       // whole waves leave together
@@ -43,6 +47,7 @@ __global__ __launch_bounds__(256) void asg_normalize_kernel(const float *emb, in
   double ss = 0.0;
   for (int32_t k = lane; k < d; k += kWave) ss += (double) e[k] * (double) e[k];
   const double norm = sqrt(wave_sum(ss));
+  if (norms && lane == 0) norms[v] = norm;
   for (int32_t k = lane; k < d; k += kWave)
     unit[v * d + k] = norm > 0.0 ? round_to_bf16((double) e[k] / norm) : (uint16_t) 0;
 }
@@ -76,16 +81,20 @@ __device__ __forceinline__ void asg_emit(int32_t t, int32_t v, int32_t cap, int3
   if (pos < cap) cand[(int64_t) t * cap + pos] = v;
 }
 
+// A member that the rounded similarity could not decide carries this bit until the exact form
+// has settled it (token ids stay below 2^31).
+constexpr uint32_t kAsgUnsure = 0x80000000u;
+
 // Appends the pair (t, v) to the workgroup's queue in LDS; pairs beyond its capacity are
-// recorded at once.
-__device__ __forceinline__ void sim_queue_pair(int32_t t, int32_t v, int32_t cap, int32_t *count,
-                                               int32_t *cand, uint32_t *qn, uint2 *q) {
+// recorded at once.  flag: 0 or kAsgUnsure.
+__device__ __forceinline__ void sim_queue_pair(int32_t t, int32_t v, uint32_t flag, int32_t cap,
+                                               int32_t *count, int32_t *cand, uint32_t *qn, uint2 *q) {
   const uint32_t k = atomicAdd(qn, 1u);
   if (k < (uint32_t) kSimQueue) {
-    q[k] = make_uint2((uint32_t) t, (uint32_t) v);
+    q[k] = make_uint2((uint32_t) t, (uint32_t) v | flag);
   } else {
-    asg_emit(t, v, cap, count, cand);
-    if (t != v) asg_emit(v, t, cap, count, cand);
+    asg_emit(t, (int32_t) ((uint32_t) v | flag), cap, count, cand);
+    if (t != v) asg_emit(v, (int32_t) ((uint32_t) t | flag), cap, count, cand);
   }
 }
 
@@ -103,9 +112,12 @@ __device__ __forceinline__ void bare_barrier() {
   asm volatile("" ::: "memory");
 }
 
+// EXACT: pairs above theta are candidates, and those not above theta_hi are marked kAsgUnsure
+// for asg_refine_kernel (theta and theta_hi bracket the threshold of Eq. 1 by the rounding band).
+template <bool EXACT>
 __global__ __launch_bounds__(kSimThreads) void asg_similarity_kernel(
-    const uint16_t *__restrict__ unit, int32_t V, int32_t d, float theta, int32_t cap,
-    int32_t *count, int32_t *cand) {
+    const uint16_t *__restrict__ unit, int32_t V, int32_t d, float theta, float theta_hi,
+    int32_t cap, int32_t *count, int32_t *cand) {
   // Workgroups go to the 8 XCDs round-robin; the 32 that run together on one XCD take a patch of
   // 16 x 2 tiles (measured: 5.0 ms against 5.2 for 8 x 4 and 5.7 for 4 x 8), so that they find each
   // other's rows in their L2.
@@ -251,30 +263,93 @@ __global__ __launch_bounds__(kSimThreads) void asg_similarity_kernel(
                                   fmaxf(fmaxf(a[12], a[13]), fmaxf(a[14], a[15]))));
       const int32_t v = v0 + (lane & 31), tl = t0 + 4 * (lane >> 5);
       if (__builtin_amdgcn_ballot_w64(m > theta) != 0) {
-        uint32_t hits = 0;
+        uint32_t hits = 0, sure = 0xffffu;
 #pragma unroll
         for (int r = 0; r < 16; ++r) hits |= (a[r] > theta ? 1u : 0u) << r;
+        if constexpr (EXACT) {
+          sure = 0;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) sure |= (a[r] > theta_hi ? 1u : 0u) << r;
+        }
         while (hits) {                                 // only the lanes that hold a pair
           const int r = __builtin_ctz(hits);
           hits &= hits - 1;
           const int32_t t = tl + 8 * (r >> 2) + (r & 3);
-          if (t < V && v < V && v > t) sim_queue_pair(t, v, cap, count, cand, qn, q);
+          if (t < V && v < V && v > t)
+            sim_queue_pair(t, v, ((sure >> r) & 1u) ? 0u : kAsgUnsure, cap, count, cand, qn, q);
         }
       }
       // a token is always a member of its own group, whatever the rounded product says
       if (t0 == v0 && lane < 32 && t0 + lane < V)
-        sim_queue_pair(t0 + lane, t0 + lane, cap, count, cand, qn, q);
+        sim_queue_pair(t0 + lane, t0 + lane, 0u, cap, count, cand, qn, q);
     }
   __syncthreads();
   const uint32_t nq = min(*qn, (uint32_t) kSimQueue);
   for (uint32_t k = tid; k < nq; k += kSimThreads) {
     const uint2 pr = q[k];
-    const int32_t t = (int32_t) pr.x, v = (int32_t) pr.y;
+    const uint32_t flag = pr.y & kAsgUnsure;
+    const int32_t t = (int32_t) pr.x, v = (int32_t) (pr.y & ~kAsgUnsure);
     const int32_t p0 = atomicAdd(&count[t], 1);
     const int32_t p1 = t != v ? atomicAdd(&count[v], 1) : cap;
-    if (p0 < cap) cand[(int64_t) t * cap + p0] = v;
-    if (p1 < cap) cand[(int64_t) v * cap + p1] = t;
+    if (p0 < cap) cand[(int64_t) t * cap + p0] = (int32_t) ((uint32_t) v | flag);
+    if (p1 < cap) cand[(int64_t) v * cap + p1] = (int32_t) ((uint32_t) t | flag);
   }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Exact form: one wave per token settles the members marked kAsgUnsure by Eq. (1) itself -- the
+// dot product of the two float32 embeddings and their norms, all in double, strict > theta --
+// and closes the gaps in the token's list.  The dot product is summed in the same order for
+// (t, v) and (v, t), so both tokens reach the same decision.  A list that did not fit into cap
+// stays undecided: its count stays above cap and the call reports PCG_ERR_CAPACITY.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void asg_refine_kernel(const float *__restrict__ emb,
+                                                         const double *__restrict__ norms, int32_t V,
+                                                         int32_t d, double theta, int32_t cap,
+                                                         int32_t *count, int32_t *cand) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int32_t t = blockIdx.x * (blockDim.x / kWave) + (threadIdx.x >> 6);
+  if (t >= V) return;                       // whole waves leave together
+  const int32_t found = count[t];
+  int32_t *row = cand + (int64_t) t * cap;
+  if (found > cap) {
+    // undecided, but plain token ids again: the kernels that follow index with them
+    for (int32_t k = lane; k < cap; k += kWave) row[k] = (int32_t) ((uint32_t) row[k] & ~kAsgUnsure);
+    return;
+  }
+  const float *et = emb + (int64_t) t * d;
+  const double nt = norms[t];
+  int32_t kept_total = 0;
+  for (int32_t c0 = 0; c0 < found; c0 += kWave) {
+    const int32_t k = c0 + lane;
+    bool keep = k < found;
+    const uint32_t raw = keep ? (uint32_t) row[k] : 0u;
+    const int32_t entry = (int32_t) (raw & ~kAsgUnsure);
+    unsigned long long unsure = __ballot(keep && (raw & kAsgUnsure) != 0);
+    while (unsure) {                                   // uniform over the wave
+      const int l = __ffsll((long long) unsure) - 1;
+      unsure &= unsure - 1;
+      const int32_t v = __builtin_amdgcn_readlane(entry, l);
+      const float *ev = emb + (int64_t) v * d;
+      double dot = 0.0;
+      for (int32_t j = 4 * lane; j < d; j += 4 * kWave) {       // d is a multiple of 64
+        const float4 a = *reinterpret_cast<const float4 *>(et + j);
+        const float4 b = *reinterpret_cast<const float4 *>(ev + j);
+        dot += ((double) a.x * (double) b.x + (double) a.y * (double) b.y) +
+               ((double) a.z * (double) b.z + (double) a.w * (double) b.w);
+      }
+      dot = wave_sum(dot);
+      const double nv = norms[v];
+      const double cosine = (nt > 0.0 && nv > 0.0) ? dot / (nt * nv) : 0.0;
+      if (lane == l && !(cosine > theta)) keep = false;
+    }
+    const unsigned long long kept = __ballot(keep);
+    const int32_t pos = kept_total + __popcll(kept & ((1ull << lane) - 1ull));
+    // positions written here lie below c0 + 64, positions read later at or above it
+    if (keep) row[pos] = entry;
+    kept_total += __popcll(kept);
+  }
+  if (lane == 0) count[t] = kept_total;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -442,45 +517,29 @@ __global__ __launch_bounds__(256) void asg_compact_kernel(int32_t V, int32_t cap
 
 using namespace pcg;
 
-extern "C" {
+namespace {
 
-int pcg_asg_normalize(const float *emb, int32_t V, int32_t d, uint16_t *unit_bf16,
-                      void *hip_stream) {
-  if (!emb || !unit_bf16) return PCG_ERR_NULL_ARG;
-  if (V < 1 || d < 1) return PCG_ERR_BAD_SHAPE;
-  if (((uintptr_t) emb % 4) || ((uintptr_t) unit_bf16 % 2)) return PCG_ERR_MISALIGNED;
-  hipStream_t stream = (hipStream_t) hip_stream;
-  asg_normalize_kernel<<<(unsigned) ((V + 3) / 4), 256, 0, stream>>>(emb, V, d, unit_bf16);
-  const hipError_t e = hipGetLastError();
-  return e == hipSuccess ? PCG_OK : record_hip_error(e);
-}
-
-size_t pcg_asg_build_workspace_bytes(int32_t V, int32_t cap) {
-  if (V < 1 || cap < 1 || cap > kAsgMaxCap) return 0;
-  const size_t v = (size_t) V;
+size_t asg_core_workspace_bytes(size_t v, int32_t cap) {
   return asg_align(v * 4) /* count */ + asg_align(v * (size_t) cap * 4) /* cand */ +
          asg_align(v * 4) /* size */ + asg_align(v * 8) /* hash */ + asg_align(v * 4) /* keep */ +
-         asg_align(v * 4) /* gid */ + asg_align(v * 8) /* off */ + asg_align(64) /* totals */ +
-         kAsgAlign;
+         asg_align(v * 4) /* gid */ + asg_align(v * 8) /* off */ + asg_align(64) /* totals */;
 }
 
-int pcg_asg_build(const uint16_t *unit_bf16, int32_t V, int32_t d, float theta, int32_t cap,
-                  int32_t *row_ptr, int32_t *members, int64_t members_capacity, int32_t *mult,
-                  int32_t *seed_of, int32_t *out_G, int64_t *out_nnz, int32_t *out_max_size,
-                  void *workspace, size_t workspace_bytes, void *hip_stream) {
-  if (!unit_bf16 || !row_ptr || !members || !mult || !out_G || !out_nnz || !out_max_size ||
-      !workspace)
-    return PCG_ERR_NULL_ARG;
-  if (V < 1 || d < kSimK || d % kSimK || cap < 1 || cap > kAsgMaxCap || members_capacity < 1 ||
-      (int64_t) V * d > INT32_MAX || !std::isfinite(theta))
-    return PCG_ERR_BAD_SHAPE;
-  if (((uintptr_t) unit_bf16 % 16) || ((uintptr_t) workspace % kAsgAlign) ||
-      ((uintptr_t) row_ptr % 4) || ((uintptr_t) members % 4) || ((uintptr_t) mult % 4))
-    return PCG_ERR_MISALIGNED;
-  if (workspace_bytes < pcg_asg_build_workspace_bytes(V, cap)) return PCG_ERR_WORKSPACE_TOO_SMALL;
-  hipStream_t stream = (hipStream_t) hip_stream;
+// How far the fp32-accumulated dot product of two bf16-rounded unit vectors can lie from the
+// cosine of the vectors they were rounded from: every component is off by at most 2^-9 of
+// itself, so the products by at most 2^-8 + 2^-18 of themselves, and their absolute values sum
+// to at most 1 (Cauchy-Schwarz); the d additions in fp32 add at most d * 2^-23 (a rounding, or a
+// truncation, of each partial sum of magnitude at most 1).
+float asg_rounding_band(int32_t d) {
+  return 0x1p-8f + 0x1p-18f + (float) d * 0x1p-23f;
+}
+
+// The groups from the unit vectors; with emb (and norms, workspace of the caller) the exact form.
+int asg_build_impl(const float *emb, const double *norms, const uint16_t *unit_bf16, int32_t V,
+                   int32_t d, float theta, int32_t cap, int32_t *row_ptr, int32_t *members,
+                   int64_t members_capacity, int32_t *mult, int32_t *seed_of, int32_t *out_G,
+                   int64_t *out_nnz, int32_t *out_max_size, char *ws, hipStream_t stream) {
   const size_t v = (size_t) V;
-  char *ws = (char *) workspace;
   int32_t *count = (int32_t *) ws; ws += asg_align(v * 4);
   int32_t *cand = (int32_t *) ws; ws += asg_align(v * (size_t) cap * 4);
   int32_t *size = (int32_t *) ws; ws += asg_align(v * 4);
@@ -500,8 +559,16 @@ int pcg_asg_build(const uint16_t *unit_bf16, int32_t V, int32_t d, float theta, 
   const int patch_rows = (tiles + kSimPatchRows - 1) / kSimPatchRows;
   const int patch_cols = (tiles + kSimPatchCols - 1) / kSimPatchCols;
   const int patches = (patch_rows * patch_cols + 7) / 8 * 8;      // dealt to the 8 XCDs in turn
-  asg_similarity_kernel<<<(unsigned) (patches * kSimPatchRows * kSimPatchCols), kSimThreads, 0, stream>>>(
-      unit_bf16, V, d, theta, cap, count, cand);
+  const unsigned sim_grid = (unsigned) (patches * kSimPatchRows * kSimPatchCols);
+  if (emb) {
+    const float band = asg_rounding_band(d);
+    asg_similarity_kernel<true><<<sim_grid, kSimThreads, 0, stream>>>(
+        unit_bf16, V, d, theta - band, theta + band, cap, count, cand);
+    asg_refine_kernel<<<wb, 256, 0, stream>>>(emb, norms, V, d, (double) theta, cap, count, cand);
+  } else {
+    asg_similarity_kernel<false><<<sim_grid, kSimThreads, 0, stream>>>(
+        unit_bf16, V, d, theta, theta, cap, count, cand);
+  }
   if ((e = hipGetLastError()) != hipSuccess) return fail(e);
   int32_t cap2 = 1;
   while (cap2 < cap) cap2 <<= 1;
@@ -527,6 +594,85 @@ int pcg_asg_build(const uint16_t *unit_bf16, int32_t V, int32_t d, float theta, 
   if ((e = hipGetLastError()) != hipSuccess) return fail(e);
   if ((e = hipStreamSynchronize(stream)) != hipSuccess) return fail(e);
   return PCG_OK;
+}
+
+int asg_check_outputs(int32_t V, int32_t d, float theta, int32_t cap, const int32_t *row_ptr,
+                      const int32_t *members, int64_t members_capacity, const int32_t *mult,
+                      const void *workspace) {
+  if (V < 1 || d < 64 || d % 64 || cap < 1 || cap > kAsgMaxCap || members_capacity < 1 ||
+      (int64_t) V * d > INT32_MAX || !std::isfinite(theta))
+    return PCG_ERR_BAD_SHAPE;
+  if (((uintptr_t) workspace % kAsgAlign) || ((uintptr_t) row_ptr % 4) || ((uintptr_t) members % 4) ||
+      ((uintptr_t) mult % 4))
+    return PCG_ERR_MISALIGNED;
+  return PCG_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int pcg_asg_normalize(const float *emb, int32_t V, int32_t d, uint16_t *unit_bf16,
+                      void *hip_stream) {
+  if (!emb || !unit_bf16) return PCG_ERR_NULL_ARG;
+  if (V < 1 || d < 1) return PCG_ERR_BAD_SHAPE;
+  if (((uintptr_t) emb % 4) || ((uintptr_t) unit_bf16 % 2)) return PCG_ERR_MISALIGNED;
+  hipStream_t stream = (hipStream_t) hip_stream;
+  asg_normalize_kernel<<<(unsigned) ((V + 3) / 4), 256, 0, stream>>>(emb, V, d, unit_bf16, nullptr);
+  const hipError_t e = hipGetLastError();
+  return e == hipSuccess ? PCG_OK : record_hip_error(e);
+}
+
+size_t pcg_asg_build_workspace_bytes(int32_t V, int32_t cap) {
+  if (V < 1 || cap < 1 || cap > kAsgMaxCap) return 0;
+  return asg_core_workspace_bytes((size_t) V, cap) + kAsgAlign;
+}
+
+int pcg_asg_build(const uint16_t *unit_bf16, int32_t V, int32_t d, float theta, int32_t cap,
+                  int32_t *row_ptr, int32_t *members, int64_t members_capacity, int32_t *mult,
+                  int32_t *seed_of, int32_t *out_G, int64_t *out_nnz, int32_t *out_max_size,
+                  void *workspace, size_t workspace_bytes, void *hip_stream) {
+  if (!unit_bf16 || !row_ptr || !members || !mult || !out_G || !out_nnz || !out_max_size ||
+      !workspace)
+    return PCG_ERR_NULL_ARG;
+  if (const int rc = asg_check_outputs(V, d, theta, cap, row_ptr, members, members_capacity, mult, workspace))
+    return rc;
+  if ((uintptr_t) unit_bf16 % 16) return PCG_ERR_MISALIGNED;
+  if (workspace_bytes < pcg_asg_build_workspace_bytes(V, cap)) return PCG_ERR_WORKSPACE_TOO_SMALL;
+  return asg_build_impl(nullptr, nullptr, unit_bf16, V, d, theta, cap, row_ptr, members,
+                        members_capacity, mult, seed_of, out_G, out_nnz, out_max_size,
+                        (char *) workspace, (hipStream_t) hip_stream);
+}
+
+size_t pcg_asg_build_exact_workspace_bytes(int32_t V, int32_t d, int32_t cap) {
+  if (V < 1 || d < 1 || cap < 1 || cap > kAsgMaxCap || (int64_t) V * d > INT32_MAX) return 0;
+  const size_t v = (size_t) V;
+  return asg_core_workspace_bytes(v, cap) + asg_align(v * (size_t) d * 2) /* unit vectors */ +
+         asg_align(v * 8) /* norms */ + kAsgAlign;
+}
+
+int pcg_asg_build_exact(const float *emb, int32_t V, int32_t d, float theta, int32_t cap,
+                        int32_t *row_ptr, int32_t *members, int64_t members_capacity,
+                        int32_t *mult, int32_t *seed_of, int32_t *out_G, int64_t *out_nnz,
+                        int32_t *out_max_size, void *workspace, size_t workspace_bytes,
+                        void *hip_stream) {
+  if (!emb || !row_ptr || !members || !mult || !out_G || !out_nnz || !out_max_size || !workspace)
+    return PCG_ERR_NULL_ARG;
+  if (const int rc = asg_check_outputs(V, d, theta, cap, row_ptr, members, members_capacity, mult, workspace))
+    return rc;
+  if ((uintptr_t) emb % 16) return PCG_ERR_MISALIGNED;
+  if (workspace_bytes < pcg_asg_build_exact_workspace_bytes(V, d, cap))
+    return PCG_ERR_WORKSPACE_TOO_SMALL;
+  hipStream_t stream = (hipStream_t) hip_stream;
+  const size_t v = (size_t) V;
+  char *ws = (char *) workspace;
+  uint16_t *unit = (uint16_t *) ws; ws += asg_align(v * (size_t) d * 2);
+  double *norms = (double *) ws; ws += asg_align(v * 8);
+  asg_normalize_kernel<<<(unsigned) ((V + 3) / 4), 256, 0, stream>>>(emb, V, d, unit, norms);
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return record_hip_error(e);
+  return asg_build_impl(emb, norms, unit, V, d, theta, cap, row_ptr, members, members_capacity,
+                        mult, seed_of, out_G, out_nnz, out_max_size, ws, stream);
 }
 
 }  // extern "C"

@@ -385,3 +385,13 @@ def test_asg_argument_checks():
     assert L.pcg_asg_normalize(None, 4, 4, P, None) == NULL_ARG
     assert L.pcg_asg_normalize(P, 0, 4, P, None) == BAD_SHAPE
     assert pcg.lib().pcg_asg_build_workspace_bytes(256, 5000) == 0
+    exact = lambda **k: L.pcg_asg_build_exact(k.get("emb", P), k.get("V", 256), k.get("d", 128), k.get("theta", 0.4),
+                                              k.get("cap", 64), P, P, k.get("room", 1000), P, None, C.byref(g),
+                                              C.byref(n), C.byref(m), k.get("ws", P), k.get("wsb", 1 << 30), None)
+    assert exact(emb=None) == NULL_ARG
+    assert exact(d=96) == BAD_SHAPE and exact(cap=0) == BAD_SHAPE and exact(theta=float("inf")) == BAD_SHAPE
+    assert exact(emb=P + 4) == MISALIGNED and exact(ws=P + 64) == MISALIGNED
+    need = L.pcg_asg_build_exact_workspace_bytes(256, 128, 64)
+    assert need >= L.pcg_asg_build_workspace_bytes(256, 64) + 256 * 128 * 2 + 256 * 8      # unit vectors, norms
+    assert exact(wsb=need - 1) == WS_SMALL
+    assert L.pcg_asg_build_exact_workspace_bytes(1 << 22, 1024, 64) == 0

@@ -1,7 +1,9 @@
-"""GPU parity of the similarity-group construction (Sec. 2.1, Eq. 1): pcg_asg_normalize and
-pcg_asg_build through the C ABI against the oracle.  Unit vectors bit-exact; membership exact
-except for pairs the oracle flags as within 1e-5 of the threshold (fp32 accumulation against
-fp64), which are counted.  Run with ``-m gpu`` on an MI355X."""
+"""GPU parity of the similarity-group construction (Sec. 2.1, Eq. 1): pcg_asg_normalize,
+pcg_asg_build and pcg_asg_build_exact through the C ABI against the oracle.  Unit vectors
+bit-exact; membership of the bf16 form exact except for pairs the oracle flags as within 1e-5
+of the threshold (fp32 accumulation against fp64), which are counted; membership of the exact
+form equal to Eq. (1) on the embeddings in double (a cosine within 1e-12 of the threshold would
+be flagged: none occurs).  Run with ``-m gpu`` on an MI355X."""
 import numpy as np
 import pytest
 import torch
@@ -147,3 +149,65 @@ def test_recipe_rows_at_full_size():
     print(f"C4 sampled rows against Eq. (1) on the embeddings: {n_diff} of {n_mem} memberships differ, "
           f"farthest from theta {worst:.2e} (band {BF16_BAND:.2e})", flush=True)
     assert tol <= 2
+
+
+@pytest.mark.parametrize("V,d,theta,centres,sigma", [
+    (128, 64, 0.3, 0, 0),          # exactly one tile
+    (300, 64, 0.25, 0, 0),         # ragged
+    (1000, 128, 0.2, 0, 0),
+    (2000, 256, 0.5, 40, 0.5),     # clustered: the threshold lies inside the clusters' cosines
+    (4096, 512, 0.12, 0, 0),
+    (1500, 192, 0.6, 30, 0.3),
+    (1200, 64, 0.42, 0, 0),        # the paper's range of theta
+    (777, 64, -2.0, 0, 0),         # everything in one group
+])
+def test_exact_groups_are_eq1_on_the_embeddings(V, d, theta, centres, sigma):
+    """pcg_asg_build_exact against the oracle's Eq. (1) in double on the float32 embeddings:
+    the whole CSR must be equal.  Also counted: how many memberships the rounded form
+    (pcg_asg_build on the same embeddings) gets differently, i.e. what the exact form repairs."""
+    E = embeddings(V, d, V + d) if centres == 0 else embeddings(V, d, V + d, centres, sigma)[0]
+    E[V // 2] = 0.0                                              # a zero row: cosine 0 with everything
+    E[V // 3] = E[V // 3 + 1]                                    # a duplicate: merged
+    th = float(np.float32(theta))
+    ref = oracle.asg_build_exact(E, th, nthreads=16)
+    dev = torch.from_numpy(E).cuda()
+    got = pcg.asg_build_exact(dev, theta, cap=64)
+    t = compare_groups(got, ref, f"exact V={V} d={d} theta={theta}")
+    t.report(f"asg exact V={V} d={d} theta={theta}")
+    assert t.flagged_group == 0 and t.tolerated == 0
+    rounded = pcg.asg_build(pcg.asg_normalize(dev), theta, cap=64)
+    a = set(zip(np.repeat(got.seed_of.cpu().numpy(), np.diff(got.row_ptr.cpu().numpy())).tolist(),
+                got.members.cpu().numpy().tolist()))
+    b = set(zip(np.repeat(rounded.seed_of.cpu().numpy(), np.diff(rounded.row_ptr.cpu().numpy())).tolist(),
+                rounded.members.cpu().numpy().tolist()))
+    print(f"asg exact V={V} d={d} theta={theta}: G={got.G} nnz={got.nnz} largest {got.max_size}; "
+          f"the rounded form differs in {len(a ^ b)} (seed, member) entries", flush=True)
+    assert got.max_size == int(np.diff(ref.groups.row_ptr).max()) or theta < -1
+
+
+def test_exact_recipe_rows_at_full_size():
+    """C4's embeddings (65 536 x 1024) through pcg_asg_build_exact: sampled rows of G(t) must
+    equal Eq. (1) in double on the embeddings, member for member (the oracle computes the rows one
+    by one and reports every cosine, so a pair close enough to theta for the order of summation
+    to matter would be seen: the closest is printed)."""
+    cfg = W.CONFIGS["C4"]
+    E = W.embeddings(cfg)
+    theta = 0.105
+    th = float(np.float32(theta))
+    got = pcg.asg_build_exact(torch.from_numpy(E).cuda(), theta, cap=512)
+    rp, mem, seed = got.row_ptr.cpu().numpy(), got.members.cpu().numpy(), got.seed_of.cpu().numpy()
+    print(f"C4 exact theta={theta}: G={got.G} nnz={got.nnz} mean size {got.nnz / got.G:.1f} largest {got.max_size}", flush=True)
+    assert got.G == cfg.V
+    np.testing.assert_array_equal(got.mult.cpu().numpy(), np.bincount(mem, minlength=cfg.V))
+    where = {int(s): k for k, s in enumerate(seed)}
+    closest = 1.0
+    n_mem = 0
+    for t in [0, 1, 127, 128, 4095, 32768, 65535, 12345, 50000, 256, 65280, 33333]:
+        exact, cos = oracle.asg_row_exact(E, th, t)
+        closest = min(closest, float(np.abs(np.delete(cos, t) - th).min()))
+        mine = mem[rp[where[t]]:rp[where[t] + 1]]
+        np.testing.assert_array_equal(mine, exact, err_msg=f"token {t}")
+        n_mem += len(exact)
+    print(f"C4 exact: {n_mem} memberships of 12 sampled rows equal to Eq. (1) in double; "
+          f"closest cosine to theta {closest:.2e} away", flush=True)
+    assert closest > 1e-12

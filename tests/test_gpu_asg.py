@@ -211,3 +211,43 @@ def test_exact_recipe_rows_at_full_size():
     print(f"C4 exact: {n_mem} memberships of 12 sampled rows equal to Eq. (1) in double; "
           f"closest cosine to theta {closest:.2e} away", flush=True)
     assert closest > 1e-12
+
+
+def test_exact_rows_of_a_clustered_recipe_at_full_size():
+    """C5's embeddings (32 768 x 512, clusters of very different sizes) at a threshold inside the
+    clusters' own cosines: groups from one to over a thousand members, a large share of every
+    group's candidates inside the rounding band, and a first room per group that is too small
+    (the call is repeated with the room the library reports).  Sampled rows, from the largest
+    cluster to singletons, must equal Eq. (1) in double on the embeddings."""
+    cfg = W.CONFIGS["C5"]
+    E = W.embeddings(cfg)
+    theta = 0.83
+    th = float(np.float32(theta))
+    got = pcg.asg_build_exact(torch.from_numpy(E).cuda(), theta, cap=256)
+    rp, mem, seed = got.row_ptr.cpu().numpy(), got.members.cpu().numpy(), got.seed_of.cpu().numpy()
+    sizes = np.diff(rp)
+    print(f"C5 exact theta={theta}: G={got.G} nnz={got.nnz} sizes {sizes.min()}..{sizes.max()} "
+          f"largest G(t) {got.max_size}", flush=True)
+    assert got.max_size > 256 and sizes.max() == got.max_size
+    np.testing.assert_array_equal(got.mult.cpu().numpy(), np.bincount(mem, minlength=cfg.V))
+    where = {int(s): k for k, s in enumerate(seed)}
+    order = np.argsort(sizes)
+    picks = [int(seed[order[-1]]), int(seed[order[len(order) // 2]]), int(seed[order[0]]), 0, 1, cfg.V - 1, 12345, 20000]
+    closest, n_mem, n_band = 1.0, 0, 0
+    for t in picks:
+        exact, cos = oracle.asg_row_exact(E, th, t)
+        others = np.delete(cos, t)
+        closest = min(closest, float(np.abs(others - th).min()))
+        n_band += int((np.abs(others - th) < 4e-3).sum())
+        if t in where:
+            mine = mem[rp[where[t]]:rp[where[t] + 1]]
+        else:           # an exact duplicate of an earlier token's set: find it through a member
+            k = next(k for k in (where.get(int(v)) for v in exact) if k is not None and
+                     np.array_equal(mem[rp[k]:rp[k + 1]], exact))
+            mine = mem[rp[k]:rp[k + 1]]
+        np.testing.assert_array_equal(mine, exact, err_msg=f"token {t}")
+        n_mem += len(exact)
+    print(f"C5 exact: {n_mem} memberships of {len(picks)} sampled rows equal to Eq. (1) in double; "
+          f"{n_band} of their pairs lay inside the rounding band; closest cosine to theta {closest:.2e} away",
+          flush=True)
+    assert closest > 1e-12 and n_band > 0

@@ -1,0 +1,75 @@
+"""A seeded sweep over random shapes: vocabulary, number and width of groups, batch, draft
+length, element type, temperature and membership layout are all drawn, so that sizes nobody
+thought of by hand (ragged parts, groups per chunk, tiles, widths of the reductions) are met.
+Every case runs pcg_group_probs, pcg_verify and pcg_verify_thinning against the oracle under
+the same rules as the hand-picked cases.  Run with ``-m gpu`` on an MI355X."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2511_13732_amd as pcg
+import workloads as W
+from parity import (Tally, as_oracle_logits, compare_thinning, compare_verify, group_probs_error,
+                    oracle_groups, run_both, run_both_thinning)
+
+pytestmark = pytest.mark.gpu
+
+
+def draw_case(case: int):
+    rng = np.random.default_rng([2511, 13732, case])
+    V = int(np.exp(rng.uniform(np.log(3), np.log(120000))))
+    widest = int(min(V, np.exp(rng.uniform(np.log(2), np.log(300)))))
+    smin = int(rng.integers(1, max(2, widest // 2 + 1)))
+    smax = int(rng.integers(smin, max(smin, widest) + 1))
+    # keep the membership (and with it the oracle's time) bounded
+    G = int(min(np.exp(rng.uniform(0, np.log(2 * V + 1))), 600000 // max(1, (smin + smax) // 2)))
+    G = max(1, G)
+    B = int(rng.integers(1, 71))
+    K = int(rng.integers(1, 13))
+    while B * (2 * K + 1) * V > 40_000_000:          # oracle time
+        B = max(1, B // 2)
+    dtype = "bf16" if rng.random() < 0.5 else "f32"
+    tau = float(np.round(rng.uniform(0.5, 1.5), 3))
+    layout = ["prepared", "prepared-4096", "csr"][int(rng.integers(0, 3))]
+    cover = bool(rng.random() < 0.5)
+    return V, G, smin, smax, B, K, dtype, tau, layout, cover
+
+
+@pytest.mark.parametrize("case", range(40))
+def test_random_shape(case):
+    V, G, smin, smax, B, K, dtype, tau, layout, cover = draw_case(case)
+    name = f"random #{case}: V={V} G={G} sizes {smin}..{smax} B={B} K={K} {dtype} tau={tau} {layout} cover={cover}"
+    print(name, flush=True)
+    rp, mem = W.random_groups(V, G, smin, smax, seed=1000 + case, cover=cover)
+    og = oracle_groups(V, rp, mem)
+    dg = pcg.Groups.from_csr(V, rp, mem, "cuda", prepare=layout != "csr",
+                             chunk_groups=4096 if layout.endswith("4096") else 0, reverse=True)
+    rev = oracle.reverse_index(og)
+    rng = np.random.default_rng([case, 5])
+    sigma_t, sigma_d = float(rng.uniform(1.0, 5.0)), float(rng.uniform(0.3, 1.5))
+    total, thin = Tally(), Tally()
+    for step in range(2):
+        tgt = (sigma_t * rng.standard_normal((B, K + 1, V))).astype(np.float32)
+        dft = (tgt[:, :K] + sigma_d * rng.standard_normal((B, K, V))).astype(np.float32)
+        tgt, dft = torch.from_numpy(tgt), torch.from_numpy(dft)
+        if dtype == "bf16":
+            tgt, dft = tgt.to(torch.bfloat16), dft.to(torch.bfloat16)
+        ptok, pgrp = W.proposals(dft, tau, og.row_ptr, og.members, np.random.default_rng([case, step]))
+        gpu, ref, _, diag = run_both(V, rp, mem, tgt, dft, ptok, pgrp, temperature=tau, seed=case,
+                                     offset=step, dg=dg, og=og)
+        total.add(compare_verify(gpu, ref, og, ptok, pgrp))
+        assert diag["sequences"] == B and diag["bad_proposal"] == 0
+        g2, trials, r2, _ = run_both_thinning(V, tgt, dft, ptok, pgrp, dg=dg, og=og, rev=rev,
+                                              temperature=tau, seed=case, offset=step)
+        thin.add(compare_thinning(g2, trials, r2, og, ptok, pgrp))
+        if step == 0:
+            rows = tgt[: min(B, 3), 0].contiguous()
+            out = pcg.group_probs(dg, rows.cuda(), tau)
+            torch.cuda.synchronize()
+            err = group_probs_error(out, oracle.group_probs(og, as_oracle_logits(rows), tau))
+            assert err <= 1e-5, (name, err)
+    total.report(name)
+    thin.report(name + " (thinning)")
+    assert total.tolerated <= max(1, total.sequences // 100)
+    assert thin.tolerated <= max(1, thin.sequences // 100)

@@ -1,8 +1,9 @@
 """A seeded sweep over random shapes: vocabulary, number and width of groups, batch, draft
 length, element type, temperature and membership layout are all drawn, so that sizes nobody
 thought of by hand (ragged parts, groups per chunk, tiles, widths of the reductions) are met.
-Every case runs pcg_group_probs, pcg_verify and pcg_verify_thinning against the oracle under
-the same rules as the hand-picked cases.  Run with ``-m gpu`` on an MI355X."""
+Every case runs pcg_group_probs, pcg_propose, pcg_verify and pcg_verify_thinning against the
+oracle under the same rules as the hand-picked cases; a third of the cases carry general weights
+(Eq. 2) instead of the equal split.  Run with ``-m gpu`` on an MI355X."""
 import numpy as np
 import pytest
 import torch
@@ -10,6 +11,7 @@ import torch
 import oracle
 import paper_2511_13732_amd as pcg
 import workloads as W
+from test_gpu_propose import compare_proposals
 from parity import (Tally, as_oracle_logits, compare_thinning, compare_verify, group_probs_error,
                     oracle_groups, run_both, run_both_thinning)
 
@@ -33,29 +35,37 @@ def draw_case(case: int):
     tau = float(np.round(rng.uniform(0.5, 1.5), 3))
     layout = ["prepared", "prepared-4096", "csr"][int(rng.integers(0, 3))]
     cover = bool(rng.random() < 0.5)
-    return V, G, smin, smax, B, K, dtype, tau, layout, cover
+    weighted = bool(rng.random() < 1 / 3)
+    return V, G, smin, smax, B, K, dtype, tau, layout, cover, weighted
 
 
 @pytest.mark.parametrize("case", range(40))
 def test_random_shape(case):
-    V, G, smin, smax, B, K, dtype, tau, layout, cover = draw_case(case)
-    name = f"random #{case}: V={V} G={G} sizes {smin}..{smax} B={B} K={K} {dtype} tau={tau} {layout} cover={cover}"
+    V, G, smin, smax, B, K, dtype, tau, layout, cover, weighted = draw_case(case)
+    name = f"random #{case}: V={V} G={G} sizes {smin}..{smax} B={B} K={K} {dtype} tau={tau} {layout} cover={cover} weights={weighted}"
     print(name, flush=True)
     rp, mem = W.random_groups(V, G, smin, smax, seed=1000 + case, cover=cover)
     og = oracle_groups(V, rp, mem)
-    dg = pcg.Groups.from_csr(V, rp, mem, "cuda", prepare=layout != "csr",
+    w = W.random_weights(og.V, og.members, case) if weighted else None
+    if weighted:
+        og = oracle.with_weights(og, w)
+    dg = pcg.Groups.from_csr(V, rp, mem, "cuda", prepare=layout != "csr", weights=w,
                              chunk_groups=4096 if layout.endswith("4096") else 0, reverse=True)
     rev = oracle.reverse_index(og)
     rng = np.random.default_rng([case, 5])
     sigma_t, sigma_d = float(rng.uniform(1.0, 5.0)), float(rng.uniform(0.3, 1.5))
-    total, thin = Tally(), Tally()
+    total, thin, prop = Tally(), Tally(), Tally()
     for step in range(2):
         tgt = (sigma_t * rng.standard_normal((B, K + 1, V))).astype(np.float32)
         dft = (tgt[:, :K] + sigma_d * rng.standard_normal((B, K, V))).astype(np.float32)
         tgt, dft = torch.from_numpy(tgt), torch.from_numpy(dft)
         if dtype == "bf16":
             tgt, dft = tgt.to(torch.bfloat16), dft.to(torch.bfloat16)
-        ptok, pgrp = W.proposals(dft, tau, og.row_ptr, og.members, np.random.default_rng([case, step]))
+        # proposals by the library itself, checked against the oracle's, whose own go on
+        tok, grp = pcg.propose(dg, dft.cuda(), temperature=tau, seed=case + 7, offset=step)
+        pref = oracle.propose(og, rev, as_oracle_logits(dft), temperature=tau, seed=case + 7, offset=step, nthreads=8)
+        prop.add(compare_proposals(tok, grp, pref, og))
+        ptok, pgrp = pref.tokens, pref.groups
         gpu, ref, _, diag = run_both(V, rp, mem, tgt, dft, ptok, pgrp, temperature=tau, seed=case,
                                      offset=step, dg=dg, og=og)
         total.add(compare_verify(gpu, ref, og, ptok, pgrp))
@@ -71,5 +81,7 @@ def test_random_shape(case):
             assert err <= 1e-5, (name, err)
     total.report(name)
     thin.report(name + " (thinning)")
+    prop.report(name + " (propose)")
+    assert prop.tolerated <= max(1, prop.sequences // 100)
     assert total.tolerated <= max(1, total.sequences // 100)
     assert thin.tolerated <= max(1, thin.sequences // 100)

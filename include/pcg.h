@@ -389,6 +389,12 @@ size_t pcg_asg_build_exact_workspace_bytes(int32_t V, int32_t d, int32_t cap);
 
 /* ---- group membership on the host -------------------------------------------------------- */
 
+/* Every helper below takes the membership as (row_ptr [G + 1], members [row_ptr[G]]): the number of
+ * entries is read from row_ptr[G], so the members array (and every per-entry array: weights) must
+ * really hold that many -- a C function cannot see an array's length, and a row_ptr[G] beyond it
+ * makes the helper read past the end.  Everything else about the arrays is checked and refused
+ * with PCG_ERR_BAD_CSR: row_ptr[0] != 0, a decreasing row_ptr, a member outside [0, V). */
+
 /* PCG_OK iff (row_ptr, members, mult), all HOST, form a membership the kernels may use (see
  * pcg_groups above); PCG_ERR_BAD_CSR otherwise. */
 int pcg_groups_validate_host(int32_t V, int32_t G, const int32_t *row_ptr,

@@ -204,6 +204,9 @@ def canonicalize(V: int, row_ptr, members) -> Groups:
     """Append a singleton group for every token that is in no group; fill mult."""
     row_ptr, members = _i32(row_ptr), _i32(members)
     G = len(row_ptr) - 1
+    # the C routine learns the number of entries from row_ptr[G]; only here is the array's length known
+    if G < 0 or not 0 <= int(row_ptr[-1]) <= len(members):
+        raise OracleError("canonicalize: row_ptr[G] does not fit the members array")
     oG, onnz = C.c_int32(), C.c_int64()
     _check(lib().pcg_ref_canonicalize(C.c_int32(V), C.c_int32(G), _p(row_ptr), _p(members),
                                       C.byref(oG), C.byref(onnz), None, None, None),

@@ -170,15 +170,34 @@ def _np_i32(a) -> np.ndarray:
     return np.ascontiguousarray(np.asarray(a), dtype=np.int32)
 
 
+ERR_BAD_CSR = -7
+
+
+def _csr_i32(row_ptr, members):
+    """The two CSR arrays as int32, after the one check that only the caller of the C ABI can
+    make: the library learns the number of entries from row_ptr[G] and cannot see how long the
+    members array really is."""
+    rp, mem = _np_i32(row_ptr), _np_i32(members)
+    if rp.ndim != 1 or mem.ndim != 1 or len(rp) < 1 or not 0 <= int(rp[-1]) <= len(mem):
+        raise PcgError(ERR_BAD_CSR, "row_ptr[G] does not fit the members array")
+    return rp, mem
+
+
 def groups_validate_host(V: int, row_ptr, members, mult) -> int:
-    rp, mem, mu = _np_i32(row_ptr), _np_i32(members), _np_i32(mult)
+    try:
+        rp, mem = _csr_i32(row_ptr, members)
+    except PcgError as e:
+        return e.status
+    mu = _np_i32(mult)
+    if len(mu) < V:
+        return ERR_BAD_CSR
     return lib().pcg_groups_validate_host(V, len(rp) - 1, rp.ctypes.data, mem.ctypes.data,
                                           mu.ctypes.data)
 
 
 def groups_canonicalize_host(V: int, row_ptr, members):
     """(row_ptr, members, mult) with a singleton group appended for every uncovered token."""
-    rp, mem = _np_i32(row_ptr), _np_i32(members)
+    rp, mem = _csr_i32(row_ptr, members)
     G = len(rp) - 1
     oG, onnz = C.c_int32(), C.c_int64()
     _check(lib().pcg_groups_canonicalize_host(V, G, rp.ctypes.data, mem.ctypes.data, C.byref(oG),
@@ -194,7 +213,7 @@ def groups_canonicalize_host(V: int, row_ptr, members):
 
 def groups_reverse_host(V: int, row_ptr, members):
     """(tok_ptr [V+1], tok_groups [nnz]): the groups holding each token."""
-    rp, mem = _np_i32(row_ptr), _np_i32(members)
+    rp, mem = _csr_i32(row_ptr, members)
     tok_ptr = np.empty(V + 1, np.int32)
     tok_groups = np.empty(max(1, len(mem)), np.int32)
     _check(lib().pcg_groups_reverse_host(V, len(rp) - 1, rp.ctypes.data, mem.ctypes.data,
@@ -203,7 +222,7 @@ def groups_reverse_host(V: int, row_ptr, members):
 
 
 def groups_validate_weights_host(V: int, row_ptr, members, weights, tol: float = 1e-6) -> int:
-    rp, mem = _np_i32(row_ptr), _np_i32(members)
+    rp, mem = _csr_i32(row_ptr, members)
     w = np.ascontiguousarray(weights, dtype=np.float32)
     return lib().pcg_groups_validate_weights_host(V, len(rp) - 1, rp.ctypes.data, mem.ctypes.data,
                                                   w.ctypes.data, tol)
@@ -211,7 +230,7 @@ def groups_validate_weights_host(V: int, row_ptr, members, weights, tol: float =
 
 def groups_reverse_weights_host(V: int, row_ptr, members, weights) -> np.ndarray:
     """The per-entry weights in the order of the token -> groups index."""
-    rp, mem = _np_i32(row_ptr), _np_i32(members)
+    rp, mem = _csr_i32(row_ptr, members)
     w = np.ascontiguousarray(weights, dtype=np.float32)
     out = np.empty(max(1, len(mem)), np.float32)
     _check(lib().pcg_groups_reverse_weights_host(V, len(rp) - 1, rp.ctypes.data, mem.ctypes.data,
@@ -230,7 +249,7 @@ def suggest_chunk_groups(G: int, batch: int) -> int:
 def groups_prepare_host(V: int, row_ptr, members, chunk_groups: int = 0, weights=None):
     """(blob uint8 array, PreparedInfo) of a canonical host CSR; see pcg_groups_prepare_host and,
     with ``weights`` (float32 [nnz]), pcg_groups_prepare_weights_host."""
-    rp, mem = _np_i32(row_ptr), _np_i32(members)
+    rp, mem = _csr_i32(row_ptr, members)
     G = len(rp) - 1
     L = lib()
     sizer = L.pcg_groups_prepare_bytes if weights is None else L.pcg_groups_prepare_weights_bytes

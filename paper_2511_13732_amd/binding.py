@@ -224,6 +224,8 @@ def groups_reverse_host(V: int, row_ptr, members):
 def groups_validate_weights_host(V: int, row_ptr, members, weights, tol: float = 1e-6) -> int:
     rp, mem = _csr_i32(row_ptr, members)
     w = np.ascontiguousarray(weights, dtype=np.float32)
+    if w.ndim != 1 or len(w) < int(rp[-1]):
+        return ERR_BAD_CSR
     return lib().pcg_groups_validate_weights_host(V, len(rp) - 1, rp.ctypes.data, mem.ctypes.data,
                                                   w.ctypes.data, tol)
 
@@ -232,6 +234,8 @@ def groups_reverse_weights_host(V: int, row_ptr, members, weights) -> np.ndarray
     """The per-entry weights in the order of the token -> groups index."""
     rp, mem = _csr_i32(row_ptr, members)
     w = np.ascontiguousarray(weights, dtype=np.float32)
+    if w.ndim != 1 or len(w) < int(rp[-1]):
+        raise PcgError(ERR_BAD_CSR, "fewer weights than row_ptr[G] entries")
     out = np.empty(max(1, len(mem)), np.float32)
     _check(lib().pcg_groups_reverse_weights_host(V, len(rp) - 1, rp.ctypes.data, mem.ctypes.data,
                                                  w.ctypes.data, out.ctypes.data), "reverse_weights")

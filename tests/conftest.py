@@ -19,7 +19,7 @@ def _sanitizer_run():
     missing or stale).  An instrumented library can only be loaded into a Python that has the
     sanitizer runtime preloaded, so the whole run is started as
 
-        LD_PRELOAD=$(python -c "from paper_2511_13732_amd import build; print(build.asan_runtime())") \\
+        LD_PRELOAD=$(python -c "from paper_2511_13732_amd import build; print(build.asan_runtime())")${LD_PRELOAD:+:$LD_PRELOAD} \\
         ASAN_OPTIONS=detect_leaks=0 PCG_SANITIZE=1 python -m pytest tests -q -m "not gpu"
 
     (leak detection off: the interpreter itself does not free everything at exit).  Any finding

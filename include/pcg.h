@@ -180,6 +180,9 @@ typedef struct {
  *   workspace         DEVICE, >= pcg_group_probs_workspace_bytes(V, rows)
  * Rows are independent; rows == 0 is a no-op.  Logits must be finite or -inf
  * with at least one finite entry per row, else that row's output is NaN.
+ * Accuracy: a group's sum is one float32 running sum over its entries, so next to the 1e-5
+ * relative error of the terms themselves it carries up to n 2^-24 of rounding for a group of n
+ * entries (measured: within 1e-5 in total for groups of up to a few hundred entries).
  */
 int pcg_group_probs(const pcg_groups *groups, const void *logits, pcg_dtype dt, int64_t rows,
                     int64_t row_stride, float temperature, float *out, void *workspace,

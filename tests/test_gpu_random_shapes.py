@@ -4,6 +4,8 @@ thought of by hand (ragged parts, groups per chunk, tiles, widths of the reducti
 Every case runs pcg_group_probs, pcg_propose, pcg_verify and pcg_verify_thinning against the
 oracle under the same rules as the hand-picked cases; a third of the cases carry general weights
 (Eq. 2) instead of the equal split.  Run with ``-m gpu`` on an MI355X."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -39,7 +41,8 @@ def draw_case(case: int):
     return V, G, smin, smax, B, K, dtype, tau, layout, cover, weighted
 
 
-@pytest.mark.parametrize("case", range(40))
+# PCG_RANDOM_CASES=n widens the sweep (the default keeps the suite short)
+@pytest.mark.parametrize("case", range(int(os.environ.get("PCG_RANDOM_CASES", "40"))))
 def test_random_shape(case):
     V, G, smin, smax, B, K, dtype, tau, layout, cover, weighted = draw_case(case)
     name = f"random #{case}: V={V} G={G} sizes {smin}..{smax} B={B} K={K} {dtype} tau={tau} {layout} cover={cover} weights={weighted}"
@@ -78,7 +81,13 @@ def test_random_shape(case):
             out = pcg.group_probs(dg, rows.cuda(), tau)
             torch.cuda.synchronize()
             err = group_probs_error(out, oracle.group_probs(og, as_oracle_logits(rows), tau))
-            assert err <= 1e-5, (name, err)
+            # A group's sum is one fp32 running sum over its n entries: its rounding alone is bounded
+            # by n 2^-24 of the sum.  Up to a few hundred members (the paper's groups have 4 to 140)
+            # that stays inside the 1e-5 asserted everywhere else; the sweep also makes groups of
+            # thousands of members (few groups covering a large vocabulary), which get that bound.
+            widest = int(np.diff(og.row_ptr).max())
+            tol = max(1e-5, 2.0 * widest * 2.0 ** -24)
+            assert err <= tol, (name, err, widest, tol)
     total.report(name)
     thin.report(name + " (thinning)")
     prop.report(name + " (propose)")

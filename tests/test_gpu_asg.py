@@ -251,3 +251,32 @@ def test_exact_rows_of_a_clustered_recipe_at_full_size():
           f"{n_band} of their pairs lay inside the rounding band; closest cosine to theta {closest:.2e} away",
           flush=True)
     assert closest > 1e-12 and n_band > 0
+
+
+@pytest.mark.parametrize("case", range(16))
+def test_random_construction_shapes(case):
+    """Seeded random shapes of the construction: vocabulary, embedding width, threshold, iid or
+    clustered embeddings are drawn; both forms run against their oracles (whole CSR)."""
+    rng = np.random.default_rng([1, 2511, case])
+    V = int(np.exp(rng.uniform(np.log(2), np.log(2500))))
+    d = 64 * int(rng.integers(1, 7))
+    clustered = bool(rng.random() < 0.5) and V >= 8
+    centres = int(rng.integers(2, max(3, V // 4))) if clustered else 0
+    sigma = float(rng.uniform(0.1, 0.8))
+    E = embeddings(V, d, 100 + case, centres, sigma)[0] if clustered else embeddings(V, d, 100 + case)
+    # a threshold that cuts through the cosines that occur: a quantile of a sample of them
+    X = E[: min(V, 400)].astype(np.float64)
+    X /= np.linalg.norm(X, axis=1, keepdims=True)
+    S = (X @ X.T)[np.triu_indices(len(X), 1)] if len(X) > 1 else np.array([0.0])
+    theta = float(np.float32(np.quantile(S, rng.uniform(0.5, 0.999)))) if len(S) else 0.0
+    name = f"asg random #{case}: V={V} d={d} theta={theta:.4f} centres={centres} sigma={sigma:.2f}"
+    print(name, flush=True)
+    dev = torch.from_numpy(E).cuda()
+    exact = pcg.asg_build_exact(dev, theta, cap=64)
+    t = compare_groups(exact, oracle.asg_build_exact(E, theta, nthreads=16), name + " exact")
+    assert t.flagged_group == 0 and t.tolerated == 0
+    bits = oracle.asg_normalize(E)
+    ref = oracle.asg_build(bits, theta, nthreads=16)
+    t = compare_groups(pcg.asg_build(as_bf16_tensor(bits).cuda(), theta, cap=64), ref, name)
+    t.report(name)
+    assert t.tolerated <= max(2, t.flagged_group)

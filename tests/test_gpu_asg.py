@@ -4,6 +4,8 @@ bit-exact; membership of the bf16 form exact except for pairs the oracle flags a
 of the threshold (fp32 accumulation against fp64), which are counted; membership of the exact
 form equal to Eq. (1) on the embeddings in double (a cosine within 1e-12 of the threshold would
 be flagged: none occurs).  Run with ``-m gpu`` on an MI355X."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -253,7 +255,7 @@ def test_exact_rows_of_a_clustered_recipe_at_full_size():
     assert closest > 1e-12 and n_band > 0
 
 
-@pytest.mark.parametrize("case", range(16))
+@pytest.mark.parametrize("case", range(int(os.environ.get("PCG_RANDOM_CASES", "16"))))
 def test_random_construction_shapes(case):
     """Seeded random shapes of the construction: vocabulary, embedding width, threshold, iid or
     clustered embeddings are drawn; both forms run against their oracles (whole CSR)."""

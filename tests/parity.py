@@ -121,7 +121,7 @@ def compare_verify(gpu: pcg.VerifyOutput, ref: oracle.VerifyResult, og: oracle.G
 
 def run_both(V, row_ptr, members, tgt: torch.Tensor, dft: torch.Tensor, ptok, pgrp, *,
              temperature=1.0, seed=0, offset=0, dg: pcg.Groups = None, og: oracle.Groups = None,
-             nthreads=16):
+             nthreads=16, static_scratch=False):
     """Run the HIP library and the oracle on the same inputs; returns (gpu, ref, og, diag)."""
     og = og or oracle_groups(V, row_ptr, members)
     dg = dg or device_groups(V, row_ptr, members)
@@ -129,7 +129,8 @@ def run_both(V, row_ptr, members, tgt: torch.Tensor, dft: torch.Tensor, ptok, pg
     gpu = pcg.verify(dg, tgt.cuda(), dft.cuda(),
                      torch.from_numpy(np.ascontiguousarray(ptok, dtype=np.int32)).cuda(),
                      torch.from_numpy(np.ascontiguousarray(pgrp, dtype=np.int32)).cuda(),
-                     temperature=temperature, seed=seed, offset=offset, diag=diag)
+                     temperature=temperature, seed=seed, offset=offset, diag=diag,
+                     static_scratch=static_scratch)
     torch.cuda.synchronize()
     ref = oracle.verify(og, as_oracle_logits(tgt), as_oracle_logits(dft), ptok, pgrp,
                         temperature=temperature, seed=seed, offset=offset, nthreads=nthreads)

@@ -69,8 +69,9 @@ def test_random_shape(case):
         pref = oracle.propose(og, rev, as_oracle_logits(dft), temperature=tau, seed=case + 7, offset=step, nthreads=8)
         prop.add(compare_proposals(tok, grp, pref, og))
         ptok, pgrp = pref.tokens, pref.groups
+        # every third case through the entry point that uses the library's own scratch array
         gpu, ref, _, diag = run_both(V, rp, mem, tgt, dft, ptok, pgrp, temperature=tau, seed=case,
-                                     offset=step, dg=dg, og=og)
+                                     offset=step, dg=dg, og=og, static_scratch=case % 3 == 1)
         total.add(compare_verify(gpu, ref, og, ptok, pgrp))
         assert diag["sequences"] == B and diag["bad_proposal"] == 0
         g2, trials, r2, _ = run_both_thinning(V, tgt, dft, ptok, pgrp, dg=dg, og=og, rev=rev,

@@ -72,3 +72,46 @@ def test_a_recorded_step_replays_to_the_eager_result():
         for g, w in zip(got, want):
             np.testing.assert_array_equal(g.cpu().numpy(), w.cpu().numpy())
         assert (out_v.accept_len >= 0).all() and (out_v.accept_len <= K).all()
+
+
+def test_calls_on_two_streams_with_their_own_workspaces_do_not_disturb_each_other():
+    """The library keeps no device state between calls (pcg_verify_static's array aside), so
+    calls that run at the same time on two streams, each with a workspace of its own, must give
+    what the same calls give one after the other.  Default-priority streams, several rounds."""
+    V, B, K, tau = 20000, 24, 6, 0.9
+    rp, mem = W.random_groups(V, 9000, 4, 30, seed=77, cover=False)
+    dg = pcg.Groups.from_csr(V, rp, mem, "cuda", reverse=True)
+    dev = dg.device
+    inputs = []
+    for seed in (1, 2):
+        t, d = logits_pair(B, K, V, "bf16", seed=seed, sigma_d=0.7)
+        t, d = t.to(dev), d.to(dev)
+        ptok, pgrp = pcg.propose(dg, d, temperature=tau, seed=5, offset=seed)
+        inputs.append((t, d, ptok, pgrp))
+    torch.cuda.synchronize()
+    nbytes = max(pcg.verify_workspace_bytes(V, dg.G, B, K), pcg.verify_thinning_workspace_bytes(V, B, K))
+    ws = [torch.empty(nbytes, dtype=torch.uint8, device=dev) for _ in range(2)]
+
+    def one(k, rounds):
+        t, d, ptok, pgrp = inputs[k]
+        res = []
+        for r in range(rounds):
+            v = pcg.verify(dg, t, d, ptok, pgrp, temperature=tau, seed=9, offset=r, workspace=ws[k])
+            th, trials = pcg.verify_thinning(dg, t, d, ptok, pgrp, temperature=tau, seed=9, offset=r, workspace=ws[k])
+            res.append((v.accept_len, v.out_tokens, v.out_groups, th.accept_len, th.out_tokens, th.out_groups, trials))
+        return res
+
+    rounds = 12
+    want = [one(0, rounds), one(1, rounds)]             # one after the other on the current stream
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    got = [None, None]
+    for k in (0, 1):
+        with torch.cuda.stream(streams[k]):
+            got[k] = one(k, rounds)
+    for s in streams:
+        s.synchronize()
+    for k in (0, 1):
+        for a, b in zip(got[k], want[k]):
+            for x, y in zip(a, b):
+                np.testing.assert_array_equal(x.cpu().numpy(), y.cpu().numpy())

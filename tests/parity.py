@@ -73,7 +73,7 @@ def device_groups(V: int, row_ptr, members, prepare: bool = True, chunk_groups: 
 
 
 def as_oracle_logits(t: torch.Tensor):
-    t = t.detach().cpu()
+    t = t.detach().cpu().contiguous()           # the device side may be a strided view
     return oracle.bf16_bits(t) if t.dtype == torch.bfloat16 else t.numpy()
 
 

@@ -64,6 +64,22 @@ def test_random_shape(case):
         tgt, dft = torch.from_numpy(tgt), torch.from_numpy(dft)
         if dtype == "bf16":
             tgt, dft = tgt.to(torch.bfloat16), dft.to(torch.bfloat16)
+        if case % 4 == 2:
+            # a few tokens masked out on every row (never all of a row)
+            mask = torch.from_numpy(rng.random(V) < 0.2)
+            mask[int(rng.integers(0, V))] = False
+            tgt[:, :, mask] = -float("inf")
+            dft[:, :, mask] = -float("inf")
+        if case % 2 == 1:
+            # the rows as views into larger buffers: row strides above V, starts that are not
+            # 16-byte aligned (the kernels then take their element-wise loads), and the draft
+            # inside a [B, K + 1, V] buffer whose last row is never read
+            pad, off = int(rng.integers(1, 40)), int(rng.integers(0, 9))
+            big_t = torch.zeros((B, K + 1, V + pad + off), dtype=tgt.dtype, device="cuda")
+            big_d = torch.full((B, K + 1, V + pad + off), 7.0, dtype=dft.dtype, device="cuda")
+            big_t[:, :, off:off + V] = tgt.cuda()
+            big_d[:, :K, off:off + V] = dft.cuda()
+            tgt, dft = big_t[:, :, off:off + V], big_d[:, :K, off:off + V]
         # proposals by the library itself, checked against the oracle's, whose own go on
         tok, grp = pcg.propose(dg, dft.cuda(), temperature=tau, seed=case + 7, offset=step)
         pref = oracle.propose(og, rev, as_oracle_logits(dft), temperature=tau, seed=case + 7, offset=step, nthreads=8)
@@ -78,7 +94,7 @@ def test_random_shape(case):
                                               temperature=tau, seed=case, offset=step)
         thin.add(compare_thinning(g2, trials, r2, og, ptok, pgrp))
         if step == 0:
-            rows = tgt[: min(B, 3), 0].contiguous()
+            rows = tgt[: min(B, 3), 0]               # strided when the rows are views
             out = pcg.group_probs(dg, rows.cuda(), tau)
             torch.cuda.synchronize()
             err = group_probs_error(out, oracle.group_probs(og, as_oracle_logits(rows), tau))

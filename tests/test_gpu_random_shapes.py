@@ -35,6 +35,10 @@ def draw_case(case: int):
         B = max(1, B // 2)
     dtype = "bf16" if rng.random() < 0.5 else "f32"
     tau = float(np.round(rng.uniform(0.5, 1.5), 3))
+    if case % 7 == 3:
+        tau = 0.07                                    # nearly greedy: most of every row underflows
+    if case % 7 == 5:
+        tau = 6.0                                     # nearly uniform
     layout = ["prepared", "prepared-4096", "csr"][int(rng.integers(0, 3))]
     cover = bool(rng.random() < 0.5)
     weighted = bool(rng.random() < 1 / 3)
